@@ -1,0 +1,398 @@
+"""Pins for the CPU oracle: each test checks oracle/alora_oracle.py against something other
+than itself -- a closed form, a library routine on a special case, a separately written
+pure-loop brute force, or an invariant the paper proves (Proposition 1) -- chosen so that a
+dropped term, a wrong sign or index, or a transposed operand fails at least one of them."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import alora_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_layer(seed, d=24, hq=4, hkv=2, h=6, r=3, n_ad=2, rms=True, scale=(2.0, 0.5), mlp=0):
+    g = np.random.default_rng(seed)
+    nq, nkv = hq * h, hkv * h
+    kw = {}
+    if mlp:
+        kw = dict(W_o=g.normal(size=(d, nq)) / math.sqrt(nq), rms2_gain=g.normal(1, 0.1, size=d),
+                  W_gate=g.normal(size=(mlp, d)) / math.sqrt(d), W_up=g.normal(size=(mlp, d)) / math.sqrt(d),
+                  W_down=g.normal(size=(d, mlp)) / math.sqrt(mlp))
+    return orc.Layer(hq, hkv, h,
+                     W_qkv=g.normal(size=(nq + 2 * nkv, d)) / math.sqrt(d),
+                     A=g.normal(size=(n_ad, 3, r, d)) / math.sqrt(d),
+                     B_q=g.normal(size=(n_ad, nq, r)) * 0.3,
+                     B_k=g.normal(size=(n_ad, nkv, r)) * 0.3,
+                     B_v=g.normal(size=(n_ad, nkv, r)) * 0.3,
+                     scale=list(scale)[:n_ad],
+                     rms_gain=g.normal(1, 0.1, size=d) if rms else None, **kw)
+
+
+# ---------------------------------------------------------------------------- bf16 rounding
+def test_round_to_bf16_matches_library_and_ties():
+    g = np.random.default_rng(0)
+    a32 = (g.normal(size=20000) * np.exp(g.normal(size=20000) * 4)).astype(np.float32)
+    want = torch.from_numpy(a32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = orc.round_to_bf16(a32.astype(np.float64))
+    assert np.array_equal(got, want)
+    # exact ties between two bf16 neighbours go to the even one: 1 + 2^-8 -> 1 ; 1 + 3*2^-8 -> 1 + 2^-6
+    ties = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -(1 + 2.0 ** -8), 0.0, 1.0])
+    assert np.array_equal(orc.round_to_bf16(ties), np.array([1.0, 1 + 2.0 ** -6, -1.0, 0.0, 1.0]))
+    # a float64 just above a tie must round up although float32 would first land on the tie
+    assert orc.round_to_bf16(np.array([1 + 2.0 ** -8 + 2.0 ** -40]))[0] == 1 + 2.0 ** -7
+
+
+# ---------------------------------------------------------------------------- RMSNorm
+def test_rmsnorm_closed_forms():
+    c, eps = 3.0, 1e-5
+    gain = np.array([1.0, 2.0, -1.0, 0.5])
+    out = orc.rmsnorm(np.full((1, 4), c), gain, eps)
+    assert np.allclose(out[0], gain * c / math.sqrt(c * c + eps), rtol=1e-14)
+    x = np.random.default_rng(1).normal(size=(5, 64)) * 7
+    y = orc.rmsnorm(x, np.ones(64), 0.0)
+    assert np.allclose(np.sqrt(np.mean(y * y, axis=1)), 1.0, rtol=1e-13)
+    assert orc.rmsnorm(x, None, 1e-5) is not None and np.array_equal(orc.rmsnorm(x, None, 1e-5), x)
+
+
+# ---------------------------------------------------------------------------- rotary embedding
+def test_rope_two_dim_rotation_by_hand():
+    u = np.array([[3.0, 4.0]])
+    for p in (0, 1, 7):
+        got = orc.rope(u, np.array([p]), 1, 2, 10000.0)[0]
+        want = np.array([3 * math.cos(p) - 4 * math.sin(p), 4 * math.cos(p) + 3 * math.sin(p)])
+        assert np.allclose(got, want, rtol=1e-14, atol=1e-14)
+
+
+def test_rope_pairing_frequencies_identity_norm():
+    h, theta = 8, 100.0
+    u = np.random.default_rng(2).normal(size=(4, 2 * h))
+    pos = np.array([0, 1, 5, 1000])
+    r = orc.rope(u, pos, 2, h, theta)
+    assert np.array_equal(r[0], u[0])                      # position 0 is the identity
+    for i, p in enumerate(pos):
+        for head in range(2):
+            for c in range(h // 2):
+                ang = p * theta ** (-2.0 * c / h)
+                a, b = u[i, head * h + c], u[i, head * h + c + h // 2]
+                assert math.isclose(r[i, head * h + c], a * math.cos(ang) - b * math.sin(ang), rel_tol=1e-12, abs_tol=1e-12)
+                assert math.isclose(r[i, head * h + c + h // 2], b * math.cos(ang) + a * math.sin(ang), rel_tol=1e-12, abs_tol=1e-12)
+    assert np.allclose(np.linalg.norm(r, axis=1), np.linalg.norm(u, axis=1), rtol=1e-13)
+
+
+def test_rope_makes_attention_depend_on_relative_position_only():
+    # <rope(q,m), rope(k,n)> depends on m-n only, so a cache-reuse call whose prefix keys and
+    # new rows are ALL shifted by the same offset gives the same attention output.
+    L = rand_layer(3, rms=False)
+    g = np.random.default_rng(4)
+    q = g.normal(size=(1, L.n_q))
+    kk = g.normal(size=(6, L.n_kv))
+    v = g.normal(size=(6, L.n_kv))
+    outs = []
+    for shift in (0, 11):
+        qr = orc.rope(q, np.array([5 + shift]), L.n_q_heads, L.head_dim, L.rope_theta)
+        kr = orc.rope(kk, np.arange(6) + shift, L.n_kv_heads, L.head_dim, L.rope_theta)
+        outs.append(orc.causal_attention(qr, np.array([5]), kr, v, L.n_q_heads, L.n_kv_heads, L.head_dim))
+    assert np.allclose(outs[0], outs[1], rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------- attention
+def test_attention_matches_library_sdpa_with_gqa():
+    hq, hkv, h, S, Lk = 6, 2, 8, 5, 9
+    g = np.random.default_rng(5)
+    q = g.normal(size=(S, hq * h))
+    K = g.normal(size=(Lk, hkv * h))
+    V = g.normal(size=(Lk, hkv * h))
+    pos = np.array([4, 5, 6, 7, 8])
+    got = orc.causal_attention(q, pos, K, V, hq, hkv, h)
+    tq = torch.from_numpy(q).view(S, hq, h).transpose(0, 1)                      # [hq, S, h]
+    tk = torch.from_numpy(K).view(Lk, hkv, h).transpose(0, 1).repeat_interleave(hq // hkv, dim=0)
+    tv = torch.from_numpy(V).view(Lk, hkv, h).transpose(0, 1).repeat_interleave(hq // hkv, dim=0)
+    mask = torch.arange(Lk)[None, :] <= torch.from_numpy(pos)[:, None]
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)
+    want = want.transpose(0, 1).reshape(S, hq * h).numpy()
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
+
+
+def test_attention_closed_forms():
+    hq, hkv, h = 4, 2, 4
+    g = np.random.default_rng(6)
+    K = g.normal(size=(7, hkv * h))
+    V = g.normal(size=(7, hkv * h))
+    pos = np.array([0, 3, 6])
+    # zero queries: uniform weights over the visible rows -> mean of visible V rows per kv head
+    o = orc.causal_attention(np.zeros((3, hq * h)), pos, K, V, hq, hkv, h).reshape(3, hq, h)
+    Vh = V.reshape(7, hkv, h)
+    for i, p in enumerate(pos):
+        for head in range(hq):
+            assert np.allclose(o[i, head], Vh[:p + 1, head // 2].mean(axis=0), rtol=1e-13)
+    # a single visible key: output is that value row, whatever the query
+    q = g.normal(size=(1, hq * h))
+    o = orc.causal_attention(q, np.array([0]), K, V, hq, hkv, h).reshape(hq, h)
+    for head in range(hq):
+        assert np.allclose(o[head], Vh[0, head // 2], rtol=1e-14)
+    # all value rows equal: output is that row
+    Vc = np.tile(g.normal(size=(1, hkv * h)), (7, 1))
+    o = orc.causal_attention(g.normal(size=(2, hq * h)), np.array([2, 6]), K, Vc, hq, hkv, h).reshape(2, hq, h)
+    for head in range(hq):
+        assert np.allclose(o[:, head], Vc.reshape(7, hkv, h)[0, head // 2], rtol=1e-13)
+    # a key far more aligned with the query than the rest takes (almost) all the weight
+    K2 = np.zeros((3, hkv * h)); K2[1] = 50.0
+    qq = np.ones((1, hq * h))
+    o = orc.causal_attention(qq, np.array([2]), K2, V[:3], hq, hkv, h).reshape(hq, h)
+    assert np.allclose(o[0], Vh[1, 0], atol=1e-9)
+
+
+# ---------------------------------------------------------------------------- gating (Eq.6, Prop.1)
+def _x(seed, n, d):
+    return np.random.default_rng(seed).normal(size=(n, d))
+
+
+def test_zero_delta_or_late_invocation_is_the_base_model():
+    L = rand_layer(7)
+    x = _x(8, 9, 24)
+    base = orc.ref_full(L, x, 0, -1)
+    Lz = rand_layer(7); Lz.B_q[:] = 0; Lz.B_k[:] = 0; Lz.B_v[:] = 0
+    for got in (orc.ref_full(Lz, x, 3, 0), orc.ref_full(rand_layer(7, scale=(0.0, 0.0)), x, 3, 1),
+                orc.ref_full(L, x, 9, 0), orc.ref_full(L, x, 100, 1)):
+        for a, b in zip(got, base):
+            assert np.array_equal(a, b)
+    assert not np.allclose(orc.ref_full(L, x, 3, 0)[0], base[0])
+
+
+def test_invocation_at_start_is_standard_lora_with_merged_weights():
+    # k = 0: Eq.6 reduces to Eq.5, i.e. plain attention with the dense W' = W + s B A
+    L = rand_layer(9)
+    x = _x(10, 8, 24)
+    a = 1
+    got_o, got_k, got_v = orc.ref_full(L, x, 0, a)
+    s = L.scale[a]
+    Wm = torch.from_numpy(L.W_qkv.copy())
+    nq, nkv = L.n_q, L.n_kv
+    for p, (B, lo) in enumerate(((L.B_q, 0), (L.B_k, nq), (L.B_v, nq + nkv))):
+        Bt, At = torch.from_numpy(B[a]), torch.from_numpy(L.A[a, p])
+        Wm[lo:lo + Bt.shape[0]] += s * (Bt @ At)
+    Lm = rand_layer(9)
+    Lm.W_qkv = Wm.numpy()
+    want_o, want_k, want_v = orc.ref_full(Lm, x, 0, -1)
+    assert np.allclose(got_o, want_o, rtol=1e-11, atol=1e-12)
+    assert np.allclose(got_k, want_k, rtol=1e-11, atol=1e-12)
+    assert np.allclose(got_v, want_v, rtol=1e-11, atol=1e-12)
+
+
+def test_prefix_rows_identical_for_base_and_every_adapter_suffix_rows_differ():
+    L = rand_layer(11)
+    x = _x(12, 10, 24)
+    k = 6
+    ob, kb, vb = orc.ref_full(L, x, k, -1)
+    o0, k0, v0 = orc.ref_full(L, x, k, 0)
+    o1, k1, v1 = orc.ref_full(L, x, k, 1)
+    for t in ((o0, k0, v0), (o1, k1, v1)):
+        for a, b in zip(t, (ob, kb, vb)):
+            assert np.array_equal(a[:k], b[:k])            # all states before k: bit-identical
+    assert np.abs(k0[k:] - kb[k:]).min() > 0 and np.abs(v0[k:] - v1[k:]).min() > 0
+    assert np.abs(o0[k:] - o1[k:]).max() > 1e-3
+
+
+def test_low_rank_product_equals_dense_delta():
+    L = rand_layer(13, rms=False)
+    x = _x(14, 4, 24)
+    q, kk, v = orc.project_qkv(L, x, np.arange(4), 0, 0)
+    s = L.scale[0]
+    for got, W, B, p in ((q, L.W_qkv[:L.n_q], L.B_q, 0), (kk, L.W_qkv[L.n_q:L.n_q + L.n_kv], L.B_k, 1),
+                         (v, L.W_qkv[L.n_q + L.n_kv:], L.B_v, 2)):
+        dense = W + s * (B[0] @ L.A[0, p])
+        assert np.allclose(got, x @ dense.T, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------- cache reuse
+@pytest.mark.parametrize("P,S,k", [(6, 4, 6), (6, 4, 3), (6, 4, 8), (6, 4, 10), (6, 4, 50), (0, 10, 0),
+                                   (0, 10, 4), (9, 1, 9), (1, 9, 1)])
+@pytest.mark.parametrize("cache_dtype", ["f64", "bf16"])
+def test_cache_reuse_equals_recompute(P, S, k, cache_dtype):
+    """The brute-force identity: recomputing the whole sequence with position-gated weights
+    gives, on the new rows, what the cache-reuse path gives from the stored prefix."""
+    L = rand_layer(15)
+    x = _x(16, P + S, 24)
+    a = 1
+    of, Kf, Vf = orc.ref_full(L, x, k, a, cache_dtype)
+    oc, kn, vn = orc.ref_cached(L, Kf[:P], Vf[:P], P, x[P:], k, a, cache_dtype)
+    assert np.allclose(oc, of[P:], rtol=1e-11, atol=1e-12)
+    # same rows, up to the summation order of the matrix products (a one-row and a many-row
+    # product may differ in the last float64 bit, which can move a bf16 rounding by one step)
+    tol = 1e-12 if cache_dtype == "f64" else 2.0 ** -7
+    assert np.allclose(kn, Kf[P:], rtol=tol, atol=1e-13) and np.allclose(vn, Vf[P:], rtol=tol, atol=1e-13)
+    assert np.mean(kn == Kf[P:]) > 0.99 or cache_dtype == "f64"
+    assert kn.shape == (S, L.n_kv)                      # Prop.2: exactly S new cache rows
+    if k >= P:
+        # the prefix the adapter run reuses is the base model's own prefix (Prop.1)
+        ob, Kb, Vb = orc.ref_full(L, x[:P], 0, -1, cache_dtype)
+        assert np.allclose(Kb, Kf[:P], rtol=tol, atol=1e-13) and np.allclose(Vb, Vf[:P], rtol=tol, atol=1e-13)
+
+
+def test_chunked_prefill_and_token_by_token_decode_agree():
+    L = rand_layer(17)
+    P, S, k, a = 5, 6, 5, 0
+    x = _x(18, P + S, 24)
+    _, Kb, Vb = orc.ref_full(L, x[:P], 0, -1)
+    whole, kn, vn = orc.ref_cached(L, Kb, Vb, P, x[P:], k, a)
+    # two chunks
+    o1, k1, v1 = orc.ref_cached(L, Kb, Vb, P, x[P:P + 2], k, a)
+    K2, V2 = np.concatenate([Kb, k1]), np.concatenate([Vb, v1])
+    o2, k2, v2 = orc.ref_cached(L, K2, V2, P + 2, x[P + 2:], k, a)
+    assert np.allclose(np.concatenate([o1, o2]), whole, rtol=1e-12, atol=1e-13)
+    # one token at a time
+    K, V, outs = Kb, Vb, []
+    for t in range(S):
+        o, kt, vt = orc.ref_cached(L, K, V, P + t, x[P + t:P + t + 1], k, a)
+        K, V = np.concatenate([K, kt]), np.concatenate([V, vt])
+        outs.append(o)
+    assert np.allclose(np.concatenate(outs), whole, rtol=1e-12, atol=1e-13)
+    assert np.allclose(K[P:], kn, rtol=1e-13) and np.allclose(V[P:], vn, rtol=1e-13)
+
+
+def test_batch_is_a_loop_over_independent_sequences():
+    L = rand_layer(19)
+    P, S = [4, 0, 7], [3, 5, 1]
+    k, ad = [4, 2, 3], [0, 1, -1]
+    xs = [_x(20 + b, P[b] + S[b], 24) for b in range(3)]
+    caches = []
+    for b in range(3):
+        _, Kb, Vb = orc.ref_full(L, xs[b][:P[b]], k[b], ad[b])
+        caches.append((Kb, Vb))
+    packed = np.concatenate([xs[b][P[b]:] for b in range(3)])
+    cu = [0, 3, 8, 9]
+    O, rows = orc.ref_prefill_batch(L, caches, P, packed, cu, k, ad)
+    for b in range(3):
+        of, Kf, Vf = orc.ref_full(L, xs[b], k[b], ad[b])
+        assert np.allclose(O[cu[b]:cu[b + 1]], of[P[b]:], rtol=1e-11, atol=1e-12)
+        assert np.allclose(rows[b][0], Kf[P[b]:], rtol=1e-12)
+
+
+def test_inputs_and_cache_are_not_modified():
+    L = rand_layer(21)
+    x = _x(22, 8, 24)
+    _, Kb, Vb = orc.ref_full(L, x[:5], 0, -1)
+    canary_k = np.concatenate([Kb, np.full((3, L.n_kv), 777.0)])
+    canary_v = np.concatenate([Vb, np.full((3, L.n_kv), -777.0)])
+    ck, cv, cx = canary_k.copy(), canary_v.copy(), x.copy()
+    orc.ref_cached(L, canary_k, canary_v, 5, x[5:], 5, 0)
+    assert np.array_equal(ck, canary_k) and np.array_equal(cv, canary_v) and np.array_equal(cx, x)
+
+
+# ---------------------------------------------------------------------------- pure-loop brute force
+def _loops_full(L, x, k, a):
+    """Everything again, scalar by scalar, with python loops and the math module only."""
+    n, d = len(x), len(x[0])
+    hq, hkv, h = L.n_q_heads, L.n_kv_heads, L.head_dim
+    G = hq // hkv
+    nq, nkv = hq * h, hkv * h
+    rows = []
+    for i in range(n):
+        xi = list(x[i])
+        if L.rms_gain is not None:
+            ms = sum(c * c for c in xi) / d
+            xi = [xi[c] * L.rms_gain[c] / math.sqrt(ms + L.rms_eps) for c in range(d)]
+        y = [sum(L.W_qkv[o][c] * xi[c] for c in range(d)) for o in range(nq + 2 * nkv)]
+        if a >= 0 and i >= k:
+            for p, (B, lo, width) in enumerate(((L.B_q, 0, nq), (L.B_k, nq, nkv), (L.B_v, nq + nkv, nkv))):
+                t = [sum(L.A[a][p][j][c] * xi[c] for c in range(d)) for j in range(L.A.shape[2])]
+                for o in range(width):
+                    y[lo + o] += L.scale[a] * sum(B[a][o][j] * t[j] for j in range(len(t)))
+        for lo, heads in ((0, hq), (nq, hkv)):
+            for hd in range(heads):
+                for c in range(h // 2):
+                    ang = i * L.rope_theta ** (-2.0 * c / h)
+                    u, w = y[lo + hd * h + c], y[lo + hd * h + c + h // 2]
+                    y[lo + hd * h + c] = u * math.cos(ang) - w * math.sin(ang)
+                    y[lo + hd * h + c + h // 2] = w * math.cos(ang) + u * math.sin(ang)
+        rows.append(y)
+    out = []
+    for i in range(n):
+        oi = []
+        for hd in range(hq):
+            g = hd // G
+            e = [sum(rows[i][hd * h + c] * rows[j][nq + g * h + c] for c in range(h)) / math.sqrt(h)
+                 for j in range(i + 1)]
+            m = max(e)
+            w = [math.exp(v - m) for v in e]
+            z = sum(w)
+            oi += [sum(w[j] / z * rows[j][nq + nkv + g * h + c] for j in range(i + 1)) for c in range(h)]
+        out.append(oi)
+    K = [r[nq:nq + nkv] for r in rows]
+    V = [r[nq + nkv:] for r in rows]
+    return np.array(out), np.array(K), np.array(V)
+
+
+@pytest.mark.parametrize("k,a", [(2, 0), (0, 1), (3, -1), (5, 1)])
+def test_against_scalar_loop_brute_force(k, a):
+    L = rand_layer(23, d=6, hq=2, hkv=1, h=4, r=2)
+    x = _x(24, 5, 6)
+    got = orc.ref_full(L, x, k, a)
+    want = _loops_full(L, x.tolist(), k, a)
+    for g_, w_ in zip(got, want):
+        assert np.allclose(g_, w_, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------- hand-worked example
+def test_two_token_example_worked_by_hand():
+    """tests/golden/two_token_example.txt: d = 2, one head of width 2, two tokens, adapter on
+    from the second token.  The expected values are closed forms derived there by hand."""
+    txt = open(os.path.join(GOLDEN, "two_token_example.txt")).read()
+    assert "Eq.6" in txt and "Eq.1" in txt
+    L = orc.Layer(1, 1, 2,
+                  W_qkv=np.array([[1.0, 2.0], [0.0, 1.0], [1.0, 0.0], [0.0, 1.0], [1.0, 0.0], [3.0, 1.0]]),
+                  A=np.array([[[[0.0, 1.0]], [[0.0, 1.0]], [[0.0, 1.0]]]]),
+                  B_q=np.array([[[1.0], [0.0]]]), B_k=np.array([[[0.0], [1.0]]]), B_v=np.array([[[0.0], [0.0]]]),
+                  scale=[2.0], rms_gain=None)
+    x = np.array([[1.0, 0.0], [0.0, 1.0]])
+    c, s, r2 = math.cos(1.0), math.sin(1.0), math.sqrt(2.0)
+    # adapter on at k = 1
+    o, K, V = orc.ref_full(L, x, 1, 0)
+    e0, e1 = (4 * c - s) / r2, 3 / r2
+    p1 = 1 / (1 + math.exp(e0 - e1))
+    assert np.allclose(o[0], [1.0, 3.0], rtol=1e-14)
+    assert np.allclose(o[1], [(1 - p1) * 1.0, (1 - p1) * 3.0 + p1 * 1.0], rtol=1e-13)
+    assert np.allclose(K, [[1.0, 0.0], [-3 * s, 3 * c]], rtol=1e-14, atol=1e-15)
+    assert np.allclose(V, [[1.0, 3.0], [0.0, 1.0]], rtol=1e-14)
+    # base model
+    o, K, V = orc.ref_full(L, x, 1, -1)
+    e0, e1 = (2 * c - s) / r2, 1 / r2
+    p1 = 1 / (1 + math.exp(e0 - e1))
+    assert np.allclose(o[1], [(1 - p1) * 1.0, (1 - p1) * 3.0 + p1 * 1.0], rtol=1e-13)
+    assert np.allclose(K, [[1.0, 0.0], [-s, c]], rtol=1e-14, atol=1e-15)
+
+
+# ---------------------------------------------------------------------------- decoder-layer tail
+def test_layer_tail_against_library_ops():
+    L = rand_layer(25, mlp=40)
+    g = np.random.default_rng(26)
+    x = g.normal(size=(3, 24))
+    attn = g.normal(size=(3, L.n_q))
+    got = orc.layer_tail(L, x, attn)
+    tx, ta = torch.from_numpy(x), torch.from_numpy(attn)
+    hres = tx + torch.nn.functional.linear(ta, torch.from_numpy(L.W_o))
+    hn = hres * torch.rsqrt(hres.pow(2).mean(-1, keepdim=True) + L.rms_eps) * torch.from_numpy(L.rms2_gain)
+    m = torch.nn.functional.silu(torch.nn.functional.linear(hn, torch.from_numpy(L.W_gate))) * \
+        torch.nn.functional.linear(hn, torch.from_numpy(L.W_up))
+    want = hres + torch.nn.functional.linear(m, torch.from_numpy(L.W_down))
+    assert np.allclose(got, want.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_stack_cache_reuse_equals_recompute():
+    layers = [rand_layer(30 + i, mlp=32) for i in range(3)]
+    P, S, k, a = 5, 3, 5, 0
+    x = _x(33, P + S, 24)
+    full, caches = orc.ref_stack_full(layers, x, k, a)
+    # per-layer prefix caches are those of the base model run on the prefix alone (Prop.1:
+    # all internal states before the invocation index agree)
+    base_out, base_caches = orc.ref_stack_full(layers, x[:P], 0, -1)
+    for (Kf, Vf), (Kb, Vb) in zip(caches, base_caches):
+        assert np.allclose(Kf[:P], Kb, rtol=1e-12, atol=1e-13) and np.allclose(Vf[:P], Vb, rtol=1e-12, atol=1e-13)
+    assert np.allclose(full[:P], base_out, rtol=1e-12, atol=1e-13)
+    got, rows = orc.ref_stack_cached(layers, base_caches, P, x[P:], k, a)
+    assert np.allclose(got, full[P:], rtol=1e-10, atol=1e-11)
+    assert all(kn.shape[0] == S for kn, _ in rows)
