@@ -1,0 +1,155 @@
+/* libalora -- Activated LoRA (aLoRA) attention over a reused base-model KV cache,
+ * hand-written HIP for AMD MI355X (gfx950).  Plain C ABI: pointers and sizes only.
+ *
+ * The operation (paper Section 2, Eq.6, with Eq.1-4 of its background section):
+ * for every sequence b of a packed batch, tokens at absolute positions before the
+ * invocation index k_b use the base projection weights; tokens at positions >= k_b use
+ *      y = W_p x + s_a * B_{a,p} (A_{a,p} x),      p in {q, k, v},  a = adapter of b.
+ * Keys and values of positions already in the cache are taken from it unchanged
+ * (Proposition 1); only the new rows are projected, rotated (rotary embedding),
+ * appended behind the cached rows, and the new queries attend causally -- each over cache
+ * rows 0..its own position, itself included (Eq.4) -- with softmax scale 1/sqrt(head_dim)
+ * (Eq.1) and grouped-query head sharing (kv head = q head / (n_q_heads/n_kv_heads)).
+ *
+ * Conventions
+ *   - "HOST" pointers are ordinary host memory, read (and for seq_len written) during the
+ *     call; "DEVICE" pointers are HIP device memory of the context's GPU.
+ *   - All matrices are row-major.  W is stored [out, in], A [rank, in], B [out, rank].
+ *   - dtype selects the storage type of x, W, A, B, gains, cache and outputs
+ *     (ALORA_BF16 or ALORA_F32); accumulation is always fp32.
+ *   - Rotary embedding: "rotate-half" pairing -- within a head, element c < head_dim/2 is
+ *     paired with element c + head_dim/2 and the pair is rotated by pos * theta^(-2c/head_dim);
+ *     absolute positions; applied to q and k before k is stored, never to v.
+ *   - k_b is the 0-based absolute position of the first adapted token (the paper's
+ *     1-based t_invoke minus 1).  k_b may lie before the cached length (the cache already
+ *     holds adapted rows, as during decoding), inside the new rows, or beyond them (all new
+ *     rows are base rows).  adapter -1 means base model only.  k_b = 0 with an empty cache
+ *     is standard LoRA (Eq.5).
+ *   - Calls are asynchronous on the given stream.  The library owns only its context
+ *     (a workspace that grows on demand, staged copies of the small HOST arrays, a rotary
+ *     table); it never frees or keeps caller memory.  One context per stream; a context
+ *     is not thread-safe.
+ *   - Every argument is validated on the host before anything is launched.  On any error
+ *     nothing has been enqueued, the cache and seq_len are untouched, and
+ *     alora_last_error() describes the problem.
+ */
+#ifndef ALORA_H
+#define ALORA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct alora_ctx alora_ctx;
+
+typedef enum {
+  ALORA_OK = 0,
+  ALORA_EINVAL = 1,     /* null pointer, B < 1, negative length, bad option            */
+  ALORA_ESHAPE = 2,     /* unsupported or inconsistent layer shape                     */
+  ALORA_ECAPACITY = 3,  /* P_b + S_b exceeds the sequence's cache capacity or the pool */
+  ALORA_EADAPTER = 4,   /* adapter id outside [-1, n_adapters)                         */
+  ALORA_EDTYPE = 5,     /* dtype not ALORA_F32 / ALORA_BF16                            */
+  ALORA_EHIP = 6        /* a HIP runtime call failed                                   */
+} alora_status;
+
+typedef enum { ALORA_F32 = 0, ALORA_BF16 = 1 } alora_dtype;
+
+/* One decoder layer.  Immutable, caller-owned.  (Eq.2, Eq.5, Eq.6.) */
+typedef struct {
+  int32_t d;            /* hidden size (input width of the projections)                */
+  int32_t n_q_heads;    /* query heads; must be a multiple of n_kv_heads               */
+  int32_t n_kv_heads;
+  int32_t head_dim;     /* even, <= 256                                                */
+  int32_t rank;         /* adapter rank r, 1..256 (0 allowed when n_adapters == 0)     */
+  int32_t n_adapters;   /* number of adapters stored in A / B_*                        */
+  int32_t dtype;        /* alora_dtype                                                 */
+  int32_t intermediate; /* SwiGLU width I; 0 = attention block only                    */
+  const void *W_qkv;    /* DEVICE [N_q + 2 N_kv, d], rows ordered q | k | v            */
+  const void *A;        /* DEVICE [n_adapters, 3, rank, d]   (order q, k, v)           */
+  const void *B_q;      /* DEVICE [n_adapters, N_q,  rank]                             */
+  const void *B_k;      /* DEVICE [n_adapters, N_kv, rank]                             */
+  const void *B_v;      /* DEVICE [n_adapters, N_kv, rank]                             */
+  const float *scale;   /* HOST   [n_adapters]: s_a                                    */
+  const void *rms_gain; /* DEVICE [d], or NULL: no RMSNorm before the projections      */
+  float rms_eps;
+  float rope_theta;
+  /* Rest of the layer, used by alora_stack_prefill only (all unadapted, may be NULL
+   * otherwise): h = x + W_o attn; out = h + W_down( silu(W_gate n) * (W_up n) ),
+   * n = RMSNorm(h; rms2_gain).                                                       */
+  const void *W_o;      /* DEVICE [d, N_q]                                             */
+  const void *rms2_gain;/* DEVICE [d]                                                  */
+  const void *W_gate;   /* DEVICE [I, d]                                               */
+  const void *W_up;     /* DEVICE [I, d]                                               */
+  const void *W_down;   /* DEVICE [d, I]                                               */
+} alora_layer_desc;
+
+/* KV cache of one layer (Eq.3: the stored K_{1:t}, V_{1:t}).  A flat pool of token rows;
+ * sequence b owns rows [seq_offset[b], seq_offset[b] + seq_capacity[b]); its row j holds
+ * the key / value of absolute position j.  Keys are stored after rotation. */
+typedef struct {
+  void *k;                     /* DEVICE [pool_tokens, n_kv_heads, head_dim]           */
+  void *v;                     /* DEVICE [pool_tokens, n_kv_heads, head_dim]           */
+  int64_t pool_tokens;
+  const int64_t *seq_offset;   /* HOST [B]                                             */
+  const int32_t *seq_capacity; /* HOST [B]                                             */
+  int32_t *seq_len;            /* HOST [B]  in: P_b (rows already valid)
+                                            out: P_b + S_b, written only on ALORA_OK   */
+} alora_kv_cache;
+
+/* Context: create on the device that holds the buffers.  Returns ALORA_EHIP if the device
+ * cannot be used.  device = -1 creates a validation-only context that needs no GPU: calls on
+ * it check their arguments as usual and then return ALORA_EHIP instead of launching.
+ * alora_destroy(NULL) is a no-op; destroy synchronises the device. */
+alora_status alora_create(alora_ctx **ctx, int device);
+void alora_destroy(alora_ctx *ctx);
+/* Text of the last error on this context ("" if none); valid until the next call. */
+const char *alora_last_error(const alora_ctx *ctx);
+const char *alora_status_string(alora_status s);
+
+/* Kernel selection and tuning knobs, by name.  "kernels": 0 = automatic (MFMA kernels
+ * for bf16 where the shape allows, plain fp32-FMA kernels otherwise), 1 = force the plain
+ * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
+ * of attention into n chunks.  Unknown key or bad value: ALORA_EINVAL. */
+alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
+
+/* Adapter-activated prefill (Section 2, Eq.6; cost model of Proposition 2: only the T new
+ * rows are projected, and each attends over its sequence's cached-plus-new rows).
+ *   x_suffix        DEVICE [T, d]: hidden states of the new tokens, sequences back to back
+ *   cu_seqlens      HOST [B+1]: cu[0] = 0, non-decreasing, cu[B] = T; S_b = cu[b+1]-cu[b]
+ *   k_per_seq       HOST [B]: invocation index k_b >= 0
+ *   adapter_per_seq HOST [B]: adapter id, or -1 for base only
+ *   attn_out        DEVICE [T, N_q]: attention output of the new rows (before W_o)
+ * Effects: cache rows [P_b, P_b + S_b) of every sequence are written; rows before P_b are
+ * not touched (they are bit-identical afterwards); seq_len[b] += S_b.  Sequences with
+ * S_b = 0 are allowed and left alone.  T = 0 is a valid no-op. */
+alora_status alora_prefill(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
+                           const void *x_suffix, const int32_t *cu_seqlens,
+                           const int32_t *k_per_seq, const int32_t *adapter_per_seq, int32_t B,
+                           void *attn_out, void *stream);
+
+/* One decode step (Eq.3-4 with the rows of Eq.6): one new token per sequence.  Same result
+ * as alora_prefill with every S_b = 1, but attention runs through the memory-bound
+ * split-K kernel.   x_tok DEVICE [B, d]; attn_out DEVICE [B, N_q]. */
+alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
+                          const void *x_tok, const int32_t *k_per_seq,
+                          const int32_t *adapter_per_seq, int32_t B, void *attn_out, void *stream);
+
+/* First-token pass through a stack of decoder layers (Proposition 2: the attention block as
+ * in alora_prefill, then the per-token unadapted output projection and SwiGLU MLP with
+ * residuals, layer after layer).  layers[l] must all have the same shape and dtype and
+ * carry W_o / rms2_gain / W_gate / W_up / W_down.  caches[l] is layer l's cache; the
+ * sequence layout (seq_offset, seq_capacity, seq_len) is read from caches[0] and applies
+ * to every layer; only caches[0].seq_len is updated.
+ *   x        DEVICE [T, d]  input hidden states of the new tokens (not modified)
+ *   out      DEVICE [T, d]  hidden states after the last layer                         */
+alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers,
+                                 alora_kv_cache *caches, const void *x, const int32_t *cu_seqlens,
+                                 const int32_t *k_per_seq, const int32_t *adapter_per_seq,
+                                 int32_t B, void *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALORA_H */

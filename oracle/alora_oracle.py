@@ -209,6 +209,17 @@ def ref_full(layer: Layer, x_all: np.ndarray, k: int, adapter: int, cache_dtype:
     return o, Kc, Vc
 
 
+def base_kv(layer: Layer, x_all: np.ndarray, cache_dtype: str = "f64") -> Tuple[np.ndarray, np.ndarray]:
+    """Keys (rotated) and values the base model stores for a whole prefix at positions 0..L-1:
+    the first three steps of `ref_full` with no adapter, without the attention step."""
+    x_all = np.asarray(x_all, dtype=F64)
+    pos = np.arange(x_all.shape[0])
+    xh = rmsnorm(x_all, layer.rms_gain, layer.rms_eps)
+    _, kk, v = project_qkv(layer, xh, pos, 0, -1)
+    kk = rope(kk, pos, layer.n_kv_heads, layer.head_dim, layer.rope_theta)
+    return _store(kk, cache_dtype), _store(v, cache_dtype)
+
+
 def ref_cached(layer: Layer, cache_K: np.ndarray, cache_V: np.ndarray, P: int, x_suffix: np.ndarray,
                k: int, adapter: int, cache_dtype: str = "f64"
                ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:

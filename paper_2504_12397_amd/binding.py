@@ -1,0 +1,236 @@
+"""ctypes binding of libalora (include/alora.h).  Argument marshalling only: torch supplies
+device memory and streams, every step of the path runs in the library's HIP kernels.
+There is no fallback: if the shared library is missing, importing this module raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libalora.so")
+
+ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDTYPE, ALORA_EHIP = range(7)
+ALORA_F32, ALORA_BF16 = 0, 1
+
+EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
+           "alora_prefill", "alora_decode", "alora_stack_prefill"]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("d", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("rank", C.c_int32), ("n_adapters", C.c_int32), ("dtype", C.c_int32), ("intermediate", C.c_int32),
+                ("W_qkv", C.c_void_p), ("A", C.c_void_p), ("B_q", C.c_void_p), ("B_k", C.c_void_p),
+                ("B_v", C.c_void_p), ("scale", C.POINTER(C.c_float)), ("rms_gain", C.c_void_p),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                ("W_o", C.c_void_p), ("rms2_gain", C.c_void_p), ("W_gate", C.c_void_p), ("W_up", C.c_void_p),
+                ("W_down", C.c_void_p)]
+
+
+class KVCacheDesc(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("pool_tokens", C.c_int64),
+                ("seq_offset", C.POINTER(C.c_int64)), ("seq_capacity", C.POINTER(C.c_int32)),
+                ("seq_len", C.POINTER(C.c_int32))]
+
+
+def load_library() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_12397_amd.build` "
+                          "(there is no CPU or PyTorch fallback)")
+    lib = C.CDLL(LIB_PATH)
+    lib.alora_create.restype = C.c_int
+    lib.alora_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
+    lib.alora_destroy.restype = None
+    lib.alora_destroy.argtypes = [C.c_void_p]
+    lib.alora_last_error.restype = C.c_char_p
+    lib.alora_last_error.argtypes = [C.c_void_p]
+    lib.alora_status_string.restype = C.c_char_p
+    lib.alora_status_string.argtypes = [C.c_int]
+    lib.alora_set_option.restype = C.c_int
+    lib.alora_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    i32p = C.POINTER(C.c_int32)
+    lib.alora_prefill.restype = C.c_int
+    lib.alora_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
+                                  i32p, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.alora_decode.restype = C.c_int
+    lib.alora_decode.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
+                                 C.c_int32, C.c_void_p, C.c_void_p]
+    lib.alora_stack_prefill.restype = C.c_int
+    lib.alora_stack_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int32, C.POINTER(KVCacheDesc),
+                                        C.c_void_p, i32p, i32p, i32p, C.c_int32, C.c_void_p, C.c_void_p]
+    return lib
+
+
+_lib = load_library()
+
+
+class AloraError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_lib.alora_status_string(status).decode()}: {message}")
+        self.status = status
+        self.message = message
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "libalora takes contiguous row-major buffers"
+    return t.data_ptr()
+
+
+def _i32(a: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Layer:
+    """Holds the device tensors of one decoder layer and the C descriptor that points at them."""
+
+    def __init__(self, tensors: Dict[str, Optional[torch.Tensor]], n_q_heads: int, n_kv_heads: int, head_dim: int,
+                 rms_eps: float = 1e-5, rope_theta: float = 10000.0, intermediate: int = 0):
+        self.t = tensors
+        W = tensors["W_qkv"]
+        dt = {torch.float32: ALORA_F32, torch.bfloat16: ALORA_BF16}[W.dtype]
+        A = tensors.get("A")
+        n_ad = int(A.shape[0]) if A is not None else 0
+        rank = int(A.shape[2]) if A is not None else 0
+        self.scale = np.ascontiguousarray(np.asarray(tensors.get("scale") or [], dtype=np.float32))
+        g = tensors.get
+        self.desc = LayerDesc(int(W.shape[1]), n_q_heads, n_kv_heads, head_dim, rank, n_ad, dt, int(intermediate),
+                              _ptr(W), _ptr(A), _ptr(g("B_q")), _ptr(g("B_k")), _ptr(g("B_v")),
+                              self.scale.ctypes.data_as(C.POINTER(C.c_float)) if n_ad else None,
+                              _ptr(g("rms_gain")), float(rms_eps), float(rope_theta),
+                              _ptr(g("W_o")), _ptr(g("rms2_gain")), _ptr(g("W_gate")), _ptr(g("W_up")),
+                              _ptr(g("W_down")))
+        self.n_q = n_q_heads * head_dim
+        self.d = int(W.shape[1])
+        self.dtype = W.dtype
+        self.device = W.device
+
+
+class KVCache:
+    """A flat pool of token rows [pool_tokens, n_kv_heads, head_dim] for keys and for values, plus the
+    host-side table that says which rows belong to which sequence and how many are valid."""
+
+    def __init__(self, capacities: Sequence[int], n_kv_heads: int, head_dim: int, dtype: torch.dtype, device,
+                 fill: Optional[float] = None, guard_rows: int = 0):
+        caps = [int(c) for c in capacities]
+        self.seq_capacity = _i32(caps)
+        offs, o = [], guard_rows
+        for c in caps:
+            offs.append(o)
+            o += c + guard_rows
+        self.seq_offset = np.ascontiguousarray(np.asarray(offs, dtype=np.int64))
+        self.pool_tokens = int(o)
+        self.seq_len = np.zeros(len(caps), dtype=np.int32)
+        shape = (self.pool_tokens, n_kv_heads, head_dim)
+        if fill is None:
+            self.k = torch.zeros(shape, dtype=dtype, device=device)
+            self.v = torch.zeros(shape, dtype=dtype, device=device)
+        else:
+            self.k = torch.full(shape, fill, dtype=dtype, device=device)
+            self.v = torch.full(shape, -fill, dtype=dtype, device=device)
+        self._refresh()
+
+    def _refresh(self):
+        self.desc = KVCacheDesc(self.k.data_ptr(), self.v.data_ptr(), self.pool_tokens,
+                                self.seq_offset.ctypes.data_as(C.POINTER(C.c_int64)),
+                                self.seq_capacity.ctypes.data_as(C.POINTER(C.c_int32)),
+                                self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)))
+
+    def rows(self, b: int, lo: int, hi: int):
+        o = int(self.seq_offset[b])
+        return self.k[o + lo:o + hi], self.v[o + lo:o + hi]
+
+    def load_prefix(self, b: int, K: torch.Tensor, V: torch.Tensor):
+        """Copy already-computed cache rows (e.g. the base model's) for positions 0..n-1 of sequence b."""
+        n = K.shape[0]
+        o = int(self.seq_offset[b])
+        self.k[o:o + n] = K.to(self.k.dtype).view(n, *self.k.shape[1:]).to(self.k.device)
+        self.v[o:o + n] = V.to(self.v.dtype).view(n, *self.v.shape[1:]).to(self.v.device)
+        self.seq_len[b] = n
+
+
+class Context:
+    def __init__(self, device: int = 0):
+        h = C.c_void_p()
+        st = _lib.alora_create(C.byref(h), int(device))
+        if st != ALORA_OK:
+            raise AloraError(st, f"alora_create on device {device} failed")
+        self._h = h
+        self.device = int(device)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.alora_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != ALORA_OK:
+            raise AloraError(st, _lib.alora_last_error(self._h).decode())
+
+    def set_option(self, key: str, value: int):
+        self._check(_lib.alora_set_option(self._h, key.encode(), int(value)))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def alora_prefill(ctx: Context, layer: Layer, cache: KVCache, x_suffix: torch.Tensor, cu_seqlens: Sequence[int],
+                  k_per_seq: Sequence[int], adapter_per_seq: Sequence[int], attn_out: Optional[torch.Tensor] = None,
+                  stream=None) -> torch.Tensor:
+    cu, kk, ad = _i32(cu_seqlens), _i32(k_per_seq), _i32(adapter_per_seq)
+    B = len(kk)
+    if attn_out is None:
+        attn_out = torch.empty((x_suffix.shape[0], layer.n_q), dtype=layer.dtype, device=layer.device)
+    p = C.POINTER(C.c_int32)
+    st = _lib.alora_prefill(ctx._h, C.byref(layer.desc), C.byref(cache.desc), _ptr(x_suffix),
+                            cu.ctypes.data_as(p), kk.ctypes.data_as(p), ad.ctypes.data_as(p), B,
+                            _ptr(attn_out), _stream_ptr(stream))
+    ctx._check(st)
+    return attn_out
+
+
+def alora_decode(ctx: Context, layer: Layer, cache: KVCache, x_tok: torch.Tensor, k_per_seq: Sequence[int],
+                 adapter_per_seq: Sequence[int], attn_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    kk, ad = _i32(k_per_seq), _i32(adapter_per_seq)
+    B = len(kk)
+    if attn_out is None:
+        attn_out = torch.empty((B, layer.n_q), dtype=layer.dtype, device=layer.device)
+    p = C.POINTER(C.c_int32)
+    st = _lib.alora_decode(ctx._h, C.byref(layer.desc), C.byref(cache.desc), _ptr(x_tok), kk.ctypes.data_as(p),
+                           ad.ctypes.data_as(p), B, _ptr(attn_out), _stream_ptr(stream))
+    ctx._check(st)
+    return attn_out
+
+
+def alora_stack_prefill(ctx: Context, layers: List[Layer], caches: List[KVCache], x: torch.Tensor,
+                        cu_seqlens: Sequence[int], k_per_seq: Sequence[int], adapter_per_seq: Sequence[int],
+                        out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    cu, kk, ad = _i32(cu_seqlens), _i32(k_per_seq), _i32(adapter_per_seq)
+    B = len(kk)
+    n = len(layers)
+    descs = (LayerDesc * n)(*[l.desc for l in layers])
+    cdescs = (KVCacheDesc * n)(*[c.desc for c in caches])
+    if out is None:
+        out = torch.empty_like(x)
+    p = C.POINTER(C.c_int32)
+    st = _lib.alora_stack_prefill(ctx._h, descs, n, cdescs, _ptr(x), cu.ctypes.data_as(p), kk.ctypes.data_as(p),
+                                  ad.ctypes.data_as(p), B, _ptr(out), _stream_ptr(stream))
+    ctx._check(st)
+    # the library updated the seq_len array that caches[0] points at; mirror it to the others
+    for c in caches[1:]:
+        if c.seq_len is not caches[0].seq_len:
+            c.seq_len[:] = caches[0].seq_len
+    return out

@@ -1,0 +1,450 @@
+// Host side of libalora: the C ABI of include/alora.h -- argument validation, staging of
+// the small per-sequence arrays, workspace management and launch planning.  No arithmetic
+// of the method happens here; every step runs in the kernels.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/alora.h"
+#include "common.h"
+#include "mfma_kernels.h"
+
+using namespace alora;
+
+namespace {
+
+constexpr int N_SLOTS = 8;
+
+struct MetaSlot {
+  SeqMeta *host = nullptr;   // pinned
+  SeqMeta *dev = nullptr;
+  int cap = 0;
+  hipEvent_t ev = nullptr;
+  bool in_flight = false;
+};
+
+}  // namespace
+
+struct alora_ctx {
+  int device = 0;
+  std::string err;
+  char *ws = nullptr;
+  size_t ws_cap = 0;
+  float2 *rope = nullptr;
+  int rope_pos = 0, rope_half = 0;
+  float rope_theta = 0.f;
+  MetaSlot slots[N_SLOTS];
+  int next_slot = 0;
+  int opt_kernels = 0;
+  int opt_splits = 0;
+  int n_cu = 256;
+};
+
+namespace {
+
+alora_status fail(alora_ctx *ctx, alora_status st, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  return st;
+}
+
+#define HIP_TRY(ctx, call)                                                                   \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail(ctx, ALORA_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));           \
+  } while (0)
+
+struct Bump {
+  char *base;
+  size_t off = 0;
+  explicit Bump(char *b) : base(b) {}
+  template <typename U> U *take(size_t n) {
+    size_t bytes = (n * sizeof(U) + 255) & ~(size_t)255;
+    U *p = base ? reinterpret_cast<U *>(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+alora_status ensure_workspace(alora_ctx *ctx, size_t bytes) {
+  if (bytes <= ctx->ws_cap) return ALORA_OK;
+  HIP_TRY(ctx, hipDeviceSynchronize());        // earlier calls may still be using the old block
+  if (ctx->ws) HIP_TRY(ctx, hipFree(ctx->ws));
+  ctx->ws = nullptr;
+  ctx->ws_cap = 0;
+  size_t want = bytes + bytes / 8;
+  HIP_TRY(ctx, hipMalloc((void **)&ctx->ws, want));
+  ctx->ws_cap = want;
+  return ALORA_OK;
+}
+
+alora_status ensure_rope(alora_ctx *ctx, int n_pos, int half, float theta, hipStream_t s) {
+  if (ctx->rope && ctx->rope_pos >= n_pos && ctx->rope_half == half && ctx->rope_theta == theta)
+    return ALORA_OK;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  if (ctx->rope) HIP_TRY(ctx, hipFree(ctx->rope));
+  ctx->rope = nullptr;
+  int want = std::max(n_pos + n_pos / 4, 4096);
+  HIP_TRY(ctx, hipMalloc((void **)&ctx->rope, (size_t)want * half * sizeof(float2)));
+  launch_rope_table(ctx->rope, want, half, theta, s);
+  HIP_TRY(ctx, hipGetLastError());
+  ctx->rope_pos = want;
+  ctx->rope_half = half;
+  ctx->rope_theta = theta;
+  return ALORA_OK;
+}
+
+alora_status acquire_slot(alora_ctx *ctx, int n_seqs, MetaSlot **out) {
+  MetaSlot &sl = ctx->slots[ctx->next_slot];
+  ctx->next_slot = (ctx->next_slot + 1) % N_SLOTS;
+  if (sl.in_flight) {
+    HIP_TRY(ctx, hipEventSynchronize(sl.ev));
+    sl.in_flight = false;
+  }
+  if (sl.cap < n_seqs) {
+    if (sl.host) HIP_TRY(ctx, hipHostFree(sl.host));
+    if (sl.dev) HIP_TRY(ctx, hipFree(sl.dev));
+    sl.host = nullptr; sl.dev = nullptr; sl.cap = 0;
+    int cap = std::max(64, n_seqs + n_seqs / 2);
+    HIP_TRY(ctx, hipHostMalloc((void **)&sl.host, (size_t)cap * sizeof(SeqMeta), hipHostMallocDefault));
+    HIP_TRY(ctx, hipMalloc((void **)&sl.dev, (size_t)cap * sizeof(SeqMeta)));
+    sl.cap = cap;
+  }
+  if (!sl.ev) HIP_TRY(ctx, hipEventCreateWithFlags(&sl.ev, hipEventDisableTiming));
+  *out = &sl;
+  return ALORA_OK;
+}
+
+struct Plan {
+  LayerDims L;
+  int T = 0, B = 0;
+  int max_len = 0;        // max over sequences of P_b + S_b
+  bool any_adapter = false;
+  std::vector<SeqMeta> seqs;
+};
+
+alora_status check_layer(alora_ctx *ctx, const alora_layer_desc *ly, bool need_tail, LayerDims *L) {
+  if (!ly) return fail(ctx, ALORA_EINVAL, "layer descriptor is NULL");
+  if (ly->dtype != ALORA_F32 && ly->dtype != ALORA_BF16)
+    return fail(ctx, ALORA_EDTYPE, "dtype %d is neither ALORA_F32 nor ALORA_BF16", ly->dtype);
+  if (ly->d < 1 || ly->d > 16000) return fail(ctx, ALORA_ESHAPE, "d = %d outside [1, 16000]", ly->d);
+  if (ly->n_q_heads < 1 || ly->n_kv_heads < 1 || ly->n_q_heads % ly->n_kv_heads != 0)
+    return fail(ctx, ALORA_ESHAPE, "n_q_heads = %d must be a positive multiple of n_kv_heads = %d",
+                ly->n_q_heads, ly->n_kv_heads);
+  if (ly->head_dim < 2 || ly->head_dim > 256 || (ly->head_dim & 1))
+    return fail(ctx, ALORA_ESHAPE, "head_dim = %d must be even and in [2, 256]", ly->head_dim);
+  if (ly->n_adapters < 0) return fail(ctx, ALORA_ESHAPE, "n_adapters = %d is negative", ly->n_adapters);
+  if (ly->rank < 0 || ly->rank > 256 || (ly->n_adapters > 0 && ly->rank < 1))
+    return fail(ctx, ALORA_ESHAPE, "rank = %d outside [1, 256]", ly->rank);
+  if (!ly->W_qkv) return fail(ctx, ALORA_EINVAL, "W_qkv is NULL");
+  if (ly->n_adapters > 0 && (!ly->A || !ly->B_q || !ly->B_k || !ly->B_v || !ly->scale))
+    return fail(ctx, ALORA_EINVAL, "adapter tensors (A, B_q, B_k, B_v, scale) must be given when n_adapters > 0");
+  if (!(ly->rope_theta > 0.f)) return fail(ctx, ALORA_ESHAPE, "rope_theta must be positive");
+  if (need_tail) {
+    if (ly->intermediate < 1) return fail(ctx, ALORA_ESHAPE, "intermediate = %d must be positive", ly->intermediate);
+    if (!ly->W_o || !ly->rms2_gain || !ly->W_gate || !ly->W_up || !ly->W_down)
+      return fail(ctx, ALORA_EINVAL, "W_o, rms2_gain, W_gate, W_up and W_down are required for a layer stack");
+  }
+  L->d = ly->d; L->n_q_heads = ly->n_q_heads; L->n_kv_heads = ly->n_kv_heads; L->head_dim = ly->head_dim;
+  L->rank = ly->rank; L->n_adapters = ly->n_adapters;
+  L->n_q = ly->n_q_heads * ly->head_dim;
+  L->n_kv = ly->n_kv_heads * ly->head_dim;
+  L->n_qkv = L->n_q + 2 * L->n_kv;
+  return ALORA_OK;
+}
+
+alora_status check_batch(alora_ctx *ctx, const alora_layer_desc *ly, const alora_kv_cache *cache,
+                         const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, Plan *pl) {
+  if (!cache) return fail(ctx, ALORA_EINVAL, "cache is NULL");
+  if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
+  if (!cu || !kps || !aps) return fail(ctx, ALORA_EINVAL, "cu_seqlens / k_per_seq / adapter_per_seq is NULL");
+  if (!cache->seq_offset || !cache->seq_capacity || !cache->seq_len)
+    return fail(ctx, ALORA_EINVAL, "cache seq_offset / seq_capacity / seq_len is NULL");
+  if (!cache->k || !cache->v) return fail(ctx, ALORA_EINVAL, "cache k / v is NULL");
+  if (cu[0] != 0) return fail(ctx, ALORA_EINVAL, "cu_seqlens[0] = %d must be 0", cu[0]);
+  pl->B = B;
+  pl->seqs.resize(B);
+  pl->max_len = 0;
+  pl->any_adapter = false;
+  for (int b = 0; b < B; ++b) {
+    const int S = cu[b + 1] - cu[b];
+    if (S < 0) return fail(ctx, ALORA_EINVAL, "cu_seqlens decreases at sequence %d", b);
+    const int P = cache->seq_len[b];
+    const int cap = cache->seq_capacity[b];
+    const int64_t off = cache->seq_offset[b];
+    if (P < 0) return fail(ctx, ALORA_EINVAL, "seq_len[%d] = %d is negative", b, P);
+    if (kps[b] < 0) return fail(ctx, ALORA_EINVAL, "k_per_seq[%d] = %d is negative", b, kps[b]);
+    if (aps[b] < -1 || aps[b] >= ly->n_adapters)
+      return fail(ctx, ALORA_EADAPTER, "adapter_per_seq[%d] = %d outside [-1, %d)", b, aps[b], ly->n_adapters);
+    if (cap < 0 || off < 0 || off + cap > cache->pool_tokens)
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: rows [%lld, %lld) lie outside the pool of %lld tokens", b,
+                  (long long)off, (long long)(off + cap), (long long)cache->pool_tokens);
+    if ((int64_t)P + S > cap)
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: %d cached + %d new tokens exceed its capacity %d", b, P, S, cap);
+    if ((int64_t)P + S > (1 << 24))
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: position %lld beyond the supported 2^24", b, (long long)P + S);
+    SeqMeta &m = pl->seqs[b];
+    m.row_start = cu[b]; m.n_new = S; m.P = P; m.k = kps[b]; m.adapter = aps[b];
+    m.scale = aps[b] >= 0 ? ly->scale[aps[b]] : 0.f;
+    m.pool_off = off;
+    if (aps[b] >= 0 && S > 0 && (int64_t)P + S > kps[b]) pl->any_adapter = true;
+    pl->max_len = std::max(pl->max_len, P + S);
+  }
+  pl->T = cu[B];
+  return ALORA_OK;
+}
+
+struct Workspace {
+  RowMeta rm;
+  void *xh;        // [T, d]
+  float *tlow;     // [T, 3r]
+  float *Y;        // [T, n_qkv] fp32 (plain path)
+  void *Q;         // [T, n_q]
+  float *partials;
+  // layer-stack buffers
+  void *attn, *h1, *hn, *gate, *up, *xa, *xb;
+  size_t bytes;
+};
+
+int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
+  if (ctx->opt_splits > 0) return ctx->opt_splits;
+  // enough (row, kv head, split) work items to fill the chip, chunks of at least 256 keys
+  int64_t items = (int64_t)T * n_kv_heads;
+  int want = (int)std::min<int64_t>(64, std::max<int64_t>(1, (4 * ctx->n_cu + items - 1) / std::max<int64_t>(items, 1)));
+  int max_by_len = std::max(1, max_len / 256);
+  return std::max(1, std::min(want, max_by_len));
+}
+
+Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, int n_splits, int intermediate,
+                           bool stack) {
+  Bump b(base);
+  Workspace w{};
+  w.rm.seq = b.take<int32_t>(T);
+  w.rm.pos = b.take<int32_t>(T);
+  w.rm.adapter = b.take<int32_t>(T);
+  w.rm.slot = b.take<int64_t>(T);
+  w.xh = b.take<char>((size_t)T * L.d * esz);
+  w.tlow = b.take<float>((size_t)T * 3 * std::max(L.rank, 1));
+  w.Y = b.take<float>((size_t)T * L.n_qkv);
+  w.Q = b.take<char>((size_t)T * L.n_q * esz);
+  w.partials = b.take<float>(attn_plain_partial_floats(L, T, n_splits));
+  if (stack) {
+    w.attn = b.take<char>((size_t)T * L.n_q * esz);
+    w.h1 = b.take<char>((size_t)T * L.d * esz);
+    w.hn = b.take<char>((size_t)T * L.d * esz);
+    w.gate = b.take<char>((size_t)T * intermediate * esz);
+    w.up = b.take<char>((size_t)T * intermediate * esz);
+    w.xa = b.take<char>((size_t)T * L.d * esz);
+    w.xb = b.take<char>((size_t)T * L.d * esz);
+  }
+  w.bytes = b.off;
+  return w;
+}
+
+// One attention block on already-staged metadata: rows -> projections -> rotation/append ->
+// attention.  write_meta is false for layers after the first of a stack (same rows).
+template <typename T>
+void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, const alora_kv_cache *cache,
+                     const T *x, const Plan &pl, const SeqMeta *seqs_dev, const Workspace &w, bool write_meta,
+                     int n_splits, T *out, hipStream_t s) {
+  launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
+                      pl.any_adapter ? L.rank : 0, write_meta, (T *)w.xh, w.tlow, w.rm, s);
+  launch_qkv_gemm_plain<T>((const T *)w.xh, (const T *)ly->W_qkv, w.tlow, (const T *)ly->B_q, (const T *)ly->B_k,
+                           (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
+  launch_rope_append<T>(w.Y, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k, (T *)cache->v, s);
+  launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T, n_splits,
+                       w.partials, out, s);
+}
+
+template <typename T>
+void layer_tail(const alora_layer_desc *ly, const LayerDims &L, const T *x, const Workspace &w, int T_rows, T *out,
+                hipStream_t s) {
+  RowMeta none{};
+  // h1 = x + attn W_o^T
+  launch_gemm_plain<T>((const T *)w.attn, (const T *)ly->W_o, x, (T *)w.h1, T_rows, L.d, L.n_q, s);
+  launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
+                      (const T *)nullptr, 0, false, (T *)w.hn, nullptr, none, s);
+  launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_gate, (const T *)nullptr, (T *)w.gate, T_rows,
+                       ly->intermediate, L.d, s);
+  launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_up, (const T *)nullptr, (T *)w.up, T_rows,
+                       ly->intermediate, L.d, s);
+  launch_silu_mul<T>((const T *)w.gate, (const T *)w.up, (T *)w.gate, (int64_t)T_rows * ly->intermediate, s);
+  launch_gemm_plain<T>((const T *)w.gate, (const T *)ly->W_down, (const T *)w.h1, out, T_rows, L.d,
+                       ly->intermediate, s);
+}
+
+alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, alora_kv_cache *caches,
+                 const void *x, const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, void *out,
+                 void *stream, bool stack) {
+  if (!ctx) return ALORA_EINVAL;
+  ctx->err.clear();
+  if (n_layers < 1) return fail(ctx, ALORA_EINVAL, "n_layers = %d must be at least 1", n_layers);
+  if (!layers || !caches) return fail(ctx, ALORA_EINVAL, "layers / caches is NULL");
+  LayerDims L{};
+  alora_status st = check_layer(ctx, &layers[0], stack, &L);
+  if (st != ALORA_OK) return st;
+  for (int l = 1; l < n_layers; ++l) {
+    LayerDims Ll{};
+    st = check_layer(ctx, &layers[l], stack, &Ll);
+    if (st != ALORA_OK) return st;
+    if (memcmp(&Ll, &L, sizeof L) != 0 || layers[l].dtype != layers[0].dtype ||
+        layers[l].intermediate != layers[0].intermediate)
+      return fail(ctx, ALORA_ESHAPE, "layer %d differs in shape or dtype from layer 0", l);
+    if (!caches[l].k || !caches[l].v) return fail(ctx, ALORA_EINVAL, "caches[%d] k / v is NULL", l);
+    if (caches[l].pool_tokens != caches[0].pool_tokens)
+      return fail(ctx, ALORA_ECAPACITY, "caches[%d] pool size differs from caches[0]", l);
+  }
+  Plan pl;
+  pl.L = L;
+  st = check_batch(ctx, &layers[0], &caches[0], cu, kps, aps, B, &pl);
+  if (st != ALORA_OK) return st;
+  if (pl.T > 0 && (!x || !out)) return fail(ctx, ALORA_EINVAL, "x / out is NULL");
+  if (pl.T == 0) return ALORA_OK;
+  if (ctx->device < 0)
+    return fail(ctx, ALORA_EHIP, "arguments are valid, but this is a validation-only context (device -1)");
+
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t s = (hipStream_t)stream;
+  const size_t esz = layers[0].dtype == ALORA_BF16 ? 2 : 4;
+  const int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
+  Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, layers[0].intermediate, stack);
+  st = ensure_workspace(ctx, probe.bytes);
+  if (st != ALORA_OK) return st;
+  st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
+  if (st != ALORA_OK) return st;
+  MetaSlot *slot = nullptr;
+  st = acquire_slot(ctx, B, &slot);
+  if (st != ALORA_OK) return st;
+  memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
+  HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, (size_t)B * sizeof(SeqMeta), hipMemcpyHostToDevice, s));
+  Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, layers[0].intermediate, stack);
+
+  const bool bf = layers[0].dtype == ALORA_BF16;
+  if (!stack) {
+    if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, slot->dev, w, true, n_splits, (bf16 *)out, s);
+    else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, slot->dev, w, true, n_splits, (float *)out, s);
+  } else {
+    const void *cur = x;
+    for (int l = 0; l < n_layers; ++l) {
+      void *nxt = (l == n_layers - 1) ? out : ((l & 1) ? w.xb : w.xa);
+      if (bf) {
+        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, slot->dev, w, l == 0, n_splits, (bf16 *)w.attn, s);
+        layer_tail<bf16>(&layers[l], L, (const bf16 *)cur, w, pl.T, (bf16 *)nxt, s);
+      } else {
+        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, slot->dev, w, l == 0, n_splits, (float *)w.attn, s);
+        layer_tail<float>(&layers[l], L, (const float *)cur, w, pl.T, (float *)nxt, s);
+      }
+      cur = nxt;
+    }
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  HIP_TRY(ctx, hipEventRecord(slot->ev, s));
+  slot->in_flight = true;
+  for (int b = 0; b < B; ++b) caches[0].seq_len[b] += cu[b + 1] - cu[b];
+  return ALORA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+alora_status alora_create(alora_ctx **out, int device) {
+  if (!out) return ALORA_EINVAL;
+  *out = nullptr;
+  if (device == -1) {              // validation-only context: checks arguments, never launches
+    alora_ctx *ctx = new alora_ctx();
+    ctx->device = -1;
+    *out = ctx;
+    return ALORA_OK;
+  }
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return ALORA_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return ALORA_EHIP;
+  alora_ctx *ctx = new alora_ctx();
+  ctx->device = device;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->n_cu = prop.multiProcessorCount;
+  *out = ctx;
+  return ALORA_OK;
+}
+
+void alora_destroy(alora_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->device < 0) { delete ctx; return; }
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  if (ctx->rope) (void)hipFree(ctx->rope);
+  for (MetaSlot &sl : ctx->slots) {
+    if (sl.host) (void)hipHostFree(sl.host);
+    if (sl.dev) (void)hipFree(sl.dev);
+    if (sl.ev) (void)hipEventDestroy(sl.ev);
+  }
+  delete ctx;
+}
+
+const char *alora_last_error(const alora_ctx *ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+const char *alora_status_string(alora_status s) {
+  switch (s) {
+    case ALORA_OK: return "ALORA_OK";
+    case ALORA_EINVAL: return "ALORA_EINVAL";
+    case ALORA_ESHAPE: return "ALORA_ESHAPE";
+    case ALORA_ECAPACITY: return "ALORA_ECAPACITY";
+    case ALORA_EADAPTER: return "ALORA_EADAPTER";
+    case ALORA_EDTYPE: return "ALORA_EDTYPE";
+    case ALORA_EHIP: return "ALORA_EHIP";
+  }
+  return "unknown status";
+}
+
+alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
+  if (!ctx) return ALORA_EINVAL;
+  ctx->err.clear();
+  if (!key) return fail(ctx, ALORA_EINVAL, "option key is NULL");
+  if (!strcmp(key, "kernels")) {
+    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "kernels must be 0 or 1");
+    ctx->opt_kernels = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "kv_splits")) {
+    if (value < 0 || value > 256) return fail(ctx, ALORA_EINVAL, "kv_splits must be in [0, 256]");
+    ctx->opt_splits = value;
+    return ALORA_OK;
+  }
+  return fail(ctx, ALORA_EINVAL, "unknown option '%s'", key);
+}
+
+alora_status alora_prefill(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
+                           const void *x_suffix, const int32_t *cu_seqlens, const int32_t *k_per_seq,
+                           const int32_t *adapter_per_seq, int32_t B, void *attn_out, void *stream) {
+  return run(ctx, layer, 1, cache, x_suffix, cu_seqlens, k_per_seq, adapter_per_seq, B, attn_out, stream, false);
+}
+
+alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache, const void *x_tok,
+                          const int32_t *k_per_seq, const int32_t *adapter_per_seq, int32_t B, void *attn_out,
+                          void *stream) {
+  if (!ctx) return ALORA_EINVAL;
+  if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
+  std::vector<int32_t> cu(B + 1);
+  for (int b = 0; b <= B; ++b) cu[b] = b;
+  return run(ctx, layer, 1, cache, x_tok, cu.data(), k_per_seq, adapter_per_seq, B, attn_out, stream, false);
+}
+
+alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers,
+                                 alora_kv_cache *caches, const void *x, const int32_t *cu_seqlens,
+                                 const int32_t *k_per_seq, const int32_t *adapter_per_seq, int32_t B, void *out,
+                                 void *stream) {
+  return run(ctx, layers, n_layers, caches, x, cu_seqlens, k_per_seq, adapter_per_seq, B, out, stream, true);
+}
+
+}  // extern "C"

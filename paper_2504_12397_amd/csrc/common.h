@@ -1,0 +1,87 @@
+// Shared declarations of the libalora kernels (device side and their host launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace alora {
+
+typedef __bf16 bf16;
+
+// Per-sequence metadata staged to the device once per call.
+struct SeqMeta {
+  int32_t row_start;   // first packed row of the sequence's new tokens
+  int32_t n_new;       // S_b
+  int32_t P;           // rows already valid in the cache
+  int32_t k;           // invocation index (first adapted absolute position)
+  int32_t adapter;     // adapter id or -1
+  float scale;         // s_a of that adapter (0 if none)
+  int64_t pool_off;    // first pool row of the sequence
+};
+
+// Per-row metadata written by the row-preparation kernel and read by everything after it.
+struct RowMeta {
+  int32_t *seq;        // [T] sequence index
+  int32_t *pos;        // [T] absolute position p(i)
+  int32_t *adapter;    // [T] adapter id if the row is adapted (a >= 0 and p >= k), else -1
+  int64_t *slot;       // [T] pool row where this token's key/value go
+};
+
+struct LayerDims {
+  int d, n_q_heads, n_kv_heads, head_dim, rank, n_adapters;
+  int n_q, n_kv, n_qkv;
+};
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- launchers: plain kernels (any dtype, any shape) ------------------------------------
+enum GemmEpilogue { EPI_F32_LORA = 0, EPI_STORE = 1, EPI_STORE_RESIDUAL = 2 };
+
+void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipStream_t s);
+
+template <typename T>
+void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
+                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow,
+                      RowMeta rm, hipStream_t s);
+
+// Y[T, n_qkv] (fp32) = xh W^T + gated low-rank term (Eq.6)
+template <typename T>
+void launch_qkv_gemm_plain(const T *xh, const T *W, const float *tlow, const T *Bq, const T *Bk,
+                           const T *Bv, const LayerDims &L, RowMeta rm, int T_rows, float *Y,
+                           hipStream_t s);
+
+// C[M,N] (T) = A[M,K] B[N,K]^T (+ R[M,N])
+template <typename T>
+void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, int K, hipStream_t s);
+
+template <typename T>
+void launch_rope_append(const float *Y, const LayerDims &L, RowMeta rm, int T_rows,
+                        const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s);
+
+// split-KV attention with plain fp32 arithmetic: partial pass + merge
+template <typename T>
+void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
+                       const LayerDims &L, int T_rows, int n_splits, float *partials, T *out,
+                       hipStream_t s);
+
+template <typename T>
+void launch_silu_mul(const T *gate, const T *up, T *out, int64_t n, hipStream_t s);
+
+size_t attn_plain_partial_floats(const LayerDims &L, int T_rows, int n_splits);
+
+}  // namespace alora

@@ -1,0 +1,444 @@
+// Plain kernels: every step of the path in straightforward fp32-FMA HIP, for any dtype and
+// any shape.  They are the fp32 path (small single-block configuration) and the fallback
+// for shapes the MFMA kernels do not cover.
+#include "common.h"
+
+namespace alora {
+
+// ---------------------------------------------------------------------------------------
+// rotary table: table[pos * half + c] = (cos, sin)(pos * theta^(-2c/h)), evaluated in
+// double so that positions in the tens of thousands keep full fp32 accuracy.
+// ---------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(float2 *table, int n_pos, int half, double log2_theta) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n_pos * half) return;
+  int pos = (int)(i / half), c = (int)(i % half);
+  double inv = exp2(-(double)c / (double)half * log2_theta);   // theta^(-2c/h), h = 2*half
+  double ang = (double)pos * inv;
+  double sn, cs;
+  sincos(ang, &sn, &cs);
+  table[i] = make_float2((float)cs, (float)sn);
+}
+
+void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipStream_t s) {
+  int64_t n = (int64_t)n_pos * half_dim;
+  if (n == 0) return;
+  int grid = (int)((n + 255) / 256);
+  hipLaunchKernelGGL(rope_table_kernel, dim3(grid), dim3(256), 0, s, table, n_pos, half_dim,
+                     log2((double)theta));
+}
+
+// ---------------------------------------------------------------------------------------
+// row preparation: per-row metadata, RMSNorm, and the low-rank down projection
+// t = s_a * A_a x_hat for adapted rows (Eq.6's Delta applied right to left).
+// One workgroup per packed row.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x, const T *__restrict__ gain,
+                                                        float eps, int d, const SeqMeta *__restrict__ seqs,
+                                                        int n_seqs, const T *__restrict__ A, int rank,
+                                                        int write_meta, T *__restrict__ xh,
+                                                        float *__restrict__ tlow, RowMeta rm) {
+  extern __shared__ float xs[];
+  __shared__ float red[4];
+  __shared__ int s_adapter;
+  __shared__ float s_scale;
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) {
+    int adapter = -1;
+    float scale = 0.f;
+    if (seqs != nullptr) {
+      int lo = 0, hi = n_seqs - 1;   // last sequence whose first row is <= row
+      while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (seqs[mid].row_start <= row) lo = mid; else hi = mid - 1;
+      }
+      SeqMeta sm = seqs[lo];
+      int pos = sm.P + (row - sm.row_start);
+      if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
+      if (write_meta) {
+        rm.seq[row] = lo;
+        rm.pos[row] = pos;
+        rm.adapter[row] = adapter;
+        rm.slot[row] = sm.pool_off + pos;
+      }
+    }
+    s_adapter = adapter;
+    s_scale = scale;
+  }
+  const T *xr = x + (int64_t)row * d;
+  float ssq = 0.f;
+  for (int c = tid; c < d; c += 256) {
+    float v = to_f32<T>(xr[c]);
+    xs[c] = v;
+    ssq += v * v;
+  }
+  ssq = wave_sum(ssq);
+  if (lane == 0) red[wave] = ssq;
+  __syncthreads();
+  float rinv = 1.f;
+  if (gain != nullptr) rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+  for (int c = tid; c < d; c += 256) {
+    float v = xs[c];
+    if (gain != nullptr) v = v * to_f32<T>(gain[c]) * rinv;
+    T stored = from_f32<T>(v);
+    xh[(int64_t)row * d + c] = stored;
+    xs[c] = to_f32<T>(stored);      // the projections consume the stored (rounded) value
+  }
+  __syncthreads();
+  const int a = s_adapter;
+  if (a < 0 || rank == 0) return;
+  const float scale = s_scale;
+  for (int j = wave; j < 3 * rank; j += 4) {
+    const T *ar = A + ((int64_t)a * 3 * rank + j) * d;
+    float acc = 0.f;
+    for (int c = lane; c < d; c += 64) acc += to_f32<T>(ar[c]) * xs[c];
+    acc = wave_sum(acc);
+    if (lane == 0) tlow[(int64_t)row * 3 * rank + j] = scale * acc;
+  }
+}
+
+template <typename T>
+void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
+                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow,
+                      RowMeta rm, hipStream_t s) {
+  if (T_rows == 0) return;
+  hipLaunchKernelGGL((prep_rows_kernel<T>), dim3(T_rows), dim3(256), (size_t)d * sizeof(float), s, x, gain,
+                     eps, d, seqs, n_seqs, A, rank, write_meta ? 1 : 0, xh, tlow, rm);
+}
+template void launch_prep_rows<float>(const float *, const float *, float, int, int, const SeqMeta *, int,
+                                      const float *, int, bool, float *, float *, RowMeta, hipStream_t);
+template void launch_prep_rows<bf16>(const bf16 *, const bf16 *, float, int, int, const SeqMeta *, int,
+                                     const bf16 *, int, bool, bf16 *, float *, RowMeta, hipStream_t);
+
+// ---------------------------------------------------------------------------------------
+// plain tiled GEMM  C[M,N] = A[M,K] B[N,K]^T, 64x64 tile, 16-deep, 4x4 outputs per thread
+// ---------------------------------------------------------------------------------------
+struct LoraEpi {
+  const float *tlow;
+  const void *Bq, *Bk, *Bv;
+  const int32_t *row_adapter;
+  int rank, n_q, n_kv;
+};
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void gemm_plain_kernel(const T *__restrict__ A, const T *__restrict__ B,
+                                                         const T *__restrict__ R, void *__restrict__ Cv,
+                                                         int M, int N, int K, LoraEpi epi) {
+  __shared__ float As[16][68];
+  __shared__ float Bs[16][68];
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int lr = tid >> 2, lk = (tid & 3) * 4;
+  const int ty = tid >> 4, tx = tid & 15;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int kk = k0 + lk + i;
+      int ar = m0 + lr, br = n0 + lr;
+      As[lk + i][lr] = (ar < M && kk < K) ? to_f32<T>(A[(int64_t)ar * K + kk]) : 0.f;
+      Bs[lk + i][lr] = (br < N && kk < K) ? to_f32<T>(B[(int64_t)br * K + kk]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int row = m0 + ty * 4 + i;
+    if (row >= M) continue;
+    int a = -1;
+    if (MODE == EPI_F32_LORA) a = epi.row_adapter[row];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int col = n0 + tx * 4 + j;
+      if (col >= N) continue;
+      float v = acc[i][j];
+      if (MODE == EPI_F32_LORA) {
+        if (a >= 0) {     // adapted row: add s * B (A x); other rows get nothing added
+          const int r = epi.rank;
+          const T *bp;
+          int p;
+          if (col < epi.n_q) { p = 0; bp = (const T *)epi.Bq + ((int64_t)a * epi.n_q + col) * r; }
+          else if (col < epi.n_q + epi.n_kv) { p = 1; bp = (const T *)epi.Bk + ((int64_t)a * epi.n_kv + (col - epi.n_q)) * r; }
+          else { p = 2; bp = (const T *)epi.Bv + ((int64_t)a * epi.n_kv + (col - epi.n_q - epi.n_kv)) * r; }
+          const float *t = epi.tlow + (int64_t)row * 3 * r + p * r;
+          float lo = 0.f;
+          for (int jj = 0; jj < r; ++jj) lo += t[jj] * to_f32<T>(bp[jj]);
+          v += lo;
+        }
+        ((float *)Cv)[(int64_t)row * N + col] = v;
+      } else {
+        if (MODE == EPI_STORE_RESIDUAL) v += to_f32<T>(R[(int64_t)row * N + col]);
+        ((T *)Cv)[(int64_t)row * N + col] = from_f32<T>(v);
+      }
+    }
+  }
+}
+
+template <typename T>
+void launch_qkv_gemm_plain(const T *xh, const T *W, const float *tlow, const T *Bq, const T *Bk,
+                           const T *Bv, const LayerDims &L, RowMeta rm, int T_rows, float *Y,
+                           hipStream_t s) {
+  if (T_rows == 0) return;
+  LoraEpi epi{tlow, Bq, Bk, Bv, rm.adapter, L.rank, L.n_q, L.n_kv};
+  dim3 grid((L.n_qkv + 63) / 64, (T_rows + 63) / 64);
+  hipLaunchKernelGGL((gemm_plain_kernel<T, EPI_F32_LORA>), grid, dim3(256), 0, s, xh, W, (const T *)nullptr,
+                     (void *)Y, T_rows, L.n_qkv, L.d, epi);
+}
+template void launch_qkv_gemm_plain<float>(const float *, const float *, const float *, const float *,
+                                           const float *, const float *, const LayerDims &, RowMeta, int,
+                                           float *, hipStream_t);
+template void launch_qkv_gemm_plain<bf16>(const bf16 *, const bf16 *, const float *, const bf16 *,
+                                          const bf16 *, const bf16 *, const LayerDims &, RowMeta, int,
+                                          float *, hipStream_t);
+
+template <typename T>
+void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, int K, hipStream_t s) {
+  if (M == 0 || N == 0) return;
+  LoraEpi epi{};
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  if (R)
+    hipLaunchKernelGGL((gemm_plain_kernel<T, EPI_STORE_RESIDUAL>), grid, dim3(256), 0, s, A, B, R, (void *)C,
+                       M, N, K, epi);
+  else
+    hipLaunchKernelGGL((gemm_plain_kernel<T, EPI_STORE>), grid, dim3(256), 0, s, A, B, R, (void *)C, M, N, K,
+                       epi);
+}
+template void launch_gemm_plain<float>(const float *, const float *, const float *, float *, int, int, int,
+                                       hipStream_t);
+template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, bf16 *, int, int, int,
+                                      hipStream_t);
+
+// ---------------------------------------------------------------------------------------
+// rotary embedding + cache append (Eq.3: K_{1:t} = [K_{1:t-1}; K_t]).  One workgroup per row.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, LayerDims L, RowMeta rm,
+                                                          const float2 *__restrict__ table, T *__restrict__ Q,
+                                                          T *__restrict__ cacheK, T *__restrict__ cacheV) {
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int h = L.head_dim, h2 = h >> 1;
+  const int pos = rm.pos[row];
+  const int64_t slot = rm.slot[row];
+  const float *y = Y + (int64_t)row * L.n_qkv;
+  const float2 *tab = table + (int64_t)pos * h2;
+  const int q_pairs = L.n_q_heads * h2, k_pairs = L.n_kv_heads * h2;
+  for (int i = tid; i < q_pairs + k_pairs; i += 256) {
+    const bool is_q = i < q_pairs;
+    const int ii = is_q ? i : i - q_pairs;
+    const int head = ii / h2, c = ii % h2;
+    const int base = (is_q ? 0 : L.n_q) + head * h;
+    const float u = y[base + c], w = y[base + c + h2];
+    const float2 cs = tab[c];
+    const float lo = u * cs.x - w * cs.y, hi = w * cs.x + u * cs.y;
+    if (is_q) {
+      T *q = Q + (int64_t)row * L.n_q + head * h;
+      q[c] = from_f32<T>(lo);
+      q[c + h2] = from_f32<T>(hi);
+    } else {
+      T *kk = cacheK + slot * L.n_kv + head * h;
+      kk[c] = from_f32<T>(lo);
+      kk[c + h2] = from_f32<T>(hi);
+    }
+  }
+  const float *yv = y + L.n_q + L.n_kv;
+  for (int i = tid; i < L.n_kv; i += 256) cacheV[slot * L.n_kv + i] = from_f32<T>(yv[i]);
+}
+
+template <typename T>
+void launch_rope_append(const float *Y, const LayerDims &L, RowMeta rm, int T_rows,
+                        const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
+  if (T_rows == 0) return;
+  hipLaunchKernelGGL((rope_append_kernel<T>), dim3(T_rows), dim3(256), 0, s, Y, L, rm, rope_table, Q, cacheK,
+                     cacheV);
+}
+template void launch_rope_append<float>(const float *, const LayerDims &, RowMeta, int, const float2 *, float *,
+                                        float *, float *, hipStream_t);
+template void launch_rope_append<bf16>(const float *, const LayerDims &, RowMeta, int, const float2 *, bf16 *,
+                                       bf16 *, bf16 *, hipStream_t);
+
+// ---------------------------------------------------------------------------------------
+// plain split-KV attention (Eq.1 / Eq.4, causal, GQA).  One wave per (row, kv head, chunk of
+// up to 8 query heads, key split).  Scores: one key per lane; values: lanes across head_dim.
+// Partial layout: part[(((row*Hq + hq) * n_splits) + split) * (h + 2)] = acc[h], m, l.
+// ---------------------------------------------------------------------------------------
+#define ATT_GMAX 8
+#define ATT_DMAX 4     // head_dim <= 256
+
+template <typename T>
+__global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ Q, const T *__restrict__ cacheK,
+                                                          const T *__restrict__ cacheV,
+                                                          const SeqMeta *__restrict__ seqs, RowMeta rm,
+                                                          LayerDims L, int n_splits, float *__restrict__ part) {
+  extern __shared__ float smem[];       // qs[GMAX][h] then ps[GMAX][64]
+  const int lane = threadIdx.x;
+  const int h = L.head_dim;
+  const int G = L.n_q_heads / L.n_kv_heads;
+  const int row = blockIdx.x / L.n_kv_heads, g = blockIdx.x % L.n_kv_heads;
+  const int split = blockIdx.y;
+  const int g0 = blockIdx.z * ATT_GMAX;
+  const int ng = min(ATT_GMAX, G - g0);
+  float *qs = smem, *ps = smem + ATT_GMAX * h;
+  const int n_keys = rm.pos[row] + 1;
+  int chunk = (n_keys + n_splits - 1) / n_splits;
+  chunk = (chunk + 63) & ~63;
+  const int begin = split * chunk, end = min(n_keys, begin + chunk);
+  const int64_t base = seqs[rm.seq[row]].pool_off;
+  const float sm_scale = 1.0f / sqrtf((float)h);
+  for (int i = lane; i < ng * h; i += 64) {
+    int gi = i / h, c = i % h;
+    qs[gi * h + c] = to_f32<T>(Q[(int64_t)row * L.n_q + (g * G + g0 + gi) * h + c]) * sm_scale;
+  }
+  __syncthreads();
+  float m[ATT_GMAX], l[ATT_GMAX], acc[ATT_GMAX][ATT_DMAX];
+#pragma unroll
+  for (int gi = 0; gi < ATT_GMAX; ++gi) {
+    m[gi] = -INFINITY; l[gi] = 0.f;
+#pragma unroll
+    for (int dd = 0; dd < ATT_DMAX; ++dd) acc[gi][dd] = 0.f;
+  }
+  for (int t0 = begin; t0 < end; t0 += 64) {
+    const int key = t0 + lane;
+    const bool valid = key < end;
+    float sc[ATT_GMAX];
+#pragma unroll
+    for (int gi = 0; gi < ATT_GMAX; ++gi) sc[gi] = 0.f;
+    if (valid) {
+      const T *kr = cacheK + (base + key) * L.n_kv + g * h;
+      for (int c = 0; c < h; ++c) {
+        float kv = to_f32<T>(kr[c]);
+#pragma unroll
+        for (int gi = 0; gi < ATT_GMAX; ++gi)
+          if (gi < ng) sc[gi] += qs[gi * h + c] * kv;
+      }
+    }
+    __syncthreads();      // previous tile's ps fully consumed
+#pragma unroll
+    for (int gi = 0; gi < ATT_GMAX; ++gi) {
+      if (gi < ng) {
+        float s = valid ? sc[gi] : -INFINITY;
+        float mn = fmaxf(m[gi], wave_max(s));
+        float p = valid ? __expf(s - mn) : 0.f;
+        float corr = __expf(m[gi] - mn);
+        l[gi] = l[gi] * corr + wave_sum(p);
+        m[gi] = mn;
+#pragma unroll
+        for (int dd = 0; dd < ATT_DMAX; ++dd) acc[gi][dd] *= corr;
+        ps[gi * 64 + lane] = p;
+      }
+    }
+    __syncthreads();
+    const int nk = min(64, end - t0);
+    for (int j = 0; j < nk; ++j) {
+      const T *vr = cacheV + (base + t0 + j) * L.n_kv + g * h;
+#pragma unroll
+      for (int dd = 0; dd < ATT_DMAX; ++dd) {
+        int c = lane + 64 * dd;
+        if (c < h) {
+          float vv = to_f32<T>(vr[c]);
+#pragma unroll
+          for (int gi = 0; gi < ATT_GMAX; ++gi)
+            if (gi < ng) acc[gi][dd] += ps[gi * 64 + j] * vv;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int gi = 0; gi < ATT_GMAX; ++gi) {
+    if (gi < ng) {
+      float *o = part + (((int64_t)row * L.n_q_heads + (g * G + g0 + gi)) * n_splits + split) * (h + 2);
+#pragma unroll
+      for (int dd = 0; dd < ATT_DMAX; ++dd) {
+        int c = lane + 64 * dd;
+        if (c < h) o[c] = acc[gi][dd];
+      }
+      if (lane == 0) { o[h] = m[gi]; o[h + 1] = l[gi]; }
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(64) void attn_merge_kernel(const float *__restrict__ part, LayerDims L, int n_splits,
+                                                        T *__restrict__ out) {
+  const int lane = threadIdx.x, h = L.head_dim;
+  const int64_t rh = blockIdx.x;                 // row * Hq + hq
+  const float *p = part + rh * n_splits * (h + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[s * (h + 2) + h]);
+  float denom = 0.f;
+  float acc[ATT_DMAX] = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < n_splits; ++s) {
+    const float *ps = p + s * (h + 2);
+    float ms = ps[h];
+    float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
+    denom += w * ps[h + 1];
+#pragma unroll
+    for (int dd = 0; dd < ATT_DMAX; ++dd) {
+      int c = lane + 64 * dd;
+      if (c < h) acc[dd] += w * ps[c];
+    }
+  }
+  const float inv = 1.0f / denom;
+#pragma unroll
+  for (int dd = 0; dd < ATT_DMAX; ++dd) {
+    int c = lane + 64 * dd;
+    if (c < h) out[rh * h + c] = from_f32<T>(acc[dd] * inv);
+  }
+}
+
+size_t attn_plain_partial_floats(const LayerDims &L, int T_rows, int n_splits) {
+  return (size_t)T_rows * L.n_q_heads * n_splits * (L.head_dim + 2);
+}
+
+template <typename T>
+void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
+                       const LayerDims &L, int T_rows, int n_splits, float *partials, T *out,
+                       hipStream_t s) {
+  if (T_rows == 0) return;
+  const int G = L.n_q_heads / L.n_kv_heads;
+  dim3 grid(T_rows * L.n_kv_heads, n_splits, (G + ATT_GMAX - 1) / ATT_GMAX);
+  size_t smem = (size_t)(ATT_GMAX * L.head_dim + ATT_GMAX * 64) * sizeof(float);
+  hipLaunchKernelGGL((attn_partial_kernel<T>), grid, dim3(64), smem, s, Q, cacheK, cacheV, seqs, rm, L, n_splits,
+                     partials);
+  hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(T_rows * L.n_q_heads), dim3(64), 0, s, partials, L, n_splits,
+                     out);
+}
+template void launch_attn_plain<float>(const float *, const float *, const float *, const SeqMeta *, RowMeta,
+                                       const LayerDims &, int, int, float *, float *, hipStream_t);
+template void launch_attn_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, const SeqMeta *, RowMeta,
+                                      const LayerDims &, int, int, float *, bf16 *, hipStream_t);
+
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void silu_mul_kernel(const T *__restrict__ gate, const T *__restrict__ up, T *__restrict__ out,
+                                int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    float gv = to_f32<T>(gate[i]);
+    float uv = to_f32<T>(up[i]);
+    out[i] = from_f32<T>(gv / (1.0f + __expf(-gv)) * uv);
+  }
+}
+
+template <typename T>
+void launch_silu_mul(const T *gate, const T *up, T *out, int64_t n, hipStream_t s) {
+  if (n == 0) return;
+  int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  hipLaunchKernelGGL((silu_mul_kernel<T>), dim3(grid), dim3(256), 0, s, gate, up, out, n);
+}
+template void launch_silu_mul<float>(const float *, const float *, float *, int64_t, hipStream_t);
+template void launch_silu_mul<bf16>(const bf16 *, const bf16 *, bf16 *, int64_t, hipStream_t);
+
+}  // namespace alora

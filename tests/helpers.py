@@ -1,0 +1,146 @@
+"""Shared test plumbing: building seeded cases, running them through the C ABI, error metrics.
+Holds no arithmetic of the method: expected values always come from oracle/."""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import alora_oracle as orc
+from paper_2504_12397_amd import workloads as wl
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def rel_err(got, ref) -> float:
+    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)): elementwise relative error, with elements
+    smaller than the tensor's RMS judged on the tensor's scale (a sum of many signed terms has
+    an absolute error set by the terms, not by how close the sum happens to fall to zero)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    floor = float(np.sqrt(np.mean(ref * ref)))
+    floor = floor if floor > 0 else 1.0
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor)))
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def oracle_layer(tensors: dict, shape: wl.LayerShape) -> orc.Layer:
+    return orc.layer_from_tensors(tensors, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                                  shape.rms_eps, shape.rope_theta)
+
+
+@dataclasses.dataclass
+class Case:
+    shape: wl.LayerShape
+    tensors: dict                 # cpu torch tensors, storage dtype
+    layer: orc.Layer              # same values, float64
+    P: List[int]
+    S: List[int]
+    k: List[int]
+    adapter: List[int]
+    x_prefix: List[Optional[torch.Tensor]]   # hidden states of the cached tokens (None if cache is random)
+    x_new: List[torch.Tensor]                # hidden states of the new tokens
+    cache_K: List[np.ndarray]                # [P_b, N_kv] float64 values representable in the storage dtype
+    cache_V: List[np.ndarray]
+
+    @property
+    def cu(self) -> List[int]:
+        out = [0]
+        for s in self.S:
+            out.append(out[-1] + s)
+        return out
+
+    @property
+    def x_packed(self) -> torch.Tensor:
+        return torch.cat(self.x_new, dim=0) if self.x_new else torch.zeros((0, self.shape.d))
+
+
+def make_case(shape: wl.LayerShape, P: Sequence[int], S: Sequence[int], k: Sequence[int], adapter: Sequence[int],
+              seed: int, prefix: str = "oracle", prefix_k: Optional[Sequence[int]] = None) -> Case:
+    """prefix = "oracle": cache rows come from the oracle's pass over seeded prefix hidden states with the
+    same (k, adapter) gating (so k < P gives adapted rows in the cache); "random": N(0,1) keys/values."""
+    rng = wl.Rng(seed)
+    tensors = wl.make_layer(shape, rng)
+    layer = oracle_layer(tensors, shape)
+    xp, xn, cK, cV = [], [], [], []
+    for b in range(len(P)):
+        xn.append(wl.make_hidden(rng, f"x_new{b}", S[b], shape))
+        if prefix == "oracle":
+            xb = wl.make_hidden(rng, f"x_prefix{b}", P[b], shape)
+            xp.append(xb)
+            pos = np.arange(P[b])
+            xh = orc.rmsnorm(f64(xb), layer.rms_gain, layer.rms_eps)
+            _, kk, vv = orc.project_qkv(layer, xh, pos, k[b], adapter[b])
+            kk = orc.rope(kk, pos, layer.n_kv_heads, layer.head_dim, layer.rope_theta)
+            cK.append(orc._store(kk, shape.dtype))
+            cV.append(orc._store(vv, shape.dtype))
+        else:
+            xp.append(None)
+            K, V = wl.make_random_kv(rng, f"kv{b}", P[b], shape)
+            cK.append(f64(K).reshape(P[b], shape.n_kv))
+            cV.append(f64(V).reshape(P[b], shape.n_kv))
+    return Case(shape, tensors, layer, list(P), list(S), list(k), list(adapter), xp, xn, cK, cV)
+
+
+def oracle_prefill(case: Case):
+    caches = list(zip(case.cache_K, case.cache_V))
+    return orc.ref_prefill_batch(case.layer, caches, case.P, f64(case.x_packed), case.cu, case.k, case.adapter,
+                                 case.shape.dtype)
+
+
+# ------------------------------------------------------------------------------ GPU side
+def gpu_layer(case_or_tensors, shape: wl.LayerShape, device="cuda"):
+    from paper_2504_12397_amd import binding as ab
+    tensors = case_or_tensors.tensors if isinstance(case_or_tensors, Case) else case_or_tensors
+    dev = {k_: (v.to(device).contiguous() if isinstance(v, torch.Tensor) else v) for k_, v in tensors.items()}
+    return ab.Layer(dev, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rms_eps, shape.rope_theta,
+                    shape.intermediate)
+
+
+CANARY = 777.0
+
+
+def gpu_cache(case: Case, extra_capacity: int = 5, guard_rows: int = 3, device="cuda"):
+    """A pool with canary-filled guard rows between sequences and unused capacity behind each one."""
+    from paper_2504_12397_amd import binding as ab
+    caps = [case.P[b] + case.S[b] + extra_capacity for b in range(len(case.P))]
+    cache = ab.KVCache(caps, case.shape.n_kv_heads, case.shape.head_dim, case.shape.torch_dtype, device,
+                       fill=CANARY, guard_rows=guard_rows)
+    for b in range(len(case.P)):
+        cache.load_prefix(b, torch.from_numpy(case.cache_K[b]), torch.from_numpy(case.cache_V[b]))
+    return cache
+
+
+def check_cache_after(case: Case, cache, before_k: torch.Tensor, before_v: torch.Tensor, new_rows, tol: float):
+    """Indexing is exact: only rows [P_b, P_b+S_b) of each sequence changed; they hold the new keys/values."""
+    k_now, v_now = cache.k.cpu(), cache.v.cpu()
+    written = torch.zeros(cache.pool_tokens, dtype=torch.bool)
+    for b in range(len(case.P)):
+        o = int(cache.seq_offset[b])
+        written[o + case.P[b]:o + case.P[b] + case.S[b]] = True
+        assert int(cache.seq_len[b]) == case.P[b] + case.S[b]
+    keep = ~written
+    assert torch.equal(k_now[keep].view(torch.int16 if k_now.dtype == torch.bfloat16 else torch.int32),
+                       before_k[keep].view(torch.int16 if k_now.dtype == torch.bfloat16 else torch.int32)), \
+        "cache rows outside [P, P+S) changed"
+    assert torch.equal(v_now[keep].view(torch.int16 if v_now.dtype == torch.bfloat16 else torch.int32),
+                       before_v[keep].view(torch.int16 if v_now.dtype == torch.bfloat16 else torch.int32))
+    errs = []
+    for b in range(len(case.P)):
+        if case.S[b] == 0:
+            continue
+        o = int(cache.seq_offset[b]) + case.P[b]
+        gk = f64(k_now[o:o + case.S[b]]).reshape(case.S[b], -1)
+        gv = f64(v_now[o:o + case.S[b]]).reshape(case.S[b], -1)
+        errs.append(rel_err(gk, new_rows[b][0]))
+        errs.append(rel_err(gv, new_rows[b][1]))
+    worst = max(errs) if errs else 0.0
+    assert worst <= tol, f"new cache rows off by {worst:.3e} > {tol}"
+    return worst

@@ -1,0 +1,138 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every entry point that
+include/alora.h declares, and rejects bad arguments on the host before anything is launched
+(through a validation-only context, device -1, which needs no GPU)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ab():
+    from paper_2504_12397_amd import binding
+    return binding
+
+
+def declared_entry_points():
+    text = open(os.path.join(ROOT, "include", "alora.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(alora_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(ab):
+    names = declared_entry_points()
+    assert set(names) == set(ab.EXPORTS)
+    lib = C.CDLL(ab.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layout_matches_header(ab):
+    # natural alignment, no packing: 8 int32, then pointers / floats as declared
+    assert C.sizeof(ab.LayerDesc) == 8 * 4 + 7 * 8 + 2 * 4 + 5 * 8
+    assert ab.LayerDesc.W_qkv.offset == 32 and ab.LayerDesc.rms_eps.offset == 88 and ab.LayerDesc.W_o.offset == 96
+    assert C.sizeof(ab.KVCacheDesc) == 48
+
+
+def test_status_strings(ab):
+    lib = ab._lib
+    assert lib.alora_status_string(0) == b"ALORA_OK"
+    assert lib.alora_status_string(3) == b"ALORA_ECAPACITY"
+
+
+class FakeBuf:
+    """Stands in for device memory in validation-only calls: never dereferenced."""
+    PTR = 0x1000
+
+
+def make_args(ab, **over):
+    d = dict(d=64, n_q_heads=4, n_kv_heads=2, head_dim=16, rank=4, n_adapters=2, dtype=ab.ALORA_BF16, intermediate=0)
+    d.update({k: v for k, v in over.items() if k in d})
+    scale = np.ones(2, dtype=np.float32)
+    p = FakeBuf.PTR
+    desc = ab.LayerDesc(d["d"], d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["rank"], d["n_adapters"], d["dtype"],
+                        d["intermediate"], p, p, p, p, p, scale.ctypes.data_as(C.POINTER(C.c_float)), p, 1e-5,
+                        over.get("rope_theta", 10000.0), None, None, None, None, None)
+    B = over.get("B", 2)
+    off = np.asarray(over.get("seq_offset", [0, 100]), dtype=np.int64)
+    cap = np.asarray(over.get("seq_capacity", [100, 100]), dtype=np.int32)
+    ln = np.asarray(over.get("seq_len", [10, 20]), dtype=np.int32)
+    cache = ab.KVCacheDesc(p, p, over.get("pool_tokens", 200), off.ctypes.data_as(C.POINTER(C.c_int64)),
+                           cap.ctypes.data_as(C.POINTER(C.c_int32)), ln.ctypes.data_as(C.POINTER(C.c_int32)))
+    cu = np.asarray(over.get("cu", [0, 3, 8]), dtype=np.int32)
+    k = np.asarray(over.get("k", [10, 20]), dtype=np.int32)
+    a = np.asarray(over.get("a", [0, -1]), dtype=np.int32)
+    keep = (scale, off, cap, ln, cu, k, a)
+    return desc, cache, cu, k, a, B, keep, ln
+
+
+@pytest.fixture()
+def vctx(ab):
+    h = C.c_void_p()
+    assert ab._lib.alora_create(C.byref(h), -1) == ab.ALORA_OK
+    yield h
+    ab._lib.alora_destroy(h)
+
+
+def call(ab, h, desc, cache, cu, k, a, B):
+    p = C.POINTER(C.c_int32)
+    return ab._lib.alora_prefill(h, C.byref(desc), C.byref(cache), FakeBuf.PTR, cu.ctypes.data_as(p),
+                                 k.ctypes.data_as(p), a.ctypes.data_as(p), B, FakeBuf.PTR, None)
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(dtype=7), "ALORA_EDTYPE"),
+    (dict(n_q_heads=5), "ALORA_ESHAPE"),
+    (dict(head_dim=15), "ALORA_ESHAPE"),
+    (dict(head_dim=512), "ALORA_ESHAPE"),
+    (dict(d=0), "ALORA_ESHAPE"),
+    (dict(rank=0), "ALORA_ESHAPE"),
+    (dict(rope_theta=0.0), "ALORA_ESHAPE"),
+    (dict(B=0), "ALORA_EINVAL"),
+    (dict(cu=[1, 3, 8]), "ALORA_EINVAL"),
+    (dict(cu=[0, 5, 3]), "ALORA_EINVAL"),
+    (dict(k=[-1, 0]), "ALORA_EINVAL"),
+    (dict(seq_len=[-1, 0]), "ALORA_EINVAL"),
+    (dict(a=[2, 0]), "ALORA_EADAPTER"),
+    (dict(a=[-2, 0]), "ALORA_EADAPTER"),
+    (dict(seq_len=[98, 20]), "ALORA_ECAPACITY"),
+    (dict(seq_capacity=[100, 101]), "ALORA_ECAPACITY"),
+    (dict(seq_offset=[0, -1]), "ALORA_ECAPACITY"),
+])
+def test_bad_arguments_are_rejected_before_launch(ab, vctx, over, status):
+    desc, cache, cu, k, a, B, keep, ln = make_args(ab, **over)
+    before = ln.copy()
+    st = call(ab, vctx, desc, cache, cu, k, a, B)
+    assert ab._lib.alora_status_string(st).decode() == status
+    assert len(ab._lib.alora_last_error(vctx)) > 0
+    assert np.array_equal(ln, before)          # seq_len untouched on error
+
+
+def test_valid_arguments_pass_validation_and_empty_batch_is_a_noop(ab, vctx):
+    desc, cache, cu, k, a, B, keep, ln = make_args(ab)
+    st = call(ab, vctx, desc, cache, cu, k, a, B)
+    # a validation-only context cannot launch: everything checked out, then it says so
+    assert st == ab.ALORA_EHIP and b"validation-only" in ab._lib.alora_last_error(vctx)
+    assert list(ln) == [10, 20]
+    desc, cache, cu, k, a, B, keep, ln = make_args(ab, cu=[0, 0, 0])
+    assert call(ab, vctx, desc, cache, cu, k, a, B) == ab.ALORA_OK
+    assert list(ln) == [10, 20]
+
+
+def test_null_pointers(ab, vctx):
+    desc, cache, cu, k, a, B, keep, ln = make_args(ab)
+    p = C.POINTER(C.c_int32)
+    st = ab._lib.alora_prefill(vctx, None, C.byref(cache), FakeBuf.PTR, cu.ctypes.data_as(p), k.ctypes.data_as(p),
+                               a.ctypes.data_as(p), B, FakeBuf.PTR, None)
+    assert st == ab.ALORA_EINVAL
+    st = ab._lib.alora_prefill(vctx, C.byref(desc), C.byref(cache), None, cu.ctypes.data_as(p), k.ctypes.data_as(p),
+                               a.ctypes.data_as(p), B, FakeBuf.PTR, None)
+    assert st == ab.ALORA_EINVAL
+    assert ab._lib.alora_set_option(vctx, b"nonsense", 1) == ab.ALORA_EINVAL
+    assert ab._lib.alora_set_option(vctx, b"kernels", 1) == ab.ALORA_OK
+    assert ab._lib.alora_prefill(None, C.byref(desc), C.byref(cache), FakeBuf.PTR, cu.ctypes.data_as(p),
+                                 k.ctypes.data_as(p), a.ctypes.data_as(p), B, FakeBuf.PTR, None) == ab.ALORA_EINVAL

@@ -1,0 +1,224 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Cache prefix bytes, written row indices and seq_len are bit-exact; floating-point
+outputs are within 1e-4 (fp32) / 2e-2 (bf16 storage, fp32 accumulation) in helpers.rel_err."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import alora_oracle as orc
+from paper_2504_12397_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+SMALL_BF16 = wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, n_adapters=3)
+SMALL_F32 = dataclasses.replace(wl.SHAPE_TINY, n_adapters=2, rmsnorm=True, n_kv_heads=2)
+
+
+@pytest.fixture(scope="module")
+def ab():
+    from paper_2504_12397_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(ab):
+    c = ab.Context(0)
+    yield c
+    c.close()
+
+
+def run_prefill(ab, ctx, case, decode=False):
+    layer = H.gpu_layer(case, case.shape)
+    cache = H.gpu_cache(case)
+    bk, bv = cache.k.cpu().clone(), cache.v.cpu().clone()
+    x = case.x_packed.cuda().contiguous()
+    if decode:
+        out = ab.alora_decode(ctx, layer, cache, x, case.k, case.adapter)
+    else:
+        out = ab.alora_prefill(ctx, layer, cache, x, case.cu, case.k, case.adapter)
+    torch.cuda.synchronize()
+    return out, cache, bk, bv
+
+
+def check_case(ab, ctx, case, decode=False):
+    tol = H.TOL[case.shape.dtype]
+    out, cache, bk, bv = run_prefill(ab, ctx, case, decode)
+    ref_o, new_rows = H.oracle_prefill(case)
+    H.check_cache_after(case, cache, bk, bv, new_rows, tol)
+    err = H.rel_err(H.f64(out), ref_o)
+    assert err <= tol, f"attention output off by {err:.3e} > {tol}"
+    return out, cache
+
+
+# ------------------------------------------------------------------ config 1 (fp32 single block)
+def test_config1_fp32_block(ab, ctx):
+    b = wl.config1()
+    case = H.make_case(b.shape, b.P, b.S, b.k, b.adapter, b.seed)
+    check_case(ab, ctx, case)
+
+
+@pytest.mark.parametrize("P,S,k,a", [(64, 16, 64, 0), (64, 16, 40, 1), (64, 16, 70, 0), (64, 16, 200, 1),
+                                     (64, 16, 64, -1), (0, 33, 0, 1), (0, 33, 9, 0), (77, 1, 77, 0)])
+def test_fp32_invocation_positions(ab, ctx, P, S, k, a):
+    case = H.make_case(SMALL_F32, [P], [S], [k], [a], seed=100 + P + S + k)
+    check_case(ab, ctx, case)
+
+
+# ------------------------------------------------------------------ bf16, several tiles + ragged tails
+@pytest.mark.parametrize("P,S,k,a", [(300, 77, 300, 0), (300, 77, 150, 2), (300, 77, 333, 1), (300, 77, 300, -1),
+                                     (0, 201, 0, 1), (1, 130, 1, 0), (513, 1, 513, 2)])
+def test_bf16_single_sequence(ab, ctx, P, S, k, a):
+    case = H.make_case(SMALL_BF16, [P], [S], [k], [a], seed=200 + P + S + k)
+    check_case(ab, ctx, case)
+
+
+def test_bf16_mixed_batch_with_empty_sequence(ab, ctx):
+    P = [257, 0, 64, 700, 31, 128]
+    S = [65, 130, 0, 3, 97, 1]
+    k = [257, 0, 64, 650, 60, 128]
+    a = [0, 1, 2, -1, 2, 1]
+    case = H.make_case(SMALL_BF16, P, S, k, a, seed=301)
+    check_case(ab, ctx, case)
+
+
+def test_decode_matches_oracle_and_prefill(ab, ctx):
+    P = [400, 33, 1000, 64]
+    k = [380, 33, 2000, 0]
+    a = [0, 1, 2, -1]
+    case = H.make_case(SMALL_BF16, P, [1] * 4, k, a, seed=302)
+    out_d, _ = check_case(ab, ctx, case, decode=True)
+    out_p, _ = check_case(ab, ctx, case, decode=False)
+    assert H.rel_err(H.f64(out_d), H.f64(out_p)) <= 1e-2
+
+
+def test_token_by_token_decode_chain(ab, ctx):
+    """Proposition 1, second part: inference one token at a time with cache reuse."""
+    shape = SMALL_BF16
+    P, S, k, a = 90, 6, 90, 1
+    case = H.make_case(shape, [P], [S], [k], [a], seed=303)
+    layer = H.gpu_layer(case, shape)
+    cache = H.gpu_cache(case, extra_capacity=0)
+    outs = []
+    for t in range(S):
+        x = case.x_new[0][t:t + 1].cuda().contiguous()
+        outs.append(ab.alora_decode(ctx, layer, cache, x, [k], [a]))
+    torch.cuda.synchronize()
+    assert int(cache.seq_len[0]) == P + S
+    ref_o, _ = H.oracle_prefill(case)
+    assert H.rel_err(H.f64(torch.cat(outs)), ref_o) <= H.TOL["bf16"]
+
+
+# ------------------------------------------------------------------ invariants on the GPU
+def test_recompute_with_gated_weights_equals_cache_reuse(ab, ctx):
+    """The brute-force identity through the ABI: P=0, S=L, k=P0 recomputes everything with
+    position-gated weights and must agree with the cache-reuse call on the last S0 rows."""
+    shape = SMALL_BF16
+    P0, S0, a = 200, 60, 1
+    case = H.make_case(shape, [P0], [S0], [P0], [a], seed=304)
+    layer = H.gpu_layer(case, shape)
+    x_all = torch.cat([case.x_prefix[0], case.x_new[0]]).cuda().contiguous()
+    full_case = dataclasses.replace(case, P=[0], S=[P0 + S0], x_new=[x_all.cpu()], cache_K=[np.zeros((0, shape.n_kv))],
+                                    cache_V=[np.zeros((0, shape.n_kv))])
+    cache_full = H.gpu_cache(full_case)
+    out_full = ab.alora_prefill(ctx, layer, cache_full, x_all, [0, P0 + S0], [P0], [a])
+    # base-only run on the prefix, then the adapter reuses that cache
+    base_case = dataclasses.replace(case, P=[0], S=[P0], x_new=[case.x_prefix[0]], cache_K=[np.zeros((0, shape.n_kv))],
+                                    cache_V=[np.zeros((0, shape.n_kv))])
+    cache = H.gpu_cache(dataclasses.replace(base_case, S=[P0 + S0]))
+    ab.alora_prefill(ctx, layer, cache, case.x_prefix[0].cuda().contiguous(), [0, P0], [0], [-1])
+    out_reuse = ab.alora_prefill(ctx, layer, cache, case.x_new[0].cuda().contiguous(), [0, S0], [P0], [a])
+    torch.cuda.synchronize()
+    # prefix rows written by the gated recompute are bitwise the base model's rows (Prop.1, strong form)
+    kf, vf = cache_full.rows(0, 0, P0)
+    kb, vb = cache.rows(0, 0, P0)
+    assert torch.equal(kf.view(torch.int16), kb.view(torch.int16))
+    assert torch.equal(vf.view(torch.int16), vb.view(torch.int16))
+    assert H.rel_err(H.f64(out_reuse), H.f64(out_full[P0:])) <= 1e-2
+    ref_o, _ = H.oracle_prefill(case)
+    assert H.rel_err(H.f64(out_reuse), ref_o) <= H.TOL["bf16"]
+    assert H.rel_err(H.f64(out_full[P0:]), ref_o) <= H.TOL["bf16"]
+
+
+def test_base_rows_bitwise_independent_of_batch_composition(ab, ctx):
+    """Rows before k must not depend on which adapters or sequences share the batch."""
+    shape = SMALL_BF16
+    rng = wl.Rng(305)
+    tensors = wl.make_layer(shape, rng)
+    layer = H.gpu_layer(tensors, shape)
+    x0 = wl.make_hidden(rng, "x0", 150, shape)
+    x1 = wl.make_hidden(rng, "x1", 70, shape)
+
+    def run(seqs, ks, ads):
+        caps = [s.shape[0] for s in seqs]
+        cache = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda")
+        cu = [0]
+        for s in seqs:
+            cu.append(cu[-1] + s.shape[0])
+        out = ab.alora_prefill(ctx, layer, cache, torch.cat(seqs).cuda().contiguous(), cu, ks, ads)
+        torch.cuda.synchronize()
+        return out, cache
+
+    out_a, cache_a = run([x0], [100], [2])
+    out_b, cache_b = run([x1, x0], [0, 100], [1, 0])
+    out_c, cache_c = run([x0], [0], [-1])
+    ka, va = cache_a.rows(0, 0, 100)
+    kb, vb = cache_b.rows(1, 0, 100)
+    kc, vc = cache_c.rows(0, 0, 100)
+    for other_k, other_v in ((kb, vb), (kc, vc)):
+        assert torch.equal(ka.view(torch.int16), other_k.view(torch.int16))
+        assert torch.equal(va.view(torch.int16), other_v.view(torch.int16))
+    # attention outputs of those rows agree too (bitwise only if the key split happens to match)
+    assert H.rel_err(H.f64(out_a[:100]), H.f64(out_c[:100])) <= 1e-2
+    assert H.rel_err(H.f64(out_b[70:170]), H.f64(out_c[:100])) <= 1e-2
+    # rows from k on are adapter-private: they differ between adapters
+    assert not torch.equal(cache_a.rows(0, 100, 150)[0], cache_b.rows(1, 100, 150)[0])
+
+
+def test_zero_delta_reproduces_base_model(ab, ctx):
+    shape = SMALL_BF16
+    case = H.make_case(shape, [120], [50], [120], [0], seed=306)
+    zeroed = dict(case.tensors)
+    for n in ("B_q", "B_k", "B_v"):
+        zeroed[n] = torch.zeros_like(case.tensors[n])
+    outs = []
+    for tensors, scale, a in ((zeroed, None, 0), (case.tensors, 0.0, 0), (case.tensors, None, -1)):
+        t = dict(tensors)
+        if scale is not None:
+            t["scale"] = [scale] * shape.n_adapters
+        layer = H.gpu_layer(t, shape)
+        cache = H.gpu_cache(case)
+        outs.append(ab.alora_prefill(ctx, layer, cache, case.x_packed.cuda().contiguous(), case.cu, case.k, [a]))
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[2]) and torch.equal(outs[1], outs[2])
+
+
+def test_deterministic_across_runs(ab, ctx):
+    case = H.make_case(SMALL_BF16, [300, 10], [77, 40], [300, 20], [0, 2], seed=307)
+    a, _, _, _ = run_prefill(ab, ctx, case)
+    b, _, _, _ = run_prefill(ab, ctx, case)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ------------------------------------------------------------------ error handling through the ABI
+def test_errors_leave_everything_untouched(ab, ctx):
+    case = H.make_case(SMALL_BF16, [10], [5], [10], [0], seed=308)
+    layer = H.gpu_layer(case, case.shape)
+    cache = H.gpu_cache(case, extra_capacity=0)
+    bk = cache.k.clone()
+    x = case.x_packed.cuda().contiguous()
+    with pytest.raises(ab.AloraError) as e:
+        ab.alora_prefill(ctx, layer, cache, x, [0, 5], [10], [7])
+    assert e.value.status == ab.ALORA_EADAPTER
+    cache.seq_len[0] = 11
+    with pytest.raises(ab.AloraError) as e:
+        ab.alora_prefill(ctx, layer, cache, x, [0, 5], [10], [0])
+    assert e.value.status == ab.ALORA_ECAPACITY
+    cache.seq_len[0] = 10
+    with pytest.raises(ab.AloraError) as e:
+        ab.alora_prefill(ctx, layer, cache, x, [0, 5], [-1], [0])
+    assert e.value.status == ab.ALORA_EINVAL
+    torch.cuda.synchronize()
+    assert torch.equal(cache.k, bk) and int(cache.seq_len[0]) == 10

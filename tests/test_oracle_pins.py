@@ -254,6 +254,15 @@ def test_chunked_prefill_and_token_by_token_decode_agree():
     assert np.allclose(K[P:], kn, rtol=1e-13) and np.allclose(V[P:], vn, rtol=1e-13)
 
 
+def test_base_kv_is_the_cache_of_a_base_run():
+    L = rand_layer(27)
+    x = _x(28, 7, 24)
+    for dt in ("f64", "bf16"):
+        _, Kb, Vb = orc.ref_full(L, x, 0, -1, dt)
+        K2, V2 = orc.base_kv(L, x, dt)
+        assert np.array_equal(Kb, K2) and np.array_equal(Vb, V2)
+
+
 def test_batch_is_a_loop_over_independent_sequences():
     L = rand_layer(19)
     P, S = [4, 0, 7], [3, 5, 1]
