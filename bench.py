@@ -1,0 +1,297 @@
+#!/usr/bin/env python3
+"""Benchmark of the aLoRA hot path on one MI355X.
+
+A step is one pass of the whole hot path (row preparation, fused base + gated low-rank QKV
+projection, rotary embedding + cache append, attention over [base prefix ; adapted suffix])
+over one batch of seeded synthetic input that is already resident in HBM.
+
+    python bench.py [--workload c2|c3|c4|c5] [--steps K] [--warmup W]
+
+prints ONE JSON line: suffix tokens/s, ms per step, the roofline of the dominant kernel
+(per-kernel durations from HIP events recorded by the library on the launch stream) and the
+CPU oracle timed on the host cores on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2516.6
+MFMA_RIDGE = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)      # flop per byte where the two rooflines meet
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0)
+    ap.add_argument("--warmup", type=int, default=0)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--rotate", type=int, default=-1,
+                    help="distinct weight/cache sets cycled through so the last-level cache cannot hold the working set")
+    ap.add_argument("--layers", type=int, default=0, help="c5 only: number of layers (default 32)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-lora", action="store_true", help="c5 only: skip the k=0 recompute baseline")
+    ap.add_argument("--plain", action="store_true", help="force the plain fp32-FMA kernels")
+    return ap.parse_args()
+
+
+# ------------------------------------------------------------------------------------------
+# algorithmic work per kernel launch (what the method must do, never what a kernel happens to do)
+# ------------------------------------------------------------------------------------------
+def algorithmic_work(batch, shape, n_layers=1):
+    esz = 2 if shape.dtype == "bf16" else 4
+    T = batch.T
+    d, N, r = shape.d, shape.n_qkv, shape.rank
+    active_rows = sum(max(0, min(S, P + S - k)) if a >= 0 else 0
+                      for P, S, k, a in zip(batch.P, batch.S, batch.k, batch.adapter))
+    n_ad_used = len({a for a in batch.adapter if a >= 0})
+    w = {}
+    qkv_flops = 2.0 * T * d * N + 2.0 * active_rows * r * (3 * d + N)
+    qkv_bytes = esz * (N * d + T * d + T * N + n_ad_used * r * (3 * d + N))
+    w["qkv_gemm"] = dict(flops=qkv_flops, bytes=qkv_bytes)
+    attn_flops = sum(4.0 * shape.head_dim * shape.n_q_heads * sum(range(P + 1, P + S + 1))
+                     for P, S in zip(batch.P, batch.S))
+    kv_bytes = sum((P + S) * 2 * shape.n_kv * esz for P, S in zip(batch.P, batch.S) if S > 0)
+    w["attn_prefill"] = dict(flops=attn_flops, bytes=kv_bytes + 2 * T * shape.n_q * esz)
+    w["attn_decode"] = dict(flops=attn_flops, bytes=kv_bytes)
+    w["prep_rows"] = dict(flops=4.0 * T * d, bytes=2 * T * d * esz)
+    w["rope_append"] = dict(flops=6.0 * T * (shape.n_q + shape.n_kv), bytes=T * N * esz * 2)
+    w["attn_merge"] = dict(flops=0.0, bytes=T * shape.n_q * esz)
+    if shape.intermediate:
+        I = shape.intermediate
+        w["o_proj"] = dict(flops=2.0 * T * d * shape.n_q, bytes=esz * (d * shape.n_q + T * shape.n_q + 2 * T * d))
+        w["gate_up"] = dict(flops=4.0 * T * d * I, bytes=esz * (2 * I * d + T * d + 2 * T * I))
+        w["down_proj"] = dict(flops=2.0 * T * d * I, bytes=esz * (I * d + T * I + 2 * T * d))
+        w["mlp_norm"] = dict(flops=4.0 * T * d, bytes=2 * T * d * esz)
+        w["silu_mul"] = dict(flops=4.0 * T * I, bytes=3 * T * I * esz)
+    return w
+
+
+def roofline_of(kernel, work, avg_ms):
+    flops, nbytes = work["flops"], work["bytes"]
+    t_mfma = flops / (PEAK_BF16_TFLOPS * 1e12)
+    t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
+    sec = avg_ms * 1e-3
+    if t_mfma >= t_hbm:
+        ach = flops / sec / 1e12
+        return dict(kernel=kernel, bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=ach / PEAK_BF16_TFLOPS, traffic=None, avg_ms=avg_ms)
+    ach = nbytes / sec / 1e9
+    return dict(kernel=kernel, bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                traffic=None, avg_ms=avg_ms)
+
+
+# ------------------------------------------------------------------------------------------
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2504_12397_amd import binding as ab, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    name = args.workload
+    batch = {"c2": wl.config2, "c3": wl.config3, "c4": wl.config4, "c5": wl.config5}[name]()
+    shape = batch.shape
+    n_layers = 1
+    if name == "c5":
+        n_layers = args.layers or wl.N_LAYERS_STACK
+    steps = args.steps or {"c2": 200, "c3": 20, "c4": 50, "c5": 5}[name]
+    warmup = args.warmup or {"c2": 20, "c3": 3, "c4": 5, "c5": 1}[name]
+    rotate = args.rotate if args.rotate >= 0 else {"c2": 8, "c3": 2, "c4": 1, "c5": 1}[name]
+    rotate = max(1, rotate)
+
+    ctx = ab.Context(0)
+    if args.plain:
+        ctx.set_option("kernels", 1)
+    rng = wl.Rng(batch.seed, dev)
+
+    def make_set(tag):
+        layers = [ab.Layer(wl.make_layer(shape, rng, f"{tag}.L{l}"), shape.n_q_heads, shape.n_kv_heads,
+                           shape.head_dim, shape.rms_eps, shape.rope_theta, shape.intermediate)
+                  for l in range(n_layers)]
+        caps = [P + S for P, S in zip(batch.P, batch.S)]
+        caches = []
+        for l in range(n_layers):
+            c = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, dev)
+            caches.append(c)
+        return layers, caches
+
+    sets = [make_set(f"set{i}") for i in range(rotate)]
+    x_new = wl.make_hidden(rng, "x_new", batch.T, shape)
+
+    # ---- prefix caches: what the base model stored earlier -------------------------------
+    def fill_prefix(layers, caches, tag):
+        if name == "c2":
+            # the real flow: a base-model prefill (adapter -1) of the prefix creates the cache
+            xp = wl.make_hidden(rng, f"{tag}.x_prefix", batch.P[0], shape)
+            ab.alora_prefill(ctx, layers[0], caches[0], xp, [0, batch.P[0]], [0], [-1])
+        else:
+            # prefixes too long for a base pass inside a benchmark: N(0,1) keys/values, the
+            # distribution the seeded weights and inputs produce
+            for l, c in enumerate(caches):
+                for b, P in enumerate(batch.P):
+                    k, v = wl.make_random_kv(rng, f"{tag}.kv{l}.{b}", P, shape)
+                    o = int(c.seq_offset[b])
+                    c.k[o:o + P] = k
+                    c.v[o:o + P] = v
+                    c.seq_len[b] = P
+        torch.cuda.synchronize()
+
+    for i, (layers, caches) in enumerate(sets):
+        fill_prefix(layers, caches, f"set{i}")
+    P_arr = np.asarray(batch.P, dtype=np.int32)
+
+    out = torch.empty((batch.T, shape.d if name == "c5" else shape.n_q), dtype=shape.torch_dtype, device=dev)
+
+    def step(i, b=batch, x=x_new, o=out):
+        layers, caches = sets[i % rotate]
+        for c in caches:
+            c.seq_len[:] = np.asarray(b.P, dtype=np.int32)
+        if name == "c4":
+            ab.alora_decode(ctx, layers[0], caches[0], x, b.k, b.adapter, o)
+        elif name == "c5":
+            ab.alora_stack_prefill(ctx, layers, caches, x, b.cu_seqlens, b.k, b.adapter, o)
+        else:
+            ab.alora_prefill(ctx, layers[0], caches[0], x, b.cu_seqlens, b.k, b.adapter, o)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / steps * 1e3
+    tok_s = batch.T / (elapsed / steps)
+
+    # ---- per-kernel durations: the same steps again with the library's event brackets ----
+    ctx.set_option("profile", 1)
+    ctx.profile_reset()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.set_option("profile", 0)
+    work = algorithmic_work(batch, shape, n_layers)
+    kernels = {}
+    for kname, rec in prof.items():
+        avg = rec["ms"] / rec["launches"]
+        per_step = rec["ms"] / steps
+        rl = roofline_of(kname, work[kname], avg) if kname in work else None
+        kernels[kname] = dict(avg_ms=round(avg, 5), ms_per_step=round(per_step, 5), launches=rec["launches"],
+                              bound=rl["bound"] if rl else None, frac=round(rl["frac"], 4) if rl else None)
+    dominant = max(prof, key=lambda k_: prof[k_]["ms"])
+    roof = roofline_of(dominant, work[dominant], prof[dominant]["ms"] / prof[dominant]["launches"])
+
+    result = {
+        "metric": "alora_suffix_prefill_tok_per_s" if name != "c4" else "alora_decode_tok_per_s",
+        "value": tok_s, "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{name}: " + (batch.__doc__ or ""), "sequences": batch.n_seqs, "suffix_tokens": batch.T,
+                   "prefix_tokens": int(sum(batch.P)), "rank": shape.rank, "layers": n_layers,
+                   "rotating_buffer_sets": rotate, "kernels": "plain" if args.plain else "auto"},
+        "ttft_ms": ms_per_step,
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    result["config"]["workload"] = {
+        "c2": "c2: one 8B-class layer, bf16, 4096 cached base tokens + 256 adapted suffix tokens, rank 32",
+        "c3": "c3: mixed batch, 16 sequences, prefix 512-8192, suffix 32-512, 4 rank-32 adapters, 3 base-only",
+        "c4": "c4: decode step, 64 sequences x (16384 base + 64 adapted cached tokens), 1 new token each",
+        "c5": "c5: %d-layer 8B-class stack, 32768 cached base tokens + 128 adapted suffix tokens, rank 64" % n_layers,
+    }[name]
+
+    # ---- full-LoRA baseline for the first-token workload: same kernels, k = 0, empty cache ----
+    if name == "c5" and not args.no_full_lora:
+        fb = wl.config5(full_lora=True)
+        x_full = wl.make_hidden(rng, "x_full", fb.T, shape)
+        out_full = torch.empty((fb.T, shape.d), dtype=shape.torch_dtype, device=dev)
+        layers, caches = sets[0]
+
+        def full_step():
+            for c in caches:
+                c.seq_len[:] = 0
+            ab.alora_stack_prefill(ctx, layers, caches, x_full, fb.cu_seqlens, fb.k, fb.adapter, out_full)
+
+        full_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_full = 2
+        for _ in range(n_full):
+            full_step()
+        torch.cuda.synchronize()
+        full_ms = (time.perf_counter() - t0) / n_full * 1e3
+        result["full_lora_ttft_ms"] = full_ms
+        result["ttft_speedup_vs_full_lora"] = full_ms / ms_per_step
+
+    # ---- the CPU oracle on the same workload, timed on the host cores -------------------------
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(name, batch, shape, sets[0], x_new, n_layers)
+
+    print(json.dumps(result))
+    ctx.close()
+
+
+def cpu_baseline(name, batch, shape, first_set, x_new, n_layers):
+    """The oracle as it stands, on a bounded sample of the workload (stated in "sample")."""
+    import numpy as np
+    import torch
+    from oracle import alora_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    layers, caches = first_set
+
+    def host_layer(l):
+        t = {k_: (v.cpu() if isinstance(v, torch.Tensor) else v) for k_, v in layers[l].t.items()}
+        return orc.layer_from_tensors(t, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rms_eps,
+                                      shape.rope_theta)
+
+    # bounded sample: whole c2; 2 sequences of c3; 4 sequences of c4; one layer of c5
+    seqs = {"c2": [0], "c3": [0, 1], "c4": [0, 1, 2, 3], "c5": [0]}[name]
+    L0 = host_layer(0)
+    xs = x_new.cpu().double().numpy()
+    cu = batch.cu_seqlens
+    data = []
+    for b in seqs:
+        o = int(caches[0].seq_offset[b])
+        K = caches[0].k[o:o + batch.P[b]].cpu().double().numpy().reshape(batch.P[b], -1)
+        V = caches[0].v[o:o + batch.P[b]].cpu().double().numpy().reshape(batch.P[b], -1)
+        data.append((b, K, V, xs[cu[b]:cu[b + 1]]))
+    t0 = time.perf_counter()
+    toks = 0
+    for b, K, V, x in data:
+        o, kn, vn = orc.ref_cached(L0, K, V, batch.P[b], x, batch.k[b], batch.adapter[b], shape.dtype)
+        if name == "c5":
+            t = {k_: (v.cpu() if isinstance(v, torch.Tensor) else v) for k_, v in layers[0].t.items()}
+            orc.layer_tail(orc.layer_from_tensors(t, shape.n_q_heads, shape.n_kv_heads, shape.head_dim), x, o, shape.dtype)
+        toks += x.shape[0]
+    sec = time.perf_counter() - t0
+    scale_layers = n_layers if name == "c5" else 1
+    return {"value": toks / (sec * scale_layers), "unit": "tok/s", "cores": int(cores), "kind": "oracle",
+            "seconds": sec,
+            "sample": {"c2": "the whole workload (256 suffix tokens over 4096 cached), one run",
+                       "c3": "2 of the 16 sequences, tokens/s over their suffix tokens",
+                       "c4": "4 of the 64 sequences, one decode step each",
+                       "c5": "one layer of the stack on the 128 suffix tokens, time scaled by the layer count"}[name]}
+
+
+if __name__ == "__main__":
+    main()

@@ -111,8 +111,17 @@ const char *alora_status_string(alora_status s);
 /* Kernel selection and tuning knobs, by name.  "kernels": 0 = automatic (MFMA kernels
  * for bf16 where the shape allows, plain fp32-FMA kernels otherwise), 1 = force the plain
  * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
- * of attention into n chunks.  Unknown key or bad value: ALORA_EINVAL. */
+ * of attention into n chunks.  "profile": 0/1, see alora_profile_read.  Unknown key or bad
+ * value: ALORA_EINVAL. */
 alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
+
+/* Per-kernel timing.  With option "profile" = 1 the library brackets every kernel it launches
+ * with HIP events on the call's stream.  alora_profile_read waits for the pending events and
+ * returns the accumulated time and launch count of one kernel family: "prep_rows",
+ * "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
+ * "mlp_norm", "gate_up", "silu_mul", "down_proj".  alora_profile_reset clears the totals. */
+alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
+alora_status alora_profile_reset(alora_ctx *ctx);
 
 /* Adapter-activated prefill (Section 2, Eq.6; cost model of Proposition 2: only the T new
  * rows are projected, and each attends over its sequence's cached-plus-new rows).

@@ -19,7 +19,11 @@ Delta = s * B A with W stored [out, in], A [r, in], B [out, r]; softmax scale
 1/sqrt(head_dim); causal attention includes the current token (Eq.4 attends K_{1:t});
 rotary embedding in the "rotate-half" pairing (c, c + h/2) with absolute positions,
 applied to q and k before caching; grouped-query attention with contiguous groups
-(kv head = q head // G); RMSNorm before the projections.
+(kv head = q head // G); RMSNorm before the projections.  Storage points: the data path
+keeps activations and the cache in the storage dtype ("bf16 weights/activations with fp32
+accumulation"), so the two tensors it materialises between steps -- the normalised hidden
+state and the cached keys/values -- are rounded to that dtype here; every product and sum
+is exact float64 and the attention output is left unrounded.
 
 Pins: every function here is pinned by tests/test_oracle_pins.py (closed forms, library
 special cases, a pure-loop brute force written separately, Proposition-1 invariants, a
@@ -191,8 +195,8 @@ def causal_attention(q: np.ndarray, pos: np.ndarray, K: np.ndarray, V: np.ndarra
 # --------------------------------------------------------------------------------------
 # attention block: the definition and the cached method
 # --------------------------------------------------------------------------------------
-def ref_full(layer: Layer, x_all: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64"
-             ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def ref_full(layer: Layer, x_all: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64",
+             act_dtype: Optional[str] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """The definition on one whole sequence of L tokens (positions 0..L-1): Eq.6 rows, rotary
     embedding, then causal attention of every row over rows 0..i.  Returns O [L, N_q] and the
     keys (after rotation) and values as a cache of `cache_dtype` would hold them; attention
@@ -200,7 +204,7 @@ def ref_full(layer: Layer, x_all: np.ndarray, k: int, adapter: int, cache_dtype:
     x_all = np.asarray(x_all, dtype=F64)
     L = x_all.shape[0]
     pos = np.arange(L)
-    xh = rmsnorm(x_all, layer.rms_gain, layer.rms_eps)
+    xh = _normed(layer, x_all, act_dtype or cache_dtype)
     q, kk, v = project_qkv(layer, xh, pos, k, adapter)
     q = rope(q, pos, layer.n_q_heads, layer.head_dim, layer.rope_theta)
     kk = rope(kk, pos, layer.n_kv_heads, layer.head_dim, layer.rope_theta)
@@ -209,19 +213,27 @@ def ref_full(layer: Layer, x_all: np.ndarray, k: int, adapter: int, cache_dtype:
     return o, Kc, Vc
 
 
-def base_kv(layer: Layer, x_all: np.ndarray, cache_dtype: str = "f64") -> Tuple[np.ndarray, np.ndarray]:
+def _normed(layer: Layer, x: np.ndarray, act_dtype: str) -> np.ndarray:
+    """RMSNorm output as the data path stores it (rounded to the activation dtype)."""
+    if layer.rms_gain is None:
+        return x
+    return _store(rmsnorm(x, layer.rms_gain, layer.rms_eps), act_dtype)
+
+
+def base_kv(layer: Layer, x_all: np.ndarray, cache_dtype: str = "f64", act_dtype: Optional[str] = None
+            ) -> Tuple[np.ndarray, np.ndarray]:
     """Keys (rotated) and values the base model stores for a whole prefix at positions 0..L-1:
     the first three steps of `ref_full` with no adapter, without the attention step."""
     x_all = np.asarray(x_all, dtype=F64)
     pos = np.arange(x_all.shape[0])
-    xh = rmsnorm(x_all, layer.rms_gain, layer.rms_eps)
+    xh = _normed(layer, x_all, act_dtype or cache_dtype)
     _, kk, v = project_qkv(layer, xh, pos, 0, -1)
     kk = rope(kk, pos, layer.n_kv_heads, layer.head_dim, layer.rope_theta)
     return _store(kk, cache_dtype), _store(v, cache_dtype)
 
 
 def ref_cached(layer: Layer, cache_K: np.ndarray, cache_V: np.ndarray, P: int, x_suffix: np.ndarray,
-               k: int, adapter: int, cache_dtype: str = "f64"
+               k: int, adapter: int, cache_dtype: str = "f64", act_dtype: Optional[str] = None
                ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """The method: cache rows [0, P) are taken as they are; the S new rows at positions
     P..P+S-1 are projected (Eq.6), rotated, stored behind the prefix, and each attends over
@@ -230,7 +242,7 @@ def ref_cached(layer: Layer, cache_K: np.ndarray, cache_V: np.ndarray, P: int, x
     x_suffix = np.asarray(x_suffix, dtype=F64)
     S = x_suffix.shape[0]
     pos = P + np.arange(S)
-    xh = rmsnorm(x_suffix, layer.rms_gain, layer.rms_eps)
+    xh = _normed(layer, x_suffix, act_dtype or cache_dtype)
     q, kk, v = project_qkv(layer, xh, pos, k, adapter)
     q = rope(q, pos, layer.n_q_heads, layer.head_dim, layer.rope_theta)
     kk = rope(kk, pos, layer.n_kv_heads, layer.head_dim, layer.rope_theta)
@@ -262,11 +274,11 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
-def layer_tail(layer: Layer, x: np.ndarray, attn: np.ndarray) -> np.ndarray:
+def layer_tail(layer: Layer, x: np.ndarray, attn: np.ndarray, act_dtype: str = "f64") -> np.ndarray:
     """Output projection + residual, then RMSNorm + SwiGLU MLP + residual, all per token and
     with the base weights (the MLP blocks are not adapted)."""
     h = x + attn @ layer.W_o.T
-    hn = rmsnorm(h, layer.rms2_gain, layer.rms_eps)
+    hn = _store(rmsnorm(h, layer.rms2_gain, layer.rms_eps), act_dtype)
     m = silu(hn @ layer.W_gate.T) * (hn @ layer.W_up.T)
     return h + m @ layer.W_down.T
 
@@ -279,7 +291,7 @@ def ref_stack_full(layers: List[Layer], x_all: np.ndarray, k: int, adapter: int,
     for layer in layers:
         o, Kc, Vc = ref_full(layer, x, k, adapter, cache_dtype)
         caches.append((Kc, Vc))
-        x = layer_tail(layer, x, o)
+        x = layer_tail(layer, x, o, cache_dtype)
     return x, caches
 
 
@@ -292,5 +304,5 @@ def ref_stack_cached(layers: List[Layer], caches: List[Tuple[np.ndarray, np.ndar
     for layer, (cK, cV) in zip(layers, caches):
         o, kn, vn = ref_cached(layer, cK, cV, P, x, k, adapter, cache_dtype)
         new_rows.append((kn, vn))
-        x = layer_tail(layer, x, o)
+        x = layer_tail(layer, x, o, cache_dtype)
     return x, new_rows

@@ -17,7 +17,9 @@ ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDT
 ALORA_F32, ALORA_BF16 = 0, 1
 
 EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
-           "alora_prefill", "alora_decode", "alora_stack_prefill"]
+           "alora_profile_read", "alora_profile_reset", "alora_prefill", "alora_decode", "alora_stack_prefill"]
+KERNELS = ["prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
+           "mlp_norm", "gate_up", "silu_mul", "down_proj"]
 
 
 class LayerDesc(C.Structure):
@@ -51,6 +53,10 @@ def load_library() -> C.CDLL:
     lib.alora_status_string.argtypes = [C.c_int]
     lib.alora_set_option.restype = C.c_int
     lib.alora_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    lib.alora_profile_read.restype = C.c_int
+    lib.alora_profile_read.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.alora_profile_reset.restype = C.c_int
+    lib.alora_profile_reset.argtypes = [C.c_void_p]
     i32p = C.POINTER(C.c_int32)
     lib.alora_prefill.restype = C.c_int
     lib.alora_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
@@ -179,6 +185,19 @@ class Context:
 
     def set_option(self, key: str, value: int):
         self._check(_lib.alora_set_option(self._h, key.encode(), int(value)))
+
+    def profile_reset(self):
+        self._check(_lib.alora_profile_reset(self._h))
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        """{kernel: {"ms": total, "launches": n}} for every kernel family that ran."""
+        out = {}
+        for name in KERNELS:
+            ms, n = C.c_double(), C.c_int64()
+            self._check(_lib.alora_profile_read(self._h, name.encode(), C.byref(ms), C.byref(n)))
+            if n.value:
+                out[name] = {"ms": ms.value, "launches": int(n.value)}
+        return out
 
 
 def _stream_ptr(stream) -> Optional[int]:

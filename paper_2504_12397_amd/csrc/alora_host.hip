@@ -29,7 +29,22 @@ struct MetaSlot {
 
 }  // namespace
 
+struct ProfEvent {
+  hipEvent_t start, stop;
+  int kernel;
+};
+
+static const char *const KERNEL_NAMES[] = {"prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode",
+                                           "attn_merge", "o_proj", "mlp_norm", "gate_up", "silu_mul", "down_proj"};
+enum KernelId { K_PREP = 0, K_QKV, K_ROPE, K_ATTN_PREFILL, K_ATTN_DECODE, K_ATTN_MERGE, K_OPROJ, K_MLPNORM,
+                K_GATEUP, K_SILU, K_DOWN, K_COUNT };
+
 struct alora_ctx {
+  int opt_profile = 0;
+  std::vector<ProfEvent> prof_pending;
+  std::vector<hipEvent_t> prof_free;
+  double prof_ms[K_COUNT] = {};
+  int64_t prof_n[K_COUNT] = {};
   int device = 0;
   std::string err;
   char *ws = nullptr;
@@ -62,6 +77,28 @@ alora_status fail(alora_ctx *ctx, alora_status st, const char *fmt, ...) {
     if (e_ != hipSuccess)                                                                    \
       return fail(ctx, ALORA_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));           \
   } while (0)
+
+// Brackets one kernel launch with events when profiling is on.
+struct ProfScope {
+  alora_ctx *ctx;
+  hipStream_t s;
+  ProfEvent ev{};
+  bool on;
+  ProfScope(alora_ctx *c, int kernel, hipStream_t st) : ctx(c), s(st), on(c->opt_profile != 0) {
+    if (!on) return;
+    ev.kernel = kernel;
+    for (hipEvent_t *e : {&ev.start, &ev.stop}) {
+      if (!ctx->prof_free.empty()) { *e = ctx->prof_free.back(); ctx->prof_free.pop_back(); }
+      else if (hipEventCreate(e) != hipSuccess) { on = false; return; }
+    }
+    (void)hipEventRecord(ev.start, s);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(ev.stop, s);
+    ctx->prof_pending.push_back(ev);
+  }
+};
 
 struct Bump {
   char *base;
@@ -255,36 +292,66 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
 template <typename T>
 void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, const alora_kv_cache *cache,
                      const T *x, const Plan &pl, const SeqMeta *seqs_dev, const Workspace &w, bool write_meta,
-                     int n_splits, T *out, hipStream_t s) {
-  launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
-                      pl.any_adapter ? L.rank : 0, write_meta, (T *)w.xh, w.tlow, w.rm, s);
-  launch_qkv_gemm_plain<T>((const T *)w.xh, (const T *)ly->W_qkv, w.tlow, (const T *)ly->B_q, (const T *)ly->B_k,
-                           (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
-  launch_rope_append<T>(w.Y, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k, (T *)cache->v, s);
-  launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T, n_splits,
-                       w.partials, out, s);
+                     int n_splits, bool decode, T *out, hipStream_t s) {
+  {
+    ProfScope p(ctx, K_PREP, s);
+    launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
+                        pl.any_adapter ? L.rank : 0, write_meta, (T *)w.xh, w.tlow, w.rm, s);
+  }
+  {
+    ProfScope p(ctx, K_QKV, s);
+    launch_qkv_gemm_plain<T>((const T *)w.xh, (const T *)ly->W_qkv, w.tlow, (const T *)ly->B_q,
+                             (const T *)ly->B_k, (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
+  }
+  {
+    ProfScope p(ctx, K_ROPE, s);
+    launch_rope_append<T>(w.Y, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k, (T *)cache->v, s);
+  }
+  {
+    ProfScope p(ctx, decode ? K_ATTN_DECODE : K_ATTN_PREFILL, s);
+    launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
+                         n_splits, w.partials, s);
+  }
+  {
+    ProfScope p(ctx, K_ATTN_MERGE, s);
+    launch_attn_merge<T>(w.partials, L, pl.T, n_splits, out, s);
+  }
 }
 
 template <typename T>
-void layer_tail(const alora_layer_desc *ly, const LayerDims &L, const T *x, const Workspace &w, int T_rows, T *out,
-                hipStream_t s) {
+void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, const T *x, const Workspace &w,
+                int T_rows, T *out, hipStream_t s) {
   RowMeta none{};
-  // h1 = x + attn W_o^T
-  launch_gemm_plain<T>((const T *)w.attn, (const T *)ly->W_o, x, (T *)w.h1, T_rows, L.d, L.n_q, s);
-  launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
-                      (const T *)nullptr, 0, false, (T *)w.hn, nullptr, none, s);
-  launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_gate, (const T *)nullptr, (T *)w.gate, T_rows,
-                       ly->intermediate, L.d, s);
-  launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_up, (const T *)nullptr, (T *)w.up, T_rows,
-                       ly->intermediate, L.d, s);
-  launch_silu_mul<T>((const T *)w.gate, (const T *)w.up, (T *)w.gate, (int64_t)T_rows * ly->intermediate, s);
-  launch_gemm_plain<T>((const T *)w.gate, (const T *)ly->W_down, (const T *)w.h1, out, T_rows, L.d,
-                       ly->intermediate, s);
+  {   // h1 = x + attn W_o^T
+    ProfScope p(ctx, K_OPROJ, s);
+    launch_gemm_plain<T>((const T *)w.attn, (const T *)ly->W_o, x, (T *)w.h1, T_rows, L.d, L.n_q, s);
+  }
+  {
+    ProfScope p(ctx, K_MLPNORM, s);
+    launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
+                        (const T *)nullptr, 0, false, (T *)w.hn, nullptr, none, s);
+  }
+  {
+    ProfScope p(ctx, K_GATEUP, s);
+    launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_gate, (const T *)nullptr, (T *)w.gate, T_rows,
+                         ly->intermediate, L.d, s);
+    launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_up, (const T *)nullptr, (T *)w.up, T_rows,
+                         ly->intermediate, L.d, s);
+  }
+  {
+    ProfScope p(ctx, K_SILU, s);
+    launch_silu_mul<T>((const T *)w.gate, (const T *)w.up, (T *)w.gate, (int64_t)T_rows * ly->intermediate, s);
+  }
+  {
+    ProfScope p(ctx, K_DOWN, s);
+    launch_gemm_plain<T>((const T *)w.gate, (const T *)ly->W_down, (const T *)w.h1, out, T_rows, L.d,
+                         ly->intermediate, s);
+  }
 }
 
 alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, alora_kv_cache *caches,
                  const void *x, const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, void *out,
-                 void *stream, bool stack) {
+                 void *stream, bool stack, bool decode = false) {
   if (!ctx) return ALORA_EINVAL;
   ctx->err.clear();
   if (n_layers < 1) return fail(ctx, ALORA_EINVAL, "n_layers = %d must be at least 1", n_layers);
@@ -330,18 +397,18 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {
-    if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, slot->dev, w, true, n_splits, (bf16 *)out, s);
-    else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, slot->dev, w, true, n_splits, (float *)out, s);
+    if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, slot->dev, w, true, n_splits, decode, (bf16 *)out, s);
+    else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, slot->dev, w, true, n_splits, decode, (float *)out, s);
   } else {
     const void *cur = x;
     for (int l = 0; l < n_layers; ++l) {
       void *nxt = (l == n_layers - 1) ? out : ((l & 1) ? w.xb : w.xa);
       if (bf) {
-        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, slot->dev, w, l == 0, n_splits, (bf16 *)w.attn, s);
-        layer_tail<bf16>(&layers[l], L, (const bf16 *)cur, w, pl.T, (bf16 *)nxt, s);
+        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, slot->dev, w, l == 0, n_splits, false, (bf16 *)w.attn, s);
+        layer_tail<bf16>(ctx, &layers[l], L, (const bf16 *)cur, w, pl.T, (bf16 *)nxt, s);
       } else {
-        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, slot->dev, w, l == 0, n_splits, (float *)w.attn, s);
-        layer_tail<float>(&layers[l], L, (const float *)cur, w, pl.T, (float *)nxt, s);
+        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, slot->dev, w, l == 0, n_splits, false, (float *)w.attn, s);
+        layer_tail<float>(ctx, &layers[l], L, (const float *)cur, w, pl.T, (float *)nxt, s);
       }
       cur = nxt;
     }
@@ -354,6 +421,20 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
 }
 
 }  // namespace
+
+alora_status drain_profile(alora_ctx *ctx) {
+  for (ProfEvent &e : ctx->prof_pending) {
+    HIP_TRY(ctx, hipEventSynchronize(e.stop));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, e.start, e.stop));
+    ctx->prof_ms[e.kernel] += ms;
+    ctx->prof_n[e.kernel] += 1;
+    ctx->prof_free.push_back(e.start);
+    ctx->prof_free.push_back(e.stop);
+  }
+  ctx->prof_pending.clear();
+  return ALORA_OK;
+}
 
 extern "C" {
 
@@ -384,6 +465,8 @@ void alora_destroy(alora_ctx *ctx) {
   (void)hipDeviceSynchronize();
   if (ctx->ws) (void)hipFree(ctx->ws);
   if (ctx->rope) (void)hipFree(ctx->rope);
+  (void)drain_profile(ctx);
+  for (hipEvent_t e : ctx->prof_free) (void)hipEventDestroy(e);
   for (MetaSlot &sl : ctx->slots) {
     if (sl.host) (void)hipHostFree(sl.host);
     if (sl.dev) (void)hipFree(sl.dev);
@@ -421,7 +504,36 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
     ctx->opt_splits = value;
     return ALORA_OK;
   }
+  if (!strcmp(key, "profile")) {
+    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "profile must be 0 or 1");
+    ctx->opt_profile = value;
+    return ALORA_OK;
+  }
   return fail(ctx, ALORA_EINVAL, "unknown option '%s'", key);
+}
+
+alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches) {
+  if (!ctx) return ALORA_EINVAL;
+  ctx->err.clear();
+  if (!kernel || !total_ms || !launches) return fail(ctx, ALORA_EINVAL, "NULL argument");
+  alora_status st = drain_profile(ctx);
+  if (st != ALORA_OK) return st;
+  for (int i = 0; i < K_COUNT; ++i)
+    if (!strcmp(kernel, KERNEL_NAMES[i])) {
+      *total_ms = ctx->prof_ms[i];
+      *launches = ctx->prof_n[i];
+      return ALORA_OK;
+    }
+  return fail(ctx, ALORA_EINVAL, "unknown kernel name '%s'", kernel);
+}
+
+alora_status alora_profile_reset(alora_ctx *ctx) {
+  if (!ctx) return ALORA_EINVAL;
+  ctx->err.clear();
+  alora_status st = drain_profile(ctx);
+  if (st != ALORA_OK) return st;
+  for (int i = 0; i < K_COUNT; ++i) { ctx->prof_ms[i] = 0.0; ctx->prof_n[i] = 0; }
+  return ALORA_OK;
 }
 
 alora_status alora_prefill(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
@@ -437,7 +549,7 @@ alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_k
   if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
   std::vector<int32_t> cu(B + 1);
   for (int b = 0; b <= B; ++b) cu[b] = b;
-  return run(ctx, layer, 1, cache, x_tok, cu.data(), k_per_seq, adapter_per_seq, B, attn_out, stream, false);
+  return run(ctx, layer, 1, cache, x_tok, cu.data(), k_per_seq, adapter_per_seq, B, attn_out, stream, false, true);
 }
 
 alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers,

@@ -76,8 +76,11 @@ void launch_rope_append(const float *Y, const LayerDims &L, RowMeta rm, int T_ro
 // split-KV attention with plain fp32 arithmetic: partial pass + merge
 template <typename T>
 void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
-                       const LayerDims &L, int T_rows, int n_splits, float *partials, T *out,
-                       hipStream_t s);
+                       const LayerDims &L, int T_rows, int n_splits, float *partials, hipStream_t s);
+// merge of the per-split partials (log-sum-exp weights); partial layout per (row, q head, split):
+// head_dim accumulators, running max, running sum
+template <typename T>
+void launch_attn_merge(const float *partials, const LayerDims &L, int T_rows, int n_splits, T *out, hipStream_t s);
 
 template <typename T>
 void launch_silu_mul(const T *gate, const T *up, T *out, int64_t n, hipStream_t s);

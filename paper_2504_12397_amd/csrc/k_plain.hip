@@ -403,21 +403,27 @@ size_t attn_plain_partial_floats(const LayerDims &L, int T_rows, int n_splits) {
 
 template <typename T>
 void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
-                       const LayerDims &L, int T_rows, int n_splits, float *partials, T *out,
-                       hipStream_t s) {
+                       const LayerDims &L, int T_rows, int n_splits, float *partials, hipStream_t s) {
   if (T_rows == 0) return;
   const int G = L.n_q_heads / L.n_kv_heads;
   dim3 grid(T_rows * L.n_kv_heads, n_splits, (G + ATT_GMAX - 1) / ATT_GMAX);
   size_t smem = (size_t)(ATT_GMAX * L.head_dim + ATT_GMAX * 64) * sizeof(float);
   hipLaunchKernelGGL((attn_partial_kernel<T>), grid, dim3(64), smem, s, Q, cacheK, cacheV, seqs, rm, L, n_splits,
                      partials);
+}
+template void launch_attn_plain<float>(const float *, const float *, const float *, const SeqMeta *, RowMeta,
+                                       const LayerDims &, int, int, float *, hipStream_t);
+template void launch_attn_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, const SeqMeta *, RowMeta,
+                                      const LayerDims &, int, int, float *, hipStream_t);
+
+template <typename T>
+void launch_attn_merge(const float *partials, const LayerDims &L, int T_rows, int n_splits, T *out, hipStream_t s) {
+  if (T_rows == 0) return;
   hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(T_rows * L.n_q_heads), dim3(64), 0, s, partials, L, n_splits,
                      out);
 }
-template void launch_attn_plain<float>(const float *, const float *, const float *, const SeqMeta *, RowMeta,
-                                       const LayerDims &, int, int, float *, float *, hipStream_t);
-template void launch_attn_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, const SeqMeta *, RowMeta,
-                                      const LayerDims &, int, int, float *, bf16 *, hipStream_t);
+template void launch_attn_merge<float>(const float *, const LayerDims &, int, int, float *, hipStream_t);
+template void launch_attn_merge<bf16>(const float *, const LayerDims &, int, int, bf16 *, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 template <typename T>
