@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/alora.h"
@@ -250,6 +251,8 @@ struct Workspace {
   // layer-stack buffers
   void *attn, *h1, *hn, *gate, *up, *xa, *xb;
   size_t bytes;
+  bool mfma = false;
+  int k_splits = 1;
 };
 
 int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
@@ -261,8 +264,8 @@ int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
   return std::max(1, std::min(want, max_by_len));
 }
 
-Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, int n_splits, int intermediate,
-                           bool stack) {
+Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, int n_splits, int k_splits,
+                           int intermediate, bool stack) {
   Bump b(base);
   Workspace w{};
   w.rm.seq = b.take<int32_t>(T);
@@ -271,7 +274,7 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
   w.rm.slot = b.take<int64_t>(T);
   w.xh = b.take<char>((size_t)T * L.d * esz);
   w.tlow = b.take<float>((size_t)T * 3 * std::max(L.rank, 1));
-  w.Y = b.take<float>((size_t)T * L.n_qkv);
+  w.Y = b.take<float>((size_t)T * L.n_qkv * std::max(k_splits, 1));
   w.Q = b.take<char>((size_t)T * L.n_q * esz);
   w.partials = b.take<float>(attn_plain_partial_floats(L, T, n_splits));
   if (stack) {
@@ -293,19 +296,37 @@ template <typename T>
 void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, const alora_kv_cache *cache,
                      const T *x, const Plan &pl, const SeqMeta *seqs_dev, const Workspace &w, bool write_meta,
                      int n_splits, bool decode, T *out, hipStream_t s) {
+  const bool mfma = w.mfma && std::is_same<T, bf16>::value;
   {
     ProfScope p(ctx, K_PREP, s);
     launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
-                        pl.any_adapter ? L.rank : 0, write_meta, (T *)w.xh, w.tlow, w.rm, s);
+                        pl.any_adapter ? L.rank : 0, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr,
+                        w.rm, s);
   }
   {
     ProfScope p(ctx, K_QKV, s);
-    launch_qkv_gemm_plain<T>((const T *)w.xh, (const T *)ly->W_qkv, w.tlow, (const T *)ly->B_q,
-                             (const T *)ly->B_k, (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
+    if (mfma) {
+      GemmArgs g{};
+      g.A = (const bf16 *)w.xh; g.lda = L.d;
+      g.B = (const bf16 *)ly->W_qkv; g.ldb = L.d;
+      g.M = pl.T; g.N = L.n_qkv; g.K = L.d;
+      g.k_splits = w.k_splits;
+      g.Cpart = w.Y;
+      g.tlow = pl.any_adapter ? (const bf16 *)w.tlow : nullptr;
+      g.rank = L.rank;
+      g.Bq = (const bf16 *)ly->B_q; g.Bk = (const bf16 *)ly->B_k; g.Bv = (const bf16 *)ly->B_v;
+      g.n_q = L.n_q; g.n_kv = L.n_kv;
+      g.row_adapter = w.rm.adapter;
+      launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+    } else {
+      launch_qkv_gemm_plain<T>((const T *)w.xh, (const T *)ly->W_qkv, w.tlow, (const T *)ly->B_q,
+                               (const T *)ly->B_k, (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
+    }
   }
   {
     ProfScope p(ctx, K_ROPE, s);
-    launch_rope_append<T>(w.Y, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k, (T *)cache->v, s);
+    launch_rope_append<T>(w.Y, mfma ? w.k_splits : 1, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k,
+                          (T *)cache->v, s);
   }
   {
     ProfScope p(ctx, decode ? K_ATTN_DECODE : K_ATTN_PREFILL, s);
@@ -322,30 +343,50 @@ template <typename T>
 void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, const T *x, const Workspace &w,
                 int T_rows, T *out, hipStream_t s) {
   RowMeta none{};
+  const bool mfma = w.mfma && std::is_same<T, bf16>::value;
+  auto dense = [&](const void *A, const void *W, const void *R, void *C, int N, int K) {
+    if (mfma) {
+      GemmArgs g{};
+      g.A = (const bf16 *)A; g.lda = K;
+      g.B = (const bf16 *)W; g.ldb = K;
+      g.M = T_rows; g.N = N; g.K = K; g.k_splits = 1;
+      g.C = (bf16 *)C; g.ldc = N; g.R = (const bf16 *)R;
+      launch_gemm_mfma(g, GEMM_EPI_BF16, s);
+    } else {
+      launch_gemm_plain<T>((const T *)A, (const T *)W, (const T *)R, (T *)C, T_rows, N, K, s);
+    }
+  };
   {   // h1 = x + attn W_o^T
     ProfScope p(ctx, K_OPROJ, s);
-    launch_gemm_plain<T>((const T *)w.attn, (const T *)ly->W_o, x, (T *)w.h1, T_rows, L.d, L.n_q, s);
+    dense(w.attn, ly->W_o, x, w.h1, L.d, L.n_q);
   }
   {
     ProfScope p(ctx, K_MLPNORM, s);
     launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
-                        (const T *)nullptr, 0, false, (T *)w.hn, nullptr, none, s);
+                        (const T *)nullptr, 0, false, (T *)w.hn, nullptr, nullptr, none, s);
   }
-  {
+  if (mfma) {   // act = silu(hn W_gate^T) * (hn W_up^T) in one pass
     ProfScope p(ctx, K_GATEUP, s);
-    launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_gate, (const T *)nullptr, (T *)w.gate, T_rows,
-                         ly->intermediate, L.d, s);
-    launch_gemm_plain<T>((const T *)w.hn, (const T *)ly->W_up, (const T *)nullptr, (T *)w.up, T_rows,
-                         ly->intermediate, L.d, s);
-  }
-  {
-    ProfScope p(ctx, K_SILU, s);
-    launch_silu_mul<T>((const T *)w.gate, (const T *)w.up, (T *)w.gate, (int64_t)T_rows * ly->intermediate, s);
+    GemmArgs g{};
+    g.A = (const bf16 *)w.hn; g.lda = L.d;
+    g.B = (const bf16 *)ly->W_gate; g.B2 = (const bf16 *)ly->W_up; g.ldb = L.d;
+    g.M = T_rows; g.N = 2 * ly->intermediate; g.K = L.d; g.k_splits = 1;
+    g.C = (bf16 *)w.gate; g.ldc = ly->intermediate;
+    launch_gemm_mfma(g, GEMM_EPI_SWIGLU, s);
+  } else {
+    {
+      ProfScope p(ctx, K_GATEUP, s);
+      dense(w.hn, ly->W_gate, nullptr, w.gate, ly->intermediate, L.d);
+      dense(w.hn, ly->W_up, nullptr, w.up, ly->intermediate, L.d);
+    }
+    {
+      ProfScope p(ctx, K_SILU, s);
+      launch_silu_mul<T>((const T *)w.gate, (const T *)w.up, (T *)w.gate, (int64_t)T_rows * ly->intermediate, s);
+    }
   }
   {
     ProfScope p(ctx, K_DOWN, s);
-    launch_gemm_plain<T>((const T *)w.gate, (const T *)ly->W_down, (const T *)w.h1, out, T_rows, L.d,
-                         ly->intermediate, s);
+    dense(w.gate, ly->W_down, w.h1, out, L.d, ly->intermediate);
   }
 }
 
@@ -383,7 +424,12 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   hipStream_t s = (hipStream_t)stream;
   const size_t esz = layers[0].dtype == ALORA_BF16 ? 2 : 4;
   const int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
-  Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, layers[0].intermediate, stack);
+  // kernel family: MFMA for bf16 shapes it covers, plain otherwise
+  const bool mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && L.d % 64 == 0 &&
+                    (L.n_adapters == 0 || (L.rank % 16 == 0 && L.n_adapters <= 64)) && L.n_q % 32 == 0 &&
+                    L.n_kv % 32 == 0 && (!stack || (layers[0].intermediate % 64 == 0 && L.n_q % 64 == 0));
+  const int k_splits = mfma ? gemm_mfma_pick_splits(pl.T, L.n_qkv, L.d, ctx->n_cu) : 1;
+  Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
   st = ensure_workspace(ctx, probe.bytes);
   if (st != ALORA_OK) return st;
   st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
@@ -393,7 +439,9 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (st != ALORA_OK) return st;
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
   HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, (size_t)B * sizeof(SeqMeta), hipMemcpyHostToDevice, s));
-  Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, layers[0].intermediate, stack);
+  Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
+  w.mfma = mfma;
+  w.k_splits = k_splits;
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {

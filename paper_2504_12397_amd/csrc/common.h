@@ -56,7 +56,7 @@ void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipS
 
 template <typename T>
 void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
-                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow,
+                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow, bf16 *tlow16,
                       RowMeta rm, hipStream_t s);
 
 // Y[T, n_qkv] (fp32) = xh W^T + gated low-rank term (Eq.6)
@@ -70,7 +70,7 @@ template <typename T>
 void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, int K, hipStream_t s);
 
 template <typename T>
-void launch_rope_append(const float *Y, const LayerDims &L, RowMeta rm, int T_rows,
+void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
                         const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s);
 
 // split-KV attention with plain fp32 arithmetic: partial pass + merge

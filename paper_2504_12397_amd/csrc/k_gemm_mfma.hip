@@ -1,0 +1,252 @@
+// bf16 MFMA GEMM for gfx950:  C[M,N] = A[M,K] B[N,K]^T  (both operands K-contiguous, which is
+// how activations [tokens, in] and weights [out, in] are stored).
+//
+// * v_mfma_f32_32x32x16_bf16.  Operand layout (checked on hardware): lane l feeds row l%32 with
+//   the 8 consecutive k values 8*(l/32)..+7; accumulator register v of lane l is
+//   C[8*(v/4) + 4*(l/32) + v%4][l%32].
+// * Block tile BM x BN x 64, four waves, each WM x WN.  Tiles go global -> registers -> LDS with a
+//   one-tile register prefetch and two LDS buffers (one barrier per k-tile).  LDS rows are 128 B
+//   (8 chunks of 16 B); chunk c of row r sits at position c ^ (r & 7), so both the row-major
+//   stores and the 32-rows-one-chunk operand reads are bank-conflict free.
+// * Gated low-rank term of Eq.6 as extra k-steps BEFORE the main loop: for every adapter present
+//   in the row tile, A-operand = t = s*A_a x (bf16, zero for rows that are not adapted by a),
+//   B-operand = B_{a,p}.  Rows that are not adapted accumulate exact zeros into zero
+//   accumulators, so their results are bitwise what a base-only call gives.
+// * Epilogues: fp32 partial sums (split-K capable, summed later in a fixed order), bf16 store
+//   (+ residual), SwiGLU (gate and up columns interleaved in 32-column blocks inside the tile).
+#include "mfma_kernels.h"
+
+namespace alora {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
+  constexpr int BK = 64;
+  constexpr int WAVES_N = BN / WN;
+  static_assert((BM / WM) * WAVES_N == 4, "four waves per block");
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
+  extern __shared__ uint4 smem[];
+  __shared__ unsigned long long s_present;
+  uint4 *As0 = smem, *Bs0 = smem + BM * 8, *As1 = smem + (BM + BN) * 8, *Bs1 = As1 + BM * 8;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN, split = blockIdx.z;
+  const int M = g.M, N = g.N, K = g.K;
+  const int k_len = K / g.k_splits, k_beg = split * k_len, nk = k_len / BK;
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- gated low-rank extension (Eq.6), split 0 only --------------------------------------
+  if (g.tlow != nullptr && split == 0) {
+    if (tid == 0) s_present = 0ull;
+    __syncthreads();
+    for (int r = tid; r < BM; r += 256) {
+      int row = m0 + r;
+      if (row < M) {
+        int a = g.row_adapter[row];
+        if (a >= 0) atomicOr(&s_present, 1ull << a);
+      }
+    }
+    __syncthreads();
+    unsigned long long present = s_present;
+    const int r = g.rank;
+    int a_row[TM];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi) {
+      int row = m0 + wm0 + mi * 32 + l32;
+      a_row[mi] = row < M ? g.row_adapter[row] : -1;
+    }
+    while (present) {
+      const int a = __builtin_ctzll(present);
+      present &= present - 1;
+      for (int ks = 0; ks < r; ks += 16) {
+        bf16x8 bfrag[TN];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) {
+          int col = n0 + wn0 + ni * 32 + l32;
+          uint4 u = make_uint4(0, 0, 0, 0);
+          if (col < N) {
+            const bf16 *bp;
+            if (col < g.n_q) bp = g.Bq + ((int64_t)a * g.n_q + col) * r;
+            else if (col < g.n_q + g.n_kv) bp = g.Bk + ((int64_t)a * g.n_kv + (col - g.n_q)) * r;
+            else bp = g.Bv + ((int64_t)a * g.n_kv + (col - g.n_q - g.n_kv)) * r;
+            u = *reinterpret_cast<const uint4 *>(bp + ks + lhi * 8);
+          }
+          bfrag[ni] = as_bf16x8(u);
+        }
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) {
+          int row = m0 + wm0 + mi * 32 + l32;
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) {
+            // the section (q, k or v) of this 32-column block selects which t to use
+            int colb = n0 + wn0 + ni * 32;
+            int p = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
+            uint4 u = make_uint4(0, 0, 0, 0);
+            if (a_row[mi] == a) u = *reinterpret_cast<const uint4 *>(g.tlow + ((int64_t)row * 3 + p) * r + ks + lhi * 8);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(u), bfrag[ni], acc[mi][ni], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- main loop --------------------------------------------------------------------------
+  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+  auto b_src_row = [&](int j) -> int {      // LDS row j of the B tile -> row of the weight matrix
+    if (EPI == GEMM_EPI_SWIGLU) {
+      int blk = j >> 5;
+      int src = (n0 >> 1) + (blk >> 1) * 32 + (j & 31);
+      return src < (N >> 1) ? src : (N >> 1) - 1;
+    }
+    int src = n0 + j;
+    return src < N ? src : N - 1;
+  };
+  auto load_tiles = [&](int kt) {
+    const int k0 = k_beg + kt * BK;
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      int gr = m0 + row;
+      gr = gr < M ? gr : M - 1;
+      ra[i] = *reinterpret_cast<const uint4 *>(g.A + (int64_t)gr * g.lda + k0 + c * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      const bf16 *base = g.B;
+      if (EPI == GEMM_EPI_SWIGLU && ((row >> 5) & 1)) base = g.B2;
+      rb[i] = *reinterpret_cast<const uint4 *>(base + (int64_t)b_src_row(row) * g.ldb + k0 + c * 8);
+    }
+  };
+  auto store_tiles = [&](uint4 *As, uint4 *Bs) {
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      As[row * 8 + (c ^ (row & 7))] = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      Bs[row * 8 + (c ^ (row & 7))] = rb[i];
+    }
+  };
+
+  if (nk > 0) {
+    load_tiles(0);
+    store_tiles(As0, Bs0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    uint4 *As = (kt & 1) ? As1 : As0, *Bs = (kt & 1) ? Bs1 : Bs0;
+    if (kt + 1 < nk) load_tiles(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+      const int c = 2 * ks + lhi;
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi) {
+        int row = wm0 + mi * 32 + l32;
+        af[mi] = as_bf16x8(As[row * 8 + (c ^ (row & 7))]);
+      }
+#pragma unroll
+      for (int ni = 0; ni < TN; ++ni) {
+        int row = wn0 + ni * 32 + l32;
+        bfr[ni] = as_bf16x8(Bs[row * 8 + (c ^ (row & 7))]);
+      }
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_tiles((kt & 1) ? As0 : As1, (kt & 1) ? Bs0 : Bs1);
+    __syncthreads();
+  }
+
+  // ---- epilogue ---------------------------------------------------------------------------
+#pragma unroll
+  for (int mi = 0; mi < TM; ++mi) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+      if (row >= M) continue;
+      if (EPI == GEMM_EPI_SWIGLU) {
+#pragma unroll
+        for (int q = 0; q < TN / 2; ++q) {
+          int col = (n0 >> 1) + (wn0 >> 1) + q * 32 + l32;
+          if (col < (N >> 1)) {
+            float gv = acc[mi][2 * q][v], uv = acc[mi][2 * q + 1][v];
+            g.C[(int64_t)row * g.ldc + col] = (bf16)(gv / (1.0f + __expf(-gv)) * uv);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) {
+          int col = n0 + wn0 + ni * 32 + l32;
+          if (col >= N) continue;
+          float val = acc[mi][ni][v];
+          if (EPI == GEMM_EPI_PARTIAL) {
+            g.Cpart[((int64_t)split * M + row) * N + col] = val;
+          } else {
+            if (g.R) val += (float)g.R[(int64_t)row * g.ldc + col];
+            g.C[(int64_t)row * g.ldc + col] = (bf16)val;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+static void launch_cfg(const GemmArgs &g, hipStream_t s) {
+  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, g.k_splits);
+  size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI>;
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, g);
+}
+
+bool gemm_mfma_supported(int M, int N, int K) { return M > 0 && N > 0 && K >= 64 && K % 64 == 0; }
+
+int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
+  // split the reduction only while the grid underfills the chip, in chunks of at least 512
+  int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+  int s = 1;
+  while (tiles * s < 2 * n_cu && s < 8 && (K / (s * 2)) % 64 == 0 && K / (s * 2) >= 512) s *= 2;
+  return s;
+}
+
+void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0) return;
+  if (epi == GEMM_EPI_PARTIAL) {
+    launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
+  } else if (epi == GEMM_EPI_SWIGLU) {
+    g.k_splits = 1;
+    if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
+    else launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
+  } else {
+    g.k_splits = 1;
+    if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
+    else launch_cfg<256, 128, 128, 64, GEMM_EPI_BF16>(g, s);
+  }
+}
+
+}  // namespace alora

@@ -38,7 +38,8 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x,
                                                         float eps, int d, const SeqMeta *__restrict__ seqs,
                                                         int n_seqs, const T *__restrict__ A, int rank,
                                                         int write_meta, T *__restrict__ xh,
-                                                        float *__restrict__ tlow, RowMeta rm) {
+                                                        float *__restrict__ tlow, bf16 *__restrict__ tlow16,
+                                                        RowMeta rm) {
   extern __shared__ float xs[];
   __shared__ float red[4];
   __shared__ int s_adapter;
@@ -94,22 +95,25 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x,
     float acc = 0.f;
     for (int c = lane; c < d; c += 64) acc += to_f32<T>(ar[c]) * xs[c];
     acc = wave_sum(acc);
-    if (lane == 0) tlow[(int64_t)row * 3 * rank + j] = scale * acc;
+    if (lane == 0) {
+      if (tlow16) tlow16[(int64_t)row * 3 * rank + j] = (bf16)(scale * acc);
+      else tlow[(int64_t)row * 3 * rank + j] = scale * acc;
+    }
   }
 }
 
 template <typename T>
 void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
-                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow,
+                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow, bf16 *tlow16,
                       RowMeta rm, hipStream_t s) {
   if (T_rows == 0) return;
   hipLaunchKernelGGL((prep_rows_kernel<T>), dim3(T_rows), dim3(256), (size_t)d * sizeof(float), s, x, gain,
-                     eps, d, seqs, n_seqs, A, rank, write_meta ? 1 : 0, xh, tlow, rm);
+                     eps, d, seqs, n_seqs, A, rank, write_meta ? 1 : 0, xh, tlow, tlow16, rm);
 }
 template void launch_prep_rows<float>(const float *, const float *, float, int, int, const SeqMeta *, int,
-                                      const float *, int, bool, float *, float *, RowMeta, hipStream_t);
+                                      const float *, int, bool, float *, float *, bf16 *, RowMeta, hipStream_t);
 template void launch_prep_rows<bf16>(const bf16 *, const bf16 *, float, int, int, const SeqMeta *, int,
-                                     const bf16 *, int, bool, bf16 *, float *, RowMeta, hipStream_t);
+                                     const bf16 *, int, bool, bf16 *, float *, bf16 *, RowMeta, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // plain tiled GEMM  C[M,N] = A[M,K] B[N,K]^T, 64x64 tile, 16-deep, 4x4 outputs per thread
@@ -224,10 +228,17 @@ template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, 
 // rotary embedding + cache append (Eq.3: K_{1:t} = [K_{1:t-1}; K_t]).  One workgroup per row.
 // ---------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, LayerDims L, RowMeta rm,
+__global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, int n_parts,
+                                                          int64_t part_stride, LayerDims L, RowMeta rm,
                                                           const float2 *__restrict__ table, T *__restrict__ Q,
                                                           T *__restrict__ cacheK, T *__restrict__ cacheV) {
   const int row = blockIdx.x, tid = threadIdx.x;
+  // Y may arrive as n_parts partial sums over the reduction axis: add them in a fixed order
+  auto ysum = [&](const float *p) {
+    float v = p[0];
+    for (int s = 1; s < n_parts; ++s) v += p[(int64_t)s * part_stride];
+    return v;
+  };
   const int h = L.head_dim, h2 = h >> 1;
   const int pos = rm.pos[row];
   const int64_t slot = rm.slot[row];
@@ -239,7 +250,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     const int ii = is_q ? i : i - q_pairs;
     const int head = ii / h2, c = ii % h2;
     const int base = (is_q ? 0 : L.n_q) + head * h;
-    const float u = y[base + c], w = y[base + c + h2];
+    const float u = ysum(y + base + c), w = ysum(y + base + c + h2);
     const float2 cs = tab[c];
     const float lo = u * cs.x - w * cs.y, hi = w * cs.x + u * cs.y;
     if (is_q) {
@@ -253,19 +264,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     }
   }
   const float *yv = y + L.n_q + L.n_kv;
-  for (int i = tid; i < L.n_kv; i += 256) cacheV[slot * L.n_kv + i] = from_f32<T>(yv[i]);
+  for (int i = tid; i < L.n_kv; i += 256) cacheV[slot * L.n_kv + i] = from_f32<T>(ysum(yv + i));
 }
 
 template <typename T>
-void launch_rope_append(const float *Y, const LayerDims &L, RowMeta rm, int T_rows,
+void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
                         const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
   if (T_rows == 0) return;
-  hipLaunchKernelGGL((rope_append_kernel<T>), dim3(T_rows), dim3(256), 0, s, Y, L, rm, rope_table, Q, cacheK,
-                     cacheV);
+  hipLaunchKernelGGL((rope_append_kernel<T>), dim3(T_rows), dim3(256), 0, s, Y, n_parts,
+                     (int64_t)T_rows * L.n_qkv, L, rm, rope_table, Q, cacheK, cacheV);
 }
-template void launch_rope_append<float>(const float *, const LayerDims &, RowMeta, int, const float2 *, float *,
-                                        float *, float *, hipStream_t);
-template void launch_rope_append<bf16>(const float *, const LayerDims &, RowMeta, int, const float2 *, bf16 *,
+template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *,
+                                        float *, float *, float *, hipStream_t);
+template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, bf16 *,
                                        bf16 *, bf16 *, hipStream_t);
 
 // ---------------------------------------------------------------------------------------

@@ -222,3 +222,106 @@ def test_errors_leave_everything_untouched(ab, ctx):
     assert e.value.status == ab.ALORA_EINVAL
     torch.cuda.synchronize()
     assert torch.equal(cache.k, bk) and int(cache.seq_len[0]) == 10
+
+
+# ------------------------------------------------------------------ layer stack (first-token pass)
+def make_stack_case(shape, n_layers, P, S, seed):
+    rng = wl.Rng(seed)
+    tensors = [wl.make_layer(shape, rng, f"L{l}") for l in range(n_layers)]
+    layers = [H.oracle_layer(t, shape) for t in tensors]
+    x_all = wl.make_hidden(rng, "x_all", P + S, shape)
+    return tensors, layers, x_all
+
+
+@pytest.mark.parametrize("shape", [
+    dataclasses.replace(SMALL_BF16, intermediate=1024),
+    dataclasses.replace(SMALL_F32, intermediate=320),
+])
+def test_stack_cache_reuse_against_oracle_recompute(ab, ctx, shape):
+    """Proposition 1 through a stack: the base model prefills the prefix (adapter -1) layer by layer, the
+    adapter then reuses those caches for the suffix; the oracle recomputes the whole sequence with
+    position-gated weights."""
+    n_layers, P, S, a = 2, 150, 45, 1
+    tensors, layers, x_all = make_stack_case(shape, n_layers, P, S, seed=400)
+    want, _ = orc.ref_stack_full(layers, H.f64(x_all), P, a, shape.dtype)
+    glayers = [H.gpu_layer(t, shape) for t in tensors]
+    caches = [ab.KVCache([P + S], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda") for _ in range(n_layers)]
+    xg = x_all.cuda().contiguous()
+    base_out = ab.alora_stack_prefill(ctx, glayers, caches, xg[:P].contiguous(), [0, P], [0], [-1])
+    assert int(caches[0].seq_len[0]) == P
+    got = ab.alora_stack_prefill(ctx, glayers, caches, xg[P:].contiguous(), [0, S], [P], [a])
+    torch.cuda.synchronize()
+    assert int(caches[0].seq_len[0]) == P + S and int(caches[1].seq_len[0]) == P + S
+    tol = H.TOL[shape.dtype] * (2 if shape.dtype == "bf16" else 1)   # two layers of bf16 activations
+    assert H.rel_err(H.f64(base_out), want[:P]) <= tol
+    assert H.rel_err(H.f64(got), want[P:]) <= tol
+
+
+# ------------------------------------------------------------------ full-size configurations
+def test_config2_full_size(ab, ctx):
+    """One 8B-class layer: 4096 cached base tokens (cache from the oracle's base pass), 256 adapted tokens."""
+    b = wl.config2()
+    case = H.make_case(b.shape, b.P, b.S, b.k, b.adapter, b.seed)
+    check_case(ab, ctx, case)
+
+
+def test_config3_mixed_batch_sampled(ab, ctx):
+    """16 sequences, 4 adapters, 3 base-only; all run on the GPU, the oracle checks three whole sequences."""
+    b = wl.config3()
+    case = H.make_case(b.shape, b.P, b.S, b.k, b.adapter, b.seed, prefix="random")
+    out, cache, bk, bv = run_prefill(ab, ctx, case)
+    base_only = [i for i, a in enumerate(b.adapter) if a < 0]
+    picks = sorted({base_only[0], int(np.argmin(b.S)), int(np.argmax([a for a in b.adapter]))})
+    cu = case.cu
+    for i in picks:
+        o, kn, vn = orc.ref_cached(case.layer, case.cache_K[i], case.cache_V[i], b.P[i], H.f64(case.x_new[i]),
+                                   b.k[i], b.adapter[i], "bf16")
+        assert H.rel_err(H.f64(out[cu[i]:cu[i + 1]]), o) <= H.TOL["bf16"]
+        gk, gv = cache.rows(i, b.P[i], b.P[i] + b.S[i])
+        assert H.rel_err(H.f64(gk).reshape(b.S[i], -1), kn) <= H.TOL["bf16"]
+        assert H.rel_err(H.f64(gv).reshape(b.S[i], -1), vn) <= H.TOL["bf16"]
+    # indexing over the whole pool: only rows [P_b, P_b + S_b) changed
+    written = torch.zeros(cache.pool_tokens, dtype=torch.bool)
+    for i in range(b.n_seqs):
+        o = int(cache.seq_offset[i])
+        written[o + b.P[i]:o + b.P[i] + b.S[i]] = True
+        assert int(cache.seq_len[i]) == b.P[i] + b.S[i]
+    assert torch.equal(cache.k.cpu()[~written].view(torch.int16), bk[~written].view(torch.int16))
+    assert torch.equal(cache.v.cpu()[~written].view(torch.int16), bv[~written].view(torch.int16))
+
+
+def test_config4_decode_sampled(ab, ctx):
+    """64 sequences x 16448 cached tokens, one new token each; the oracle checks six sequences."""
+    b = wl.config4()
+    shape = b.shape
+    rng = wl.Rng(b.seed, "cuda")
+    tensors = wl.make_layer(shape, rng)
+    layer = ab.Layer(tensors, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rms_eps, shape.rope_theta)
+    cache = ab.KVCache([p + 1 for p in b.P], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda")
+    for i, P in enumerate(b.P):
+        k_, v_ = wl.make_random_kv(rng, f"kv{i}", P, shape)
+        o = int(cache.seq_offset[i])
+        cache.k[o:o + P] = k_
+        cache.v[o:o + P] = v_
+        cache.seq_len[i] = P
+    x = wl.make_hidden(rng, "x", b.T, shape)
+    out = ab.alora_decode(ctx, layer, cache, x, b.k, b.adapter)
+    torch.cuda.synchronize()
+    host = {k_: (v.cpu() if isinstance(v, torch.Tensor) else v) for k_, v in tensors.items()}
+    L = H.oracle_layer(host, shape)
+    for i in (0, 1, 2, 3, 31, 63):
+        kc, vc = cache.rows(i, 0, b.P[i])
+        o, kn, vn = orc.ref_cached(L, H.f64(kc).reshape(b.P[i], -1), H.f64(vc).reshape(b.P[i], -1), b.P[i],
+                                   H.f64(x[i:i + 1]), b.k[i], b.adapter[i], "bf16")
+        assert H.rel_err(H.f64(out[i:i + 1]), o) <= H.TOL["bf16"]
+        gk, gv = cache.rows(i, b.P[i], b.P[i] + 1)
+        assert H.rel_err(H.f64(gk).reshape(1, -1), kn) <= H.TOL["bf16"]
+        assert int(cache.seq_len[i]) == b.P[i] + 1
+
+
+def test_config5_one_layer_full_length(ab, ctx):
+    """The first-token shape on one layer: 128 adapted tokens over a 32768-token cache, rank 64."""
+    b = wl.config5()
+    shape = dataclasses.replace(b.shape, intermediate=0)
+    case = H.make_case(shape, b.P, b.S, b.k, b.adapter, b.seed, prefix="random")
+    check_case(ab, ctx, case)
