@@ -21,9 +21,9 @@ namespace {
 constexpr int N_SLOTS = 8;
 
 struct MetaSlot {
-  SeqMeta *host = nullptr;   // pinned
-  SeqMeta *dev = nullptr;
-  int cap = 0;
+  char *host = nullptr;      // pinned
+  char *dev = nullptr;
+  size_t cap = 0;            // bytes
   hipEvent_t ev = nullptr;
   bool in_flight = false;
 };
@@ -141,20 +141,20 @@ alora_status ensure_rope(alora_ctx *ctx, int n_pos, int half, float theta, hipSt
   return ALORA_OK;
 }
 
-alora_status acquire_slot(alora_ctx *ctx, int n_seqs, MetaSlot **out) {
+alora_status acquire_slot(alora_ctx *ctx, size_t bytes, MetaSlot **out) {
   MetaSlot &sl = ctx->slots[ctx->next_slot];
   ctx->next_slot = (ctx->next_slot + 1) % N_SLOTS;
   if (sl.in_flight) {
     HIP_TRY(ctx, hipEventSynchronize(sl.ev));
     sl.in_flight = false;
   }
-  if (sl.cap < n_seqs) {
+  if (sl.cap < bytes) {
     if (sl.host) HIP_TRY(ctx, hipHostFree(sl.host));
     if (sl.dev) HIP_TRY(ctx, hipFree(sl.dev));
     sl.host = nullptr; sl.dev = nullptr; sl.cap = 0;
-    int cap = std::max(64, n_seqs + n_seqs / 2);
-    HIP_TRY(ctx, hipHostMalloc((void **)&sl.host, (size_t)cap * sizeof(SeqMeta), hipHostMallocDefault));
-    HIP_TRY(ctx, hipMalloc((void **)&sl.dev, (size_t)cap * sizeof(SeqMeta)));
+    size_t cap = std::max<size_t>(4096, bytes + bytes / 2);
+    HIP_TRY(ctx, hipHostMalloc((void **)&sl.host, cap, hipHostMallocDefault));
+    HIP_TRY(ctx, hipMalloc((void **)&sl.dev, cap));
     sl.cap = cap;
   }
   if (!sl.ev) HIP_TRY(ctx, hipEventCreateWithFlags(&sl.ev, hipEventDisableTiming));
@@ -253,6 +253,9 @@ struct Workspace {
   size_t bytes;
   bool mfma = false;
   int k_splits = 1;
+  bool attn_mfma = false;
+  const int2 *qtiles = nullptr;
+  int n_qtiles = 0;
 };
 
 int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
@@ -328,12 +331,25 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
     launch_rope_append<T>(w.Y, mfma ? w.k_splits : 1, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k,
                           (T *)cache->v, s);
   }
+  const bool direct = w.attn_mfma && std::is_same<T, bf16>::value && n_splits == 1;
   {
     ProfScope p(ctx, decode ? K_ATTN_DECODE : K_ATTN_PREFILL, s);
-    launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
-                         n_splits, w.partials, s);
+    if (w.attn_mfma && std::is_same<T, bf16>::value) {
+      AttnArgs a{};
+      a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
+      a.seqs = seqs_dev; a.qtiles = w.qtiles;
+      a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
+      a.n_splits = n_splits;
+      a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
+      a.partials = direct ? nullptr : w.partials;
+      a.out = direct ? (bf16 *)out : nullptr;
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, s);
+    } else {
+      launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
+                           n_splits, w.partials, s);
+    }
   }
-  {
+  if (!direct) {
     ProfScope p(ctx, K_ATTN_MERGE, s);
     launch_attn_merge<T>(w.partials, L, pl.T, n_splits, out, s);
   }
@@ -423,7 +439,19 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   hipStream_t s = (hipStream_t)stream;
   const size_t esz = layers[0].dtype == ALORA_BF16 ? 2 : 4;
-  const int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
+  const bool attn_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && !decode &&
+                         attn_prefill_mfma_supported(L);
+  int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
+  if (attn_mfma && ctx->opt_splits == 0) {
+    // one workgroup per (q-tile, kv head, split): aim at one full wave of workgroups over the chip,
+    // with at least 256 keys per split
+    const int tq = attn_prefill_mfma_tokens_per_tile(L);
+    int64_t tiles = 0;
+    for (int b = 0; b < B; ++b) tiles += (pl.seqs[b].n_new + tq - 1) / tq;
+    tiles *= L.n_kv_heads;
+    int want = (int)std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1));
+    n_splits = std::max(1, std::min(std::min(want, 16), std::max(1, pl.max_len / 256)));
+  }
   // kernel family: MFMA for bf16 shapes it covers, plain otherwise
   const bool mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && L.d % 64 == 0 &&
                     (L.n_adapters == 0 || (L.rank % 16 == 0 && L.n_adapters <= 64)) && L.n_q % 32 == 0 &&
@@ -434,28 +462,42 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (st != ALORA_OK) return st;
   st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
   if (st != ALORA_OK) return st;
+  // staged metadata: per-sequence records, then the q-tile list of the MFMA attention kernel
+  std::vector<int2> qtiles;
+  if (attn_mfma) {
+    const int tq = attn_prefill_mfma_tokens_per_tile(L);
+    for (int b = 0; b < B; ++b)
+      for (int q0 = 0; q0 < pl.seqs[b].n_new; q0 += tq) qtiles.push_back(make_int2(b, q0));
+  }
+  const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
+  const size_t meta_bytes = seq_bytes + qtiles.size() * sizeof(int2);
   MetaSlot *slot = nullptr;
-  st = acquire_slot(ctx, B, &slot);
+  st = acquire_slot(ctx, meta_bytes, &slot);
   if (st != ALORA_OK) return st;
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
-  HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, (size_t)B * sizeof(SeqMeta), hipMemcpyHostToDevice, s));
+  if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(int2));
+  HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
+  const SeqMeta *seqs_dev = (const SeqMeta *)slot->dev;
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
   w.mfma = mfma;
   w.k_splits = k_splits;
+  w.attn_mfma = attn_mfma;
+  w.qtiles = (const int2 *)(slot->dev + seq_bytes);
+  w.n_qtiles = (int)qtiles.size();
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {
-    if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, slot->dev, w, true, n_splits, decode, (bf16 *)out, s);
-    else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, slot->dev, w, true, n_splits, decode, (float *)out, s);
+    if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, seqs_dev, w, true, n_splits, decode, (bf16 *)out, s);
+    else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, seqs_dev, w, true, n_splits, decode, (float *)out, s);
   } else {
     const void *cur = x;
     for (int l = 0; l < n_layers; ++l) {
       void *nxt = (l == n_layers - 1) ? out : ((l & 1) ? w.xb : w.xa);
       if (bf) {
-        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, slot->dev, w, l == 0, n_splits, false, (bf16 *)w.attn, s);
+        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, seqs_dev, w, l == 0, n_splits, false, (bf16 *)w.attn, s);
         layer_tail<bf16>(ctx, &layers[l], L, (const bf16 *)cur, w, pl.T, (bf16 *)nxt, s);
       } else {
-        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, slot->dev, w, l == 0, n_splits, false, (float *)w.attn, s);
+        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, seqs_dev, w, l == 0, n_splits, false, (float *)w.attn, s);
         layer_tail<float>(ctx, &layers[l], L, (const float *)cur, w, pl.T, (float *)nxt, s);
       }
       cur = nxt;

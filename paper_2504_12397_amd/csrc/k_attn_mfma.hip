@@ -1,0 +1,292 @@
+// Flash-style causal attention of new queries over [cached prefix ; new suffix] (Eq.1 with the
+// causal mask, rows as in Eq.6) with bf16 MFMA on gfx950, head_dim 128, grouped-query sharing.
+//
+// Work item: one workgroup = (q-tile of 256/G tokens of one sequence, kv head, key split).
+// The G query heads of the kv group are packed next to the tokens into 256 "packed rows"
+// (packed row = token * G + head), 64 per wave, so every K/V tile fetched from HBM and read
+// from LDS serves all heads of the group.
+//
+// Per 64-key tile, each wave computes S^T = K Q^T (keys are MFMA rows, packed query rows are
+// MFMA columns).  In that orientation a lane owns one query row (column l%32) in every
+// accumulator register, so the online-softmax state (running max, running sum, rescale
+// factor) is one scalar per lane and the probabilities can be fed straight back, from
+// registers, as the B operand of O^T += V^T P^T.  The only data that needs a transpose is V:
+// the loader threads turn 4 keys x 8 columns into 8 columns x 4 keys in registers (byte
+// permutes) and store V^T tiles to LDS in the exact k-order the P registers have.
+//
+// K tile in LDS: [64 keys][16 chunks of 16 B], chunk c of key r at c ^ (r & 15).
+// V^T tile in LDS: [128 columns][8 chunks of 16 B]; chunk (2*s4 + kh) of a column holds keys
+//   32*(s4/2) + 16*(s4%2) + {4kh..4kh+3, 8+4kh..8+4kh+3}  (s4 = k-step 0..3, kh = lane/32),
+//   stored at chunk ^ (column & 7).
+#include "mfma_kernels.h"
+
+namespace alora {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bf16x8 u4_as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  bf16x2 p;
+  p[0] = (bf16)a;
+  p[1] = (bf16)b;
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+constexpr int ATT_BN = 64;        // keys per tile
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+template <int G>
+__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
+  constexpr int H = 128;
+  constexpr int TQ = 256 / G;
+  __shared__ u32x4 Ks[2][ATT_BN * 16];
+  __shared__ u32x4 Vs[2][H * 8];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, kh = lane >> 5;
+  const int2 qt = a.qtiles[blockIdx.x];
+  const int g = blockIdx.y, split = blockIdx.z;
+  const SeqMeta sm = a.seqs[qt.x];
+  const int q0 = qt.y;
+  const int ntok = min(TQ, sm.n_new - q0);
+  const int row0 = sm.row_start + q0;
+  const int n_visible = sm.P + q0 + ntok;            // keys visible to the tile's last token
+  int chunk = (n_visible + a.n_splits - 1) / a.n_splits;
+  chunk = (chunk + ATT_BN - 1) & ~(ATT_BN - 1);
+  const int kbeg = split * chunk, kend = min(n_visible, kbeg + chunk);
+  const int ntiles = kend > kbeg ? (kend - kbeg + ATT_BN - 1) / ATT_BN : 0;
+  const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
+  const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
+  const int first_pos = sm.P + q0;                   // smallest query position in the tile
+
+  // ---- this wave's queries as B operands: 2 column blocks x 8 k-steps ---------------------
+  u32x4 qf[2][8];
+  int pos[2], tok[2], head[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int pr = wave * 64 + nb * 32 + l32;
+    tok[nb] = pr / G;
+    head[nb] = g * G + pr % G;
+    const int tc = min(tok[nb], ntok - 1);
+    pos[nb] = tok[nb] < ntok ? first_pos + tok[nb] : -1;       // -1: padding row, sees nothing
+    const bf16 *qp = a.Q + (int64_t)(row0 + tc) * a.n_q + head[nb] * H + kh * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const u32x4 *>(qp + ks * 16);
+  }
+
+  f32x16 o[4][2];
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[cb][nb][v] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  const float c_scale = a.sm_scale * LOG2E;
+
+  // ---- tile loader: K rows as they are, V transposed in registers -------------------------
+  u32x4 rk[4], rv[4];
+  const int v_qd = tid >> 4, v_hc = tid & 15;
+  auto load_tile = [&](int t) {
+    const int k0 = kbeg + t * ATT_BN;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int q = tid + i * 256, key = q >> 4, c = q & 15;
+      const int kidx = min(k0 + key, n_visible - 1);
+      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kidx * a.n_kv + c * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
+      rv[i] = *reinterpret_cast<const u32x4 *>(Vp + (int64_t)kidx * a.n_kv + v_hc * 8);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int q = tid + i * 256, key = q >> 4, c = q & 15;
+      Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
+    }
+    // V: this thread holds keys 4*v_qd..+3 for columns 8*v_hc..+7
+    const int grp16 = v_qd >> 2, qi = v_qd & 3;
+    const int vkh = qi & 1, halfpos = qi >> 1;
+    const int vchunk = grp16 * 2 + vkh;
+    const u32x4 w0 = rv[0], w1 = rv[1], w2 = rv[2], w3 = rv[3];
+    u32x2 *vs2 = reinterpret_cast<u32x2 *>(Vs[buf]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // even column 2j: low halves; odd column 2j+1: high halves
+      u32x2 ev, od;
+      ev.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x05040100u);
+      ev.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x05040100u);
+      od.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x07060302u);
+      od.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x07060302u);
+      const int c0 = v_hc * 8 + 2 * j, c1 = c0 + 1;
+      vs2[(c0 * 8 + (vchunk ^ (c0 & 7))) * 2 + halfpos] = ev;
+      vs2[(c1 * 8 + (vchunk ^ (c1 & 7))) * 2 + halfpos] = od;
+    }
+  };
+
+  if (ntiles > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    const int buf = t & 1;
+    const int k0 = kbeg + t * ATT_BN;
+    if (t + 1 < ntiles) load_tile(t + 1);
+
+    const bool need_mask = (k0 + ATT_BN - 1 > first_pos) || (k0 + ATT_BN > kend);
+    // the 64-key tile is consumed as two 32-key blocks, each with its own softmax update, so that
+    // only one block of scores and probabilities is live at a time
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      // ---- S^T = K Q^T ----------------------------------------------------------------------
+      f32x16 s[2];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const int key = kb * 32 + l32, c = 2 * ks + kh;
+        const bf16x8 kf = u4_as_bf16x8(Ks[buf][key * 16 + (c ^ (key & 15))]);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+          s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, u4_as_bf16x8(qf[nb][ks]), s[nb], 0, 0, 0);
+      }
+
+      // ---- causal mask: only tiles that reach past the first query position or the split end --
+      if (need_mask) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = k0 + kb * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
+            if (key > pos[nb] || key >= kend) s[nb][v] = -INFINITY;
+          }
+      }
+
+      // ---- online softmax (log2 domain), one query row per lane -------------------------------
+      u32x4 pf[2][2];      // [half][nb]: 8 probabilities as bf16
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[nb], mx * c_scale);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_safe);
+        m_run[nb] = m_new;
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float pv = __builtin_amdgcn_exp2f(fmaf(s[nb][v], c_scale, -m_safe));
+          s[nb][v] = pv;
+          rs += pv;
+        }
+        l_run[nb] = l_run[nb] * alpha + rs;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[cb][nb][v] *= alpha;
+        }
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const int e = 8 * hf;
+          pf[hf][nb] = u32x4{pack_bf16x2(s[nb][e], s[nb][e + 1]), pack_bf16x2(s[nb][e + 2], s[nb][e + 3]),
+                             pack_bf16x2(s[nb][e + 4], s[nb][e + 5]), pack_bf16x2(s[nb][e + 6], s[nb][e + 7])};
+        }
+      }
+
+      // ---- O^T += V^T P^T ---------------------------------------------------------------------
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int s4 = kb * 2 + hf;
+        bf16x8 vf[4];
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+          const int col = cb * 32 + l32, c = 2 * s4 + kh;
+          vf[cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ (col & 7))]);
+        }
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb)
+            o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[cb], u4_as_bf16x8(pf[hf][nb]), o[cb][nb], 0, 0, 0);
+      }
+    }
+
+    if (t + 1 < ntiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- write the partial (or final) result ----------------------------------------------------
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 32, 64);
+    if (tok[nb] >= ntok) continue;
+    const int64_t row = row0 + tok[nb];
+    if (a.out != nullptr) {
+      const float inv = 1.0f / l_tot;
+      bf16 *op = a.out + row * a.n_q + head[nb] * H;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const int col = cb * 32 + 8 * v4 + 4 * kh;
+          uint2 w;
+          w.x = pack_bf16x2(o[cb][nb][4 * v4] * inv, o[cb][nb][4 * v4 + 1] * inv);
+          w.y = pack_bf16x2(o[cb][nb][4 * v4 + 2] * inv, o[cb][nb][4 * v4 + 3] * inv);
+          *reinterpret_cast<uint2 *>(op + col) = w;
+        }
+    } else {
+      float *pp = a.partials + ((row * a.n_q_heads + head[nb]) * a.n_splits + split) * (H + 2);
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const int col = cb * 32 + 8 * v4 + 4 * kh;
+          // (H + 2) floats per record keeps 8-byte, not 16-byte, alignment
+          *reinterpret_cast<float2 *>(pp + col) = make_float2(o[cb][nb][4 * v4], o[cb][nb][4 * v4 + 1]);
+          *reinterpret_cast<float2 *>(pp + col + 2) = make_float2(o[cb][nb][4 * v4 + 2], o[cb][nb][4 * v4 + 3]);
+        }
+      if (kh == 0) {
+        pp[H] = m_run[nb] == -INFINITY ? -INFINITY : m_run[nb] * LN2;    // natural-log domain
+        pp[H + 1] = l_tot;
+      }
+    }
+  }
+}
+
+bool attn_prefill_mfma_supported(const LayerDims &L) {
+  const int G = L.n_q_heads / L.n_kv_heads;
+  return L.head_dim == 128 && (G == 1 || G == 2 || G == 4 || G == 8);
+}
+
+int attn_prefill_mfma_tokens_per_tile(const LayerDims &L) { return 256 / (L.n_q_heads / L.n_kv_heads); }
+
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_qtiles, int G, hipStream_t s) {
+  if (n_qtiles == 0) return;
+  dim3 grid(n_qtiles, a.n_kv_heads, a.n_splits);
+  switch (G) {
+    case 1: hipLaunchKernelGGL(attn_prefill_mfma_kernel<1>, grid, dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL(attn_prefill_mfma_kernel<2>, grid, dim3(256), 0, s, a); break;
+    case 4: hipLaunchKernelGGL(attn_prefill_mfma_kernel<4>, grid, dim3(256), 0, s, a); break;
+    case 8: hipLaunchKernelGGL(attn_prefill_mfma_kernel<8>, grid, dim3(256), 0, s, a); break;
+    default: break;
+  }
+}
+
+}  // namespace alora

@@ -9,8 +9,8 @@
 //   (8 chunks of 16 B); chunk c of row r sits at position c ^ (r & 7), so both the row-major
 //   stores and the 32-rows-one-chunk operand reads are bank-conflict free.
 // * Gated low-rank term of Eq.6 as extra k-steps BEFORE the main loop: for every adapter present
-//   in the row tile, A-operand = t = s*A_a x (bf16, zero for rows that are not adapted by a),
-//   B-operand = B_{a,p}.  Rows that are not adapted accumulate exact zeros into zero
+//   in the row tile, A-operand = t = s*A_a x (as a bf16 pair hi + lo, zero for rows that are not
+//   adapted by a), B-operand = B_{a,p} (twice).  Rows that are not adapted accumulate exact zeros into zero
 //   accumulators, so their results are bitwise what a base-only call gives.
 // * Epilogues: fp32 partial sums (split-K capable, summed later in a fixed order), bf16 store
 //   (+ residual), SwiGLU (gate and up columns interleaved in 32-column blocks inside the tile).
@@ -72,7 +72,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     while (present) {
       const int a = __builtin_ctzll(present);
       present &= present - 1;
-      for (int ks = 0; ks < r; ks += 16) {
+      for (int ks2 = 0; ks2 < 2 * r; ks2 += 16) {     // k runs over [t_hi | t_lo] against [B | B]
+        const int ks = ks2 < r ? ks2 : ks2 - r;
         bf16x8 bfrag[TN];
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
             int colb = n0 + wn0 + ni * 32;
             int p = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
             uint4 u = make_uint4(0, 0, 0, 0);
-            if (a_row[mi] == a) u = *reinterpret_cast<const uint4 *>(g.tlow + ((int64_t)row * 3 + p) * r + ks + lhi * 8);
+            if (a_row[mi] == a)
+              u = *reinterpret_cast<const uint4 *>(g.tlow + ((int64_t)row * 3 + p) * 2 * r + ks2 + lhi * 8);
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(u), bfrag[ni], acc[mi][ni], 0, 0, 0);
           }
         }

@@ -96,8 +96,18 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x,
     for (int c = lane; c < d; c += 64) acc += to_f32<T>(ar[c]) * xs[c];
     acc = wave_sum(acc);
     if (lane == 0) {
-      if (tlow16) tlow16[(int64_t)row * 3 * rank + j] = (bf16)(scale * acc);
-      else tlow[(int64_t)row * 3 * rank + j] = scale * acc;
+      const float t = scale * acc;
+      if (tlow16) {
+        // bf16 pair (hi, lo) with hi + lo = t to ~2^-17: the MFMA path feeds both as extra k-steps,
+        // so the low-rank term keeps fp32-level accuracy.  Layout [row][p][hi|lo][rank].
+        const int p = j / rank, jj = j % rank;
+        const bf16 hi = (bf16)t;
+        bf16 *dst = tlow16 + (((int64_t)row * 3 + p) * 2) * rank + jj;
+        dst[0] = hi;
+        dst[rank] = (bf16)(t - (float)hi);
+      } else {
+        tlow[(int64_t)row * 3 * rank + j] = t;
+      }
     }
   }
 }

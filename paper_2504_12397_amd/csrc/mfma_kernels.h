@@ -17,12 +17,28 @@ struct GemmArgs {
   bf16 *C; int ldc;            // BF16 / SWIGLU output
   const bf16 *R;               // BF16: optional residual [M, ldc]
   // gated low-rank term (Eq.6); tlow == nullptr switches it off
-  const bf16 *tlow;            // [M, 3, rank]: s_a * A_{a,p} x for adapted rows
+  const bf16 *tlow;            // [M, 3, 2, rank]: s_a * A_{a,p} x for adapted rows as bf16 (hi, lo) pairs
   int rank;
   const bf16 *Bq, *Bk, *Bv;
   int n_q, n_kv;
   const int32_t *row_adapter;  // [M]: adapter id of adapted rows, -1 otherwise
 };
+
+// Prefill attention (Eq.1 with the causal mask) over the pool cache.
+struct AttnArgs {
+  const bf16 *Q;            // [T, n_q] rotated queries of the new rows
+  const bf16 *K, *V;        // pool [tokens, n_kv]
+  const SeqMeta *seqs;
+  const int2 *qtiles;       // per q-tile: (sequence, first new-token index of the tile)
+  int n_q, n_kv, n_q_heads, n_kv_heads;
+  int n_splits;             // key splits (grid.z)
+  float sm_scale;           // 1 / sqrt(head_dim)
+  float *partials;          // [T, n_q_heads, n_splits, head_dim + 2] (acc, max, sum), used when out == nullptr
+  bf16 *out;                // [T, n_q] final output, only with n_splits == 1
+};
+bool attn_prefill_mfma_supported(const LayerDims &L);
+int attn_prefill_mfma_tokens_per_tile(const LayerDims &L);
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_qtiles, int G, hipStream_t s);
 
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
