@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-lora", action="store_true", help="c5 only: skip the k=0 recompute baseline")
     ap.add_argument("--plain", action="store_true", help="force the plain fp32-FMA kernels")
+    ap.add_argument("--opt", action="append", default=[], help="library option key=value (repeatable)")
     return ap.parse_args()
 
 
@@ -116,6 +117,9 @@ def main():
     ctx = ab.Context(0)
     if args.plain:
         ctx.set_option("kernels", 1)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        ctx.set_option(key, int(val))
     rng = wl.Rng(batch.seed, dev)
 
     def make_set(tag):

@@ -57,6 +57,7 @@ struct alora_ctx {
   int next_slot = 0;
   int opt_kernels = 0;
   int opt_splits = 0;
+  int opt_gemm_splits = 0;
   int n_cu = 256;
 };
 
@@ -254,6 +255,7 @@ struct Workspace {
   bool mfma = false;
   int k_splits = 1;
   bool attn_mfma = false;
+  bool decode_mfma = false;
   const int2 *qtiles = nullptr;
   int n_qtiles = 0;
 };
@@ -302,9 +304,19 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
   const bool mfma = w.mfma && std::is_same<T, bf16>::value;
   {
     ProfScope p(ctx, K_PREP, s);
-    launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
-                        pl.any_adapter ? L.rank : 0, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr,
-                        w.rm, s);
+    const int rank_used = pl.any_adapter ? L.rank : 0;
+    if (mfma && prep_rows_mfma_supported(L.d, rank_used)) {
+      PrepArgs pa{};
+      pa.x = (const bf16 *)x; pa.gain = (const bf16 *)ly->rms_gain; pa.eps = ly->rms_eps;
+      pa.T = pl.T; pa.d = L.d; pa.seqs = seqs_dev; pa.n_seqs = pl.B;
+      pa.A = rank_used ? (const bf16 *)ly->A : nullptr; pa.rank = rank_used;
+      pa.write_meta = write_meta ? 1 : 0;
+      pa.xh = (bf16 *)w.xh; pa.tlow16 = (bf16 *)w.tlow; pa.rm = w.rm;
+      launch_prep_rows_mfma(pa, s);
+    } else {
+      launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
+                          rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
+    }
   }
   {
     ProfScope p(ctx, K_QKV, s);
@@ -344,6 +356,15 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.partials = direct ? nullptr : w.partials;
       a.out = direct ? (bf16 *)out : nullptr;
       launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, s);
+    } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
+      DecodeArgs a{};
+      a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
+      a.seqs = seqs_dev; a.rm = w.rm;
+      a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
+      a.n_splits = n_splits;
+      a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
+      a.partials = w.partials;
+      launch_attn_decode_mfma(a, pl.T, s);
     } else {
       launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
                            n_splits, w.partials, s);
@@ -378,8 +399,15 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
   }
   {
     ProfScope p(ctx, K_MLPNORM, s);
-    launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
-                        (const T *)nullptr, 0, false, (T *)w.hn, nullptr, nullptr, none, s);
+    if (mfma && prep_rows_mfma_supported(L.d, 0)) {
+      PrepArgs pa{};
+      pa.x = (const bf16 *)w.h1; pa.gain = (const bf16 *)ly->rms2_gain; pa.eps = ly->rms_eps;
+      pa.T = T_rows; pa.d = L.d; pa.xh = (bf16 *)w.hn; pa.rm = none;
+      launch_prep_rows_mfma(pa, s);
+    } else {
+      launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
+                          (const T *)nullptr, 0, false, (T *)w.hn, nullptr, nullptr, none, s);
+    }
   }
   if (mfma) {   // act = silu(hn W_gate^T) * (hn W_up^T) in one pass
     ProfScope p(ctx, K_GATEUP, s);
@@ -442,6 +470,14 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   const bool attn_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && !decode &&
                          attn_prefill_mfma_supported(L);
   int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
+  const bool decode_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && decode &&
+                           attn_decode_mfma_supported(L);
+  if (decode_mfma && ctx->opt_splits == 0) {
+    // (row, kv head, split) workgroups of four waves: several per compute unit, >= 1024 keys each
+    const int64_t items = (int64_t)pl.T * L.n_kv_heads;
+    int want = (int)std::max<int64_t>(1, (8 * (int64_t)ctx->n_cu + items - 1) / items);
+    n_splits = std::max(1, std::min(std::min(want, 64), std::max(1, pl.max_len / 1024)));
+  }
   if (attn_mfma && ctx->opt_splits == 0) {
     // one workgroup per (q-tile, kv head, split): aim at one full wave of workgroups over the chip,
     // with at least 256 keys per split
@@ -456,7 +492,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   const bool mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && L.d % 64 == 0 &&
                     (L.n_adapters == 0 || (L.rank % 16 == 0 && L.n_adapters <= 64)) && L.n_q % 32 == 0 &&
                     L.n_kv % 32 == 0 && (!stack || (layers[0].intermediate % 64 == 0 && L.n_q % 64 == 0));
-  const int k_splits = mfma ? gemm_mfma_pick_splits(pl.T, L.n_qkv, L.d, ctx->n_cu) : 1;
+  int k_splits = mfma ? gemm_mfma_pick_splits(pl.T, L.n_qkv, L.d, ctx->n_cu) : 1;
+  if (mfma && ctx->opt_gemm_splits > 0 && L.d % (64 * ctx->opt_gemm_splits) == 0) k_splits = ctx->opt_gemm_splits;
   Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
   st = ensure_workspace(ctx, probe.bytes);
   if (st != ALORA_OK) return st;
@@ -482,6 +519,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.mfma = mfma;
   w.k_splits = k_splits;
   w.attn_mfma = attn_mfma;
+  w.decode_mfma = decode_mfma;
   w.qtiles = (const int2 *)(slot->dev + seq_bytes);
   w.n_qtiles = (int)qtiles.size();
 
@@ -592,6 +630,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "kv_splits")) {
     if (value < 0 || value > 256) return fail(ctx, ALORA_EINVAL, "kv_splits must be in [0, 256]");
     ctx->opt_splits = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "gemm_splits")) {
+    if (value < 0 || value > 64) return fail(ctx, ALORA_EINVAL, "gemm_splits must be in [0, 64]");
+    ctx->opt_gemm_splits = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "profile")) {

@@ -17,7 +17,7 @@
 // K tile in LDS: [64 keys][16 chunks of 16 B], chunk c of key r at c ^ (r & 15).
 // V^T tile in LDS: [128 columns][8 chunks of 16 B]; chunk (2*s4 + kh) of a column holds keys
 //   32*(s4/2) + 16*(s4%2) + {4kh..4kh+3, 8+4kh..8+4kh+3}  (s4 = k-step 0..3, kh = lane/32),
-//   stored at chunk ^ (column & 7).
+//   stored at chunk ^ ((column ^ column/8) & 7).
 #include "mfma_kernels.h"
 
 namespace alora {
@@ -37,6 +37,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   p[1] = (bf16)b;
   return __builtin_bit_cast(uint32_t, p);
 }
+
+// chunk swizzle of the V^T tile: mixes the low column bits (operand reads walk consecutive
+// columns) with the next three (the transposing stores walk columns 8 apart)
+__device__ __forceinline__ int v_swz(int col) { return (col ^ (col >> 3)) & 7; }
 
 constexpr int ATT_BN = 64;        // keys per tile
 constexpr float LOG2E = 1.4426950408889634f;
@@ -129,8 +133,8 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
       od.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x07060302u);
       od.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x07060302u);
       const int c0 = v_hc * 8 + 2 * j, c1 = c0 + 1;
-      vs2[(c0 * 8 + (vchunk ^ (c0 & 7))) * 2 + halfpos] = ev;
-      vs2[(c1 * 8 + (vchunk ^ (c1 & 7))) * 2 + halfpos] = od;
+      vs2[(c0 * 8 + (vchunk ^ v_swz(c0))) * 2 + halfpos] = ev;
+      vs2[(c1 * 8 + (vchunk ^ v_swz(c1))) * 2 + halfpos] = od;
     }
   };
 
@@ -218,7 +222,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
           const int col = cb * 32 + l32, c = 2 * s4 + kh;
-          vf[cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ (col & 7))]);
+          vf[cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
         }
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)

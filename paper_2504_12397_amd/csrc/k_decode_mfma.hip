@@ -1,0 +1,191 @@
+// Decode attention (Eq.4: one new query per sequence over its whole cache), memory-bound:
+// every cached key/value byte is read exactly once and everything else is kept out of the way.
+//
+// Work item: one workgroup = (sequence, kv head, key split); its four waves take disjoint key
+// ranges and never synchronise until the final merge.  A wave consumes 32 keys per step:
+//   * K rows go from global memory straight into the A operand of v_mfma_f32_16x16x32_bf16
+//     (lane l: key l%16, head-dim slice 8*(l/16)..+7 of the current 32-wide k-step), the G query
+//     heads of the group are the (zero padded) 16 B-operand columns: S^T[key][head].
+//   * Accumulator register v of lane l is S^T[key 4*(l/16)+v][head l%16]: a lane owns one head, so
+//     max / sum / rescale are per-lane scalars, and the two key blocks' probabilities
+//     p[16u + 4*(l/16) + v] are, as they sit, the B operand (k = 32 keys) of O^T += V^T P^T.
+//   * V rows are loaded as 8 columns x 1 key per lane (16 B) for exactly those 8 keys and
+//     transposed inside the lane with byte permutes: MFMA number c uses column 8*i + c of lane
+//     row i, so O^T_c[i][head] = O[column 8*i + c][head].  No LDS, no cross-lane traffic.
+// Partials (acc, max, sum) per (row, head, split) are merged by the log-sum-exp merge kernel.
+#include "mfma_kernels.h"
+
+namespace alora {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t dec_pack2(float a, float b) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  bf16x2 p;
+  p[0] = (bf16)a;
+  p[1] = (bf16)b;
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+constexpr float DEC_LOG2E = 1.4426950408889634f;
+constexpr float DEC_LN2 = 0.6931471805599453f;
+
+__global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
+  constexpr int H = 128;
+  __shared__ float s_o[4][16][H + 2];      // per wave: [head][acc..., m, l]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, kg = lane >> 4;           // j: head column / key row / V row; kg: k group
+  const int row = blockIdx.x, g = blockIdx.y, split = blockIdx.z;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const SeqMeta sm = a.seqs[a.rm.seq[row]];
+  const int n_keys = a.rm.pos[row] + 1;
+  // keys of this (split, wave): contiguous, multiple of 32
+  const int n_parts = a.n_splits * 4;
+  int per = (n_keys + n_parts - 1) / n_parts;
+  per = (per + 31) & ~31;
+  const int kbeg = (split * 4 + wave) * per;
+  const int kend = min(n_keys, kbeg + per);
+  const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
+  const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
+
+  // queries: B operand columns = heads of the group (zero for padding columns)
+  u32x4 qf[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    qf[s] = u32x4{0, 0, 0, 0};
+    if (j < G) qf[s] = *reinterpret_cast<const u32x4 *>(a.Q + (int64_t)row * a.n_q + (g * G + j) * H + 32 * s + 8 * kg);
+  }
+
+  f32x4 o[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c_scale = a.sm_scale * DEC_LOG2E;
+
+  u32x4 kr[2][4], vr[2][4];      // [key block u][k-step s] and [u][n]: key 16u + 4kg + n
+  auto load_step = [&](int k0) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int kk = min(k0 + 16 * u + j, n_keys - 1);
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        kr[u][s] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kk * a.n_kv + 32 * s + 8 * kg);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const int kv = min(k0 + 16 * u + 4 * kg + n, n_keys - 1);
+        vr[u][n] = *reinterpret_cast<const u32x4 *>(Vp + (int64_t)kv * a.n_kv + 8 * j);
+      }
+    }
+  };
+
+  if (kbeg < kend) load_step(kbeg);
+  for (int k0 = kbeg; k0 < kend; k0 += 32) {
+    // consume the registers of this step, then refill them for the next one
+    u32x4 kc[2][4], vc[2][4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) { kc[u][s] = kr[u][s]; vc[u][s] = vr[u][s]; }
+    if (k0 + 32 < kend) load_step(k0 + 32);
+
+    f32x4 sc[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      sc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[u][s]),
+                                                        __builtin_bit_cast(bf16x8, qf[s]), sc[u], 0, 0, 0);
+    }
+    if (k0 + 32 > kend) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (k0 + 16 * u + 4 * kg + v >= kend) sc[u][v] = -INFINITY;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) mx = fmaxf(mx, sc[u][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * c_scale);       // finite: every step has at least one valid key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float p[2][4], rs = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        p[u][v] = __builtin_amdgcn_exp2f(fmaf(sc[u][v], c_scale, -m_new));
+        rs += p[u][v];
+      }
+    l_run = l_run * alpha + rs;
+    const u32x4 pf = u32x4{dec_pack2(p[0][0], p[0][1]), dec_pack2(p[0][2], p[0][3]), dec_pack2(p[1][0], p[1][1]),
+                           dec_pack2(p[1][2], p[1][3])};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      // column 8*j + c of the 8 keys this lane loaded: element c of each 16-byte row
+      const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      const int w = c >> 1;
+      const u32x4 vf = u32x4{__builtin_amdgcn_perm(vc[0][1][w], vc[0][0][w], sel),
+                             __builtin_amdgcn_perm(vc[0][3][w], vc[0][2][w], sel),
+                             __builtin_amdgcn_perm(vc[1][1][w], vc[1][0][w], sel),
+                             __builtin_amdgcn_perm(vc[1][3][w], vc[1][2][w], sel)};
+      f32x4 oc = o[c];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) oc[v] *= alpha;
+      o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf),
+                                                     oc, 0, 0, 0);
+    }
+  }
+
+  // ---- merge the four waves (fixed order) and write the partial ---------------------------------
+  const float l_tot = l_run + __shfl_xor(l_run, 16, 64) + __shfl_xor(l_run, 32, 64) +
+                      __shfl_xor(__shfl_xor(l_run, 16, 64), 32, 64);
+  // o[c][v] of lane (j, kg) is O[column 8*(4*kg + v) + c][head j]
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s_o[wave][j][8 * (4 * kg + v) + c] = o[c][v];
+  if (kg == 0) { s_o[wave][j][H] = m_run; s_o[wave][j][H + 1] = l_tot; }
+  __syncthreads();
+  for (int i = tid; i < G * H; i += 256) {
+    const int hd = i / H, col = i % H;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_o[w][hd][H]);
+    float acc = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = s_o[w][hd][H];
+      const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+      acc += wgt * s_o[w][hd][col];
+      den += wgt * s_o[w][hd][H + 1];
+    }
+    float *pp = a.partials + (((int64_t)row * a.n_q_heads + g * G + hd) * a.n_splits + split) * (H + 2);
+    pp[col] = acc;
+    if (col == 0) {
+      pp[H] = (M == -INFINITY) ? -INFINITY : M * DEC_LN2;     // natural-log domain for the merge kernel
+      pp[H + 1] = den;
+    }
+  }
+}
+
+bool attn_decode_mfma_supported(const LayerDims &L) {
+  const int G = L.n_q_heads / L.n_kv_heads;
+  return L.head_dim == 128 && G <= 16;
+}
+
+void launch_attn_decode_mfma(const DecodeArgs &a, int n_rows, hipStream_t s) {
+  if (n_rows == 0) return;
+  dim3 grid(n_rows, a.n_kv_heads, a.n_splits);
+  hipLaunchKernelGGL(attn_decode_mfma_kernel, grid, dim3(256), 0, s, a);
+}
+
+}  // namespace alora

@@ -5,7 +5,7 @@
 //   the 8 consecutive k values 8*(l/32)..+7; accumulator register v of lane l is
 //   C[8*(v/4) + 4*(l/32) + v%4][l%32].
 // * Block tile BM x BN x 64, four waves, each WM x WN.  Tiles go global -> registers -> LDS with a
-//   one-tile register prefetch and two LDS buffers (one barrier per k-tile).  LDS rows are 128 B
+//   two-tile register prefetch and two LDS buffers (one barrier per k-tile).  LDS rows are 128 B
 //   (8 chunks of 16 B); chunk c of row r sits at position c ^ (r & 7), so both the row-major
 //   stores and the 32-rows-one-chunk operand reads are bank-conflict free.
 // * Gated low-rank term of Eq.6 as extra k-steps BEFORE the main loop: for every adapter present
@@ -21,7 +21,9 @@ namespace alora {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
@@ -30,14 +32,28 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   static_assert((BM / WM) * WAVES_N == 4, "four waves per block");
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
-  extern __shared__ uint4 smem[];
+  extern __shared__ u32x4 smem[];
   __shared__ unsigned long long s_present;
-  uint4 *As0 = smem, *Bs0 = smem + BM * 8, *As1 = smem + (BM + BN) * 8, *Bs1 = As1 + BM * 8;
+  u32x4 *As0 = smem, *Bs0 = smem + BM * 8, *As1 = smem + (BM + BN) * 8, *Bs1 = As1 + BM * 8;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN, split = blockIdx.z;
   const int M = g.M, N = g.N, K = g.K;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): XCD x takes the
+  // column tiles x, x+8, ... with all their row tiles and splits, so a weight tile is fetched
+  // into one L2 only.  Few row tiles (weight streaming): row tile fastest, the row tiles that
+  // share a weight tile run together.  Many row tiles: column tile fastest.
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int per_xcd_n = (tiles_n + 7) / 8;
+  const int xcd = blockIdx.x & 7;
+  int q = blockIdx.x >> 3;
+  int tm, nl;
+  if (tiles_m <= 4) { tm = q % tiles_m; q /= tiles_m; nl = q % per_xcd_n; q /= per_xcd_n; }
+  else { nl = q % per_xcd_n; q /= per_xcd_n; tm = q % tiles_m; q /= tiles_m; }
+  const int split = q;
+  const int tn = xcd + 8 * nl;
+  if (tn >= tiles_n) return;
+  const int m0 = tm * BM, n0 = tn * BN;
   const int k_len = K / g.k_splits, k_beg = split * k_len, nk = k_len / BK;
   const int l32 = lane & 31, lhi = lane >> 5;
 
@@ -78,13 +94,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {
           int col = n0 + wn0 + ni * 32 + l32;
-          uint4 u = make_uint4(0, 0, 0, 0);
+          u32x4 u = u32x4{0, 0, 0, 0};
           if (col < N) {
             const bf16 *bp;
             if (col < g.n_q) bp = g.Bq + ((int64_t)a * g.n_q + col) * r;
             else if (col < g.n_q + g.n_kv) bp = g.Bk + ((int64_t)a * g.n_kv + (col - g.n_q)) * r;
             else bp = g.Bv + ((int64_t)a * g.n_kv + (col - g.n_q - g.n_kv)) * r;
-            u = *reinterpret_cast<const uint4 *>(bp + ks + lhi * 8);
+            u = *reinterpret_cast<const u32x4 *>(bp + ks + lhi * 8);
           }
           bfrag[ni] = as_bf16x8(u);
         }
@@ -96,9 +112,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
             // the section (q, k or v) of this 32-column block selects which t to use
             int colb = n0 + wn0 + ni * 32;
             int p = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
-            uint4 u = make_uint4(0, 0, 0, 0);
+            u32x4 u = u32x4{0, 0, 0, 0};
             if (a_row[mi] == a)
-              u = *reinterpret_cast<const uint4 *>(g.tlow + ((int64_t)row * 3 + p) * 2 * r + ks2 + lhi * 8);
+              u = *reinterpret_cast<const u32x4 *>(g.tlow + ((int64_t)row * 3 + p) * 2 * r + ks2 + lhi * 8);
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(u), bfrag[ni], acc[mi][ni], 0, 0, 0);
           }
         }
@@ -107,7 +123,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 
   // ---- main loop --------------------------------------------------------------------------
-  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+  // Two tiles are kept in flight in registers (R0, R1) on top of the one being consumed from
+  // LDS: with HBM latency in the microseconds, a single prefetched tile leaves the loads exposed.
+  u32x4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
   auto b_src_row = [&](int j) -> int {      // LDS row j of the B tile -> row of the weight matrix
     if (EPI == GEMM_EPI_SWIGLU) {
       int blk = j >> 5;
@@ -117,44 +135,36 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     int src = n0 + j;
     return src < N ? src : N - 1;
   };
-  auto load_tiles = [&](int kt) {
+  auto load_tiles = [&](int kt, u32x4 (&ra)[A_CHUNKS], u32x4 (&rb)[B_CHUNKS]) {
     const int k0 = k_beg + kt * BK;
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
-      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
       int gr = m0 + row;
       gr = gr < M ? gr : M - 1;
-      ra[i] = *reinterpret_cast<const uint4 *>(g.A + (int64_t)gr * g.lda + k0 + c * 8);
+      ra[i] = *reinterpret_cast<const u32x4 *>(g.A + (int64_t)gr * g.lda + k0 + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
       const bf16 *base = g.B;
       if (EPI == GEMM_EPI_SWIGLU && ((row >> 5) & 1)) base = g.B2;
-      rb[i] = *reinterpret_cast<const uint4 *>(base + (int64_t)b_src_row(row) * g.ldb + k0 + c * 8);
+      rb[i] = *reinterpret_cast<const u32x4 *>(base + (int64_t)b_src_row(row) * g.ldb + k0 + c * 8);
     }
   };
-  auto store_tiles = [&](uint4 *As, uint4 *Bs) {
+  auto store_tiles = [&](u32x4 *As, u32x4 *Bs, const u32x4 (&ra)[A_CHUNKS], const u32x4 (&rb)[B_CHUNKS]) {
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
-      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
       As[row * 8 + (c ^ (row & 7))] = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-      int q = tid + i * 256, row = q >> 3, c = q & 7;
+      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
       Bs[row * 8 + (c ^ (row & 7))] = rb[i];
     }
   };
-
-  if (nk > 0) {
-    load_tiles(0);
-    store_tiles(As0, Bs0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    uint4 *As = (kt & 1) ? As1 : As0, *Bs = (kt & 1) ? Bs1 : Bs0;
-    if (kt + 1 < nk) load_tiles(kt + 1);
+  auto compute = [&](const u32x4 *As, const u32x4 *Bs) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       bf16x8 af[TM], bfr[TN];
@@ -175,8 +185,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
         for (int ni = 0; ni < TN; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tiles((kt & 1) ? As0 : As1, (kt & 1) ? Bs0 : Bs1);
+  };
+
+  if (nk > 0) load_tiles(0, ra0, rb0);
+  if (nk > 1) load_tiles(1, ra1, rb1);
+  if (nk > 0) store_tiles(As0, Bs0, ra0, rb0);
+  __syncthreads();
+  for (int kt = 0; kt < nk;) {
+    if (kt + 2 < nk) load_tiles(kt + 2, ra0, rb0);
+    compute(As0, Bs0);
+    if (kt + 1 < nk) store_tiles(As1, Bs1, ra1, rb1);
     __syncthreads();
+    if (++kt >= nk) break;
+    if (kt + 2 < nk) load_tiles(kt + 2, ra1, rb1);
+    compute(As1, Bs1);
+    if (kt + 1 < nk) store_tiles(As0, Bs0, ra0, rb0);
+    __syncthreads();
+    ++kt;
   }
 
   // ---- epilogue ---------------------------------------------------------------------------
@@ -215,8 +240,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
 template <int BM, int BN, int WM, int WN, int EPI>
 static void launch_cfg(const GemmArgs &g, hipStream_t s) {
-  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, g.k_splits);
-  size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  dim3 grid(8 * ((tiles_n + 7) / 8) * tiles_m * g.k_splits);
+  size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(u32x4);
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI>;
   static bool configured = false;
   if (!configured) {

@@ -1,0 +1,194 @@
+// Row preparation with MFMA (bf16): per-row metadata, RMSNorm, and the low-rank down projection
+// t = s_a * A_a x_hat (Eq.6, Delta applied right to left) for 16 packed rows per workgroup.
+//
+// Eight waves split the hidden dimension; each lane owns 8 consecutive elements of one row at a
+// time, which is both the 16-byte global access and the A-operand layout of
+// v_mfma_f32_16x16x32_bf16 (lane l: row l%16, k = 8*(l/16)..+7), so the normalised row goes from
+// registers straight into the MFMA and into the x_hat store; LDS is used only for the row
+// statistics and the fixed-order sum of the eight partial accumulators.
+#include "mfma_kernels.h"
+
+namespace alora {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int PREP_ROWS = 16;
+constexpr int PREP_WAVES = 8;
+
+// NF = 16-column fragments of t this workgroup computes (0: no adapter work).  The 3*rank columns
+// of t are spread over gridDim.y workgroups so that short batches still fill the chip; group 0
+// also writes x_hat and the row metadata.
+template <int NF>
+__global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
+  __shared__ float s_rinv[PREP_ROWS];
+  __shared__ int s_adapter[PREP_ROWS];
+  __shared__ float s_scale[PREP_ROWS];
+  __shared__ unsigned long long s_present;
+  extern __shared__ float s_part[];          // [PREP_WAVES][PREP_ROWS][16 * NF]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int row0 = blockIdx.x * PREP_ROWS;
+  const int d = a.d;
+  const int col0 = blockIdx.y * 16 * NF;       // first column of t handled here
+  const bool lead = blockIdx.y == 0;
+
+  if (tid == 0) s_present = 0ull;
+  __syncthreads();
+  if (tid < PREP_ROWS) {
+    const int row = row0 + tid;
+    int adapter = -1;
+    float scale = 0.f;
+    if (row < a.T && a.seqs != nullptr) {
+      int lo = 0, hi = a.n_seqs - 1;           // last sequence whose first row is <= row
+      while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (a.seqs[mid].row_start <= row) lo = mid; else hi = mid - 1;
+      }
+      const SeqMeta sm = a.seqs[lo];
+      const int pos = sm.P + (row - sm.row_start);
+      if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
+      if (a.write_meta && lead) {
+        a.rm.seq[row] = lo;
+        a.rm.pos[row] = pos;
+        a.rm.adapter[row] = adapter;
+        a.rm.slot[row] = sm.pool_off + pos;
+      }
+    }
+    s_adapter[tid] = adapter;
+    s_scale[tid] = scale;
+    if (adapter >= 0) atomicOr(&s_present, 1ull << adapter);
+  }
+
+  // ---- pass 1: sum of squares of every row (wave w: rows 2w, 2w+1) ---------------------------
+  if (a.gain != nullptr) {
+#pragma unroll
+    for (int i = 0; i < PREP_ROWS / PREP_WAVES; ++i) {
+      const int lr = wave * (PREP_ROWS / PREP_WAVES) + i;
+      const int row = min(row0 + lr, a.T - 1);
+      const bf16 *xr = a.x + (int64_t)row * d;
+      float ssq = 0.f;
+      for (int c = lane * 8; c < d; c += 64 * 8) {
+        const bf16x8 v = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(xr + c));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ssq += f * f; }
+      }
+      ssq = wave_sum(ssq);
+      if (lane == 0) s_rinv[lr] = 1.0f / sqrtf(ssq / (float)d + a.eps);
+    }
+  } else if (tid < PREP_ROWS) {
+    s_rinv[tid] = 1.f;
+  }
+  __syncthreads();
+
+  // ---- pass 2: normalise, store x_hat, accumulate t partials over this wave's slice of d --------
+  const int row = min(row0 + r16, a.T - 1);
+  const bool row_ok = row0 + r16 < a.T;
+  const float rinv = s_rinv[r16];
+  const int my_adapter = s_adapter[r16];
+  const unsigned long long present = NF > 0 ? s_present : 0ull;
+  const int slice = d / PREP_WAVES;
+  const int k_lo = wave * slice;
+  f32x4 acc[NF > 0 ? NF : 1];
+#pragma unroll
+  for (int j = 0; j < (NF > 0 ? NF : 1); ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int rank = a.rank;
+
+  for (int k0 = k_lo; k0 < k_lo + slice; k0 += 32) {
+    const int c = k0 + kg * 8;
+    const bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(a.x + (int64_t)row * d + c));
+    bf16x8 xh;
+    if (a.gain != nullptr) {
+      const bf16x8 gv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(a.gain + c));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
+    } else {
+      xh = xv;
+    }
+    if (row_ok && lead) *reinterpret_cast<u32x4 *>(a.xh + (int64_t)row * d + c) = __builtin_bit_cast(u32x4, xh);
+    if (NF > 0) {
+      unsigned long long todo = present;
+      while (todo) {
+        const int ad = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        bf16x8 af = xh;
+        if (my_adapter != ad) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) af[e] = (bf16)0.f;
+        }
+        const bf16 *Ab = a.A + ((int64_t)ad * 3 * rank + col0) * d + c;     // rows of [3*rank, d]
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+          const bf16x8 bf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Ab + (int64_t)(j * 16 + r16) * d));
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bf, acc[j], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  if (NF > 0 && present) {
+    // accumulator register v of lane l is T[row 4*(l/16) + v][column 16*j + l%16]
+    float *mine = s_part + (size_t)wave * PREP_ROWS * 16 * NF;
+#pragma unroll
+    for (int j = 0; j < NF; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) mine[(4 * kg + v) * 16 * NF + j * 16 + r16] = acc[j][v];
+    __syncthreads();
+    const int n_out = PREP_ROWS * 16 * NF;       // 16 rows x 3*rank columns
+    for (int i = tid; i < n_out; i += 512) {
+      const int lr = i / (16 * NF), col = i % (16 * NF);
+      const int orow = row0 + lr;
+      if (orow >= a.T || s_adapter[lr] < 0) continue;
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < PREP_WAVES; ++w) t += s_part[(size_t)w * n_out + i];
+      t *= s_scale[lr];
+      const int p = (col0 + col) / rank, jj = (col0 + col) % rank;
+      const bf16 hi = (bf16)t;
+      bf16 *dst = a.tlow16 + (((int64_t)orow * 3 + p) * 2) * rank + jj;
+      dst[0] = hi;
+      dst[rank] = (bf16)(t - (float)hi);
+    }
+  }
+}
+
+bool prep_rows_mfma_supported(int d, int rank) {
+  return d % (PREP_WAVES * 32) == 0 && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
+}
+
+template <int NF>
+static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
+  const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
+  const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
+  auto kern = prep_rows_mfma_kernel<NF>;
+  static bool configured = false;
+  if (!configured && smem > 48 * 1024) {
+    (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(512), smem, s, a);
+}
+
+void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s) {
+  if (a.T == 0) return;
+  const int nf = (a.rank > 0 && a.A != nullptr) ? 3 * a.rank / 16 : 0;     // 3, 6 or 12
+  if (nf == 0) { launch_prep_nf<0>(a, 1, s); return; }
+  // fragments per workgroup: as few as it takes to reach ~256 workgroups, out of {nf, nf/2, 3, 1}
+  const int row_tiles = (a.T + PREP_ROWS - 1) / PREP_ROWS;
+  int per = nf;
+  if (row_tiles * (nf / per) < 256 && per % 2 == 0 && per > 3) per /= 2;      // 12 -> 6, 6 -> 3
+  if (row_tiles * (nf / per) < 256 && per % 2 == 0 && per > 3) per /= 2;      // 6 -> 3
+  if (row_tiles * (nf / per) < 256 && per == 3) per = 1;
+  const int groups = nf / per;
+  switch (per) {
+    case 1: launch_prep_nf<1>(a, groups, s); break;
+    case 3: launch_prep_nf<3>(a, groups, s); break;
+    case 6: launch_prep_nf<6>(a, groups, s); break;
+    case 12: launch_prep_nf<12>(a, groups, s); break;
+    default: break;
+  }
+}
+
+}  // namespace alora

@@ -24,6 +24,24 @@ struct GemmArgs {
   const int32_t *row_adapter;  // [M]: adapter id of adapted rows, -1 otherwise
 };
 
+// Row preparation: metadata, RMSNorm, t = s_a * A_a x_hat as bf16 (hi, lo) pairs.
+struct PrepArgs {
+  const bf16 *x;            // [T, d]
+  const bf16 *gain;         // [d] or nullptr
+  float eps;
+  int T, d;
+  const SeqMeta *seqs;      // nullptr: no metadata / adapters (plain RMSNorm)
+  int n_seqs;
+  const bf16 *A;            // [n_adapters, 3, rank, d] or nullptr
+  int rank;
+  int write_meta;
+  bf16 *xh;                 // [T, d]
+  bf16 *tlow16;             // [T, 3, 2, rank]
+  RowMeta rm;
+};
+bool prep_rows_mfma_supported(int d, int rank);
+void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s);
+
 // Prefill attention (Eq.1 with the causal mask) over the pool cache.
 struct AttnArgs {
   const bf16 *Q;            // [T, n_q] rotated queries of the new rows
@@ -39,6 +57,20 @@ struct AttnArgs {
 bool attn_prefill_mfma_supported(const LayerDims &L);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L);
 void launch_attn_prefill_mfma(const AttnArgs &a, int n_qtiles, int G, hipStream_t s);
+
+// Decode attention (Eq.4): one query row per sequence over its whole cache.
+struct DecodeArgs {
+  const bf16 *Q;            // [rows, n_q]
+  const bf16 *K, *V;        // pool [tokens, n_kv]
+  const SeqMeta *seqs;
+  RowMeta rm;               // seq and pos of every row
+  int n_q, n_kv, n_q_heads, n_kv_heads;
+  int n_splits;
+  float sm_scale;
+  float *partials;          // [rows, n_q_heads, n_splits, head_dim + 2]
+};
+bool attn_decode_mfma_supported(const LayerDims &L);
+void launch_attn_decode_mfma(const DecodeArgs &a, int n_rows, hipStream_t s);
 
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
