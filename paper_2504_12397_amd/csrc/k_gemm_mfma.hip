@@ -255,10 +255,11 @@ static void launch_cfg(const GemmArgs &g, hipStream_t s) {
 bool gemm_mfma_supported(int M, int N, int K) { return M > 0 && N > 0 && K >= 64 && K % 64 == 0; }
 
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
-  // split the reduction only while the grid underfills the chip, in chunks of at least 512
+  // split the reduction only while the grid underfills the chip (every split adds a pass of
+  // fp32 partial sums), in chunks of at least 512
   int tiles = ((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
-  while (tiles * s < 2 * n_cu && s < 8 && (K / (s * 2)) % 64 == 0 && K / (s * 2) >= 512) s *= 2;
+  while (4 * tiles * s < 3 * n_cu && s < 8 && (K / (s * 2)) % 64 == 0 && K / (s * 2) >= 512) s *= 2;
   return s;
 }
 

@@ -235,54 +235,53 @@ template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, 
                                       hipStream_t);
 
 // ---------------------------------------------------------------------------------------
-// rotary embedding + cache append (Eq.3: K_{1:t} = [K_{1:t-1}; K_t]).  One workgroup per row.
+// rotary embedding + cache append (Eq.3: K_{1:t} = [K_{1:t-1}; K_t]).
 // ---------------------------------------------------------------------------------------
+// One wave per (row, head slot), four slots per workgroup: slots 0..Hq-1 are query heads, then the
+// key heads, then the value heads.  Every lane handles whole rotation pairs, all loads are
+// independent.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, int n_parts,
-                                                          int64_t part_stride, LayerDims L, RowMeta rm,
-                                                          const float2 *__restrict__ table, T *__restrict__ Q,
-                                                          T *__restrict__ cacheK, T *__restrict__ cacheV) {
-  const int row = blockIdx.x, tid = threadIdx.x;
+                                                         int64_t part_stride, LayerDims L, RowMeta rm,
+                                                         const float2 *__restrict__ table, T *__restrict__ Q,
+                                                         T *__restrict__ cacheK, T *__restrict__ cacheV) {
+  const int row = blockIdx.x, slot_id = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int h = L.head_dim, h2 = h >> 1;
+  if (slot_id >= L.n_q_heads + 2 * L.n_kv_heads) return;
+  const float *y = Y + (int64_t)row * L.n_qkv;
   // Y may arrive as n_parts partial sums over the reduction axis: add them in a fixed order
   auto ysum = [&](const float *p) {
     float v = p[0];
     for (int s = 1; s < n_parts; ++s) v += p[(int64_t)s * part_stride];
     return v;
   };
-  const int h = L.head_dim, h2 = h >> 1;
-  const int pos = rm.pos[row];
-  const int64_t slot = rm.slot[row];
-  const float *y = Y + (int64_t)row * L.n_qkv;
-  const float2 *tab = table + (int64_t)pos * h2;
-  const int q_pairs = L.n_q_heads * h2, k_pairs = L.n_kv_heads * h2;
-  for (int i = tid; i < q_pairs + k_pairs; i += 256) {
-    const bool is_q = i < q_pairs;
-    const int ii = is_q ? i : i - q_pairs;
-    const int head = ii / h2, c = ii % h2;
+  if (slot_id < L.n_q_heads + L.n_kv_heads) {
+    const bool is_q = slot_id < L.n_q_heads;
+    const int head = is_q ? slot_id : slot_id - L.n_q_heads;
     const int base = (is_q ? 0 : L.n_q) + head * h;
-    const float u = ysum(y + base + c), w = ysum(y + base + c + h2);
-    const float2 cs = tab[c];
-    const float lo = u * cs.x - w * cs.y, hi = w * cs.x + u * cs.y;
-    if (is_q) {
-      T *q = Q + (int64_t)row * L.n_q + head * h;
-      q[c] = from_f32<T>(lo);
-      q[c + h2] = from_f32<T>(hi);
-    } else {
-      T *kk = cacheK + slot * L.n_kv + head * h;
-      kk[c] = from_f32<T>(lo);
-      kk[c + h2] = from_f32<T>(hi);
+    const float2 *tab = table + (int64_t)rm.pos[row] * h2;
+    T *dst = is_q ? Q + (int64_t)row * L.n_q + head * h : cacheK + rm.slot[row] * L.n_kv + head * h;
+    for (int c = lane; c < h2; c += 64) {
+      const float u = ysum(y + base + c), w = ysum(y + base + c + h2);
+      const float2 cs = tab[c];
+      dst[c] = from_f32<T>(u * cs.x - w * cs.y);
+      dst[c + h2] = from_f32<T>(w * cs.x + u * cs.y);
     }
+  } else {
+    const int head = slot_id - L.n_q_heads - L.n_kv_heads;
+    const float *yv = y + L.n_q + L.n_kv + head * h;
+    T *dst = cacheV + rm.slot[row] * L.n_kv + head * h;
+    for (int c = lane; c < h; c += 64) dst[c] = from_f32<T>(ysum(yv + c));
   }
-  const float *yv = y + L.n_q + L.n_kv;
-  for (int i = tid; i < L.n_kv; i += 256) cacheV[slot * L.n_kv + i] = from_f32<T>(ysum(yv + i));
 }
 
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
                         const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
   if (T_rows == 0) return;
-  hipLaunchKernelGGL((rope_append_kernel<T>), dim3(T_rows), dim3(256), 0, s, Y, n_parts,
-                     (int64_t)T_rows * L.n_qkv, L, rm, rope_table, Q, cacheK, cacheV);
+  dim3 grid(T_rows, (L.n_q_heads + 2 * L.n_kv_heads + 3) / 4);
+  hipLaunchKernelGGL((rope_append_kernel<T>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
+                     rope_table, Q, cacheK, cacheV);
 }
 template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *,
                                         float *, float *, float *, hipStream_t);

@@ -20,9 +20,10 @@ constexpr int PREP_WAVES = 8;
 // NF = 16-column fragments of t this workgroup computes (0: no adapter work).  The 3*rank columns
 // of t are spread over gridDim.y workgroups so that short batches still fill the chip; group 0
 // also writes x_hat and the row metadata.
-template <int NF>
+template <int NF, int PREP_UN>      // PREP_UN: k-steps (of 32) whose loads are issued together
 __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   __shared__ float s_rinv[PREP_ROWS];
+  __shared__ float s_ssq[PREP_WAVES][PREP_ROWS];
   __shared__ int s_adapter[PREP_ROWS];
   __shared__ float s_scale[PREP_ROWS];
   __shared__ unsigned long long s_present;
@@ -62,21 +63,36 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
     if (adapter >= 0) atomicOr(&s_present, 1ull << adapter);
   }
 
-  // ---- pass 1: sum of squares of every row (wave w: rows 2w, 2w+1) ---------------------------
+  // ---- pass 1: sum of squares of every row.  Each wave covers its own slice of d for all 16
+  // rows, 16 independent loads at a time, and the eight slices are added in a fixed order.
   if (a.gain != nullptr) {
+    const int slice1 = d / PREP_WAVES;
+    float ssq[PREP_ROWS];
 #pragma unroll
-    for (int i = 0; i < PREP_ROWS / PREP_WAVES; ++i) {
-      const int lr = wave * (PREP_ROWS / PREP_WAVES) + i;
-      const int row = min(row0 + lr, a.T - 1);
-      const bf16 *xr = a.x + (int64_t)row * d;
-      float ssq = 0.f;
-      for (int c = lane * 8; c < d; c += 64 * 8) {
-        const bf16x8 v = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(xr + c));
+    for (int r = 0; r < PREP_ROWS; ++r) ssq[r] = 0.f;
+    for (int c = wave * slice1 + lane * 8; c < (wave + 1) * slice1; c += 64 * 8) {
+      u32x4 raw[PREP_ROWS];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ssq += f * f; }
+      for (int r = 0; r < PREP_ROWS; ++r)
+        raw[r] = *reinterpret_cast<const u32x4 *>(a.x + (int64_t)min(row0 + r, a.T - 1) * d + c);
+#pragma unroll
+      for (int r = 0; r < PREP_ROWS; ++r) {
+        const bf16x8 v = __builtin_bit_cast(bf16x8, raw[r]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ssq[r] += f * f; }
       }
-      ssq = wave_sum(ssq);
-      if (lane == 0) s_rinv[lr] = 1.0f / sqrtf(ssq / (float)d + a.eps);
+    }
+#pragma unroll
+    for (int r = 0; r < PREP_ROWS; ++r) {
+      const float t = wave_sum(ssq[r]);
+      if (lane == 0) s_ssq[wave][r] = t;
+    }
+    __syncthreads();
+    if (tid < PREP_ROWS) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < PREP_WAVES; ++w) t += s_ssq[w][tid];
+      s_rinv[tid] = 1.0f / sqrtf(t / (float)d + a.eps);
     }
   } else if (tid < PREP_ROWS) {
     s_rinv[tid] = 1.f;
@@ -96,33 +112,64 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   for (int j = 0; j < (NF > 0 ? NF : 1); ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int rank = a.rank;
 
-  for (int k0 = k_lo; k0 < k_lo + slice; k0 += 32) {
-    const int c = k0 + kg * 8;
-    const bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(a.x + (int64_t)row * d + c));
+  // Both loops below run over this wave's slice in batches of PREP_UN k-steps whose loads are all
+  // issued before the first use, so that the global-memory latency is paid once per batch.  The
+  // adapter loop is outside the k loop (x and the gain are cache hits on the later passes), which
+  // keeps the k loop free of data-dependent control.
+  auto xhat = [&](u32x4 xraw, u32x4 graw) -> bf16x8 {
+    const bf16x8 xv = __builtin_bit_cast(bf16x8, xraw);
+    if (a.gain == nullptr) return xv;
+    const bf16x8 gv = __builtin_bit_cast(bf16x8, graw);
     bf16x8 xh;
-    if (a.gain != nullptr) {
-      const bf16x8 gv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(a.gain + c));
 #pragma unroll
-      for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
-    } else {
-      xh = xv;
+    for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
+    return xh;
+  };
+  const bf16 *xrow = a.x + (int64_t)row * d + kg * 8;
+  const bf16 *grow = (a.gain != nullptr ? a.gain : a.x) + kg * 8;      // dummy pointer when there is no gain
+  if (lead) {
+    for (int k0 = k_lo; k0 < k_lo + slice; k0 += 32 * PREP_UN) {
+      u32x4 xr[PREP_UN], gr[PREP_UN];
+#pragma unroll
+      for (int u = 0; u < PREP_UN; ++u) {
+        xr[u] = *reinterpret_cast<const u32x4 *>(xrow + k0 + 32 * u);
+        gr[u] = *reinterpret_cast<const u32x4 *>(grow + k0 + 32 * u);
+      }
+      if (row_ok) {
+#pragma unroll
+        for (int u = 0; u < PREP_UN; ++u)
+          *reinterpret_cast<u32x4 *>(a.xh + (int64_t)row * d + kg * 8 + k0 + 32 * u) =
+              __builtin_bit_cast(u32x4, xhat(xr[u], gr[u]));
+      }
     }
-    if (row_ok && lead) *reinterpret_cast<u32x4 *>(a.xh + (int64_t)row * d + c) = __builtin_bit_cast(u32x4, xh);
-    if (NF > 0) {
-      unsigned long long todo = present;
-      while (todo) {
-        const int ad = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        bf16x8 af = xh;
-        if (my_adapter != ad) {
+  }
+  if (NF > 0) {
+    unsigned long long todo = present;
+    while (todo) {
+      const int ad = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const bool mine = my_adapter == ad;
+      const bf16 *Ab = a.A + ((int64_t)ad * 3 * rank + col0 + r16) * d + kg * 8;     // row col0 + 16 j + r16
+      for (int k0 = k_lo; k0 < k_lo + slice; k0 += 32 * PREP_UN) {
+        u32x4 xr[PREP_UN], gr[PREP_UN], br[PREP_UN][NF];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) af[e] = (bf16)0.f;
+        for (int u = 0; u < PREP_UN; ++u) {
+          xr[u] = *reinterpret_cast<const u32x4 *>(xrow + k0 + 32 * u);
+          gr[u] = *reinterpret_cast<const u32x4 *>(grow + k0 + 32 * u);
+#pragma unroll
+          for (int j = 0; j < NF; ++j)
+            br[u][j] = *reinterpret_cast<const u32x4 *>(Ab + (int64_t)j * 16 * d + k0 + 32 * u);
         }
-        const bf16 *Ab = a.A + ((int64_t)ad * 3 * rank + col0) * d + c;     // rows of [3*rank, d]
 #pragma unroll
-        for (int j = 0; j < NF; ++j) {
-          const bf16x8 bf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Ab + (int64_t)(j * 16 + r16) * d));
-          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bf, acc[j], 0, 0, 0);
+        for (int u = 0; u < PREP_UN; ++u) {
+          bf16x8 af = xhat(xr[u], gr[u]);
+          if (!mine) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) af[e] = (bf16)0.f;
+          }
+#pragma unroll
+          for (int j = 0; j < NF; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, __builtin_bit_cast(bf16x8, br[u][j]), acc[j], 0, 0, 0);
         }
       }
     }
@@ -155,20 +202,32 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
 }
 
 bool prep_rows_mfma_supported(int d, int rank) {
-  return d % (PREP_WAVES * 32) == 0 && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
+  return d % (PREP_WAVES * 64 * 8) == 0 && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
 }
 
-template <int NF>
-static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
+template <int NF, int UN>
+static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
   const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
-  auto kern = prep_rows_mfma_kernel<NF>;
+  auto kern = prep_rows_mfma_kernel<NF, UN>;
   static bool configured = false;
   if (!configured && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     configured = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(512), smem, s, a);
+}
+
+template <int NF>
+static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
+  // deep batches for the narrow variants (few accumulators, registers to spare), when d allows
+  if constexpr (NF <= 1) {
+    if (a.d % (PREP_WAVES * 32 * 8) == 0) { launch_prep_cfg<NF, 8>(a, groups, s); return; }
+  }
+  if constexpr (NF <= 3) {
+    if (a.d % (PREP_WAVES * 32 * 4) == 0) { launch_prep_cfg<NF, 4>(a, groups, s); return; }
+  }
+  launch_prep_cfg<NF, 2>(a, groups, s);
 }
 
 void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s) {
