@@ -246,7 +246,8 @@ struct Workspace {
   RowMeta rm;
   void *xh;        // [T, d]
   float *tlow;     // [T, 3r]
-  float *Y;        // [T, n_qkv] fp32 (plain path)
+  float *Y;        // [k_splits, T, n_qkv] fp32 projection partials; also split-K scratch of the dense layers
+  size_t y_floats;
   void *Q;         // [T, n_q]
   float *partials;
   // layer-stack buffers
@@ -279,7 +280,9 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
   w.rm.slot = b.take<int64_t>(T);
   w.xh = b.take<char>((size_t)T * L.d * esz);
   w.tlow = b.take<float>((size_t)T * 3 * std::max(L.rank, 1));
-  w.Y = b.take<float>((size_t)T * L.n_qkv * std::max(k_splits, 1));
+  w.y_floats = (size_t)T * L.n_qkv * std::max(k_splits, 1);
+  if (stack) w.y_floats = std::max(w.y_floats, (size_t)8 * T * L.d);      // split-K partials of W_o / W_down
+  w.Y = b.take<float>(w.y_floats);
   w.Q = b.take<char>((size_t)T * L.n_q * esz);
   w.partials = b.take<float>(attn_plain_partial_floats(L, T, n_splits));
   if (stack) {
@@ -386,9 +389,19 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       GemmArgs g{};
       g.A = (const bf16 *)A; g.lda = K;
       g.B = (const bf16 *)W; g.ldb = K;
-      g.M = T_rows; g.N = N; g.K = K; g.k_splits = 1;
-      g.C = (bf16 *)C; g.ldc = N; g.R = (const bf16 *)R;
-      launch_gemm_mfma(g, GEMM_EPI_BF16, s);
+      g.M = T_rows; g.N = N; g.K = K;
+      // few row tiles: split the reduction to fill the chip, partial sums go through the Y buffer
+      const int splits = gemm_mfma_pick_splits(T_rows, N, K, ctx->n_cu);
+      if (splits > 1 && (size_t)splits * T_rows * N <= w.y_floats && ((int64_t)T_rows * N) % 4 == 0) {
+        g.k_splits = splits;
+        g.Cpart = w.Y;
+        launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+        launch_splitk_reduce(w.Y, splits, (int64_t)T_rows * N, (const bf16 *)R, (bf16 *)C, s);
+      } else {
+        g.k_splits = 1;
+        g.C = (bf16 *)C; g.ldc = N; g.R = (const bf16 *)R;
+        launch_gemm_mfma(g, GEMM_EPI_BF16, s);
+      }
     } else {
       launch_gemm_plain<T>((const T *)A, (const T *)W, (const T *)R, (T *)C, T_rows, N, K, s);
     }

@@ -3,8 +3,10 @@
 //
 // Work item: one workgroup = (q-tile of 256/G tokens of one sequence, kv head, key split).
 // The G query heads of the kv group are packed next to the tokens into 256 "packed rows"
-// (packed row = token * G + head), 64 per wave, so every K/V tile fetched from HBM and read
-// from LDS serves all heads of the group.
+// (packed row = token * G + head), 32 per wave and eight waves per workgroup, so every K/V tile
+// fetched from HBM serves all heads of the group.  Two waves share a SIMD: the softmax of one
+// (exponentials and rescaling on the vector ALU -- as many cycles per tile as the MFMAs take on
+// this chip) overlaps the matrix work of the other.
 //
 // Per 64-key tile, each wave computes S^T = K Q^T (keys are MFMA rows, packed query rows are
 // MFMA columns).  In that orientation a lane owns one query row (column l%32) in every
@@ -47,9 +49,10 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
 template <int G>
-__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
   constexpr int H = 128;
   constexpr int TQ = 256 / G;
+  constexpr int NB = 1;             // 32-row query blocks per wave
   __shared__ u32x4 Ks[2][ATT_BN * 16];
   __shared__ u32x4 Vs[2][H * 8];
 
@@ -71,11 +74,11 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
   const int first_pos = sm.P + q0;                   // smallest query position in the tile
 
   // ---- this wave's queries as B operands: 2 column blocks x 8 k-steps ---------------------
-  u32x4 qf[2][8];
-  int pos[2], tok[2], head[2];
+  u32x4 qf[NB][8];
+  int pos[NB], tok[NB], head[NB];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const int pr = wave * 64 + nb * 32 + l32;
+  for (int nb = 0; nb < NB; ++nb) {
+    const int pr = wave * (32 * NB) + nb * 32 + l32;
     tok[nb] = pr / G;
     head[nb] = g * G + pr % G;
     const int tc = min(tok[nb], ntok - 1);
@@ -85,54 +88,58 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
     for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const u32x4 *>(qp + ks * 16);
   }
 
-  f32x16 o[4][2];
+  f32x16 o[4][NB];
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[cb][nb][v] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_run[NB], l_run[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
   const float c_scale = a.sm_scale * LOG2E;
 
   // ---- tile loader: K rows as they are, V transposed in registers -------------------------
-  u32x4 rk[4], rv[4];
-  const int v_qd = tid >> 4, v_hc = tid & 15;
+  // 512 threads: K = 1024 chunks of 16 B, two per thread; V = 16 key quads x 32 column groups of
+  // 4, one (quad, group) per thread: four 8-byte loads become four columns x four keys.
+  u32x4 rk[2];
+  u32x2 rv[4];
+  const int v_qd = tid >> 5, v_cg = tid & 31;
   auto load_tile = [&](int t) {
     const int k0 = kbeg + t * ATT_BN;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int q = tid + i * 256, key = q >> 4, c = q & 15;
+    for (int i = 0; i < 2; ++i) {
+      const int q = tid + i * 512, key = q >> 4, c = q & 15;
       const int kidx = min(k0 + key, n_visible - 1);
       rk[i] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kidx * a.n_kv + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-      rv[i] = *reinterpret_cast<const u32x4 *>(Vp + (int64_t)kidx * a.n_kv + v_hc * 8);
+      rv[i] = *reinterpret_cast<const u32x2 *>(Vp + (int64_t)kidx * a.n_kv + v_cg * 4);
     }
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int q = tid + i * 256, key = q >> 4, c = q & 15;
+    for (int i = 0; i < 2; ++i) {
+      const int q = tid + i * 512, key = q >> 4, c = q & 15;
       Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
     }
-    // V: this thread holds keys 4*v_qd..+3 for columns 8*v_hc..+7
+    // V: this thread holds keys 4*v_qd..+3 for columns 4*v_cg..+3
     const int grp16 = v_qd >> 2, qi = v_qd & 3;
     const int vkh = qi & 1, halfpos = qi >> 1;
     const int vchunk = grp16 * 2 + vkh;
-    const u32x4 w0 = rv[0], w1 = rv[1], w2 = rv[2], w3 = rv[3];
     u32x2 *vs2 = reinterpret_cast<u32x2 *>(Vs[buf]);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 2; ++j) {
       // even column 2j: low halves; odd column 2j+1: high halves
       u32x2 ev, od;
-      ev.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x05040100u);
-      ev.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x05040100u);
-      od.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x07060302u);
-      od.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x07060302u);
-      const int c0 = v_hc * 8 + 2 * j, c1 = c0 + 1;
+      ev.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x05040100u);
+      ev.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x05040100u);
+      od.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x07060302u);
+      od.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x07060302u);
+      const int c0 = v_cg * 4 + 2 * j, c1 = c0 + 1;
       vs2[(c0 * 8 + (vchunk ^ v_swz(c0))) * 2 + halfpos] = ev;
       vs2[(c1 * 8 + (vchunk ^ v_swz(c1))) * 2 + halfpos] = od;
     }
@@ -155,9 +162,9 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       // ---- S^T = K Q^T ----------------------------------------------------------------------
-      f32x16 s[2];
+      f32x16 s[NB];
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
 #pragma unroll
@@ -165,14 +172,14 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
         const int key = kb * 32 + l32, c = 2 * ks + kh;
         const bf16x8 kf = u4_as_bf16x8(Ks[buf][key * 16 + (c ^ (key & 15))]);
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
           s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, u4_as_bf16x8(qf[nb][ks]), s[nb], 0, 0, 0);
       }
 
       // ---- causal mask: only tiles that reach past the first query position or the split end --
       if (need_mask) {
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int key = k0 + kb * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
@@ -181,9 +188,9 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
       }
 
       // ---- online softmax (log2 domain), one query row per lane -------------------------------
-      u32x4 pf[2][2];      // [half][nb]: 8 probabilities as bf16
+      u32x4 pf[2][NB];     // [half][nb]: 8 probabilities as bf16
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
+      for (int nb = 0; nb < NB; ++nb) {
         float mx = -INFINITY;
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
@@ -227,7 +234,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-          for (int nb = 0; nb < 2; ++nb)
+          for (int nb = 0; nb < NB; ++nb)
             o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[cb], u4_as_bf16x8(pf[hf][nb]), o[cb][nb], 0, 0, 0);
       }
     }
@@ -238,7 +245,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(AttnArgs a) {
 
   // ---- write the partial (or final) result ----------------------------------------------------
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
+  for (int nb = 0; nb < NB; ++nb) {
     const float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 32, 64);
     if (tok[nb] >= ntok) continue;
     const int64_t row = row0 + tok[nb];
@@ -285,10 +292,10 @@ void launch_attn_prefill_mfma(const AttnArgs &a, int n_qtiles, int G, hipStream_
   if (n_qtiles == 0) return;
   dim3 grid(n_qtiles, a.n_kv_heads, a.n_splits);
   switch (G) {
-    case 1: hipLaunchKernelGGL(attn_prefill_mfma_kernel<1>, grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL(attn_prefill_mfma_kernel<2>, grid, dim3(256), 0, s, a); break;
-    case 4: hipLaunchKernelGGL(attn_prefill_mfma_kernel<4>, grid, dim3(256), 0, s, a); break;
-    case 8: hipLaunchKernelGGL(attn_prefill_mfma_kernel<8>, grid, dim3(256), 0, s, a); break;
+    case 1: hipLaunchKernelGGL(attn_prefill_mfma_kernel<1>, grid, dim3(512), 0, s, a); break;
+    case 2: hipLaunchKernelGGL(attn_prefill_mfma_kernel<2>, grid, dim3(512), 0, s, a); break;
+    case 4: hipLaunchKernelGGL(attn_prefill_mfma_kernel<4>, grid, dim3(512), 0, s, a); break;
+    case 8: hipLaunchKernelGGL(attn_prefill_mfma_kernel<8>, grid, dim3(512), 0, s, a); break;
     default: break;
   }
 }

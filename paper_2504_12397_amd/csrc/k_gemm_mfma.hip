@@ -252,6 +252,29 @@ static void launch_cfg(const GemmArgs &g, hipStream_t s) {
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, g);
 }
 
+// C = bf16( sum over splits of partial sums (fixed order) + residual )
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int splits, int64_t mn,
+                                                            const bf16 *__restrict__ R, bf16 *__restrict__ C) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= mn) return;
+  float4 acc = *reinterpret_cast<const float4 *>(part + i);
+  for (int s = 1; s < splits; ++s) {
+    const float4 v = *reinterpret_cast<const float4 *>(part + (int64_t)s * mn + i);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  if (R != nullptr) {
+    acc.x += (float)R[i]; acc.y += (float)R[i + 1]; acc.z += (float)R[i + 2]; acc.w += (float)R[i + 3];
+  }
+  C[i] = (bf16)acc.x; C[i + 1] = (bf16)acc.y; C[i + 2] = (bf16)acc.z; C[i + 3] = (bf16)acc.w;
+}
+
+void launch_splitk_reduce(const float *part, int splits, int64_t mn, const bf16 *R, bf16 *C, hipStream_t s) {
+  if (mn == 0) return;
+  const int64_t threads = (mn + 3) / 4;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part, splits, mn,
+                     R, C);
+}
+
 bool gemm_mfma_supported(int M, int N, int K) { return M > 0 && N > 0 && K >= 64 && K % 64 == 0; }
 
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
@@ -259,7 +282,7 @@ int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
   // fp32 partial sums), in chunks of at least 512
   int tiles = ((M + 127) / 128) * ((N + 127) / 128);
   int s = 1;
-  while (4 * tiles * s < 3 * n_cu && s < 8 && (K / (s * 2)) % 64 == 0 && K / (s * 2) >= 512) s *= 2;
+  while (4 * tiles * s < 3 * n_cu && s < 8 && K % (s * 2 * 64) == 0 && K / (s * 2) >= 512) s *= 2;
   return s;
 }
 

@@ -75,5 +75,7 @@ void launch_attn_decode_mfma(const DecodeArgs &a, int n_rows, hipStream_t s);
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s);
+// C[mn] = bf16(sum_s part[s][mn] + R[mn]); mn must be a multiple of 4
+void launch_splitk_reduce(const float *part, int splits, int64_t mn, const bf16 *R, bf16 *C, hipStream_t s);
 
 }  // namespace alora
