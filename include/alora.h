@@ -112,7 +112,8 @@ const char *alora_status_string(alora_status s);
  * for bf16 where the shape allows, plain fp32-FMA kernels otherwise), 1 = force the plain
  * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
  * of attention into n chunks.  "gemm_splits": 0 = automatic, n > 0 = split the reduction axis
- * of the QKV projection into n chunks (partial sums are added in a fixed order).  "profile": 0/1, see alora_profile_read.  Unknown key or bad
+ * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128
+ * block tiles for the QKV projection.  "profile": 0/1, see alora_profile_read.  Unknown key or bad
  * value: ALORA_EINVAL. */
 alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
 

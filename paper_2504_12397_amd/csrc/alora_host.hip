@@ -58,6 +58,7 @@ struct alora_ctx {
   int opt_kernels = 0;
   int opt_splits = 0;
   int opt_gemm_splits = 0;
+  int opt_gemm_tile = 0;
   int n_cu = 256;
 };
 
@@ -257,7 +258,7 @@ struct Workspace {
   int k_splits = 1;
   bool attn_mfma = false;
   bool decode_mfma = false;
-  const int2 *qtiles = nullptr;
+  const int4 *qtiles = nullptr;
   int n_qtiles = 0;
 };
 
@@ -329,6 +330,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.B = (const bf16 *)ly->W_qkv; g.ldb = L.d;
       g.M = pl.T; g.N = L.n_qkv; g.K = L.d;
       g.k_splits = w.k_splits;
+      g.tile_hint = ctx->opt_gemm_tile;
       g.Cpart = w.Y;
       g.tlow = pl.any_adapter ? (const bf16 *)w.tlow : nullptr;
       g.rank = L.rank;
@@ -352,7 +354,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
     if (w.attn_mfma && std::is_same<T, bf16>::value) {
       AttnArgs a{};
       a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
-      a.seqs = seqs_dev; a.qtiles = w.qtiles;
+      a.seqs = seqs_dev; a.work = w.qtiles;
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
       a.n_splits = n_splits;
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
@@ -512,20 +514,44 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (st != ALORA_OK) return st;
   st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
   if (st != ALORA_OK) return st;
-  // staged metadata: per-sequence records, then the q-tile list of the MFMA attention kernel
-  std::vector<int2> qtiles;
+  // staged metadata: per-sequence records, then the work list of the MFMA attention kernel.
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  All q-tiles of one
+  // (sequence, kv head, key split) read the same keys and values, so they go to the same XCD, next
+  // to each other (heaviest q-tile first); the groups are dealt to the XCDs longest sequence first.
+  std::vector<int4> qtiles;
   if (attn_mfma) {
     const int tq = attn_prefill_mfma_tokens_per_tile(L);
+    std::vector<int> order;
     for (int b = 0; b < B; ++b)
-      for (int q0 = 0; q0 < pl.seqs[b].n_new; q0 += tq) qtiles.push_back(make_int2(b, q0));
+      if (pl.seqs[b].n_new > 0) order.push_back(b);
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+      return (int64_t)(pl.seqs[x].P + pl.seqs[x].n_new) * pl.seqs[x].n_new >
+             (int64_t)(pl.seqs[y].P + pl.seqs[y].n_new) * pl.seqs[y].n_new;
+    });
+    std::vector<int4> per_xcd[8];
+    int next = 0;
+    for (int b : order)
+      for (int g = 0; g < L.n_kv_heads; ++g)
+        for (int sp = 0; sp < n_splits; ++sp) {
+          std::vector<int4> &dst = per_xcd[next];
+          next = (next + 1) & 7;
+          const int last = ((pl.seqs[b].n_new - 1) / tq) * tq;
+          for (int q0 = last; q0 >= 0; q0 -= tq) dst.push_back(make_int4(b, q0, g, sp));
+        }
+    size_t longest = 0;
+    for (auto &v : per_xcd) longest = std::max(longest, v.size());
+    qtiles.reserve(longest * 8);
+    for (size_t i = 0; i < longest; ++i)
+      for (int x = 0; x < 8; ++x)
+        qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : make_int4(-1, 0, 0, 0));
   }
   const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
-  const size_t meta_bytes = seq_bytes + qtiles.size() * sizeof(int2);
+  const size_t meta_bytes = seq_bytes + qtiles.size() * sizeof(int4);
   MetaSlot *slot = nullptr;
   st = acquire_slot(ctx, meta_bytes, &slot);
   if (st != ALORA_OK) return st;
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
-  if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(int2));
+  if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(int4));
   HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
   const SeqMeta *seqs_dev = (const SeqMeta *)slot->dev;
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
@@ -533,7 +559,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.k_splits = k_splits;
   w.attn_mfma = attn_mfma;
   w.decode_mfma = decode_mfma;
-  w.qtiles = (const int2 *)(slot->dev + seq_bytes);
+  w.qtiles = (const int4 *)(slot->dev + seq_bytes);
   w.n_qtiles = (int)qtiles.size();
 
   const bool bf = layers[0].dtype == ALORA_BF16;
@@ -648,6 +674,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "gemm_splits")) {
     if (value < 0 || value > 64) return fail(ctx, ALORA_EINVAL, "gemm_splits must be in [0, 64]");
     ctx->opt_gemm_splits = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "gemm_tile")) {
+    if (value < 0 || value > 2) return fail(ctx, ALORA_EINVAL, "gemm_tile must be 0, 1 or 2");
+    ctx->opt_gemm_tile = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "profile")) {

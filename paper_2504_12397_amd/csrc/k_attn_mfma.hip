@@ -58,10 +58,13 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, kh = lane >> 5;
-  const int2 qt = a.qtiles[blockIdx.x];
-  const int g = blockIdx.y, split = blockIdx.z;
-  const SeqMeta sm = a.seqs[qt.x];
-  const int q0 = qt.y;
+  // work list built by the host: (sequence, first token of the q-tile, kv head, key split), ordered
+  // so that the q-tiles that stream the same keys and values sit on one XCD (one L2) together
+  const int4 wk = a.work[blockIdx.x];
+  if (wk.x < 0) return;
+  const int g = wk.z, split = wk.w;
+  const SeqMeta sm = a.seqs[wk.x];
+  const int q0 = wk.y;
   const int ntok = min(TQ, sm.n_new - q0);
   const int row0 = sm.row_start + q0;
   const int n_visible = sm.P + q0 + ntok;            // keys visible to the tile's last token
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
   for (int t = 0; t < ntiles; ++t) {
     const int buf = t & 1;
     const int k0 = kbeg + t * ATT_BN;
-    if (t + 1 < ntiles) load_tile(t + 1);
+    load_tile(min(t + 1, ntiles - 1));      // unconditional (clamped): keeps the load count exact for the compiler
 
     const bool need_mask = (k0 + ATT_BN - 1 > first_pos) || (k0 + ATT_BN > kend);
     // the 64-key tile is consumed as two 32-key blocks, each with its own softmax update, so that
@@ -167,13 +170,18 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
+      {
+        // all eight K fragments of this key block are fetched from LDS first: with one MFMA per
+        // fragment there is nothing else to hide the LDS latency behind
+        bf16x8 kf[8];
+        const int key = kb * 32 + l32;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const int key = kb * 32 + l32, c = 2 * ks + kh;
-        const bf16x8 kf = u4_as_bf16x8(Ks[buf][key * 16 + (c ^ (key & 15))]);
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = u4_as_bf16x8(Ks[buf][key * 16 + ((2 * ks + kh) ^ (key & 15))]);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, u4_as_bf16x8(qf[nb][ks]), s[nb], 0, 0, 0);
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], u4_as_bf16x8(qf[nb][ks]), s[nb], 0, 0, 0);
       }
 
       // ---- causal mask: only tiles that reach past the first query position or the split end --
@@ -222,24 +230,26 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
       }
 
       // ---- O^T += V^T P^T ---------------------------------------------------------------------
+      {
+        bf16x8 vf[2][4];
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        const int s4 = kb * 2 + hf;
-        bf16x8 vf[4];
+        for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-          const int col = cb * 32 + l32, c = 2 * s4 + kh;
-          vf[cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
-        }
+          for (int cb = 0; cb < 4; ++cb) {
+            const int col = cb * 32 + l32, c = 2 * (kb * 2 + hf) + kh;
+            vf[hf][cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
+          }
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
+        for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[cb], u4_as_bf16x8(pf[hf][nb]), o[cb][nb], 0, 0, 0);
+          for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][cb], u4_as_bf16x8(pf[hf][nb]), o[cb][nb], 0, 0, 0);
       }
     }
 
-    if (t + 1 < ntiles) store_tile(buf ^ 1);
+    store_tile(buf ^ 1);
     __syncthreads();
   }
 
@@ -288,9 +298,9 @@ bool attn_prefill_mfma_supported(const LayerDims &L) {
 
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L) { return 256 / (L.n_q_heads / L.n_kv_heads); }
 
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_qtiles, int G, hipStream_t s) {
-  if (n_qtiles == 0) return;
-  dim3 grid(n_qtiles, a.n_kv_heads, a.n_splits);
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, hipStream_t s) {
+  if (n_work == 0) return;
+  dim3 grid(n_work);
   switch (G) {
     case 1: hipLaunchKernelGGL(attn_prefill_mfma_kernel<1>, grid, dim3(512), 0, s, a); break;
     case 2: hipLaunchKernelGGL(attn_prefill_mfma_kernel<2>, grid, dim3(512), 0, s, a); break;

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int s = 0; s < 4; ++s) { kc[u][s] = kr[u][s]; vc[u][s] = vr[u][s]; }
-    if (k0 + 32 < kend) load_step(k0 + 32);
+    load_step(k0 + 32);      // unconditional: key indices are clamped to the last valid row
 
     f32x4 sc[2];
 #pragma unroll

@@ -164,44 +164,58 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
       Bs[row * 8 + (c ^ (row & 7))] = rb[i];
     }
   };
-  auto compute = [&](const u32x4 *As, const u32x4 *Bs) {
+  // One k-tile = four k-steps of 16.  The fragments of step ks+1 are read from LDS before the
+  // MFMAs of step ks are issued, so the LDS latency hides behind matrix work.
+  auto read_frags = [&](const u32x4 *As, const u32x4 *Bs, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+    const int c = 2 * ks + lhi;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[TM], bfr[TN];
-      const int c = 2 * ks + lhi;
+    for (int mi = 0; mi < TM; ++mi) {
+      int row = wm0 + mi * 32 + l32;
+      af[mi] = as_bf16x8(As[row * 8 + (c ^ (row & 7))]);
+    }
 #pragma unroll
-      for (int mi = 0; mi < TM; ++mi) {
-        int row = wm0 + mi * 32 + l32;
-        af[mi] = as_bf16x8(As[row * 8 + (c ^ (row & 7))]);
-      }
-#pragma unroll
-      for (int ni = 0; ni < TN; ++ni) {
-        int row = wn0 + ni * 32 + l32;
-        bfr[ni] = as_bf16x8(Bs[row * 8 + (c ^ (row & 7))]);
-      }
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+    for (int ni = 0; ni < TN; ++ni) {
+      int row = wn0 + ni * 32 + l32;
+      bfr[ni] = as_bf16x8(Bs[row * 8 + (c ^ (row & 7))]);
     }
   };
+  auto mma = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < TN; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+  };
+  auto compute = [&](const u32x4 *As, const u32x4 *Bs) {
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+    read_frags(As, Bs, 0, a0, b0);
+    read_frags(As, Bs, 1, a1, b1);
+    mma(a0, b0);
+    read_frags(As, Bs, 2, a0, b0);
+    mma(a1, b1);
+    read_frags(As, Bs, 3, a1, b1);
+    mma(a0, b0);
+    mma(a1, b1);
+  };
 
-  if (nk > 0) load_tiles(0, ra0, rb0);
-  if (nk > 1) load_tiles(1, ra1, rb1);
-  if (nk > 0) store_tiles(As0, Bs0, ra0, rb0);
+  // The loop is free of conditional loads and stores (tile indices are clamped instead: the last
+  // tile may be fetched and stored once more, into a buffer nobody reads again), so that the
+  // compiler can count outstanding loads exactly and wait only for the tile it is about to store.
+  if (nk > 0) {
+    load_tiles(0, ra0, rb0);
+    load_tiles(min(1, nk - 1), ra1, rb1);
+    store_tiles(As0, Bs0, ra0, rb0);
+  }
   __syncthreads();
-  for (int kt = 0; kt < nk;) {
-    if (kt + 2 < nk) load_tiles(kt + 2, ra0, rb0);
+  for (int kt = 0; kt < nk; kt += 2) {
+    load_tiles(min(kt + 2, nk - 1), ra0, rb0);
     compute(As0, Bs0);
-    if (kt + 1 < nk) store_tiles(As1, Bs1, ra1, rb1);
+    store_tiles(As1, Bs1, ra1, rb1);
     __syncthreads();
-    if (++kt >= nk) break;
-    if (kt + 2 < nk) load_tiles(kt + 2, ra1, rb1);
-    compute(As1, Bs1);
-    if (kt + 1 < nk) store_tiles(As0, Bs0, ra0, rb0);
+    load_tiles(min(kt + 3, nk - 1), ra1, rb1);
+    if (kt + 1 < nk) compute(As1, Bs1);
+    store_tiles(As0, Bs0, ra0, rb0);
     __syncthreads();
-    ++kt;
   }
 
   // ---- epilogue ---------------------------------------------------------------------------
@@ -289,7 +303,8 @@ int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
   if (epi == GEMM_EPI_PARTIAL) {
-    launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
+    if (g.tile_hint == 2) launch_cfg<256, 128, 128, 64, GEMM_EPI_PARTIAL>(g, s);
+    else launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
     if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);

@@ -12,6 +12,7 @@ struct GemmArgs {
   const bf16 *B; int ldb;      // [N, K]
   const bf16 *B2;              // SwiGLU only: the "up" weights; B holds the "gate" weights, N = 2 * I
   int M, N, K;
+  int tile_hint;               // 0 = automatic, 1 = 128x128 blocks, 2 = 256x128 blocks
   int k_splits;                // PARTIAL only: grid.z; K / k_splits must be a multiple of 64
   float *Cpart;                // PARTIAL: [k_splits, M, N] fp32 partial sums
   bf16 *C; int ldc;            // BF16 / SWIGLU output
@@ -47,7 +48,7 @@ struct AttnArgs {
   const bf16 *Q;            // [T, n_q] rotated queries of the new rows
   const bf16 *K, *V;        // pool [tokens, n_kv]
   const SeqMeta *seqs;
-  const int2 *qtiles;       // per q-tile: (sequence, first new-token index of the tile)
+  const int4 *work;         // per workgroup: (sequence or -1, first new token of the q-tile, kv head, key split)
   int n_q, n_kv, n_q_heads, n_kv_heads;
   int n_splits;             // key splits (grid.z)
   float sm_scale;           // 1 / sqrt(head_dim)
@@ -56,7 +57,7 @@ struct AttnArgs {
 };
 bool attn_prefill_mfma_supported(const LayerDims &L);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L);
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_qtiles, int G, hipStream_t s);
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, hipStream_t s);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
 struct DecodeArgs {
