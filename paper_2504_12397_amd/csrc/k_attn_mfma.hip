@@ -19,7 +19,7 @@
 // K tile in LDS: [64 keys][16 chunks of 16 B], chunk c of key r at c ^ (r & 15).
 // V^T tile in LDS: [128 columns][8 chunks of 16 B]; chunk (2*s4 + kh) of a column holds keys
 //   32*(s4/2) + 16*(s4%2) + {4kh..4kh+3, 8+4kh..8+4kh+3}  (s4 = k-step 0..3, kh = lane/32),
-//   stored at chunk ^ ((column ^ column/8) & 7).
+//   stored at chunk ^ v_swz(column).
 #include "mfma_kernels.h"
 
 namespace alora {
@@ -40,11 +40,23 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, p);
 }
 
-// chunk swizzle of the V^T tile: mixes the low column bits (operand reads walk consecutive
-// columns) with the next three (the transposing stores walk columns 8 apart)
-__device__ __forceinline__ int v_swz(int col) { return (col ^ (col >> 3)) & 7; }
+// chunk swizzle of the V^T tile (128-byte rows).  LDS serves 16 lanes at a time over 64 banks:
+// 16 consecutive columns of one chunk (operand reads) must land on 16 distinct 16-byte slots
+// modulo 256 B, which (col >> 1) & 7 together with the row parity gives; the extra col >> 4 term
+// spreads the transposing 8-byte stores (columns 4 apart) to a 2-way conflict at worst.
+__device__ __forceinline__ int v_swz(int col) { return ((col >> 1) ^ (col >> 4)) & 7; }
+
+// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
+__device__ __forceinline__ float sum_bf16x2(uint32_t pair, float acc) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                         false);
+}
 
 constexpr int ATT_BN = 64;        // keys per tile
+#ifndef ATT_LAZY
+#define ATT_LAZY 0.0f
+#endif
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -106,10 +118,12 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
   // ---- tile loader: K rows as they are, V transposed in registers -------------------------
   // 512 threads: K = 1024 chunks of 16 B, two per thread; V = 16 key quads x 32 column groups of
   // 4, one (quad, group) per thread: four 8-byte loads become four columns x four keys.
-  u32x4 rk[2];
-  u32x2 rv[4];
+  // Two tiles are kept in flight in registers (sets 0 and 1) on top of the one being consumed
+  // from LDS: one tile of compute is shorter than the HBM latency.
+  u32x4 rk0[2], rk1[2];
+  u32x2 rv0[4], rv1[4];
   const int v_qd = tid >> 5, v_cg = tid & 31;
-  auto load_tile = [&](int t) {
+  auto load_tile = [&](int t, u32x4 (&rk)[2], u32x2 (&rv)[4]) {
     const int k0 = kbeg + t * ATT_BN;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -123,7 +137,7 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
       rv[i] = *reinterpret_cast<const u32x2 *>(Vp + (int64_t)kidx * a.n_kv + v_cg * 4);
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf, const u32x4 (&rk)[2], const u32x2 (&rv)[4]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int q = tid + i * 512, key = q >> 4, c = q & 15;
@@ -148,17 +162,8 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
     }
   };
 
-  if (ntiles > 0) {
-    load_tile(0);
-    store_tile(0);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < ntiles; ++t) {
-    const int buf = t & 1;
+  auto compute_tile = [&](int buf, int t) {
     const int k0 = kbeg + t * ATT_BN;
-    load_tile(min(t + 1, ntiles - 1));      // unconditional (clamped): keeps the load count exact for the compiler
-
     const bool need_mask = (k0 + ATT_BN - 1 > first_pos) || (k0 + ATT_BN > kend);
     // the 64-key tile is consumed as two 32-key blocks, each with its own softmax update, so that
     // only one block of scores and probabilities is live at a time
@@ -203,30 +208,39 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[nb], mx * c_scale);
+        // The reference exponent m_run moves (and the 64 output accumulators are rescaled) only in
+        // blocks where some row of the wave sees a new maximum -- a wave-uniform decision.  ATT_LAZY
+        // > 0 would let it lag behind the true maximum by that many powers of two and skip almost
+        // all rescaling (the result is mathematically unchanged); it is 0 because with an exact
+        // maximum the largest probability of a row is exactly 1 in bf16, which measurably lowers
+        // the rounding error of peaked rows.
+        const float m_blk = mx * c_scale;
+        const bool move = __any(m_blk > m_run[nb] + ATT_LAZY);
+        const float m_new = move ? fmaxf(m_run[nb], m_blk) : m_run[nb];
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_safe);
+        const float alpha = move ? __builtin_amdgcn_exp2f(m_run[nb] - m_safe) : 1.0f;
         m_run[nb] = m_new;
-        float rs = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float pv = __builtin_amdgcn_exp2f(fmaf(s[nb][v], c_scale, -m_safe));
-          s[nb][v] = pv;
-          rs += pv;
-        }
-        l_run[nb] = l_run[nb] * alpha + rs;
-        if (__any(alpha != 1.0f)) {
+        for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(fmaf(s[nb][v], c_scale, -m_safe));
+        if (move) {
+          l_run[nb] *= alpha;
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[cb][nb][v] *= alpha;
         }
+        // probabilities as bf16 pairs; the row sum is taken from the ROUNDED values (one dot2 per
+        // pair), so numerator and denominator of the softmax carry the same rounding
+        float rs = 0.f;
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
           const int e = 8 * hf;
           pf[hf][nb] = u32x4{pack_bf16x2(s[nb][e], s[nb][e + 1]), pack_bf16x2(s[nb][e + 2], s[nb][e + 3]),
                              pack_bf16x2(s[nb][e + 4], s[nb][e + 5]), pack_bf16x2(s[nb][e + 6], s[nb][e + 7])};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) rs = sum_bf16x2(pf[hf][nb][w], rs);
         }
+        l_run[nb] += rs;
       }
 
       // ---- O^T += V^T P^T ---------------------------------------------------------------------
@@ -249,7 +263,24 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
       }
     }
 
-    store_tile(buf ^ 1);
+  };
+
+  // Loads and stores in the loop are unconditional (tile indices clamped) so that the compiler's
+  // count of outstanding loads is exact and it waits only for the tile it is about to store.
+  if (ntiles > 0) {
+    load_tile(0, rk0, rv0);
+    load_tile(min(1, ntiles - 1), rk1, rv1);
+    store_tile(0, rk0, rv0);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntiles; t += 2) {
+    load_tile(min(t + 2, ntiles - 1), rk0, rv0);
+    compute_tile(0, t);
+    store_tile(1, rk1, rv1);
+    __syncthreads();
+    load_tile(min(t + 3, ntiles - 1), rk1, rv1);
+    if (t + 1 < ntiles) compute_tile(1, t + 1);
+    store_tile(0, rk0, rv0);
     __syncthreads();
   }
 

@@ -29,6 +29,13 @@ __device__ __forceinline__ uint32_t dec_pack2(float a, float b) {
   return __builtin_bit_cast(uint32_t, p);
 }
 
+// acc + lo + hi of a packed bf16 pair
+__device__ __forceinline__ float dec_sum2(uint32_t pair, float acc) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                         false);
+}
+
 constexpr float DEC_LOG2E = 1.4426950408889634f;
 constexpr float DEC_LN2 = 0.6931471805599453f;
 
@@ -117,17 +124,17 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
     const float m_new = fmaxf(m_run, mx * c_scale);       // finite: every step has at least one valid key
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
-    float p[2][4], rs = 0.f;
+    float p[2][4];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        p[u][v] = __builtin_amdgcn_exp2f(fmaf(sc[u][v], c_scale, -m_new));
-        rs += p[u][v];
-      }
+      for (int v = 0; v < 4; ++v) p[u][v] = __builtin_amdgcn_exp2f(fmaf(sc[u][v], c_scale, -m_new));
+    const uint32_t d0 = dec_pack2(p[0][0], p[0][1]), d1 = dec_pack2(p[0][2], p[0][3]);
+    const uint32_t d2 = dec_pack2(p[1][0], p[1][1]), d3 = dec_pack2(p[1][2], p[1][3]);
+    // row sum from the rounded probabilities, so numerator and denominator carry the same rounding
+    const float rs = dec_sum2(d3, dec_sum2(d2, dec_sum2(d1, dec_sum2(d0, 0.f))));
+    const u32x4 pf = u32x4{d0, d1, d2, d3};
     l_run = l_run * alpha + rs;
-    const u32x4 pf = u32x4{dec_pack2(p[0][0], p[0][1]), dec_pack2(p[0][2], p[0][3]), dec_pack2(p[1][0], p[1][1]),
-                           dec_pack2(p[1][2], p[1][3])};
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       // column 8*j + c of the 8 keys this lane loaded: element c of each 16-byte row

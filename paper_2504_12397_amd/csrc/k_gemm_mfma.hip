@@ -6,8 +6,9 @@
 //   C[8*(v/4) + 4*(l/32) + v%4][l%32].
 // * Block tile BM x BN x 64, four waves, each WM x WN.  Tiles go global -> registers -> LDS with a
 //   two-tile register prefetch and two LDS buffers (one barrier per k-tile).  LDS rows are 128 B
-//   (8 chunks of 16 B); chunk c of row r sits at position c ^ (r & 7), so both the row-major
-//   stores and the 32-rows-one-chunk operand reads are bank-conflict free.
+//   (8 chunks of 16 B); chunk c of row r sits at position c ^ ((r >> 1) & 7): LDS serves a
+//   16-byte-per-lane access 16 lanes at a time over 64 banks, and with this swizzle 16 consecutive
+//   rows of one chunk (operand reads) as well as 2 rows x 8 chunks (stores) hit 64 distinct banks.
 // * Gated low-rank term of Eq.6 as extra k-steps BEFORE the main loop: for every adapter present
 //   in the row tile, A-operand = t = s*A_a x (as a bf16 pair hi + lo, zero for rows that are not
 //   adapted by a), B-operand = B_{a,p} (twice).  Rows that are not adapted accumulate exact zeros into zero
@@ -156,12 +157,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
       int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
-      As[row * 8 + (c ^ (row & 7))] = ra[i];
+      As[row * 8 + (c ^ ((row >> 1) & 7))] = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
       int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
-      Bs[row * 8 + (c ^ (row & 7))] = rb[i];
+      Bs[row * 8 + (c ^ ((row >> 1) & 7))] = rb[i];
     }
   };
   // One k-tile = four k-steps of 16.  The fragments of step ks+1 are read from LDS before the
@@ -171,12 +172,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
       int row = wm0 + mi * 32 + l32;
-      af[mi] = as_bf16x8(As[row * 8 + (c ^ (row & 7))]);
+      af[mi] = as_bf16x8(As[row * 8 + (c ^ ((row >> 1) & 7))]);
     }
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni) {
       int row = wn0 + ni * 32 + l32;
-      bfr[ni] = as_bf16x8(Bs[row * 8 + (c ^ (row & 7))]);
+      bfr[ni] = as_bf16x8(Bs[row * 8 + (c ^ ((row >> 1) & 7))]);
     }
   };
   auto mma = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
