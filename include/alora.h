@@ -113,7 +113,8 @@ const char *alora_status_string(alora_status s);
  * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
  * of attention into n chunks.  "gemm_splits": 0 = automatic, n > 0 = split the reduction axis
  * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128
- * block tiles for the QKV projection.  "profile": 0/1, see alora_profile_read.  Unknown key or bad
+ * block tiles for the QKV projection.  "attn_waves": 0 = automatic, 4 or 8 waves per workgroup
+ * in the prefill attention kernel.  "profile": 0/1, see alora_profile_read.  Unknown key or bad
  * value: ALORA_EINVAL. */
 alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
 

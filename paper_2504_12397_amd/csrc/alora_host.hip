@@ -59,6 +59,7 @@ struct alora_ctx {
   int opt_splits = 0;
   int opt_gemm_splits = 0;
   int opt_gemm_tile = 0;
+  int opt_attn_waves = 0;
   int n_cu = 256;
 };
 
@@ -258,6 +259,7 @@ struct Workspace {
   int k_splits = 1;
   bool attn_mfma = false;
   bool decode_mfma = false;
+  int attn_waves = 8;
   const int4 *qtiles = nullptr;
   int n_qtiles = 0;
 };
@@ -360,7 +362,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
       a.partials = direct ? nullptr : w.partials;
       a.out = direct ? (bf16 *)out : nullptr;
-      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, s);
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, s);
     } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
       DecodeArgs a{};
       a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
@@ -484,6 +486,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   const size_t esz = layers[0].dtype == ALORA_BF16 ? 2 : 4;
   const bool attn_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && !decode &&
                          attn_prefill_mfma_supported(L);
+  const int attn_waves = ctx->opt_attn_waves == 4 ? 4 : 8;
   int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
   const bool decode_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && decode &&
                            attn_decode_mfma_supported(L);
@@ -496,7 +499,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (attn_mfma && ctx->opt_splits == 0) {
     // one workgroup per (q-tile, kv head, split): aim at one full wave of workgroups over the chip,
     // with at least 256 keys per split
-    const int tq = attn_prefill_mfma_tokens_per_tile(L);
+    const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
     int64_t tiles = 0;
     for (int b = 0; b < B; ++b) tiles += (pl.seqs[b].n_new + tq - 1) / tq;
     tiles *= L.n_kv_heads;
@@ -520,7 +523,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   // to each other (heaviest q-tile first); the groups are dealt to the XCDs longest sequence first.
   std::vector<int4> qtiles;
   if (attn_mfma) {
-    const int tq = attn_prefill_mfma_tokens_per_tile(L);
+    const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
     std::vector<int> order;
     for (int b = 0; b < B; ++b)
       if (pl.seqs[b].n_new > 0) order.push_back(b);
@@ -559,6 +562,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.k_splits = k_splits;
   w.attn_mfma = attn_mfma;
   w.decode_mfma = decode_mfma;
+  w.attn_waves = attn_waves;
   w.qtiles = (const int4 *)(slot->dev + seq_bytes);
   w.n_qtiles = (int)qtiles.size();
 
@@ -674,6 +678,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "gemm_splits")) {
     if (value < 0 || value > 64) return fail(ctx, ALORA_EINVAL, "gemm_splits must be in [0, 64]");
     ctx->opt_gemm_splits = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "attn_waves")) {
+    if (value != 0 && value != 4 && value != 8) return fail(ctx, ALORA_EINVAL, "attn_waves must be 0, 4 or 8");
+    ctx->opt_attn_waves = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "gemm_tile")) {

@@ -60,10 +60,11 @@ constexpr int ATT_BN = 64;        // keys per tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-template <int G>
-__global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
+template <int G, int NW>      // NW waves per workgroup (8 or 4), 32 packed rows each
+__global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) {
   constexpr int H = 128;
-  constexpr int TQ = 256 / G;
+  constexpr int NT = 64 * NW;
+  constexpr int TQ = 32 * NW / G;
   constexpr int NB = 1;             // 32-row query blocks per wave
   __shared__ u32x4 Ks[2][ATT_BN * 16];
   __shared__ u32x4 Vs[2][H * 8];
@@ -120,43 +121,47 @@ __global__ __launch_bounds__(512) void attn_prefill_mfma_kernel(AttnArgs a) {
   // 4, one (quad, group) per thread: four 8-byte loads become four columns x four keys.
   // Two tiles are kept in flight in registers (sets 0 and 1) on top of the one being consumed
   // from LDS: one tile of compute is shorter than the HBM latency.
-  u32x4 rk0[2], rk1[2];
-  u32x2 rv0[4], rv1[4];
-  const int v_qd = tid >> 5, v_cg = tid & 31;
-  auto load_tile = [&](int t, u32x4 (&rk)[2], u32x2 (&rv)[4]) {
+  constexpr int KC = 1024 / NT;          // 16-byte K chunks per thread and tile
+  constexpr int CW = 2048 / NT;          // V columns per thread (for 4 keys): 4 or 8
+  constexpr int VW = CW / 2;             // 32-bit words per key
+  typedef uint32_t vword __attribute__((ext_vector_type(VW)));
+  u32x4 rk0[KC], rk1[KC];
+  vword rv0[4], rv1[4];
+  const int v_qd = tid / (H / CW), v_cg = tid % (H / CW);
+  auto load_tile = [&](int t, u32x4 (&rk)[KC], vword (&rv)[4]) {
     const int k0 = kbeg + t * ATT_BN;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int q = tid + i * 512, key = q >> 4, c = q & 15;
+    for (int i = 0; i < KC; ++i) {
+      const int q = tid + i * NT, key = q >> 4, c = q & 15;
       const int kidx = min(k0 + key, n_visible - 1);
       rk[i] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kidx * a.n_kv + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-      rv[i] = *reinterpret_cast<const u32x2 *>(Vp + (int64_t)kidx * a.n_kv + v_cg * 4);
+      rv[i] = *reinterpret_cast<const vword *>(Vp + (int64_t)kidx * a.n_kv + v_cg * CW);
     }
   };
-  auto store_tile = [&](int buf, const u32x4 (&rk)[2], const u32x2 (&rv)[4]) {
+  auto store_tile = [&](int buf, const u32x4 (&rk)[KC], const vword (&rv)[4]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int q = tid + i * 512, key = q >> 4, c = q & 15;
+    for (int i = 0; i < KC; ++i) {
+      const int q = tid + i * NT, key = q >> 4, c = q & 15;
       Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
     }
-    // V: this thread holds keys 4*v_qd..+3 for columns 4*v_cg..+3
+    // V: this thread holds keys 4*v_qd..+3 for columns CW*v_cg..+CW-1
     const int grp16 = v_qd >> 2, qi = v_qd & 3;
     const int vkh = qi & 1, halfpos = qi >> 1;
     const int vchunk = grp16 * 2 + vkh;
     u32x2 *vs2 = reinterpret_cast<u32x2 *>(Vs[buf]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < VW; ++j) {
       // even column 2j: low halves; odd column 2j+1: high halves
       u32x2 ev, od;
       ev.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x05040100u);
       ev.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x05040100u);
       od.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x07060302u);
       od.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x07060302u);
-      const int c0 = v_cg * 4 + 2 * j, c1 = c0 + 1;
+      const int c0 = v_cg * CW + 2 * j, c1 = c0 + 1;
       vs2[(c0 * 8 + (vchunk ^ v_swz(c0))) * 2 + halfpos] = ev;
       vs2[(c1 * 8 + (vchunk ^ v_swz(c1))) * 2 + halfpos] = od;
     }
@@ -327,18 +332,26 @@ bool attn_prefill_mfma_supported(const LayerDims &L) {
   return L.head_dim == 128 && (G == 1 || G == 2 || G == 4 || G == 8);
 }
 
-int attn_prefill_mfma_tokens_per_tile(const LayerDims &L) { return 256 / (L.n_q_heads / L.n_kv_heads); }
+int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves) {
+  return 32 * waves / (L.n_q_heads / L.n_kv_heads);
+}
 
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, hipStream_t s) {
-  if (n_work == 0) return;
+template <int NW>
+static void launch_attn_nw(const AttnArgs &a, int n_work, int G, hipStream_t s) {
   dim3 grid(n_work);
   switch (G) {
-    case 1: hipLaunchKernelGGL(attn_prefill_mfma_kernel<1>, grid, dim3(512), 0, s, a); break;
-    case 2: hipLaunchKernelGGL(attn_prefill_mfma_kernel<2>, grid, dim3(512), 0, s, a); break;
-    case 4: hipLaunchKernelGGL(attn_prefill_mfma_kernel<4>, grid, dim3(512), 0, s, a); break;
-    case 8: hipLaunchKernelGGL(attn_prefill_mfma_kernel<8>, grid, dim3(512), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((attn_prefill_mfma_kernel<1, NW>), grid, dim3(64 * NW), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((attn_prefill_mfma_kernel<2, NW>), grid, dim3(64 * NW), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((attn_prefill_mfma_kernel<4, NW>), grid, dim3(64 * NW), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((attn_prefill_mfma_kernel<8, NW>), grid, dim3(64 * NW), 0, s, a); break;
     default: break;
   }
+}
+
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, hipStream_t s) {
+  if (n_work == 0) return;
+  if (waves == 4) launch_attn_nw<4>(a, n_work, G, s);
+  else launch_attn_nw<8>(a, n_work, G, s);
 }
 
 }  // namespace alora

@@ -56,8 +56,8 @@ struct AttnArgs {
   bf16 *out;                // [T, n_q] final output, only with n_splits == 1
 };
 bool attn_prefill_mfma_supported(const LayerDims &L);
-int attn_prefill_mfma_tokens_per_tile(const LayerDims &L);
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, hipStream_t s);
+int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, hipStream_t s);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
 struct DecodeArgs {
