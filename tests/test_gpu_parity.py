@@ -325,3 +325,52 @@ def test_config5_one_layer_full_length(ab, ctx):
     shape = dataclasses.replace(b.shape, intermediate=0)
     case = H.make_case(shape, b.P, b.S, b.k, b.adapter, b.seed, prefix="random")
     check_case(ab, ctx, case)
+
+
+# ------------------------------------------------------------------ shapes off the main path and kernel options
+@pytest.mark.parametrize("hq,hkv,h,r", [(4, 4, 128, 16), (8, 4, 128, 32), (16, 2, 128, 16), (8, 2, 64, 16), (6, 2, 96, 8),
+                                         (8, 8, 128, 64)])
+def test_bf16_head_layouts(ab, ctx, hq, hkv, h, r):
+    """GQA group sizes 1, 2, 4, 8 on the MFMA kernels; head sizes and ranks they do not cover fall back to
+    the plain kernels -- every combination must still match the oracle."""
+    shape = wl.LayerShape(d=512, n_q_heads=hq, n_kv_heads=hkv, head_dim=h, rank=r, n_adapters=2)
+    case = H.make_case(shape, [130, 0, 65], [70, 40, 1], [130, 7, 60], [1, 0, 1], seed=500 + hq + h + r)
+    check_case(ab, ctx, case)
+    dcase = H.make_case(shape, [200, 31], [1, 1], [150, 31], [0, 1], seed=600 + hq + h + r)
+    check_case(ab, ctx, dcase, decode=True)
+
+
+@pytest.mark.parametrize("opts", [{"kernels": 1}, {"kv_splits": 1}, {"kv_splits": 5}, {"gemm_splits": 1}, {"gemm_splits": 4},
+                                  {"gemm_tile": 2}, {"attn_waves": 4}])
+def test_kernel_options_do_not_change_results(ab, opts):
+    c = ab.Context(0)
+    try:
+        for k_, v in opts.items():
+            c.set_option(k_, v)
+        case = H.make_case(SMALL_BF16, [700, 10], [150, 33], [700, 20], [0, 2], seed=700)
+        check_case(ab, c, case)
+        dcase = H.make_case(SMALL_BF16, [900, 64, 3], [1, 1, 1], [100, 64, 0], [1, -1, 2], seed=701)
+        check_case(ab, c, dcase, decode=True)
+    finally:
+        c.close()
+
+
+def test_long_positions_rotary_accuracy(ab, ctx):
+    """Positions near 33k: the rotary table is evaluated in double, so late positions stay accurate."""
+    shape = SMALL_BF16
+    case = H.make_case(shape, [32800], [40], [32800], [1], seed=702, prefix="random")
+    check_case(ab, ctx, case)
+
+
+def test_workspace_regrowth_and_context_reuse(ab):
+    """A small call, a larger one (workspace and rotary table regrow), then the small one again."""
+    c = ab.Context(0)
+    try:
+        small = H.make_case(SMALL_BF16, [50], [20], [50], [0], seed=703)
+        big = H.make_case(SMALL_BF16, [5000], [600], [5000], [1], seed=704, prefix="random")
+        a1, _ = check_case(ab, c, small)
+        check_case(ab, c, big)
+        a2, _ = check_case(ab, c, small)
+        assert torch.equal(a1.view(torch.int16), a2.view(torch.int16))
+    finally:
+        c.close()
