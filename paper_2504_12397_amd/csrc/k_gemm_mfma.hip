@@ -66,63 +66,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // ---- gated low-rank extension (Eq.6), split 0 only --------------------------------------
-  if (g.tlow != nullptr && split == 0) {
-    if (tid == 0) s_present = 0ull;
-    __syncthreads();
-    for (int r = tid; r < BM; r += 256) {
-      int row = m0 + r;
-      if (row < M) {
-        int a = g.row_adapter[row];
-        if (a >= 0) atomicOr(&s_present, 1ull << a);
-      }
-    }
-    __syncthreads();
-    unsigned long long present = s_present;
-    const int r = g.rank;
-    int a_row[TM];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi) {
-      int row = m0 + wm0 + mi * 32 + l32;
-      a_row[mi] = row < M ? g.row_adapter[row] : -1;
-    }
-    while (present) {
-      const int a = __builtin_ctzll(present);
-      present &= present - 1;
-      for (int ks2 = 0; ks2 < 2 * r; ks2 += 16) {     // k runs over [t_hi | t_lo] against [B | B]
-        const int ks = ks2 < r ? ks2 : ks2 - r;
-        bf16x8 bfrag[TN];
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni) {
-          int col = n0 + wn0 + ni * 32 + l32;
-          u32x4 u = u32x4{0, 0, 0, 0};
-          if (col < N) {
-            const bf16 *bp;
-            if (col < g.n_q) bp = g.Bq + ((int64_t)a * g.n_q + col) * r;
-            else if (col < g.n_q + g.n_kv) bp = g.Bk + ((int64_t)a * g.n_kv + (col - g.n_q)) * r;
-            else bp = g.Bv + ((int64_t)a * g.n_kv + (col - g.n_q - g.n_kv)) * r;
-            u = *reinterpret_cast<const u32x4 *>(bp + ks + lhi * 8);
-          }
-          bfrag[ni] = as_bf16x8(u);
-        }
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi) {
-          int row = m0 + wm0 + mi * 32 + l32;
-#pragma unroll
-          for (int ni = 0; ni < TN; ++ni) {
-            // the section (q, k or v) of this 32-column block selects which t to use
-            int colb = n0 + wn0 + ni * 32;
-            int p = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
-            u32x4 u = u32x4{0, 0, 0, 0};
-            if (a_row[mi] == a)
-              u = *reinterpret_cast<const u32x4 *>(g.tlow + ((int64_t)row * 3 + p) * 2 * r + ks2 + lhi * 8);
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(u), bfrag[ni], acc[mi][ni], 0, 0, 0);
-          }
-        }
-      }
-    }
-  }
-
   // ---- main loop --------------------------------------------------------------------------
   // Two tiles are kept in flight in registers (R0, R1) on top of the one being consumed from
   // LDS: with HBM latency in the microseconds, a single prefetched tile leaves the loads exposed.
@@ -205,8 +148,87 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   if (nk > 0) {
     load_tiles(0, ra0, rb0);
     load_tiles(min(1, nk - 1), ra1, rb1);
-    store_tiles(As0, Bs0, ra0, rb0);
   }
+
+  // ---- gated low-rank extension (Eq.6), split 0 only --------------------------------------
+  // (runs while the first two main-loop tiles are already on their way from memory; its own loads
+  // are issued two k-steps at a time before the MFMAs that use them)
+  if (g.tlow != nullptr && split == 0) {
+    if (tid == 0) s_present = 0ull;
+    __syncthreads();
+    for (int r = tid; r < BM; r += 256) {
+      int row = m0 + r;
+      if (row < M) {
+        int a = g.row_adapter[row];
+        if (a >= 0) atomicOr(&s_present, 1ull << a);
+      }
+    }
+    __syncthreads();
+    unsigned long long present = s_present;
+    const int r = g.rank;
+    int a_row[TM];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi) {
+      int row = m0 + wm0 + mi * 32 + l32;
+      a_row[mi] = row < M ? g.row_adapter[row] : -1;
+    }
+    // per 32-column block: which of q / k / v it belongs to, and the row of B it reads
+    int p_of[TN];
+    const bf16 *brow[TN];
+    bool col_ok[TN];
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni) {
+      const int colb = n0 + wn0 + ni * 32, col = colb + l32;
+      p_of[ni] = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
+      col_ok[ni] = col < N;
+      const int cc = col < N ? col : N - 1;
+      if (cc < g.n_q) brow[ni] = g.Bq + (int64_t)cc * r;
+      else if (cc < g.n_q + g.n_kv) brow[ni] = g.Bk + (int64_t)(cc - g.n_q) * r;
+      else brow[ni] = g.Bv + (int64_t)(cc - g.n_q - g.n_kv) * r;
+    }
+    while (present) {
+      const int a = __builtin_ctzll(present);
+      present &= present - 1;
+      for (int kb2 = 0; kb2 < 2 * r; kb2 += 32) {     // k runs over [t_hi | t_lo] against [B | B]
+        u32x4 bu[2][TN], au[2][TM][TN];
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          const int ks2 = kb2 + 16 * h2;
+          const bool live = ks2 < 2 * r;
+          const int ks = ks2 < r ? ks2 : ks2 - r;
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) {
+            bu[h2][ni] = u32x4{0, 0, 0, 0};
+            if (live && col_ok[ni]) {
+              const int64_t stride = (int64_t)(p_of[ni] == 0 ? g.n_q : g.n_kv) * r;
+              bu[h2][ni] = *reinterpret_cast<const u32x4 *>(brow[ni] + (int64_t)a * stride + ks + lhi * 8);
+            }
+          }
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi) {
+            const int row = m0 + wm0 + mi * 32 + l32;
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+              au[h2][mi][ni] = u32x4{0, 0, 0, 0};
+              if (live && a_row[mi] == a)
+                au[h2][mi][ni] =
+                    *reinterpret_cast<const u32x4 *>(g.tlow + ((int64_t)row * 3 + p_of[ni]) * 2 * r + ks2 + lhi * 8);
+            }
+          }
+        }
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(au[h2][mi][ni]), as_bf16x8(bu[h2][ni]),
+                                                                    acc[mi][ni], 0, 0, 0);
+      }
+    }
+  }
+
+  if (nk > 0) store_tiles(As0, Bs0, ra0, rb0);
   __syncthreads();
   for (int kt = 0; kt < nk; kt += 2) {
     load_tiles(min(kt + 2, nk - 1), ra0, rb0);
