@@ -246,6 +246,14 @@ def main():
         "roofline": roof,
         "kernels": kernels,
     }
+    # measured ceilings of this machine (register-only MFMA loop, 4 GiB streaming read) next to the nominal peaks
+    try:
+        mf, rd = ctx.measure_ceiling(0), ctx.measure_ceiling(1)
+        meas = mf if roof["bound"] == "mfma" else rd
+        result["ceilings"] = {"mfma_bf16_TFLOPs": mf, "hbm_read_GBps": rd,
+                              "dominant_kernel_frac_of_measured": roof["achieved"] / meas}
+    except ab.AloraError as e:
+        result["ceilings"] = {"error": str(e)}
     result["config"]["workload"] = {
         "c2": "c2: one 8B-class layer, bf16, 4096 cached base tokens + 256 adapted suffix tokens, rank 32",
         "c3": "c3: mixed batch, 16 sequences, prefix 512-8192, suffix 32-512, 4 rank-32 adapters, 3 base-only",

@@ -112,8 +112,8 @@ const char *alora_status_string(alora_status s);
  * for bf16 where the shape allows, plain fp32-FMA kernels otherwise), 1 = force the plain
  * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
  * of attention into n chunks.  "gemm_splits": 0 = automatic, n > 0 = split the reduction axis
- * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128
- * block tiles for the QKV projection.  "attn_waves": 0 = automatic, 4 or 8 waves per workgroup
+ * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128,
+ * 3 = 256x256 block tiles for the QKV projection.  "attn_waves": 0 = automatic, 4 or 8 waves per workgroup
  * in the prefill attention kernel.  "profile": 0/1, see alora_profile_read.  Unknown key or bad
  * value: ALORA_EINVAL. */
 alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
@@ -125,6 +125,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
  * "mlp_norm", "gate_up", "silu_mul", "down_proj".  alora_profile_reset clears the totals. */
 alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 alora_status alora_profile_reset(alora_ctx *ctx);
+
+/* Measured ceilings of this machine, to price the kernels next to the published peaks (for the
+ * callers that report roofline fractions): kind 0 = bf16 MFMA TFLOP/s of a register-only loop,
+ * kind 1 = HBM read GB/s of a 4 GiB stream (allocated and freed inside the call).  Synchronous. */
+alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value);
 
 /* Adapter-activated prefill (Section 2, Eq.6; cost model of Proposition 2: only the T new
  * rows are projected, and each attends over its sequence's cached-plus-new rows).

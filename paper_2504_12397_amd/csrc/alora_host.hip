@@ -686,7 +686,7 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
     return ALORA_OK;
   }
   if (!strcmp(key, "gemm_tile")) {
-    if (value < 0 || value > 2) return fail(ctx, ALORA_EINVAL, "gemm_tile must be 0, 1 or 2");
+    if (value < 0 || value > 3) return fail(ctx, ALORA_EINVAL, "gemm_tile must be 0, 1, 2 or 3");
     ctx->opt_gemm_tile = value;
     return ALORA_OK;
   }
@@ -711,6 +711,18 @@ alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *tota
       return ALORA_OK;
     }
   return fail(ctx, ALORA_EINVAL, "unknown kernel name '%s'", kernel);
+}
+
+alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value) {
+  if (!ctx) return ALORA_EINVAL;
+  ctx->err.clear();
+  if (!value || (kind != 0 && kind != 1)) return fail(ctx, ALORA_EINVAL, "kind must be 0 or 1 and value non-NULL");
+  if (ctx->device < 0) return fail(ctx, ALORA_EHIP, "validation-only context (device -1)");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  const double v = measure_ceiling(kind, ctx->n_cu, nullptr);
+  if (v < 0.0) return fail(ctx, ALORA_EHIP, "ceiling measurement failed");
+  *value = v;
+  return ALORA_OK;
 }
 
 alora_status alora_profile_reset(alora_ctx *ctx) {

@@ -26,13 +26,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
+// PF = tiles kept in flight in registers (2: for the weight-streaming shapes; 1: for the large
+// tiles whose accumulators leave no room for a second one).
+template <int BM, int BN, int WM, int WN, int EPI, int PF>
+__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int BK = 64;
   constexpr int WAVES_N = BN / WN;
-  static_assert((BM / WM) * WAVES_N == 4, "four waves per block");
+  constexpr int NT = 64 * (BM / WM) * WAVES_N;
+  static_assert(NT == 256 || NT == 512, "four or eight waves per block");
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
+  constexpr int A_CHUNKS = BM * 8 / NT, B_CHUNKS = BN * 8 / NT;
   extern __shared__ u32x4 smem[];
   __shared__ unsigned long long s_present;
   u32x4 *As0 = smem, *Bs0 = smem + BM * 8, *As1 = smem + (BM + BN) * 8, *Bs1 = As1 + BM * 8;
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   // ---- main loop --------------------------------------------------------------------------
   // Two tiles are kept in flight in registers (R0, R1) on top of the one being consumed from
   // LDS: with HBM latency in the microseconds, a single prefetched tile leaves the loads exposed.
-  u32x4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
+  u32x4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[PF == 2 ? A_CHUNKS : 1], rb1[PF == 2 ? B_CHUNKS : 1];
   auto b_src_row = [&](int j) -> int {      // LDS row j of the B tile -> row of the weight matrix
     if (EPI == GEMM_EPI_SWIGLU) {
       int blk = j >> 5;
@@ -83,14 +86,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     const int k0 = k_beg + kt * BK;
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
-      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
+      int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       int gr = m0 + row;
       gr = gr < M ? gr : M - 1;
       ra[i] = *reinterpret_cast<const u32x4 *>(g.A + (int64_t)gr * g.lda + k0 + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
+      int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       const bf16 *base = g.B;
       if (EPI == GEMM_EPI_SWIGLU && ((row >> 5) & 1)) base = g.B2;
       rb[i] = *reinterpret_cast<const u32x4 *>(base + (int64_t)b_src_row(row) * g.ldb + k0 + c * 8);
@@ -99,12 +102,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   auto store_tiles = [&](u32x4 *As, u32x4 *Bs, const u32x4 (&ra)[A_CHUNKS], const u32x4 (&rb)[B_CHUNKS]) {
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
-      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
+      int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       As[row * 8 + (c ^ ((row >> 1) & 7))] = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-      int q2 = tid + i * 256, row = q2 >> 3, c = q2 & 7;
+      int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       Bs[row * 8 + (c ^ ((row >> 1) & 7))] = rb[i];
     }
   };
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   // compiler can count outstanding loads exactly and wait only for the tile it is about to store.
   if (nk > 0) {
     load_tiles(0, ra0, rb0);
-    load_tiles(min(1, nk - 1), ra1, rb1);
+    if constexpr (PF == 2) load_tiles(min(1, nk - 1), ra1, rb1);
   }
 
   // ---- gated low-rank extension (Eq.6), split 0 only --------------------------------------
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   if (g.tlow != nullptr && split == 0) {
     if (tid == 0) s_present = 0ull;
     __syncthreads();
-    for (int r = tid; r < BM; r += 256) {
+    for (int r = tid; r < BM; r += NT) {
       int row = m0 + r;
       if (row < M) {
         int a = g.row_adapter[row];
@@ -189,10 +192,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     while (present) {
       const int a = __builtin_ctzll(present);
       present &= present - 1;
-      for (int kb2 = 0; kb2 < 2 * r; kb2 += 32) {     // k runs over [t_hi | t_lo] against [B | B]
-        u32x4 bu[2][TN], au[2][TM][TN];
+      constexpr int PB = TM * TN > 4 ? 1 : 2;         // k-steps whose loads are issued together
+      for (int kb2 = 0; kb2 < 2 * r; kb2 += 16 * PB) {     // k runs over [t_hi | t_lo] against [B | B]
+        u32x4 bu[PB][TN], au[PB][TM][TN];
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
+        for (int h2 = 0; h2 < PB; ++h2) {
           const int ks2 = kb2 + 16 * h2;
           const bool live = ks2 < 2 * r;
           const int ks = ks2 < r ? ks2 : ks2 - r;
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
           }
         }
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
+        for (int h2 = 0; h2 < PB; ++h2)
 #pragma unroll
           for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -230,15 +234,26 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
   if (nk > 0) store_tiles(As0, Bs0, ra0, rb0);
   __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    load_tiles(min(kt + 2, nk - 1), ra0, rb0);
-    compute(As0, Bs0);
-    store_tiles(As1, Bs1, ra1, rb1);
-    __syncthreads();
-    load_tiles(min(kt + 3, nk - 1), ra1, rb1);
-    if (kt + 1 < nk) compute(As1, Bs1);
-    store_tiles(As0, Bs0, ra0, rb0);
-    __syncthreads();
+  if constexpr (PF == 2) {
+    for (int kt = 0; kt < nk; kt += 2) {
+      load_tiles(min(kt + 2, nk - 1), ra0, rb0);
+      compute(As0, Bs0);
+      store_tiles(As1, Bs1, ra1, rb1);
+      __syncthreads();
+      load_tiles(min(kt + 3, nk - 1), ra1, rb1);
+      if (kt + 1 < nk) compute(As1, Bs1);
+      store_tiles(As0, Bs0, ra0, rb0);
+      __syncthreads();
+    }
+  } else {
+    for (int kt = 0; kt < nk; ++kt) {
+      u32x4 *Ac = (kt & 1) ? As1 : As0, *Bc = (kt & 1) ? Bs1 : Bs0;
+      u32x4 *An = (kt & 1) ? As0 : As1, *Bn = (kt & 1) ? Bs0 : Bs1;
+      load_tiles(min(kt + 1, nk - 1), ra0, rb0);
+      compute(Ac, Bc);
+      store_tiles(An, Bn, ra0, rb0);
+      __syncthreads();
+    }
   }
 
   // ---- epilogue ---------------------------------------------------------------------------
@@ -275,18 +290,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int PF = 2>
 static void launch_cfg(const GemmArgs &g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(8 * ((tiles_n + 7) / 8) * tiles_m * g.k_splits);
   size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(u32x4);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, PF>;
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
   static bool configured = false;
   if (!configured) {
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     configured = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, g);
+  hipLaunchKernelGGL(kern, grid, dim3(NT), smem, s, g);
 }
 
 // C = bf16( sum over splits of partial sums (fixed order) + residual )
@@ -327,6 +343,7 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
   if (epi == GEMM_EPI_PARTIAL) {
     if (g.tile_hint == 2) launch_cfg<256, 128, 128, 64, GEMM_EPI_PARTIAL>(g, s);
+    else if (g.tile_hint == 3) launch_cfg<256, 256, 64, 128, GEMM_EPI_PARTIAL, 1>(g, s);
     else launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;

@@ -73,6 +73,9 @@ struct DecodeArgs {
 bool attn_decode_mfma_supported(const LayerDims &L);
 void launch_attn_decode_mfma(const DecodeArgs &a, int n_rows, hipStream_t s);
 
+// Measured ceilings: kind 0 = bf16 MFMA TFLOP/s (register-only loop), kind 1 = HBM read GB/s (4 GiB stream).
+double measure_ceiling(int kind, int n_cu, hipStream_t s);
+
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s);
