@@ -388,25 +388,43 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ 
   }
 }
 
+// One wave per (row, query head), four per workgroup.  The per-split maxima are fetched by the
+// first lanes in parallel, and the accumulators are read four splits at a time (fixed order).
 template <typename T>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const float *__restrict__ part, LayerDims L, int n_splits,
-                                                        T *__restrict__ out) {
-  const int lane = threadIdx.x, h = L.head_dim;
-  const int64_t rh = blockIdx.x;                 // row * Hq + hq
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, LayerDims L, int n_splits,
+                                                         int64_t n_rh, T *__restrict__ out) {
+  const int lane = threadIdx.x & 63, h = L.head_dim;
+  const int64_t rh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);       // row * Hq + hq
+  if (rh >= n_rh) return;
   const float *p = part + rh * n_splits * (h + 2);
   float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[s * (h + 2) + h]);
+  for (int s0 = 0; s0 < n_splits; s0 += 64) {
+    const int s = s0 + lane;
+    M = fmaxf(M, s < n_splits ? p[s * (h + 2) + h] : -INFINITY);
+  }
+  M = wave_max(M);
   float denom = 0.f;
   float acc[ATT_DMAX] = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < n_splits; ++s) {
-    const float *ps = p + s * (h + 2);
-    float ms = ps[h];
-    float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
-    denom += w * ps[h + 1];
+  for (int s0 = 0; s0 < n_splits; s0 += 4) {
+    float ms[4], ls[4], v[4][ATT_DMAX];
 #pragma unroll
-    for (int dd = 0; dd < ATT_DMAX; ++dd) {
-      int c = lane + 64 * dd;
-      if (c < h) acc[dd] += w * ps[c];
+    for (int u = 0; u < 4; ++u) {
+      const int s = min(s0 + u, n_splits - 1);
+      const float *ps = p + s * (h + 2);
+      ms[u] = ps[h];
+      ls[u] = ps[h + 1];
+#pragma unroll
+      for (int dd = 0; dd < ATT_DMAX; ++dd) {
+        const int c = lane + 64 * dd;
+        v[u][dd] = c < h ? ps[c] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = (s0 + u >= n_splits || ms[u] == -INFINITY) ? 0.f : __expf(ms[u] - M);
+      denom += w * ls[u];
+#pragma unroll
+      for (int dd = 0; dd < ATT_DMAX; ++dd) acc[dd] += w * v[u][dd];
     }
   }
   const float inv = 1.0f / denom;
@@ -439,8 +457,9 @@ template void launch_attn_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, 
 template <typename T>
 void launch_attn_merge(const float *partials, const LayerDims &L, int T_rows, int n_splits, T *out, hipStream_t s) {
   if (T_rows == 0) return;
-  hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(T_rows * L.n_q_heads), dim3(64), 0, s, partials, L, n_splits,
-                     out);
+  const int64_t n_rh = (int64_t)T_rows * L.n_q_heads;
+  hipLaunchKernelGGL((attn_merge_kernel<T>), dim3((unsigned)((n_rh + 3) / 4)), dim3(256), 0, s, partials, L, n_splits,
+                     n_rh, out);
 }
 template void launch_attn_merge<float>(const float *, const LayerDims &, int, int, float *, hipStream_t);
 template void launch_attn_merge<bf16>(const float *, const LayerDims &, int, int, bf16 *, hipStream_t);

@@ -1,8 +1,8 @@
 // Row preparation with MFMA (bf16): per-row metadata, RMSNorm, and the low-rank down projection
 // t = s_a * A_a x_hat (Eq.6, Delta applied right to left) for 16 packed rows per workgroup.
 //
-// Eight waves split the hidden dimension; each lane owns 8 consecutive elements of one row at a
-// time, which is both the 16-byte global access and the A-operand layout of
+// Eight waves split the hidden dimension (d = 512, 1024, 2048 or 4096); each lane owns 8 consecutive
+// elements of one row at a time, which is both the 16-byte global access and the A-operand layout of
 // v_mfma_f32_16x16x32_bf16 (lane l: row l%16, k = 8*(l/16)..+7), so the normalised row goes from
 // registers straight into the MFMA and into the x_hat store; LDS is used only for the row
 // statistics and the fixed-order sum of the eight partial accumulators.
@@ -19,10 +19,12 @@ constexpr int PREP_WAVES = 8;
 
 // NF = 16-column fragments of t this workgroup computes (0: no adapter work).  The 3*rank columns
 // of t are spread over gridDim.y workgroups so that short batches still fill the chip; group 0
-// also writes x_hat and the row metadata.
-template <int NF, int PREP_UN>      // PREP_UN: k-steps (of 32) whose loads are issued together
+// also writes x_hat and the row metadata.  CH = d / 256: 16-byte chunks of its row each lane
+// holds.  x is read from memory once: the chunks stay in registers from the sum of squares to the
+// normalised store and the MFMAs, and every phase issues all its loads before the first use, so
+// the kernel pays about three memory round trips in total.
+template <int NF, int CH>
 __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
-  __shared__ float s_rinv[PREP_ROWS];
   __shared__ float s_ssq[PREP_WAVES][PREP_ROWS];
   __shared__ int s_adapter[PREP_ROWS];
   __shared__ float s_scale[PREP_ROWS];
@@ -32,30 +34,43 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int row0 = blockIdx.x * PREP_ROWS;
-  const int d = a.d;
+  const int d = a.d;                            // = CH * 256
   const int col0 = blockIdx.y * 16 * NF;       // first column of t handled here
   const bool lead = blockIdx.y == 0;
+  const int row = min(row0 + r16, a.T - 1);
+  const bool row_ok = row0 + r16 < a.T;
+  const int k_lo = wave * (CH * 32) + kg * 8;  // this lane's first element; chunk u is at k_lo + 32 u
+
+  // ---- all of this lane's x (and gain) chunks, issued at once ----------------------------------
+  u32x4 xr[CH], gr[CH];
+  const bf16 *xrow = a.x + (int64_t)row * d + k_lo;
+#pragma unroll
+  for (int u = 0; u < CH; ++u) xr[u] = *reinterpret_cast<const u32x4 *>(xrow + 32 * u);
+  if (a.gain != nullptr) {
+#pragma unroll
+    for (int u = 0; u < CH; ++u) gr[u] = *reinterpret_cast<const u32x4 *>(a.gain + k_lo + 32 * u);
+  }
 
   if (tid == 0) s_present = 0ull;
   __syncthreads();
   if (tid < PREP_ROWS) {
-    const int row = row0 + tid;
+    const int mrow = row0 + tid;
     int adapter = -1;
     float scale = 0.f;
-    if (row < a.T && a.seqs != nullptr) {
-      int lo = 0, hi = a.n_seqs - 1;           // last sequence whose first row is <= row
+    if (mrow < a.T && a.seqs != nullptr) {
+      int lo = 0, hi = a.n_seqs - 1;           // last sequence whose first row is <= mrow
       while (lo < hi) {
         int mid = (lo + hi + 1) >> 1;
-        if (a.seqs[mid].row_start <= row) lo = mid; else hi = mid - 1;
+        if (a.seqs[mid].row_start <= mrow) lo = mid; else hi = mid - 1;
       }
       const SeqMeta sm = a.seqs[lo];
-      const int pos = sm.P + (row - sm.row_start);
+      const int pos = sm.P + (mrow - sm.row_start);
       if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
       if (a.write_meta && lead) {
-        a.rm.seq[row] = lo;
-        a.rm.pos[row] = pos;
-        a.rm.adapter[row] = adapter;
-        a.rm.slot[row] = sm.pool_off + pos;
+        a.rm.seq[mrow] = lo;
+        a.rm.pos[mrow] = pos;
+        a.rm.adapter[mrow] = adapter;
+        a.rm.slot[mrow] = sm.pool_off + pos;
       }
     }
     s_adapter[tid] = adapter;
@@ -63,113 +78,73 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
     if (adapter >= 0) atomicOr(&s_present, 1ull << adapter);
   }
 
-  // ---- pass 1: sum of squares of every row.  Each wave covers its own slice of d for all 16
-  // rows, 16 independent loads at a time, and the eight slices are added in a fixed order.
+  // ---- sum of squares: lane -> the 4 lanes of a row -> the 8 waves (fixed order) ------------------
+  float rinv = 1.f;
   if (a.gain != nullptr) {
-    const int slice1 = d / PREP_WAVES;
-    float ssq[PREP_ROWS];
+    float ssq = 0.f;
 #pragma unroll
-    for (int r = 0; r < PREP_ROWS; ++r) ssq[r] = 0.f;
-    for (int c = wave * slice1 + lane * 8; c < (wave + 1) * slice1; c += 64 * 8) {
-      u32x4 raw[PREP_ROWS];
+    for (int u = 0; u < CH; ++u) {
+      const bf16x8 v = __builtin_bit_cast(bf16x8, xr[u]);
 #pragma unroll
-      for (int r = 0; r < PREP_ROWS; ++r)
-        raw[r] = *reinterpret_cast<const u32x4 *>(a.x + (int64_t)min(row0 + r, a.T - 1) * d + c);
-#pragma unroll
-      for (int r = 0; r < PREP_ROWS; ++r) {
-        const bf16x8 v = __builtin_bit_cast(bf16x8, raw[r]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ssq[r] += f * f; }
-      }
+      for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ssq += f * f; }
     }
-#pragma unroll
-    for (int r = 0; r < PREP_ROWS; ++r) {
-      const float t = wave_sum(ssq[r]);
-      if (lane == 0) s_ssq[wave][r] = t;
-    }
-    __syncthreads();
-    if (tid < PREP_ROWS) {
-      float t = 0.f;
-#pragma unroll
-      for (int w = 0; w < PREP_WAVES; ++w) t += s_ssq[w][tid];
-      s_rinv[tid] = 1.0f / sqrtf(t / (float)d + a.eps);
-    }
-  } else if (tid < PREP_ROWS) {
-    s_rinv[tid] = 1.f;
+    ssq += __shfl_xor(ssq, 16, 64);
+    ssq += __shfl_xor(ssq, 32, 64);
+    if (kg == 0) s_ssq[wave][r16] = ssq;
   }
   __syncthreads();
+  if (a.gain != nullptr) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < PREP_WAVES; ++w) t += s_ssq[w][r16];
+    rinv = 1.0f / sqrtf(t / (float)d + a.eps);
+    // normalise in place: x_hat = bf16(x * g * rinv)
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const bf16x8 xv = __builtin_bit_cast(bf16x8, xr[u]), gv = __builtin_bit_cast(bf16x8, gr[u]);
+      bf16x8 xh;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
+      xr[u] = __builtin_bit_cast(u32x4, xh);
+    }
+  }
+  if (lead && row_ok) {
+    bf16 *dst = a.xh + (int64_t)row * d + k_lo;
+#pragma unroll
+    for (int u = 0; u < CH; ++u) *reinterpret_cast<u32x4 *>(dst + 32 * u) = xr[u];
+  }
 
-  // ---- pass 2: normalise, store x_hat, accumulate t partials over this wave's slice of d --------
-  const int row = min(row0 + r16, a.T - 1);
-  const bool row_ok = row0 + r16 < a.T;
-  const float rinv = s_rinv[r16];
+  // ---- t partials over this wave's slice of d, one pass per adapter present in the row tile -------
   const int my_adapter = s_adapter[r16];
   const unsigned long long present = NF > 0 ? s_present : 0ull;
-  const int slice = d / PREP_WAVES;
-  const int k_lo = wave * slice;
+  const int rank = a.rank;
   f32x4 acc[NF > 0 ? NF : 1];
 #pragma unroll
   for (int j = 0; j < (NF > 0 ? NF : 1); ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int rank = a.rank;
-
-  // Both loops below run over this wave's slice in batches of PREP_UN k-steps whose loads are all
-  // issued before the first use, so that the global-memory latency is paid once per batch.  The
-  // adapter loop is outside the k loop (x and the gain are cache hits on the later passes), which
-  // keeps the k loop free of data-dependent control.
-  auto xhat = [&](u32x4 xraw, u32x4 graw) -> bf16x8 {
-    const bf16x8 xv = __builtin_bit_cast(bf16x8, xraw);
-    if (a.gain == nullptr) return xv;
-    const bf16x8 gv = __builtin_bit_cast(bf16x8, graw);
-    bf16x8 xh;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
-    return xh;
-  };
-  const bf16 *xrow = a.x + (int64_t)row * d + kg * 8;
-  const bf16 *grow = (a.gain != nullptr ? a.gain : a.x) + kg * 8;      // dummy pointer when there is no gain
-  if (lead) {
-    for (int k0 = k_lo; k0 < k_lo + slice; k0 += 32 * PREP_UN) {
-      u32x4 xr[PREP_UN], gr[PREP_UN];
-#pragma unroll
-      for (int u = 0; u < PREP_UN; ++u) {
-        xr[u] = *reinterpret_cast<const u32x4 *>(xrow + k0 + 32 * u);
-        gr[u] = *reinterpret_cast<const u32x4 *>(grow + k0 + 32 * u);
-      }
-      if (row_ok) {
-#pragma unroll
-        for (int u = 0; u < PREP_UN; ++u)
-          *reinterpret_cast<u32x4 *>(a.xh + (int64_t)row * d + kg * 8 + k0 + 32 * u) =
-              __builtin_bit_cast(u32x4, xhat(xr[u], gr[u]));
-      }
-    }
-  }
   if (NF > 0) {
+    constexpr int NFX = NF > 0 ? NF : 1;
+    constexpr int UB = (16 / NFX) < 1 ? 1 : ((16 / NFX) > CH ? CH : (16 / NFX));     // k-steps per load batch
     unsigned long long todo = present;
     while (todo) {
       const int ad = __builtin_ctzll(todo);
       todo &= todo - 1;
       const bool mine = my_adapter == ad;
-      const bf16 *Ab = a.A + ((int64_t)ad * 3 * rank + col0 + r16) * d + kg * 8;     // row col0 + 16 j + r16
-      for (int k0 = k_lo; k0 < k_lo + slice; k0 += 32 * PREP_UN) {
-        u32x4 xr[PREP_UN], gr[PREP_UN], br[PREP_UN][NF];
+      const bf16 *Ab = a.A + ((int64_t)ad * 3 * rank + col0 + r16) * d + k_lo;     // row col0 + 16 j + r16
 #pragma unroll
-        for (int u = 0; u < PREP_UN; ++u) {
-          xr[u] = *reinterpret_cast<const u32x4 *>(xrow + k0 + 32 * u);
-          gr[u] = *reinterpret_cast<const u32x4 *>(grow + k0 + 32 * u);
+      for (int u0 = 0; u0 < CH; u0 += UB) {
+        u32x4 br[UB][NFX];
 #pragma unroll
-          for (int j = 0; j < NF; ++j)
-            br[u][j] = *reinterpret_cast<const u32x4 *>(Ab + (int64_t)j * 16 * d + k0 + 32 * u);
-        }
+        for (int u = 0; u < UB; ++u)
 #pragma unroll
-        for (int u = 0; u < PREP_UN; ++u) {
-          bf16x8 af = xhat(xr[u], gr[u]);
-          if (!mine) {
+          for (int j = 0; j < NFX; ++j)
+            br[u][j] = *reinterpret_cast<const u32x4 *>(Ab + (int64_t)j * 16 * d + 32 * (u0 + u));
 #pragma unroll
-            for (int e = 0; e < 8; ++e) af[e] = (bf16)0.f;
-          }
+        for (int u = 0; u < UB; ++u) {
+          const u32x4 au = mine ? xr[u0 + u] : u32x4{0, 0, 0, 0};
 #pragma unroll
-          for (int j = 0; j < NF; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, __builtin_bit_cast(bf16x8, br[u][j]), acc[j], 0, 0, 0);
+          for (int j = 0; j < NFX; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, au),
+                                                             __builtin_bit_cast(bf16x8, br[u][j]), acc[j], 0, 0, 0);
         }
       }
     }
@@ -202,14 +177,14 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
 }
 
 bool prep_rows_mfma_supported(int d, int rank) {
-  return d % (PREP_WAVES * 64 * 8) == 0 && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
+  return (d == 4096 || d == 2048 || d == 1024 || d == 512) && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
 }
 
-template <int NF, int UN>
+template <int NF, int CH>
 static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
   const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
-  auto kern = prep_rows_mfma_kernel<NF, UN>;
+  auto kern = prep_rows_mfma_kernel<NF, CH>;
   static bool configured = false;
   if (!configured && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -220,14 +195,13 @@ static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
 
 template <int NF>
 static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
-  // deep batches for the narrow variants (few accumulators, registers to spare), when d allows
-  if constexpr (NF <= 1) {
-    if (a.d % (PREP_WAVES * 32 * 8) == 0) { launch_prep_cfg<NF, 8>(a, groups, s); return; }
+  switch (a.d) {
+    case 4096: launch_prep_cfg<NF, 16>(a, groups, s); break;
+    case 2048: launch_prep_cfg<NF, 8>(a, groups, s); break;
+    case 1024: launch_prep_cfg<NF, 4>(a, groups, s); break;
+    case 512: launch_prep_cfg<NF, 2>(a, groups, s); break;
+    default: break;
   }
-  if constexpr (NF <= 3) {
-    if (a.d % (PREP_WAVES * 32 * 4) == 0) { launch_prep_cfg<NF, 4>(a, groups, s); return; }
-  }
-  launch_prep_cfg<NF, 2>(a, groups, s);
 }
 
 void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s) {
