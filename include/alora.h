@@ -153,6 +153,18 @@ alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_k
                           const void *x_tok, const int32_t *k_per_seq,
                           const int32_t *adapter_per_seq, int32_t B, void *attn_out, void *stream);
 
+/* A run of n_steps decode steps (the short generations of an adapter: Section 3 times 16-token
+ * evaluations) with the per-sequence arrays validated and staged once: the same result as n_steps
+ * alora_decode calls, step t reading x_steps[t] and writing attn_out[t], every sequence growing by
+ * one cache row per step.  For callers that already hold the inputs of all steps (teacher forcing,
+ * replay, benchmarks); a sampling loop that needs the output of step t to build step t+1 calls
+ * alora_decode.   x_steps DEVICE [n_steps, B, d]; attn_out DEVICE [n_steps, B, N_q];
+ * seq_len[b] += n_steps; P_b + n_steps must fit the capacity. */
+alora_status alora_decode_steps(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
+                                const void *x_steps, const int32_t *k_per_seq,
+                                const int32_t *adapter_per_seq, int32_t B, int32_t n_steps,
+                                void *attn_out, void *stream);
+
 /* First-token pass through a stack of decoder layers (Proposition 2: the attention block as
  * in alora_prefill, then the per-token unadapted output projection and SwiGLU MLP with
  * residuals, layer after layer).  layers[l] must all have the same shape and dtype and

@@ -17,7 +17,7 @@ ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDT
 ALORA_F32, ALORA_BF16 = 0, 1
 
 EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
-           "alora_profile_read", "alora_profile_reset", "alora_measure_ceiling", "alora_prefill", "alora_decode", "alora_stack_prefill"]
+           "alora_profile_read", "alora_profile_reset", "alora_measure_ceiling", "alora_prefill", "alora_decode", "alora_decode_steps", "alora_stack_prefill"]
 KERNELS = ["prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
            "mlp_norm", "gate_up", "silu_mul", "down_proj"]
 
@@ -66,6 +66,9 @@ def load_library() -> C.CDLL:
     lib.alora_decode.restype = C.c_int
     lib.alora_decode.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
                                  C.c_int32, C.c_void_p, C.c_void_p]
+    lib.alora_decode_steps.restype = C.c_int
+    lib.alora_decode_steps.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
+                                       C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.alora_stack_prefill.restype = C.c_int
     lib.alora_stack_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int32, C.POINTER(KVCacheDesc),
                                         C.c_void_p, i32p, i32p, i32p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -238,6 +241,21 @@ def alora_decode(ctx: Context, layer: Layer, cache: KVCache, x_tok: torch.Tensor
     p = C.POINTER(C.c_int32)
     st = _lib.alora_decode(ctx._h, C.byref(layer.desc), C.byref(cache.desc), _ptr(x_tok), kk.ctypes.data_as(p),
                            ad.ctypes.data_as(p), B, _ptr(attn_out), _stream_ptr(stream))
+    ctx._check(st)
+    return attn_out
+
+
+def alora_decode_steps(ctx: Context, layer: Layer, cache: KVCache, x_steps: torch.Tensor, k_per_seq: Sequence[int],
+                       adapter_per_seq: Sequence[int], attn_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """x_steps [n_steps, B, d] -> attn_out [n_steps, B, N_q]: n_steps decode steps staged once."""
+    kk, ad = _i32(k_per_seq), _i32(adapter_per_seq)
+    B = len(kk)
+    n_steps = int(x_steps.shape[0])
+    if attn_out is None:
+        attn_out = torch.empty((n_steps, B, layer.n_q), dtype=layer.dtype, device=layer.device)
+    p = C.POINTER(C.c_int32)
+    st = _lib.alora_decode_steps(ctx._h, C.byref(layer.desc), C.byref(cache.desc), _ptr(x_steps), kk.ctypes.data_as(p),
+                                 ad.ctypes.data_as(p), B, n_steps, _ptr(attn_out), _stream_ptr(stream))
     ctx._check(st)
     return attn_out
 

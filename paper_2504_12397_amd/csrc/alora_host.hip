@@ -204,7 +204,7 @@ alora_status check_layer(alora_ctx *ctx, const alora_layer_desc *ly, bool need_t
 }
 
 alora_status check_batch(alora_ctx *ctx, const alora_layer_desc *ly, const alora_kv_cache *cache,
-                         const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, Plan *pl) {
+                         const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, int n_steps, Plan *pl) {
   if (!cache) return fail(ctx, ALORA_EINVAL, "cache is NULL");
   if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
   if (!cu || !kps || !aps) return fail(ctx, ALORA_EINVAL, "cu_seqlens / k_per_seq / adapter_per_seq is NULL");
@@ -229,16 +229,18 @@ alora_status check_batch(alora_ctx *ctx, const alora_layer_desc *ly, const alora
     if (cap < 0 || off < 0 || off + cap > cache->pool_tokens)
       return fail(ctx, ALORA_ECAPACITY, "sequence %d: rows [%lld, %lld) lie outside the pool of %lld tokens", b,
                   (long long)off, (long long)(off + cap), (long long)cache->pool_tokens);
-    if ((int64_t)P + S > cap)
-      return fail(ctx, ALORA_ECAPACITY, "sequence %d: %d cached + %d new tokens exceed its capacity %d", b, P, S, cap);
-    if ((int64_t)P + S > (1 << 24))
-      return fail(ctx, ALORA_ECAPACITY, "sequence %d: position %lld beyond the supported 2^24", b, (long long)P + S);
+    const int64_t grown = (int64_t)P + (int64_t)S * n_steps;      // cached length after the call
+    if (grown > cap)
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: %d cached + %lld new tokens exceed its capacity %d", b, P,
+                  (long long)S * n_steps, cap);
+    if (grown > (1 << 24))
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: position %lld beyond the supported 2^24", b, (long long)grown);
     SeqMeta &m = pl->seqs[b];
     m.row_start = cu[b]; m.n_new = S; m.P = P; m.k = kps[b]; m.adapter = aps[b];
     m.scale = aps[b] >= 0 ? ly->scale[aps[b]] : 0.f;
     m.pool_off = off;
-    if (aps[b] >= 0 && S > 0 && (int64_t)P + S > kps[b]) pl->any_adapter = true;
-    pl->max_len = std::max(pl->max_len, P + S);
+    if (aps[b] >= 0 && S > 0 && grown > kps[b]) pl->any_adapter = true;
+    pl->max_len = std::max(pl->max_len, (int)grown);
   }
   pl->T = cu[B];
   return ALORA_OK;
@@ -306,7 +308,7 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
 template <typename T>
 void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, const alora_kv_cache *cache,
                      const T *x, const Plan &pl, const SeqMeta *seqs_dev, const Workspace &w, bool write_meta,
-                     int n_splits, bool decode, T *out, hipStream_t s) {
+                     int n_splits, bool decode, int pos_shift, T *out, hipStream_t s) {
   const bool mfma = w.mfma && std::is_same<T, bf16>::value;
   {
     ProfScope p(ctx, K_PREP, s);
@@ -314,14 +316,14 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
     if (mfma && prep_rows_mfma_supported(L.d, rank_used)) {
       PrepArgs pa{};
       pa.x = (const bf16 *)x; pa.gain = (const bf16 *)ly->rms_gain; pa.eps = ly->rms_eps;
-      pa.T = pl.T; pa.d = L.d; pa.seqs = seqs_dev; pa.n_seqs = pl.B;
+      pa.T = pl.T; pa.d = L.d; pa.seqs = seqs_dev; pa.n_seqs = pl.B; pa.pos_shift = pos_shift;
       pa.A = rank_used ? (const bf16 *)ly->A : nullptr; pa.rank = rank_used;
       pa.write_meta = write_meta ? 1 : 0;
       pa.xh = (bf16 *)w.xh; pa.tlow16 = (bf16 *)w.tlow; pa.rm = w.rm;
       launch_prep_rows_mfma(pa, s);
     } else {
-      launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, (const T *)ly->A,
-                          rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
+      launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, pos_shift,
+                          (const T *)ly->A, rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
     }
   }
   {
@@ -422,7 +424,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       pa.T = T_rows; pa.d = L.d; pa.xh = (bf16 *)w.hn; pa.rm = none;
       launch_prep_rows_mfma(pa, s);
     } else {
-      launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0,
+      launch_prep_rows<T>((const T *)w.h1, (const T *)ly->rms2_gain, ly->rms_eps, T_rows, L.d, nullptr, 0, 0,
                           (const T *)nullptr, 0, false, (T *)w.hn, nullptr, nullptr, none, s);
     }
   }
@@ -453,7 +455,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
 
 alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, alora_kv_cache *caches,
                  const void *x, const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, void *out,
-                 void *stream, bool stack, bool decode = false) {
+                 void *stream, bool stack, bool decode = false, int n_steps = 1) {
   if (!ctx) return ALORA_EINVAL;
   ctx->err.clear();
   if (n_layers < 1) return fail(ctx, ALORA_EINVAL, "n_layers = %d must be at least 1", n_layers);
@@ -474,7 +476,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   }
   Plan pl;
   pl.L = L;
-  st = check_batch(ctx, &layers[0], &caches[0], cu, kps, aps, B, &pl);
+  if (n_steps < 1) return fail(ctx, ALORA_EINVAL, "n_steps = %d must be at least 1", n_steps);
+  st = check_batch(ctx, &layers[0], &caches[0], cu, kps, aps, B, n_steps, &pl);
   if (st != ALORA_OK) return st;
   if (pl.T > 0 && (!x || !out)) return fail(ctx, ALORA_EINVAL, "x / out is NULL");
   if (pl.T == 0) return ALORA_OK;
@@ -568,17 +571,22 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {
-    if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, seqs_dev, w, true, n_splits, decode, (bf16 *)out, s);
-    else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, seqs_dev, w, true, n_splits, decode, (float *)out, s);
+    // n_steps > 1: a run of decode steps on the metadata staged once; step t sits t positions further on
+    for (int t = 0; t < n_steps; ++t) {
+      const char *xt = (const char *)x + (size_t)t * pl.T * L.d * esz;
+      char *ot = (char *)out + (size_t)t * pl.T * L.n_q * esz;
+      if (bf) attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)xt, pl, seqs_dev, w, true, n_splits, decode, t, (bf16 *)ot, s);
+      else attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)xt, pl, seqs_dev, w, true, n_splits, decode, t, (float *)ot, s);
+    }
   } else {
     const void *cur = x;
     for (int l = 0; l < n_layers; ++l) {
       void *nxt = (l == n_layers - 1) ? out : ((l & 1) ? w.xb : w.xa);
       if (bf) {
-        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, seqs_dev, w, l == 0, n_splits, false, (bf16 *)w.attn, s);
+        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, seqs_dev, w, l == 0, n_splits, false, 0, (bf16 *)w.attn, s);
         layer_tail<bf16>(ctx, &layers[l], L, (const bf16 *)cur, w, pl.T, (bf16 *)nxt, s);
       } else {
-        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, seqs_dev, w, l == 0, n_splits, false, (float *)w.attn, s);
+        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, seqs_dev, w, l == 0, n_splits, false, 0, (float *)w.attn, s);
         layer_tail<float>(ctx, &layers[l], L, (const float *)cur, w, pl.T, (float *)nxt, s);
       }
       cur = nxt;
@@ -587,7 +595,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   HIP_TRY(ctx, hipGetLastError());
   HIP_TRY(ctx, hipEventRecord(slot->ev, s));
   slot->in_flight = true;
-  for (int b = 0; b < B; ++b) caches[0].seq_len[b] += cu[b + 1] - cu[b];
+  for (int b = 0; b < B; ++b) caches[0].seq_len[b] += (cu[b + 1] - cu[b]) * n_steps;
   return ALORA_OK;
 }
 
@@ -748,6 +756,17 @@ alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_k
   std::vector<int32_t> cu(B + 1);
   for (int b = 0; b <= B; ++b) cu[b] = b;
   return run(ctx, layer, 1, cache, x_tok, cu.data(), k_per_seq, adapter_per_seq, B, attn_out, stream, false, true);
+}
+
+alora_status alora_decode_steps(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
+                                const void *x_steps, const int32_t *k_per_seq, const int32_t *adapter_per_seq,
+                                int32_t B, int32_t n_steps, void *attn_out, void *stream) {
+  if (!ctx) return ALORA_EINVAL;
+  if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
+  std::vector<int32_t> cu(B + 1);
+  for (int b = 0; b <= B; ++b) cu[b] = b;
+  return run(ctx, layer, 1, cache, x_steps, cu.data(), k_per_seq, adapter_per_seq, B, attn_out, stream, false, true,
+             n_steps);
 }
 
 alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers,

@@ -56,8 +56,8 @@ void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipS
 
 template <typename T>
 void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
-                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow, bf16 *tlow16,
-                      RowMeta rm, hipStream_t s);
+                      int n_seqs, int pos_shift, const T *A, int rank, bool write_meta, T *xh, float *tlow,
+                      bf16 *tlow16, RowMeta rm, hipStream_t s);
 
 // Y[T, n_qkv] (fp32) = xh W^T + gated low-rank term (Eq.6)
 template <typename T>

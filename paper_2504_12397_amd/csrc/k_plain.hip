@@ -36,7 +36,7 @@ void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipS
 template <typename T>
 __global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                         float eps, int d, const SeqMeta *__restrict__ seqs,
-                                                        int n_seqs, const T *__restrict__ A, int rank,
+                                                        int n_seqs, int pos_shift, const T *__restrict__ A, int rank,
                                                         int write_meta, T *__restrict__ xh,
                                                         float *__restrict__ tlow, bf16 *__restrict__ tlow16,
                                                         RowMeta rm) {
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x,
         if (seqs[mid].row_start <= row) lo = mid; else hi = mid - 1;
       }
       SeqMeta sm = seqs[lo];
-      int pos = sm.P + (row - sm.row_start);
+      int pos = sm.P + pos_shift + (row - sm.row_start);
       if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
       if (write_meta) {
         rm.seq[row] = lo;
@@ -114,15 +114,15 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const T *__restrict__ x,
 
 template <typename T>
 void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
-                      int n_seqs, const T *A, int rank, bool write_meta, T *xh, float *tlow, bf16 *tlow16,
-                      RowMeta rm, hipStream_t s) {
+                      int n_seqs, int pos_shift, const T *A, int rank, bool write_meta, T *xh, float *tlow,
+                      bf16 *tlow16, RowMeta rm, hipStream_t s) {
   if (T_rows == 0) return;
   hipLaunchKernelGGL((prep_rows_kernel<T>), dim3(T_rows), dim3(256), (size_t)d * sizeof(float), s, x, gain,
-                     eps, d, seqs, n_seqs, A, rank, write_meta ? 1 : 0, xh, tlow, tlow16, rm);
+                     eps, d, seqs, n_seqs, pos_shift, A, rank, write_meta ? 1 : 0, xh, tlow, tlow16, rm);
 }
-template void launch_prep_rows<float>(const float *, const float *, float, int, int, const SeqMeta *, int,
+template void launch_prep_rows<float>(const float *, const float *, float, int, int, const SeqMeta *, int, int,
                                       const float *, int, bool, float *, float *, bf16 *, RowMeta, hipStream_t);
-template void launch_prep_rows<bf16>(const bf16 *, const bf16 *, float, int, int, const SeqMeta *, int,
+template void launch_prep_rows<bf16>(const bf16 *, const bf16 *, float, int, int, const SeqMeta *, int, int,
                                      const bf16 *, int, bool, bf16 *, float *, bf16 *, RowMeta, hipStream_t);
 
 // ---------------------------------------------------------------------------------------

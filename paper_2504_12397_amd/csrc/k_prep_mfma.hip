@@ -64,7 +64,7 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
         if (a.seqs[mid].row_start <= mrow) lo = mid; else hi = mid - 1;
       }
       const SeqMeta sm = a.seqs[lo];
-      const int pos = sm.P + (mrow - sm.row_start);
+      const int pos = sm.P + a.pos_shift + (mrow - sm.row_start);
       if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
       if (a.write_meta && lead) {
         a.rm.seq[mrow] = lo;

@@ -33,6 +33,7 @@ struct PrepArgs {
   int T, d;
   const SeqMeta *seqs;      // nullptr: no metadata / adapters (plain RMSNorm)
   int n_seqs;
+  int pos_shift;            // added to every position (step index of a multi-step decode)
   const bf16 *A;            // [n_adapters, 3, rank, d] or nullptr
   int rank;
   int write_meta;

@@ -136,3 +136,22 @@ def test_null_pointers(ab, vctx):
     assert ab._lib.alora_set_option(vctx, b"kernels", 1) == ab.ALORA_OK
     assert ab._lib.alora_prefill(None, C.byref(desc), C.byref(cache), FakeBuf.PTR, cu.ctypes.data_as(p),
                                  k.ctypes.data_as(p), a.ctypes.data_as(p), B, FakeBuf.PTR, None) == ab.ALORA_EINVAL
+
+
+def test_decode_steps_validation(ab, vctx):
+    """A run of decode steps is checked as a whole: every step must fit the capacity."""
+    p = C.POINTER(C.c_int32)
+
+    def steps(n, **over):
+        desc, cache, cu, k, a, B, keep, ln = make_args(ab, **over)
+        st = ab._lib.alora_decode_steps(vctx, C.byref(desc), C.byref(cache), FakeBuf.PTR, k.ctypes.data_as(p),
+                                        a.ctypes.data_as(p), B, n, FakeBuf.PTR, None)
+        return ab._lib.alora_status_string(st).decode(), list(ln)
+
+    assert steps(0) == ("ALORA_EINVAL", [10, 20])
+    assert steps(-3) == ("ALORA_EINVAL", [10, 20])
+    assert steps(4, B=0) == ("ALORA_EINVAL", [10, 20])
+    # 20 cached + 81 steps > capacity 100; 80 steps fit (validation-only context then declines to launch)
+    assert steps(81) == ("ALORA_ECAPACITY", [10, 20])
+    assert steps(80) == ("ALORA_EHIP", [10, 20])
+    assert steps(2, seq_len=[99, 20]) == ("ALORA_ECAPACITY", [99, 20])

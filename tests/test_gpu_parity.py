@@ -111,6 +111,43 @@ def test_token_by_token_decode_chain(ab, ctx):
     assert H.rel_err(H.f64(torch.cat(outs)), ref_o) <= H.TOL["bf16"]
 
 
+@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_F32], ids=["bf16", "fp32"])
+def test_decode_steps_equals_oracle_and_decode_chain(ab, ctx, shape):
+    """A staged run of decode steps: same cache rows and outputs as the oracle's prefill of the same
+    tokens, with the invocation point falling before, inside and after the run."""
+    n = 7
+    P = [120, 33, 257, 64]
+    k = [100, 36, 400, 0]          # active throughout / from the 4th step on / never / adapter-free
+    a = [0, 1, 1, -1]
+    case = H.make_case(shape, P, [n] * 4, k, a, seed=305)
+    layer = H.gpu_layer(case, shape)
+    x_steps = torch.stack([torch.stack([case.x_new[b][t] for b in range(4)]) for t in range(n)]).cuda().contiguous()
+    ref_o, new_rows = H.oracle_prefill(case)
+    tol = H.TOL[shape.dtype]
+
+    cache = H.gpu_cache(case, extra_capacity=0)
+    bk, bv = cache.k.cpu().clone(), cache.v.cpu().clone()
+    out = ab.alora_decode_steps(ctx, layer, cache, x_steps, k, a)
+    torch.cuda.synchronize()
+    assert out.shape == (n, 4, shape.n_q)
+    H.check_cache_after(case, cache, bk, bv, new_rows, tol)
+    got = torch.cat([out[:, b] for b in range(4)])          # the oracle's packed order: sequence-major
+    assert H.rel_err(H.f64(got), ref_o) <= tol
+
+    chain_cache = H.gpu_cache(case, extra_capacity=0)
+    chain = torch.stack([ab.alora_decode(ctx, layer, chain_cache, x_steps[t], k, a) for t in range(n)])
+    torch.cuda.synchronize()
+    assert np.array_equal(cache.seq_len, chain_cache.seq_len)
+    assert torch.equal(cache.k, chain_cache.k) and torch.equal(cache.v, chain_cache.v)
+    assert H.rel_err(H.f64(out.reshape(n * 4, -1)), H.f64(chain.reshape(n * 4, -1))) <= tol
+
+    # one step too many for the capacity: rejected before anything is written
+    full = H.gpu_cache(case, extra_capacity=0)
+    with pytest.raises(ab.AloraError):
+        ab.alora_decode_steps(ctx, layer, full, torch.cat([x_steps, x_steps[:1]]), k, a)
+    assert [int(v) for v in full.seq_len] == P
+
+
 # ------------------------------------------------------------------ invariants on the GPU
 def test_recompute_with_gated_weights_equals_cache_reuse(ab, ctx):
     """The brute-force identity through the ABI: P=0, S=L, k=P0 recomputes everything with
