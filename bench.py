@@ -5,7 +5,7 @@ A step is one pass of the whole hot path (row preparation, fused base + gated lo
 projection, rotary embedding + cache append, attention over [base prefix ; adapted suffix])
 over one batch of seeded synthetic input that is already resident in HBM.
 
-    python bench.py [--workload c2|c3|c4|c4x16|c5] [--steps K] [--warmup W]
+    python bench.py [--workload c2|c3|c4|c4x16|c5|r2] [--steps K] [--warmup W]
 
 prints ONE JSON line: suffix tokens/s, ms per step, the roofline of the dominant kernel
 (per-kernel durations from HIP events recorded by the library on the launch stream) and the
@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c4x16", "c5", "copy"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c4x16", "c5", "r2", "copy"],
                     help="copy: a plain 1 GiB device copy, the known-size kernel that calibrates the HBM counters")
     ap.add_argument("--rotate", type=int, default=-1,
                     help="distinct weight/cache sets cycled through so the last-level cache cannot hold the working set")
@@ -133,6 +133,8 @@ def main():
         print(json.dumps({"metric": "device_copy", "bytes_read": n, "bytes_written": n, "steps": steps,
                           "ms_per_step": sec * 1e3, "GBps_read_plus_write": 2 * n / sec / 1e9}))
         return
+    if name == "r2":
+        return regime2(args, ab, wl, torch, np, dev)
     # c4x16: the c4 batch generating 16 tokens per sequence (the length of an evaluator's answer,
     # Section 3) through one staged call; per-launch work is that of c4 (positions grow by 0.1%)
     n_dec = 1
@@ -303,6 +305,86 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(name, batch, shape, sets[0], x_new, n_layers)
 
+    print(json.dumps(result))
+    ctx.close()
+
+
+def regime2(args, ab, wl, torch, np, dev):
+    """Section 3, second regime: the adapter call prefills uncached context with base weights up to k
+    and the next base-model turn reuses those rows; compared with the base model prefilling the
+    context again (what it costs when the adapter call's cache cannot be reused)."""
+    first, then = wl.regime2()
+    shape = first.shape
+    steps, warmup = args.steps or 20, args.warmup or 3
+    ctx = ab.Context(0)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        ctx.set_option(key, int(val))
+    rng = wl.Rng(first.seed, dev)
+    layer = ab.Layer(wl.make_layer(shape, rng, "r2.L0"), shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                     shape.rms_eps, shape.rope_theta, shape.intermediate)
+    cache = ab.KVCache([first.T + then.T], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, dev)
+    x1 = wl.make_hidden(rng, "r2.x1", first.T, shape)
+    x2 = wl.make_hidden(rng, "r2.x2", then.T, shape)
+    o1 = torch.empty((first.T, shape.n_q), dtype=shape.torch_dtype, device=dev)
+    o2 = torch.empty((then.T, shape.n_q), dtype=shape.torch_dtype, device=dev)
+    x_re = torch.cat([x1[:then.P[0]], x2]).contiguous()
+    o_re = torch.empty((x_re.shape[0], shape.n_q), dtype=shape.torch_dtype, device=dev)
+
+    def step(_):
+        cache.seq_len[0] = 0
+        ab.alora_prefill(ctx, layer, cache, x1, first.cu_seqlens, first.k, first.adapter, o1)
+        cache.seq_len[0] = then.P[0]            # drop the adapted rows, keep the base rows before k
+        ab.alora_prefill(ctx, layer, cache, x2, then.cu_seqlens, then.k, then.adapter, o2)
+
+    def reprefill(_):
+        cache.seq_len[0] = 0
+        ab.alora_prefill(ctx, layer, cache, x_re, [0, x_re.shape[0]], [0], [-1], o_re)
+
+    def timed(f, n):
+        for i in range(warmup):
+            f(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            f(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    sec = timed(step, steps)
+    ctx.set_option("profile", 1)
+    ctx.profile_reset()
+    cache.seq_len[0] = then.P[0]
+    for _ in range(steps):
+        ab.alora_prefill(ctx, layer, cache, x2, then.cu_seqlens, then.k, then.adapter, o2)
+        cache.seq_len[0] = then.P[0]
+    torch.cuda.synchronize()
+    turn_prof = ctx.profile_read()
+    ctx.profile_reset()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.set_option("profile", 0)
+    turn_ms = sum(r["ms"] for r in turn_prof.values()) / steps
+    sec_re = timed(reprefill, max(2, steps // 2))
+    w1, w2 = algorithmic_work(first, shape), algorithmic_work(then, shape)
+    dominant = max(prof, key=lambda k_: prof[k_]["ms"])
+    both = {q: (w1[dominant][q] + w2[dominant][q]) / 2 for q in ("flops", "bytes")}     # per launch, two per step
+    roof = roofline_of(dominant, both, prof[dominant]["ms"] / prof[dominant]["launches"])
+    result = {
+        "metric": "alora_suffix_prefill_tok_per_s", "value": (first.T + then.T) / sec, "unit": "tok/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": "r2: adapter call over 4096 uncached context tokens + 256 adapted tokens (k=4096, P=0), "
+                               "then a 256-token base-model turn on the 4096 base rows that call created",
+                   "rank": shape.rank, "layers": 1},
+        "roofline": roof,
+        "kernels": {k_: dict(avg_ms=round(r["ms"] / r["launches"], 5), launches=r["launches"]) for k_, r in prof.items()},
+        "base_turn_with_reuse_ms": turn_ms,
+        "base_turn_reprefilling_context_ms": sec_re * 1e3,
+        "base_turn_saving": sec_re * 1e3 / turn_ms,
+    }
     print(json.dumps(result))
     ctx.close()
 

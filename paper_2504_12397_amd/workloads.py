@@ -184,6 +184,16 @@ def config2() -> Batch:
     return Batch(SHAPE_8B, P=[4096], S=[256], k=[4096], adapter=[0], name="c2", seed=BASE_SEED + 2)
 
 
+def regime2():
+    """Second cache-reuse regime of Section 3: an adapter call over 4096 tokens of context that the
+    base model has not cached (k = 4096 > P = 0) plus 256 adapted tokens, then a base-model turn of
+    256 tokens that reuses the 4096 base rows the adapter call left behind."""
+    seed = BASE_SEED + 6
+    first = Batch(SHAPE_8B, P=[0], S=[4096 + 256], k=[4096], adapter=[0], name="r2.adapter_call", seed=seed)
+    then = Batch(SHAPE_8B, P=[4096], S=[256], k=[0], adapter=[-1], name="r2.base_turn", seed=seed)
+    return first, then
+
+
 def config3() -> Batch:
     """Mixed batch: 16 sequences, 4 adapters, 3 sequences base-only."""
     seed = BASE_SEED + 3

@@ -148,6 +148,71 @@ def test_decode_steps_equals_oracle_and_decode_chain(ab, ctx, shape):
     assert [int(v) for v in full.seq_len] == P
 
 
+def _bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+def test_regime2_adapter_call_creates_the_base_cache(ab, ctx):
+    """Section 3, second cache-reuse regime: an adapter call over context the base model has not
+    seen yet (k > P: the call straddles its own invocation point) leaves base-model cache rows for
+    that context, and a later base-only call reuses them.  With a fixed reduction split the rows
+    before k are bit-identical whoever computes them and whatever else is in the batch."""
+    shape = SMALL_BF16
+    C0, inv, turn = 300, 40, 50            # uncached context, invocation + answer tokens, next base turn
+    ctx.set_option("gemm_splits", 1)
+    ctx.set_option("kv_splits", 1)
+    try:
+        case = H.make_case(shape, [0], [C0 + inv], [C0], [1], seed=306)
+        layer = H.gpu_layer(case, shape)
+        x = case.x_new[0].cuda().contiguous()
+
+        # (i) the adapter call alone: creates rows [0, C0) with base weights, [C0, C0+inv) adapted
+        c_ad = ab.KVCache([C0 + inv + turn], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY)
+        out_ad = ab.alora_prefill(ctx, layer, c_ad, x, [0, C0 + inv], [C0], [1])
+        ref_o, _ = H.oracle_prefill(case)
+        assert H.rel_err(H.f64(out_ad), ref_o) <= H.TOL["bf16"]
+
+        # (ii) the base model alone over the same context
+        c_base = ab.KVCache([C0 + turn], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY)
+        ab.alora_prefill(ctx, layer, c_base, x[:C0], [0, C0], [0], [-1])
+
+        # (iii) the adapter call inside a mixed batch (other sequences before and after it)
+        other = H.make_case(shape, [0, 0], [70, 129], [10, 0], [0, -1], seed=307)
+        c_mix = ab.KVCache([70, C0 + inv, 129], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY)
+        xm = torch.cat([other.x_new[0].cuda(), x, other.x_new[1].cuda()]).contiguous()
+        out_mix = ab.alora_prefill(ctx, layer, c_mix, xm, [0, 70, 70 + C0 + inv, 70 + C0 + inv + 129], [10, C0, 0],
+                                   [0, 1, -1])
+        torch.cuda.synchronize()
+
+        o_ad, o_base, o_mix = int(c_ad.seq_offset[0]), int(c_base.seq_offset[0]), int(c_mix.seq_offset[1])
+        for pool in ("k", "v"):
+            a_rows = _bits(getattr(c_ad, pool)[o_ad:o_ad + C0])
+            assert torch.equal(a_rows, _bits(getattr(c_base, pool)[o_base:o_base + C0])), f"{pool}: adapter call vs base call"
+            assert torch.equal(_bits(getattr(c_ad, pool)[o_ad:o_ad + C0 + inv]),
+                               _bits(getattr(c_mix, pool)[o_mix:o_mix + C0 + inv])), f"{pool}: alone vs in a batch"
+        assert torch.equal(_bits(out_ad), _bits(out_mix[70:70 + C0 + inv]))
+
+        # the next base-model turn over the rows the adapter call created: drop the adapted rows, continue
+        nxt = H.make_case(shape, [C0], [turn], [0], [-1], seed=308)
+        x_turn = nxt.x_new[0].cuda().contiguous()
+        c_ad.seq_len[0] = C0
+        out_reuse = ab.alora_prefill(ctx, layer, c_ad, x_turn, [0, turn], [0], [-1])
+        out_base = ab.alora_prefill(ctx, layer, c_base, x_turn, [0, turn], [0], [-1])
+        torch.cuda.synchronize()
+        assert torch.equal(_bits(out_reuse), _bits(out_base))
+        # and against the oracle: base rows for the context, then the base turn
+        lay = case.layer
+        xh = orc._normed(lay, H.f64(case.x_new[0][:C0]), "bf16")
+        pos = np.arange(C0)
+        _, kk, vv = orc.project_qkv(lay, xh, pos, 0, -1)
+        kk = orc._store(orc.rope(kk, pos, lay.n_kv_heads, lay.head_dim, lay.rope_theta), "bf16")
+        ref_turn, _, _ = orc.ref_cached(lay, kk, orc._store(vv, "bf16"), C0, H.f64(nxt.x_new[0]), 0, -1, "bf16")
+        assert H.rel_err(H.f64(out_reuse), ref_turn) <= H.TOL["bf16"]
+    finally:
+        ctx.set_option("gemm_splits", 0)
+        ctx.set_option("kv_splits", 0)
+
+
 # ------------------------------------------------------------------ invariants on the GPU
 def test_recompute_with_gated_weights_equals_cache_reuse(ab, ctx):
     """The brute-force identity through the ABI: P=0, S=L, k=P0 recomputes everything with
