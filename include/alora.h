@@ -114,7 +114,12 @@ const char *alora_status_string(alora_status s);
  * of attention into n chunks.  "gemm_splits": 0 = automatic, n > 0 = split the reduction axis
  * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128,
  * 3 = 256x256 block tiles for the QKV projection.  "attn_waves": 0 = automatic, 4 or 8 waves per workgroup
- * in the prefill attention kernel.  "profile": 0/1, see alora_profile_read.  Unknown key or bad
+ * in the prefill attention kernel.  "attn_pipeline": 1 (default) = prefill attention kernel that
+ * leaves the overlap of softmax and matrix work to the waves sharing a SIMD, 0 = the variant that
+ * software-pipelines the two inside each wave.  "attn_lazy": 0..16 (default 3), the running row
+ * maximum of the prefill attention kernels moves only when a block of scores exceeds it by more
+ * than this many powers of two (0 = exact maximum; the softmax is the same either way, only the
+ * scale of the intermediate probabilities changes).  "profile": 0/1, see alora_profile_read.  Unknown key or bad
  * value: ALORA_EINVAL. */
 alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
 

@@ -11,7 +11,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libalora.so")
+# ALORA_LIB: another build of the same library (kernel experiments); the default is the in-tree one
+LIB_PATH = os.environ.get("ALORA_LIB") or os.path.join(_HERE, "libalora.so")
 
 ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDTYPE, ALORA_EHIP = range(7)
 ALORA_F32, ALORA_BF16 = 0, 1

@@ -60,6 +60,8 @@ struct alora_ctx {
   int opt_gemm_splits = 0;
   int opt_gemm_tile = 0;
   int opt_attn_waves = 0;
+  int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
+  int opt_attn_pipeline = 1;     // 0 = software-pipelined attention kernel, 1 = the unpipelined one
   int n_cu = 256;
 };
 
@@ -362,9 +364,10 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
       a.n_splits = n_splits;
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
+      a.lazy = (float)ctx->opt_attn_lazy;
       a.partials = direct ? nullptr : w.partials;
       a.out = direct ? (bf16 *)out : nullptr;
-      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, s);
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, ctx->opt_attn_pipeline == 0, s);
     } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
       DecodeArgs a{};
       a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
@@ -521,29 +524,46 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
   if (st != ALORA_OK) return st;
   // staged metadata: per-sequence records, then the work list of the MFMA attention kernel.
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  All q-tiles of one
-  // (sequence, kv head, key split) read the same keys and values, so they go to the same XCD, next
-  // to each other (heaviest q-tile first); the groups are dealt to the XCDs longest sequence first.
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2, and an XCD starts them
+  // in list order as compute units become free.  All q-tiles of one (sequence, kv head, key split)
+  // read the same keys and values, so such a group goes to one XCD: groups are handed out heaviest
+  // first to the XCD with the least work so far, and inside an XCD the items run longest first
+  // (which keeps the q-tiles of a group next to each other: their lengths differ least).
   std::vector<int4> qtiles;
   if (attn_mfma) {
     const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
-    std::vector<int> order;
-    for (int b = 0; b < B; ++b)
-      if (pl.seqs[b].n_new > 0) order.push_back(b);
-    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
-      return (int64_t)(pl.seqs[x].P + pl.seqs[x].n_new) * pl.seqs[x].n_new >
-             (int64_t)(pl.seqs[y].P + pl.seqs[y].n_new) * pl.seqs[y].n_new;
-    });
-    std::vector<int4> per_xcd[8];
-    int next = 0;
-    for (int b : order)
+    struct Item { int64_t cost; int4 w; };
+    auto item_cost = [&](int b, int q0) {     // key tiles the item walks through
+      const int ntok = std::min(tq, pl.seqs[b].n_new - q0);
+      return (int64_t)((pl.seqs[b].P + q0 + ntok + 63) / 64 + n_splits - 1) / n_splits + 1;
+    };
+    struct Group { int64_t cost; int b, g, sp; };
+    std::vector<Group> groups;
+    for (int b = 0; b < B; ++b) {
+      if (pl.seqs[b].n_new <= 0) continue;
+      int64_t c = 0;
+      for (int q0 = 0; q0 < pl.seqs[b].n_new; q0 += tq) c += item_cost(b, q0);
       for (int g = 0; g < L.n_kv_heads; ++g)
-        for (int sp = 0; sp < n_splits; ++sp) {
-          std::vector<int4> &dst = per_xcd[next];
-          next = (next + 1) & 7;
-          const int last = ((pl.seqs[b].n_new - 1) / tq) * tq;
-          for (int q0 = last; q0 >= 0; q0 -= tq) dst.push_back(make_int4(b, q0, g, sp));
-        }
+        for (int sp = 0; sp < n_splits; ++sp) groups.push_back(Group{c, b, g, sp});
+    }
+    std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
+    std::vector<Item> per_xcd_items[8];
+    int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (const Group &gr : groups) {
+      int x = 0;
+      for (int i = 1; i < 8; ++i)
+        if (load[i] < load[x]) x = i;
+      load[x] += gr.cost;
+      const int last = ((pl.seqs[gr.b].n_new - 1) / tq) * tq;
+      for (int q0 = last; q0 >= 0; q0 -= tq)
+        per_xcd_items[x].push_back(Item{item_cost(gr.b, q0), make_int4(gr.b, q0, gr.g, gr.sp)});
+    }
+    std::vector<int4> per_xcd[8];
+    for (int x = 0; x < 8; ++x) {
+      std::stable_sort(per_xcd_items[x].begin(), per_xcd_items[x].end(),
+                       [](const Item &p, const Item &q) { return p.cost > q.cost; });
+      for (const Item &it : per_xcd_items[x]) per_xcd[x].push_back(it.w);
+    }
     size_t longest = 0;
     for (auto &v : per_xcd) longest = std::max(longest, v.size());
     qtiles.reserve(longest * 8);
@@ -686,6 +706,16 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "gemm_splits")) {
     if (value < 0 || value > 64) return fail(ctx, ALORA_EINVAL, "gemm_splits must be in [0, 64]");
     ctx->opt_gemm_splits = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "attn_lazy")) {
+    if (value < 0 || value > 16) return fail(ctx, ALORA_EINVAL, "attn_lazy must be in [0, 16]");
+    ctx->opt_attn_lazy = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "attn_pipeline")) {
+    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "attn_pipeline must be 0 or 1");
+    ctx->opt_attn_pipeline = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "attn_waves")) {

@@ -20,6 +20,8 @@
 // V^T tile in LDS: [128 columns][8 chunks of 16 B]; chunk (2*s4 + kh) of a column holds keys
 //   32*(s4/2) + 16*(s4%2) + {4kh..4kh+3, 8+4kh..8+4kh+3}  (s4 = k-step 0..3, kh = lane/32),
 //   stored at chunk ^ v_swz(column).
+#include <type_traits>
+
 #include "mfma_kernels.h"
 
 namespace alora {
@@ -46,6 +48,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // spreads the transposing 8-byte stores (columns 4 apart) to a 2-way conflict at worst.
 __device__ __forceinline__ int v_swz(int col) { return ((col >> 1) ^ (col >> 4)) & 7; }
 
+// max of a value with the one held by the lane 32 away (v_permlane32_swap: lanes 32..63 of the
+// first operand trade places with lanes 0..31 of the second)
+__device__ __forceinline__ float max_with_other_half(float x) {
+  typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const u32x2v r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, r.x), __builtin_bit_cast(float, r.y));
+}
+
 // acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
 __device__ __forceinline__ float sum_bf16x2(uint32_t pair, float acc) {
   typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -54,9 +65,6 @@ __device__ __forceinline__ float sum_bf16x2(uint32_t pair, float acc) {
 }
 
 constexpr int ATT_BN = 64;        // keys per tile
-#ifndef ATT_LAZY
-#define ATT_LAZY 0.0f
-#endif
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -214,13 +222,13 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         // The reference exponent m_run moves (and the 64 output accumulators are rescaled) only in
-        // blocks where some row of the wave sees a new maximum -- a wave-uniform decision.  ATT_LAZY
-        // > 0 would let it lag behind the true maximum by that many powers of two and skip almost
-        // all rescaling (the result is mathematically unchanged); it is 0 because with an exact
-        // maximum the largest probability of a row is exactly 1 in bf16, which measurably lowers
-        // the rounding error of peaked rows.
+        // blocks where some row of the wave exceeds it by more than a.lazy powers of two -- a
+        // wave-uniform decision.  The softmax is mathematically unchanged (numerator and
+        // denominator share the reference); probabilities reach 2^lazy instead of 1, with the same
+        // relative bf16 rounding.  With random scores a third of all blocks would otherwise move
+        // the maximum of some row and pay 64 multiplications per lane.
         const float m_blk = mx * c_scale;
-        const bool move = __any(m_blk > m_run[nb] + ATT_LAZY);
+        const bool move = __any(m_blk > m_run[nb] + a.lazy);
         const float m_new = move ? fmaxf(m_run[nb], m_blk) : m_run[nb];
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = move ? __builtin_amdgcn_exp2f(m_run[nb] - m_safe) : 1.0f;
@@ -327,6 +335,305 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Software-pipelined variant (the default).  Same work item, layouts and arithmetic as the kernel
+// above; what changes is the order in which one wave issues its work.  The loop advances in
+// 32-key blocks, and in step j a wave issues, as three independent instruction streams,
+//     matrix unit:  S(j+1) = K(j+1) Q^T   and   O^T += V(j-1)^T P(j-1)^T        (16 MFMAs)
+//     vector ALU :  online softmax of S(j) -> P(j)
+//     memory     :  LDS fragment reads for the MFMAs above, one half tile stored to LDS, one half
+//                   tile requested from global memory (two tiles ahead)
+// so the exponentials of one block run while the matrix unit works on its neighbours, inside the
+// wave, instead of relying on another wave being in a different phase.  The rescaling of O by
+// exp2(m_old - m_new) (Eq.1's softmax computed online) is applied after P(j-1) V(j-1) has been
+// accumulated, which is the same value: O_j = (O_{j-2} + P_{j-1} V_{j-1}) * alpha_j.
+//
+// LDS buffers are double: K(t+1) is stored during the first step of tile t (its slot was last
+// read two steps earlier), V(t+1) during the second (its slot was last read one step earlier);
+// one barrier per step orders them.
+template <int G>
+__global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
+  constexpr int H = 128;
+  constexpr int NT = 512;
+  constexpr int TQ = 256 / G;
+#ifndef ATT_AHEAD
+#define ATT_AHEAD 6
+#endif
+  constexpr int AH = ATT_AHEAD;      // LDS fragment reads in flight per wave
+  __shared__ u32x4 Ks[2][ATT_BN * 16];
+  __shared__ u32x4 Vs[2][H * 8];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, kh = lane >> 5;
+  const int4 wk = a.work[blockIdx.x];
+  if (wk.x < 0) return;
+  const int g = wk.z, split = wk.w;
+  const SeqMeta sm = a.seqs[wk.x];
+  const int q0 = wk.y;
+  const int ntok = min(TQ, sm.n_new - q0);
+  const int row0 = sm.row_start + q0;
+  const int n_visible = sm.P + q0 + ntok;
+  int chunk = (n_visible + a.n_splits - 1) / a.n_splits;
+  chunk = (chunk + ATT_BN - 1) & ~(ATT_BN - 1);
+  const int kbeg = split * chunk, kend = min(n_visible, kbeg + chunk);
+  const int ntiles = kend > kbeg ? (kend - kbeg + ATT_BN - 1) / ATT_BN : 0;
+  const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
+  const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
+  const int first_pos = sm.P + q0;
+
+  const int pr = wave * 32 + l32;
+  const int tok = pr / G, head = g * G + pr % G;
+  const int pos = tok < ntok ? first_pos + tok : -1;
+  u32x4 qf[8];
+  {
+    const bf16 *qp = a.Q + (int64_t)(row0 + min(tok, ntok - 1)) * a.n_q + head * H + kh * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const u32x4 *>(qp + ks * 16);
+  }
+  f32x16 o[4];
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[cb][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c_scale = a.sm_scale * LOG2E;
+
+  // ---- loaders: as in the kernel above, K and V handled separately ----------------------------
+  u32x4 rkA[2];
+  u32x2 rvA[4];
+  const int v_qd = tid >> 5, v_cg = tid & 31;
+  auto load_k = [&](int t, u32x4 (&rk)[2]) {
+    const int k0 = kbeg + min(t, ntiles - 1) * ATT_BN;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int q = tid + i * NT, key = q >> 4, c = q & 15;
+      const int kidx = min(k0 + key, n_visible - 1);
+      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kidx * a.n_kv + c * 8);
+    }
+  };
+  auto load_v = [&](int t, u32x2 (&rv)[4]) {
+    const int k0 = kbeg + min(t, ntiles - 1) * ATT_BN;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
+      rv[i] = *reinterpret_cast<const u32x2 *>(Vp + (int64_t)kidx * a.n_kv + v_cg * 4);
+    }
+  };
+  auto store_k = [&](int buf, const u32x4 (&rk)[2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int q = tid + i * NT, key = q >> 4, c = q & 15;
+      Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
+    }
+  };
+  auto store_v = [&](int buf, const u32x2 (&rv)[4]) {
+    const int grp16 = v_qd >> 2, qi = v_qd & 3;
+    const int vkh = qi & 1, halfpos = qi >> 1;
+    const int vchunk = grp16 * 2 + vkh;
+    u32x2 *vs2 = reinterpret_cast<u32x2 *>(Vs[buf]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      u32x2 ev, od;
+      ev.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x05040100u);
+      ev.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x05040100u);
+      od.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x07060302u);
+      od.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x07060302u);
+      const int c0 = v_cg * 4 + 2 * j, c1 = c0 + 1;
+      vs2[(c0 * 8 + (vchunk ^ v_swz(c0))) * 2 + halfpos] = ev;
+      vs2[(c1 * 8 + (vchunk ^ v_swz(c1))) * 2 + halfpos] = od;
+    }
+  };
+
+  f32x16 s_cur;          // S of the block whose softmax is next
+  u32x4 pf[2];           // P of the previous block (two k-steps of 16 keys), zero before the first
+  pf[0] = u32x4{0, 0, 0, 0};
+  pf[1] = u32x4{0, 0, 0, 0};
+
+  // S(block kb of the K tile in buffer kbuf)
+  auto qk_block = [&](int kbuf, int kb, f32x16 &s) {
+    const int key = kb * 32 + l32;
+    const u32x4 *kp = &Ks[kbuf][key * 16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(kp[(2 * ks + kh) ^ (key & 15)]), u4_as_bf16x8(qf[ks]), s, 0, 0, 0);
+  };
+  // O^T += V^T P^T for block kb of the V tile in buffer vbuf
+  auto pv_block = [&](int vbuf, int kb) {
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const int col = cb * 32 + l32, c = 2 * (kb * 2 + hf) + kh;
+        o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(Vs[vbuf][col * 8 + (c ^ v_swz(col))]),
+                                                        u4_as_bf16x8(pf[hf]), o[cb], 0, 0, 0);
+      }
+  };
+
+  const uint32_t k_base = (uint32_t)(l32 * 256 + ((kh ^ (l32 & 15)) << 4));
+  const uint32_t v_base = (uint32_t)(l32 * 128 + ((kh ^ v_swz(l32)) << 4));
+
+  // One pipeline step, written as 16 chunks of {one MFMA, one LDS fragment read three chunks ahead,
+  // a slice of vector work}; scheduling fences between the chunks keep the compiler from
+  // regrouping them, so the matrix unit gets a new instruction about every eight vector ones and
+  // only a few fragments are live at a time.
+  //   MFMA c < 8: O^T[cb] += V^T fragment (hf, cb) P(j-1)[hf] ; c >= 8: S(j+1) += K fragment c-8
+  //   (S(j) has been consumed by then, so S(j+1) takes over its registers)
+  //   vector slices: block maximum and rescale factor before the first MFMA (the fragment reads
+  //   are in flight meanwhile), two exponentials + pack + row-sum per chunk, then the LDS store
+  //   and the global prefetch that belong to this step (st, ld).
+  auto step_m = [&](auto need_mask, int k0, int kbuf, auto kb_c, int vbuf, auto vb_c, auto &&st, auto &&ld) {
+    constexpr int kb = decltype(kb_c)::value, vb = decltype(vb_c)::value;
+    // fragment addresses: one per-lane base each for K and V^T, the chunk swizzles are XORs with
+    // constants (bits 5..7 of the byte address) and everything else is an immediate offset
+    // (the bases pass through an empty asm so that the XORs stay inside the step, one
+    // instruction next to each read, instead of being hoisted into sixteen registers)
+    uint32_t k_bs = k_base + (uint32_t)(kbuf * (ATT_BN * 256)), v_bs = v_base + (uint32_t)(vbuf * (H * 128));
+    asm volatile("" : "+v"(k_bs), "+v"(v_bs));
+    auto rd = [&](int c) -> u32x4 {
+      const int i = c & 7;
+      if (c >= 8) {
+        // K chunk (2i + kh) ^ (key & 15) of row key = 32 kb + l32
+        const uint32_t ad = (k_bs ^ (uint32_t)(i << 5)) + (uint32_t)(kb * (32 * 256));
+        return *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(&Ks[0][0]) + ad);
+      }
+      // V^T chunk (2 (2 vb + hf) + kh) ^ v_swz(col) of row col = 32 cb + l32
+      const int hf = i >> 2, cb = i & 3;
+      const uint32_t ad = (v_bs ^ (uint32_t)(((2 * vb + hf) ^ cb) << 5)) + (uint32_t)(cb * (32 * 128));
+      return *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(&Vs[0][0]) + ad);
+    };
+    // fragments are requested AH chunks before their MFMA: with eight waves sharing the LDS a read
+    // takes a few hundred cycles to come back, so several per wave have to be in flight
+    u32x4 fr[16];
+#pragma unroll
+    for (int c = 0; c < AH; ++c) fr[c] = rd(c);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(need_mask)::value) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int kk = k0 + 8 * (v >> 2) + 4 * kh + (v & 3);
+        if (kk > pos || kk >= kend) s_cur[v] = -INFINITY;
+      }
+    }
+    float mx = s_cur[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v]);
+    mx = max_with_other_half(mx);
+    const float m_blk = mx * c_scale;
+    const bool move = __any(m_blk > m_run + a.lazy);
+    const float m_new = move ? fmaxf(m_run, m_blk) : m_run;
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);      // 1 exactly where the maximum stays
+    m_run = m_new;
+    asm volatile("" : "+v"(alpha));
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 s_nxt;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_nxt[v] = 0.f;
+    uint32_t pw[8];
+    float rs = 0.f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      if (c + AH < 16) fr[c + AH] = rd(c + AH);
+      const int i = c & 7;
+      if (c >= 8) {
+        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(fr[c]), u4_as_bf16x8(qf[i]), s_nxt, 0, 0, 0);
+      } else {
+        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(fr[c]), u4_as_bf16x8(pf[i >> 2]), o[i & 3], 0, 0, 0);
+      }
+      if (c < 8) {
+        // probabilities 2c, 2c+1 as a bf16 pair; the row sum is taken from the ROUNDED values so
+        // that numerator and denominator of the softmax carry the same rounding
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * c], c_scale, -m_safe));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * c + 1], c_scale, -m_safe));
+        pw[c] = pack_bf16x2(e0, e1);
+        rs = sum_bf16x2(pw[c], rs);
+        asm volatile("" : "+v"(pw[c]), "+v"(rs));      // keeps this slice in this chunk
+      } else if (c == 8) {
+        l_run = l_run * alpha + rs;
+      } else if (c == 10) {
+        st();
+      } else if (c == 12) {
+        ld();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (move) {     // after P(j-1) V(j-1) has been accumulated: O_j = (O + P V) * alpha
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[cb][v] *= alpha;
+    }
+    s_cur = s_nxt;
+    pf[0] = u32x4{pw[0], pw[1], pw[2], pw[3]};
+    pf[1] = u32x4{pw[4], pw[5], pw[6], pw[7]};
+  };
+  if (ntiles > 0) {
+    load_k(0, rkA); load_v(0, rvA);
+    store_k(0, rkA); store_v(0, rvA);
+    // the first step multiplies a zero P with whatever V buffer 1 holds: make that finite
+    for (int i = tid; i < H * 8; i += NT) Vs[1][i] = u32x4{0, 0, 0, 0};
+    load_k(1, rkA); load_v(1, rvA);
+    __syncthreads();
+    qk_block(0, 0, s_cur);
+  }
+  // Tile t sits in LDS buffer t & 1.  Its two steps: S(t, block 1) with V(t-1, block 1), then
+  // S(t+1, block 0) with V(t, block 0).  The causal / split-end mask is compiled into a second copy
+  // of the loop that takes over at the first tile that needs it (a branch inside a step would cut
+  // the region the three streams share).
+  auto tile_steps = [&](auto need_mask, int t) {
+    const int b = t & 1;
+    step_m(need_mask, kbeg + t * ATT_BN, b, std::integral_constant<int, 1>{}, b ^ 1, std::integral_constant<int, 1>{},
+           [&] { store_k(b ^ 1, rkA); }, [&] { load_k(t + 2, rkA); });
+    __syncthreads();
+    step_m(need_mask, kbeg + t * ATT_BN + 32, b ^ 1, std::integral_constant<int, 0>{}, b, std::integral_constant<int, 0>{},
+           [&] { store_v(b ^ 1, rvA); }, [&] { load_v(t + 2, rvA); });
+    __syncthreads();
+  };
+  // tiles [0, t_mask) lie entirely below the tile's first query position and inside the split
+  int t_mask = min(ntiles, max(0, (first_pos + 1 - kbeg) / ATT_BN));
+  if (kbeg + t_mask * ATT_BN > kend) --t_mask;
+  t_mask = max(t_mask, 0);
+  for (int t = 0; t < t_mask; ++t) tile_steps(std::false_type{}, t);
+  for (int t = t_mask; t < ntiles; ++t) tile_steps(std::true_type{}, t);
+  // drain: the last block's probabilities still wait for their V
+  if (ntiles > 0) pv_block((ntiles - 1) & 1, 1);
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (tok >= ntok) return;
+  const int64_t row = row0 + tok;
+  if (a.out != nullptr) {
+    const float inv = 1.0f / l_tot;
+    bf16 *op = a.out + row * a.n_q + head * H;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        const int col = cb * 32 + 8 * v4 + 4 * kh;
+        uint2 w;
+        w.x = pack_bf16x2(o[cb][4 * v4] * inv, o[cb][4 * v4 + 1] * inv);
+        w.y = pack_bf16x2(o[cb][4 * v4 + 2] * inv, o[cb][4 * v4 + 3] * inv);
+        *reinterpret_cast<uint2 *>(op + col) = w;
+      }
+  } else {
+    float *pp = a.partials + ((row * a.n_q_heads + head) * a.n_splits + split) * (H + 2);
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        const int col = cb * 32 + 8 * v4 + 4 * kh;
+        *reinterpret_cast<float2 *>(pp + col) = make_float2(o[cb][4 * v4], o[cb][4 * v4 + 1]);
+        *reinterpret_cast<float2 *>(pp + col + 2) = make_float2(o[cb][4 * v4 + 2], o[cb][4 * v4 + 3]);
+      }
+    if (kh == 0) {
+      pp[H] = m_run == -INFINITY ? -INFINITY : m_run * LN2;
+      pp[H + 1] = l_tot;
+    }
+  }
+}
+
 bool attn_prefill_mfma_supported(const LayerDims &L) {
   const int G = L.n_q_heads / L.n_kv_heads;
   return L.head_dim == 128 && (G == 1 || G == 2 || G == 4 || G == 8);
@@ -348,8 +655,19 @@ static void launch_attn_nw(const AttnArgs &a, int n_work, int G, hipStream_t s) 
   }
 }
 
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, hipStream_t s) {
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, hipStream_t s) {
   if (n_work == 0) return;
+  if (pipelined && waves == 8) {
+    dim3 grid(n_work);
+    switch (G) {
+      case 1: hipLaunchKernelGGL((attn_prefill_pipe_kernel<1>), grid, dim3(512), 0, s, a); break;
+      case 2: hipLaunchKernelGGL((attn_prefill_pipe_kernel<2>), grid, dim3(512), 0, s, a); break;
+      case 4: hipLaunchKernelGGL((attn_prefill_pipe_kernel<4>), grid, dim3(512), 0, s, a); break;
+      case 8: hipLaunchKernelGGL((attn_prefill_pipe_kernel<8>), grid, dim3(512), 0, s, a); break;
+      default: break;
+    }
+    return;
+  }
   if (waves == 4) launch_attn_nw<4>(a, n_work, G, s);
   else launch_attn_nw<8>(a, n_work, G, s);
 }

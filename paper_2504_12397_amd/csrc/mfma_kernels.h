@@ -53,12 +53,13 @@ struct AttnArgs {
   int n_q, n_kv, n_q_heads, n_kv_heads;
   int n_splits;             // key splits (grid.z)
   float sm_scale;           // 1 / sqrt(head_dim)
+  float lazy;               // the running maximum moves only when a block exceeds it by more than this (log2 units)
   float *partials;          // [T, n_q_heads, n_splits, head_dim + 2] (acc, max, sum), used when out == nullptr
   bf16 *out;                // [T, n_q] final output, only with n_splits == 1
 };
 bool attn_prefill_mfma_supported(const LayerDims &L);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, hipStream_t s);
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, hipStream_t s);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
 struct DecodeArgs {
