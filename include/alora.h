@@ -132,8 +132,10 @@ alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *tota
 alora_status alora_profile_reset(alora_ctx *ctx);
 
 /* Measured ceilings of this machine, to price the kernels next to the published peaks (for the
- * callers that report roofline fractions): kind 0 = bf16 MFMA TFLOP/s of a register-only loop,
- * kind 1 = HBM read GB/s of a 4 GiB stream (allocated and freed inside the call).  Synchronous. */
+ * callers that report roofline fractions): kind 0 = bf16 MFMA TFLOP/s of a register-only loop on
+ * constant operands, kind 1 = HBM read GB/s of a 4 GiB stream (allocated and freed inside the
+ * call), kind 2 = the MFMA loop on pseudo-random operands (the sustained clock depends on how much
+ * the operand bits toggle, so this is what a kernel on real data can reach).  Synchronous. */
 alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value);
 
 /* Adapter-activated prefill (Section 2, Eq.6; cost model of Proposition 2: only the T new

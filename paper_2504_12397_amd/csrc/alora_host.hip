@@ -399,6 +399,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       g.A = (const bf16 *)A; g.lda = K;
       g.B = (const bf16 *)W; g.ldb = K;
       g.M = T_rows; g.N = N; g.K = K;
+      g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
       // few row tiles: split the reduction to fill the chip, partial sums go through the Y buffer
       const int splits = gemm_mfma_pick_splits(T_rows, N, K, ctx->n_cu);
       if (splits > 1 && (size_t)splits * T_rows * N <= w.y_floats && ((int64_t)T_rows * N) % 4 == 0) {
@@ -437,6 +438,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     g.A = (const bf16 *)w.hn; g.lda = L.d;
     g.B = (const bf16 *)ly->W_gate; g.B2 = (const bf16 *)ly->W_up; g.ldb = L.d;
     g.M = T_rows; g.N = 2 * ly->intermediate; g.K = L.d; g.k_splits = 1;
+    g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
     g.C = (bf16 *)w.gate; g.ldc = ly->intermediate;
     launch_gemm_mfma(g, GEMM_EPI_SWIGLU, s);
   } else {
@@ -724,7 +726,7 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
     return ALORA_OK;
   }
   if (!strcmp(key, "gemm_tile")) {
-    if (value < 0 || value > 3) return fail(ctx, ALORA_EINVAL, "gemm_tile must be 0, 1, 2 or 3");
+    if (value < 0 || value > 4) return fail(ctx, ALORA_EINVAL, "gemm_tile must be in [0, 4]");
     ctx->opt_gemm_tile = value;
     return ALORA_OK;
   }
@@ -754,7 +756,7 @@ alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *tota
 alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value) {
   if (!ctx) return ALORA_EINVAL;
   ctx->err.clear();
-  if (!value || (kind != 0 && kind != 1)) return fail(ctx, ALORA_EINVAL, "kind must be 0 or 1 and value non-NULL");
+  if (!value || kind < 0 || kind > 2) return fail(ctx, ALORA_EINVAL, "kind must be 0, 1 or 2 and value non-NULL");
   if (ctx->device < 0) return fail(ctx, ALORA_EHIP, "validation-only context (device -1)");
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   const double v = measure_ceiling(kind, ctx->n_cu, nullptr);

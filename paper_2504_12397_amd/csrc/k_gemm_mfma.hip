@@ -344,14 +344,17 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   if (epi == GEMM_EPI_PARTIAL) {
     if (g.tile_hint == 2) launch_cfg<256, 128, 128, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (g.tile_hint == 3) launch_cfg<256, 256, 64, 128, GEMM_EPI_PARTIAL, 1>(g, s);
+    else if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_PARTIAL>(g, s);
     else launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
-    if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
+    if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_SWIGLU>(g, s);
+    else if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
   } else {
     g.k_splits = 1;
-    if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
+    if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_BF16>(g, s);
+    else if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_BF16>(g, s);
   }
 }
