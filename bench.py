@@ -5,7 +5,7 @@ A step is one pass of the whole hot path (row preparation, fused base + gated lo
 projection, rotary embedding + cache append, attention over [base prefix ; adapted suffix])
 over one batch of seeded synthetic input that is already resident in HBM.
 
-    python bench.py [--workload c2|c3|c4|c4x16|c5|r2] [--steps K] [--warmup W]
+    python bench.py [--workload c2|c3|c4|c4x16|c5|r2|r3] [--steps K] [--warmup W]
 
 prints ONE JSON line: suffix tokens/s, ms per step, the roofline of the dominant kernel
 (per-kernel durations from HIP events recorded by the library on the launch stream) and the
@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c4x16", "c5", "r2", "copy"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c4x16", "c5", "r2", "r3", "copy"],
                     help="copy: a plain 1 GiB device copy, the known-size kernel that calibrates the HBM counters")
     ap.add_argument("--rotate", type=int, default=-1,
                     help="distinct weight/cache sets cycled through so the last-level cache cannot hold the working set")
@@ -135,6 +135,8 @@ def main():
         return
     if name == "r2":
         return regime2(args, ab, wl, torch, np, dev)
+    if name == "r3":
+        return regime3(args, ab, wl, torch, np, dev)
     # c4x16: the c4 batch generating 16 tokens per sequence (the length of an evaluator's answer,
     # Section 3) through one staged call; per-launch work is that of c4 (positions grow by 0.1%)
     n_dec = 1
@@ -384,6 +386,86 @@ def regime2(args, ab, wl, torch, np, dev):
         "base_turn_with_reuse_ms": turn_ms,
         "base_turn_reprefilling_context_ms": sec_re * 1e3,
         "base_turn_saving": sec_re * 1e3 / turn_ms,
+    }
+    print(json.dumps(result))
+    ctx.close()
+
+
+def regime3(args, ab, wl, torch, np, dev):
+    """Section 3, third regime, as a decode step: sequences that run different adapters over the
+    same context read one physical copy of its cache rows, packed four to a workgroup for that
+    part; compared with the same batch holding a private copy of the context per sequence."""
+    batch, ctx_of, C0 = wl.regime3()
+    shape = batch.shape
+    n = batch.n_seqs
+    n_ctx = max(ctx_of) + 1
+    own = batch.P[0] - C0
+    steps, warmup = args.steps or 30, args.warmup or 5
+    ctx = ab.Context(0)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        ctx.set_option(key, int(val))
+    rng = wl.Rng(batch.seed, dev)
+    layer = ab.Layer(wl.make_layer(shape, rng, "r3.L0"), shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                     shape.rms_eps, shape.rope_theta, shape.intermediate)
+    x = wl.make_hidden(rng, "r3.x", n, shape)
+    out = torch.empty((n, shape.n_q), dtype=shape.torch_dtype, device=dev)
+
+    def make_cache(shared):
+        caps = [(own if shared else batch.P[b]) + 1 for b in range(n)] + ([C0] * n_ctx if shared else [])
+        c = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, dev)
+        c.k.normal_()
+        c.v.normal_()
+        for b in range(n):
+            c.seq_len[b] = batch.P[b]
+            if shared:
+                c.share_prefix(b, int(c.seq_offset[n + ctx_of[b]]), C0)
+        return c
+
+    def run(shared):
+        c = make_cache(shared)
+
+        def step():
+            c.seq_len[:n] = np.asarray(batch.P, dtype=np.int32)
+            ab.alora_decode(ctx, layer, c, x, batch.k, batch.adapter, out)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        ctx.set_option("profile", 1)
+        ctx.profile_reset()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        prof = ctx.profile_read()
+        ctx.set_option("profile", 0)
+        del c
+        return sec, prof
+
+    sec, prof = run(True)
+    sec_private, prof_private = run(False)
+    esz = 2
+    alg_bytes = (n_ctx * C0 + n * (own + 1)) * 2 * shape.n_kv * esz
+    avg = prof["attn_decode"]["ms"] / prof["attn_decode"]["launches"]
+    roof = dict(kernel="attn_decode", bound="hbm", achieved=alg_bytes / (avg * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
+                frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, traffic=None, avg_ms=avg, algorithmic_bytes=alg_bytes)
+    result = {
+        "metric": "alora_decode_tok_per_s", "value": n / sec, "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
+        "data": "synthetic",
+        "config": {"workload": "r3: decode step, %d sequences = %d contexts of %d cached base tokens x %d adapters, %d own "
+                               "adapted rows each, the context rows stored once per context" % (n, n_ctx, C0, n // n_ctx, own),
+                   "rank": shape.rank, "layers": 1},
+        "roofline": roof,
+        "kernels": {k_: dict(avg_ms=round(r["ms"] / r["launches"], 5), launches=r["launches"]) for k_, r in prof.items()},
+        "private_copies_ms_per_step": sec_private * 1e3,
+        "private_copies_attn_decode_ms": prof_private["attn_decode"]["ms"] / prof_private["attn_decode"]["launches"],
+        "speedup_vs_private_copies": sec_private / sec,
     }
     print(json.dumps(result))
     ctx.close()

@@ -87,7 +87,16 @@ typedef struct {
 
 /* KV cache of one layer (Eq.3: the stored K_{1:t}, V_{1:t}).  A flat pool of token rows;
  * sequence b owns rows [seq_offset[b], seq_offset[b] + seq_capacity[b]); its row j holds
- * the key / value of absolute position j.  Keys are stored after rotation. */
+ * the key / value of absolute position j.  Keys are stored after rotation.
+ *
+ * Shared prefix (Section 3, third cache-reuse regime; Proposition 2 for N adapters on one
+ * context): when prefix_len is given, positions [0, prefix_len[b]) of sequence b are READ from
+ * pool rows prefix_offset[b] + j -- one physical copy that any number of sequences may name, for
+ * instance the rows of the base model's own sequence -- and only positions >= prefix_len[b] live
+ * in the sequence's own rows, position j at seq_offset[b] + (j - prefix_len[b]).  seq_len stays
+ * the full cached length (prefix included); the capacity bounds the own rows.  A call never
+ * writes prefix rows (new positions are >= seq_len >= prefix_len); the caller must not hand the
+ * same rows to another sequence of the same call as rows to be written. */
 typedef struct {
   void *k;                     /* DEVICE [pool_tokens, n_kv_heads, head_dim]           */
   void *v;                     /* DEVICE [pool_tokens, n_kv_heads, head_dim]           */
@@ -96,6 +105,9 @@ typedef struct {
   const int32_t *seq_capacity; /* HOST [B]                                             */
   int32_t *seq_len;            /* HOST [B]  in: P_b (rows already valid)
                                             out: P_b + S_b, written only on ALORA_OK   */
+  const int64_t *prefix_offset;/* HOST [B], or NULL when prefix_len is NULL            */
+  const int32_t *prefix_len;   /* HOST [B], or NULL: no sequence has a shared prefix;
+                                  0 <= prefix_len[b] <= seq_len[b]                     */
 } alora_kv_cache;
 
 /* Context: create on the device that holds the buffers.  Returns ALORA_EHIP if the device

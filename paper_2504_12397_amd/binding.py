@@ -36,7 +36,8 @@ class LayerDesc(C.Structure):
 class KVCacheDesc(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("pool_tokens", C.c_int64),
                 ("seq_offset", C.POINTER(C.c_int64)), ("seq_capacity", C.POINTER(C.c_int32)),
-                ("seq_len", C.POINTER(C.c_int32))]
+                ("seq_len", C.POINTER(C.c_int32)),
+                ("prefix_offset", C.POINTER(C.c_int64)), ("prefix_len", C.POINTER(C.c_int32))]
 
 
 def load_library() -> C.CDLL:
@@ -137,6 +138,8 @@ class KVCache:
         self.seq_offset = np.ascontiguousarray(np.asarray(offs, dtype=np.int64))
         self.pool_tokens = int(o)
         self.seq_len = np.zeros(len(caps), dtype=np.int32)
+        self.prefix_offset = None        # set by share_prefix
+        self.prefix_len = None
         shape = (self.pool_tokens, n_kv_heads, head_dim)
         if fill is None:
             self.k = torch.zeros(shape, dtype=dtype, device=device)
@@ -150,7 +153,20 @@ class KVCache:
         self.desc = KVCacheDesc(self.k.data_ptr(), self.v.data_ptr(), self.pool_tokens,
                                 self.seq_offset.ctypes.data_as(C.POINTER(C.c_int64)),
                                 self.seq_capacity.ctypes.data_as(C.POINTER(C.c_int32)),
-                                self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)))
+                                self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)),
+                                None if self.prefix_len is None else self.prefix_offset.ctypes.data_as(C.POINTER(C.c_int64)),
+                                None if self.prefix_len is None else self.prefix_len.ctypes.data_as(C.POINTER(C.c_int32)))
+
+    def share_prefix(self, b: int, pool_row: int, n: int):
+        """Positions 0..n-1 of sequence b are read from pool rows pool_row.. (one copy that several sequences
+        may name); its own rows then start at position n.  seq_len[b] becomes n if it was smaller."""
+        if self.prefix_len is None:
+            self.prefix_offset = np.zeros(len(self.seq_len), dtype=np.int64)
+            self.prefix_len = np.zeros(len(self.seq_len), dtype=np.int32)
+        self.prefix_offset[b] = int(pool_row)
+        self.prefix_len[b] = int(n)
+        self.seq_len[b] = max(int(self.seq_len[b]), int(n))
+        self._refresh()
 
     def rows(self, b: int, lo: int, hi: int):
         o = int(self.seq_offset[b])

@@ -172,6 +172,7 @@ struct Plan {
   int T = 0, B = 0;
   int max_len = 0;        // max over sequences of P_b + S_b
   bool any_adapter = false;
+  bool any_prefix = false;   // some sequence reads a shared prefix
   std::vector<SeqMeta> seqs;
 };
 
@@ -213,11 +214,14 @@ alora_status check_batch(alora_ctx *ctx, const alora_layer_desc *ly, const alora
   if (!cache->seq_offset || !cache->seq_capacity || !cache->seq_len)
     return fail(ctx, ALORA_EINVAL, "cache seq_offset / seq_capacity / seq_len is NULL");
   if (!cache->k || !cache->v) return fail(ctx, ALORA_EINVAL, "cache k / v is NULL");
+  if (cache->prefix_len && !cache->prefix_offset)
+    return fail(ctx, ALORA_EINVAL, "cache prefix_len is given without prefix_offset");
   if (cu[0] != 0) return fail(ctx, ALORA_EINVAL, "cu_seqlens[0] = %d must be 0", cu[0]);
   pl->B = B;
   pl->seqs.resize(B);
   pl->max_len = 0;
   pl->any_adapter = false;
+  pl->any_prefix = false;
   for (int b = 0; b < B; ++b) {
     const int S = cu[b + 1] - cu[b];
     if (S < 0) return fail(ctx, ALORA_EINVAL, "cu_seqlens decreases at sequence %d", b);
@@ -231,21 +235,39 @@ alora_status check_batch(alora_ctx *ctx, const alora_layer_desc *ly, const alora
     if (cap < 0 || off < 0 || off + cap > cache->pool_tokens)
       return fail(ctx, ALORA_ECAPACITY, "sequence %d: rows [%lld, %lld) lie outside the pool of %lld tokens", b,
                   (long long)off, (long long)(off + cap), (long long)cache->pool_tokens);
+    const int plen = cache->prefix_len ? cache->prefix_len[b] : 0;
+    const int64_t poff = plen > 0 ? cache->prefix_offset[b] : 0;
+    if (plen < 0 || plen > P)
+      return fail(ctx, ALORA_EINVAL, "sequence %d: prefix_len = %d outside [0, seq_len = %d]", b, plen, P);
+    if (plen > 0 && (poff < 0 || poff + plen > cache->pool_tokens))
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: shared prefix rows [%lld, %lld) lie outside the pool of %lld tokens",
+                  b, (long long)poff, (long long)(poff + plen), (long long)cache->pool_tokens);
     const int64_t grown = (int64_t)P + (int64_t)S * n_steps;      // cached length after the call
-    if (grown > cap)
-      return fail(ctx, ALORA_ECAPACITY, "sequence %d: %d cached + %lld new tokens exceed its capacity %d", b, P,
+    if (grown - plen > cap)
+      return fail(ctx, ALORA_ECAPACITY, "sequence %d: %d cached + %lld new tokens exceed its capacity %d", b, P - plen,
                   (long long)S * n_steps, cap);
     if (grown > (1 << 24))
       return fail(ctx, ALORA_ECAPACITY, "sequence %d: position %lld beyond the supported 2^24", b, (long long)grown);
     SeqMeta &m = pl->seqs[b];
     m.row_start = cu[b]; m.n_new = S; m.P = P; m.k = kps[b]; m.adapter = aps[b];
     m.scale = aps[b] >= 0 ? ly->scale[aps[b]] : 0.f;
-    m.pool_off = off;
+    m.pool_off = off - plen;
+    m.prefix_off = poff;
+    m.prefix_len = plen;
+    m.pad_ = 0;
+    if (plen > 0) pl->any_prefix = true;
     if (aps[b] >= 0 && S > 0 && grown > kps[b]) pl->any_adapter = true;
     pl->max_len = std::max(pl->max_len, (int)grown);
   }
   pl->T = cu[B];
   return ALORA_OK;
+}
+
+// decode batches have one row per sequence: the sequence whose new token is packed row `row`
+static int a_seq_of_row(const Plan &pl, int row) {
+  for (int b = 0; b < pl.B; ++b)
+    if (pl.seqs[b].n_new > 0 && pl.seqs[b].row_start == row) return b;
+  return 0;
 }
 
 struct Workspace {
@@ -266,6 +288,8 @@ struct Workspace {
   int attn_waves = 8;
   const int4 *qtiles = nullptr;
   int n_qtiles = 0;
+  const DecItem *ditems = nullptr;   // work list of the MFMA decode kernel
+  int n_ditems = 0;
 };
 
 int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
@@ -367,16 +391,17 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.lazy = (float)ctx->opt_attn_lazy;
       a.partials = direct ? nullptr : w.partials;
       a.out = direct ? (bf16 *)out : nullptr;
-      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, ctx->opt_attn_pipeline == 0, s);
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, ctx->opt_attn_pipeline == 0, pl.any_prefix, s);
     } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
       DecodeArgs a{};
       a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
       a.seqs = seqs_dev; a.rm = w.rm;
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
-      a.n_splits = n_splits;
+      a.items = w.ditems;
+      a.n_parts = n_splits;
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
       a.partials = w.partials;
-      launch_attn_decode_mfma(a, pl.T, s);
+      launch_attn_decode_mfma(a, w.n_ditems, s);
     } else {
       launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
                            n_splits, w.partials, s);
@@ -498,11 +523,71 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
   const bool decode_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && decode &&
                            attn_decode_mfma_supported(L);
-  if (decode_mfma && ctx->opt_splits == 0) {
-    // (row, kv head, split) workgroups of four waves: several per compute unit, >= 1024 keys each
-    const int64_t items = (int64_t)pl.T * L.n_kv_heads;
-    int want = (int)std::max<int64_t>(1, (8 * (int64_t)ctx->n_cu + items - 1) / items);
-    n_splits = std::max(1, std::min(std::min(want, 64), std::max(1, pl.max_len / 1024)));
+  // Decode work list: per (row, kv head) n_own items over the row's own cache rows, and -- when
+  // sequences name shared prefixes -- per (group of up to 16 / G rows with the same prefix, kv head)
+  // n_shared items over that prefix.  Every (row, head) ends up with n_own + n_shared partial records.
+  std::vector<DecItem> ditems;
+  if (decode_mfma) {
+    const int G = L.n_q_heads / L.n_kv_heads;
+    const int pack = std::max(1, 16 / G);
+    int max_own = 1, max_pfx = 0;
+    for (int b = 0; b < B; ++b) {
+      max_own = std::max(max_own, pl.seqs[b].P + n_steps - pl.seqs[b].prefix_len);
+      max_pfx = std::max(max_pfx, pl.seqs[b].prefix_len);
+    }
+    // several workgroups of four waves per compute unit, at least 1024 keys each
+    auto splits_for = [&](int64_t items, int longest) {
+      if (ctx->opt_splits > 0) return ctx->opt_splits;
+      const int want = (int)std::max<int64_t>(1, (8 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1));
+      return std::max(1, std::min(std::min(want, 64), std::max(1, longest / 1024)));
+    };
+    const int n_own = splits_for((int64_t)pl.T * L.n_kv_heads, max_own);
+    int n_shared = 0;
+    std::vector<std::vector<int>> chunks;      // rows that share one prefix, at most `pack` each
+    if (pl.any_prefix) {
+      std::vector<int> order(B);
+      for (int b = 0; b < B; ++b) order[b] = b;
+      std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+        if (pl.seqs[x].prefix_off != pl.seqs[y].prefix_off) return pl.seqs[x].prefix_off < pl.seqs[y].prefix_off;
+        return pl.seqs[x].prefix_len < pl.seqs[y].prefix_len;
+      });
+      for (int i = 0; i < B; ++i) {
+        const SeqMeta &m = pl.seqs[order[i]];
+        if (m.n_new <= 0 || m.prefix_len <= 0) continue;     // nothing to read: its records are zero-filled below
+        const bool same = !chunks.empty() && (int)chunks.back().size() < pack &&
+                          pl.seqs[order[i - 1]].prefix_off == m.prefix_off && pl.seqs[order[i - 1]].prefix_len == m.prefix_len &&
+                          pl.seqs[order[i - 1]].prefix_len > 0 && pl.seqs[order[i - 1]].n_new > 0;
+        if (!same) chunks.emplace_back();
+        chunks.back().push_back(m.row_start);
+      }
+      // rows without a prefix still need their shared-part records: empty items (no keys) write them
+      for (int b = 0; b < B; ++b) {
+        const SeqMeta &m = pl.seqs[b];
+        if (m.n_new <= 0 || m.prefix_len > 0) continue;
+        if (chunks.empty() || (int)chunks.back().size() >= pack ||
+            pl.seqs[a_seq_of_row(pl, chunks.back()[0])].prefix_len > 0) chunks.emplace_back();
+        chunks.back().push_back(m.row_start);
+      }
+      n_shared = splits_for((int64_t)chunks.size() * L.n_kv_heads, max_pfx);
+    }
+    n_splits = n_own + n_shared;
+    DecItem it{};
+    for (const auto &rows : chunks)
+      for (int g = 0; g < L.n_kv_heads; ++g)
+        for (int sp = 0; sp < n_shared; ++sp) {
+          it = DecItem{};
+          it.n_rows = (int)rows.size(); it.g = g; it.split = sp; it.n_splits = n_shared; it.part = n_own + sp; it.shared = 1;
+          for (size_t i = 0; i < rows.size(); ++i) it.rows[i] = rows[i];
+          ditems.push_back(it);
+        }
+    for (int row = 0; row < pl.T; ++row)
+      for (int g = 0; g < L.n_kv_heads; ++g)
+        for (int sp = 0; sp < n_own; ++sp) {
+          it = DecItem{};
+          it.n_rows = 1; it.g = g; it.split = sp; it.n_splits = n_own; it.part = sp; it.shared = 0;
+          it.rows[0] = row;
+          ditems.push_back(it);
+        }
   }
   if (attn_mfma && ctx->opt_splits == 0) {
     // one workgroup per (q-tile, kv head, split): aim at one full wave of workgroups over the chip,
@@ -574,12 +659,14 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
         qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : make_int4(-1, 0, 0, 0));
   }
   const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
-  const size_t meta_bytes = seq_bytes + qtiles.size() * sizeof(int4);
+  const size_t work_bytes = qtiles.size() * sizeof(int4) + ditems.size() * sizeof(DecItem);   // one of the two lists
+  const size_t meta_bytes = seq_bytes + work_bytes;
   MetaSlot *slot = nullptr;
   st = acquire_slot(ctx, meta_bytes, &slot);
   if (st != ALORA_OK) return st;
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
   if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(int4));
+  if (!ditems.empty()) memcpy(slot->host + seq_bytes, ditems.data(), ditems.size() * sizeof(DecItem));
   HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
   const SeqMeta *seqs_dev = (const SeqMeta *)slot->dev;
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
@@ -590,6 +677,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.attn_waves = attn_waves;
   w.qtiles = (const int4 *)(slot->dev + seq_bytes);
   w.n_qtiles = (int)qtiles.size();
+  w.ditems = (const DecItem *)(slot->dev + seq_bytes);
+  w.n_ditems = (int)ditems.size();
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {

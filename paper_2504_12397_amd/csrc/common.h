@@ -15,8 +15,17 @@ struct SeqMeta {
   int32_t k;           // invocation index (first adapted absolute position)
   int32_t adapter;     // adapter id or -1
   float scale;         // s_a of that adapter (0 if none)
-  int64_t pool_off;    // first pool row of the sequence
+  int64_t pool_off;    // pool row of position 0 if the own rows started there: position j >= prefix_len
+                       // sits at pool_off + j (= seq_offset - prefix_len + j)
+  int64_t prefix_off;  // pool row of position 0 of the shared prefix (positions < prefix_len)
+  int32_t prefix_len;  // 0: no shared prefix
+  int32_t pad_;
 };
+
+// pool row of cached position j of a sequence
+__device__ __forceinline__ int64_t seq_pool_row(const SeqMeta &sm, int j) {
+  return (j < sm.prefix_len ? sm.prefix_off : sm.pool_off) + j;
+}
 
 // Per-row metadata written by the row-preparation kernel and read by everything after it.
 struct RowMeta {

@@ -68,7 +68,9 @@ constexpr int ATT_BN = 64;        // keys per tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-template <int G, int NW>      // NW waves per workgroup (8 or 4), 32 packed rows each
+// PFX: some sequence of the call reads a shared prefix (cached position j < prefix_len lives in
+// another place of the pool than the sequence's own rows)
+template <int G, int NW, bool PFX>      // NW waves per workgroup (8 or 4), 32 packed rows each
 __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) {
   constexpr int H = 128;
   constexpr int NT = 64 * NW;
@@ -95,6 +97,9 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
   const int ntiles = kend > kbeg ? (kend - kbeg + ATT_BN - 1) / ATT_BN : 0;
   const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
   const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
+  // offset (in elements) that turns an own-row address into the shared-prefix address of the same position
+  const int64_t pfx_delta = PFX ? (sm.prefix_off - sm.pool_off) * a.n_kv : 0;
+  const int pfx_len = PFX ? sm.prefix_len : 0;
   const int first_pos = sm.P + q0;                   // smallest query position in the tile
 
   // ---- this wave's queries as B operands: 2 column blocks x 8 k-steps ---------------------
@@ -142,12 +147,14 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     for (int i = 0; i < KC; ++i) {
       const int q = tid + i * NT, key = q >> 4, c = q & 15;
       const int kidx = min(k0 + key, n_visible - 1);
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kidx * a.n_kv + c * 8);
+      const int64_t e = (int64_t)kidx * a.n_kv + c * 8 + (PFX && kidx < pfx_len ? pfx_delta : 0);
+      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + e);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-      rv[i] = *reinterpret_cast<const vword *>(Vp + (int64_t)kidx * a.n_kv + v_cg * CW);
+      const int64_t e = (int64_t)kidx * a.n_kv + v_cg * CW + (PFX && kidx < pfx_len ? pfx_delta : 0);
+      rv[i] = *reinterpret_cast<const vword *>(Vp + e);
     }
   };
   auto store_tile = [&](int buf, const u32x4 (&rk)[KC], const vword (&rv)[4]) {
@@ -352,7 +359,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 // LDS buffers are double: K(t+1) is stored during the first step of tile t (its slot was last
 // read two steps earlier), V(t+1) during the second (its slot was last read one step earlier);
 // one barrier per step orders them.
-template <int G>
+template <int G, bool PFX>
 __global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
   constexpr int H = 128;
   constexpr int NT = 512;
@@ -380,6 +387,9 @@ __global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
   const int ntiles = kend > kbeg ? (kend - kbeg + ATT_BN - 1) / ATT_BN : 0;
   const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
   const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
+  // offset (in elements) that turns an own-row address into the shared-prefix address of the same position
+  const int64_t pfx_delta = PFX ? (sm.prefix_off - sm.pool_off) * a.n_kv : 0;
+  const int pfx_len = PFX ? sm.prefix_len : 0;
   const int first_pos = sm.P + q0;
 
   const int pr = wave * 32 + l32;
@@ -409,7 +419,8 @@ __global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
     for (int i = 0; i < 2; ++i) {
       const int q = tid + i * NT, key = q >> 4, c = q & 15;
       const int kidx = min(k0 + key, n_visible - 1);
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + (int64_t)kidx * a.n_kv + c * 8);
+      const int64_t e = (int64_t)kidx * a.n_kv + c * 8 + (PFX && kidx < pfx_len ? pfx_delta : 0);
+      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + e);
     }
   };
   auto load_v = [&](int t, u32x2 (&rv)[4]) {
@@ -417,7 +428,8 @@ __global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-      rv[i] = *reinterpret_cast<const u32x2 *>(Vp + (int64_t)kidx * a.n_kv + v_cg * 4);
+      const int64_t e = (int64_t)kidx * a.n_kv + v_cg * 4 + (PFX && kidx < pfx_len ? pfx_delta : 0);
+      rv[i] = *reinterpret_cast<const u32x2 *>(Vp + e);
     }
   };
   auto store_k = [&](int buf, const u32x4 (&rk)[2]) {
@@ -643,33 +655,43 @@ int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves) {
   return 32 * waves / (L.n_q_heads / L.n_kv_heads);
 }
 
-template <int NW>
+template <int NW, bool PFX>
 static void launch_attn_nw(const AttnArgs &a, int n_work, int G, hipStream_t s) {
   dim3 grid(n_work);
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_prefill_mfma_kernel<1, NW>), grid, dim3(64 * NW), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((attn_prefill_mfma_kernel<2, NW>), grid, dim3(64 * NW), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((attn_prefill_mfma_kernel<4, NW>), grid, dim3(64 * NW), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((attn_prefill_mfma_kernel<8, NW>), grid, dim3(64 * NW), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((attn_prefill_mfma_kernel<1, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((attn_prefill_mfma_kernel<2, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((attn_prefill_mfma_kernel<4, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((attn_prefill_mfma_kernel<8, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
     default: break;
   }
 }
 
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, hipStream_t s) {
+template <bool PFX>
+static void launch_attn_pipe(const AttnArgs &a, int n_work, int G, hipStream_t s) {
+  dim3 grid(n_work);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((attn_prefill_pipe_kernel<1, PFX>), grid, dim3(512), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((attn_prefill_pipe_kernel<2, PFX>), grid, dim3(512), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((attn_prefill_pipe_kernel<4, PFX>), grid, dim3(512), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((attn_prefill_pipe_kernel<8, PFX>), grid, dim3(512), 0, s, a); break;
+    default: break;
+  }
+}
+
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, bool prefix,
+                              hipStream_t s) {
   if (n_work == 0) return;
   if (pipelined && waves == 8) {
-    dim3 grid(n_work);
-    switch (G) {
-      case 1: hipLaunchKernelGGL((attn_prefill_pipe_kernel<1>), grid, dim3(512), 0, s, a); break;
-      case 2: hipLaunchKernelGGL((attn_prefill_pipe_kernel<2>), grid, dim3(512), 0, s, a); break;
-      case 4: hipLaunchKernelGGL((attn_prefill_pipe_kernel<4>), grid, dim3(512), 0, s, a); break;
-      case 8: hipLaunchKernelGGL((attn_prefill_pipe_kernel<8>), grid, dim3(512), 0, s, a); break;
-      default: break;
-    }
-    return;
+    if (prefix) launch_attn_pipe<true>(a, n_work, G, s);
+    else launch_attn_pipe<false>(a, n_work, G, s);
+  } else if (waves == 4) {
+    if (prefix) launch_attn_nw<4, true>(a, n_work, G, s);
+    else launch_attn_nw<4, false>(a, n_work, G, s);
+  } else {
+    if (prefix) launch_attn_nw<8, true>(a, n_work, G, s);
+    else launch_attn_nw<8, false>(a, n_work, G, s);
   }
-  if (waves == 4) launch_attn_nw<4>(a, n_work, G, s);
-  else launch_attn_nw<8>(a, n_work, G, s);
 }
 
 }  // namespace alora

@@ -1,8 +1,12 @@
 // Decode attention (Eq.4: one new query per sequence over its whole cache), memory-bound:
 // every cached key/value byte is read exactly once and everything else is kept out of the way.
 //
-// Work item: one workgroup = (sequence, kv head, key split); its four waves take disjoint key
-// ranges and never synchronise until the final merge.  A wave consumes 32 keys per step:
+// Work item: one workgroup = (rows, kv head, key split), listed by the host; its four waves take
+// disjoint key ranges and never synchronise until the final merge.  Normally an item is one row
+// (one sequence's new token) over that sequence's own cache rows.  Sequences that name the same
+// shared prefix (Section 3, several adapters on one context) are packed 16 / G to an item for the
+// prefix part: their heads fill the MFMA columns a single sequence leaves empty, and the prefix
+// is read from memory once for all of them.  A wave consumes 32 keys per step:
 //   * K rows go from global memory straight into the A operand of v_mfma_f32_16x16x32_bf16
 //     (lane l: key l%16, head-dim slice 8*(l/16)..+7 of the current 32-wide k-step), the G query
 //     heads of the group are the (zero padded) 16 B-operand columns: S^T[key][head].
@@ -45,25 +49,34 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, kg = lane >> 4;           // j: head column / key row / V row; kg: k group
-  const int row = blockIdx.x, g = blockIdx.y, split = blockIdx.z;
+  const DecItem *it = a.items + blockIdx.x;
+  const int g = it->g, split = it->split;
   const int G = a.n_q_heads / a.n_kv_heads;
-  const SeqMeta sm = a.seqs[a.rm.seq[row]];
-  const int n_keys = a.rm.pos[row] + 1;
+  const int n_cols = it->n_rows * G;                 // MFMA columns in use: column = row index * G + head
+  const int row_first = it->rows[0];
+  const SeqMeta sm = a.seqs[a.rm.seq[row_first]];
+  // the item's keys are pool rows key_row0 .. key_row0 + n_keys - 1
+  const int n_keys = it->shared ? sm.prefix_len : a.rm.pos[row_first] + 1 - sm.prefix_len;
+  const int64_t key_row0 = it->shared ? sm.prefix_off : sm.pool_off + sm.prefix_len;
   // keys of this (split, wave): contiguous, multiple of 32
-  const int n_parts = a.n_splits * 4;
-  int per = (n_keys + n_parts - 1) / n_parts;
+  const int n_ranges = it->n_splits * 4;
+  int per = (n_keys + n_ranges - 1) / n_ranges;
   per = (per + 31) & ~31;
   const int kbeg = (split * 4 + wave) * per;
   const int kend = min(n_keys, kbeg + per);
-  const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
-  const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
+  const bf16 *Kp = a.K + key_row0 * a.n_kv + g * H;
+  const bf16 *Vp = a.V + key_row0 * a.n_kv + g * H;
 
-  // queries: B operand columns = heads of the group (zero for padding columns)
+  // queries: B operand columns = (row, head of the group) pairs (zero for padding columns)
   u32x4 qf[4];
+  {
+    const int rj = j / G, hj = j - rj * G;
+    const int qrow = it->rows[j < n_cols ? rj : 0];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    qf[s] = u32x4{0, 0, 0, 0};
-    if (j < G) qf[s] = *reinterpret_cast<const u32x4 *>(a.Q + (int64_t)row * a.n_q + (g * G + j) * H + 32 * s + 8 * kg);
+    for (int s = 0; s < 4; ++s) {
+      qf[s] = u32x4{0, 0, 0, 0};
+      if (j < n_cols) qf[s] = *reinterpret_cast<const u32x4 *>(a.Q + (int64_t)qrow * a.n_q + (g * G + hj) * H + 32 * s + 8 * kg);
+    }
   }
 
   f32x4 o[8];
@@ -162,8 +175,10 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
     for (int v = 0; v < 4; ++v) s_o[wave][j][8 * (4 * kg + v) + c] = o[c][v];
   if (kg == 0) { s_o[wave][j][H] = m_run; s_o[wave][j][H + 1] = l_tot; }
   __syncthreads();
-  for (int i = tid; i < G * H; i += 256) {
+  for (int i = tid; i < n_cols * H; i += 256) {
     const int hd = i / H, col = i % H;
+    const int rj = hd / G, hj = hd - rj * G;
+    const int orow = it->rows[rj];
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; ++w) M = fmaxf(M, s_o[w][hd][H]);
@@ -175,7 +190,7 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
       acc += wgt * s_o[w][hd][col];
       den += wgt * s_o[w][hd][H + 1];
     }
-    float *pp = a.partials + (((int64_t)row * a.n_q_heads + g * G + hd) * a.n_splits + split) * (H + 2);
+    float *pp = a.partials + (((int64_t)orow * a.n_q_heads + g * G + hj) * a.n_parts + it->part) * (H + 2);
     pp[col] = acc;
     if (col == 0) {
       pp[H] = (M == -INFINITY) ? -INFINITY : M * DEC_LN2;     // natural-log domain for the merge kernel
@@ -189,10 +204,9 @@ bool attn_decode_mfma_supported(const LayerDims &L) {
   return L.head_dim == 128 && G <= 16;
 }
 
-void launch_attn_decode_mfma(const DecodeArgs &a, int n_rows, hipStream_t s) {
-  if (n_rows == 0) return;
-  dim3 grid(n_rows, a.n_kv_heads, a.n_splits);
-  hipLaunchKernelGGL(attn_decode_mfma_kernel, grid, dim3(256), 0, s, a);
+void launch_attn_decode_mfma(const DecodeArgs &a, int n_items, hipStream_t s) {
+  if (n_items == 0) return;
+  hipLaunchKernelGGL(attn_decode_mfma_kernel, dim3(n_items), dim3(256), 0, s, a);
 }
 
 }  // namespace alora

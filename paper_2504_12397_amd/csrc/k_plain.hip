@@ -314,7 +314,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ 
   int chunk = (n_keys + n_splits - 1) / n_splits;
   chunk = (chunk + 63) & ~63;
   const int begin = split * chunk, end = min(n_keys, begin + chunk);
-  const int64_t base = seqs[rm.seq[row]].pool_off;
+  const SeqMeta sm = seqs[rm.seq[row]];
   const float sm_scale = 1.0f / sqrtf((float)h);
   for (int i = lane; i < ng * h; i += 64) {
     int gi = i / h, c = i % h;
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ 
 #pragma unroll
     for (int gi = 0; gi < ATT_GMAX; ++gi) sc[gi] = 0.f;
     if (valid) {
-      const T *kr = cacheK + (base + key) * L.n_kv + g * h;
+      const T *kr = cacheK + seq_pool_row(sm, key) * L.n_kv + g * h;
       for (int c = 0; c < h; ++c) {
         float kv = to_f32<T>(kr[c]);
 #pragma unroll
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ 
     __syncthreads();
     const int nk = min(64, end - t0);
     for (int j = 0; j < nk; ++j) {
-      const T *vr = cacheV + (base + t0 + j) * L.n_kv + g * h;
+      const T *vr = cacheV + seq_pool_row(sm, t0 + j) * L.n_kv + g * h;
 #pragma unroll
       for (int dd = 0; dd < ATT_DMAX; ++dd) {
         int c = lane + 64 * dd;

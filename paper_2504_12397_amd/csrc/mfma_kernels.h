@@ -59,21 +59,36 @@ struct AttnArgs {
 };
 bool attn_prefill_mfma_supported(const LayerDims &L);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, hipStream_t s);
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, bool prefix,
+                              hipStream_t s);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
+// One workgroup of the decode kernel: the query heads (of one GQA group) of up to 16 / G rows
+// against one range of keys.  shared = 0: the row's own cached positions [prefix_len, pos];
+// shared = 1: the prefix [0, prefix_len) that all the item's rows name (one physical copy), so
+// its keys and values are read once for all of them.
+struct DecItem {
+  int32_t n_rows;           // rows whose heads fill the MFMA columns (column = row index * G + head)
+  int32_t g;                // kv head
+  int32_t split, n_splits;  // this item's share of its key range
+  int32_t part;             // which of the n_parts partial records of (row, head) it writes
+  int32_t shared;
+  int32_t pad_[2];
+  int32_t rows[16];
+};
 struct DecodeArgs {
   const bf16 *Q;            // [rows, n_q]
   const bf16 *K, *V;        // pool [tokens, n_kv]
   const SeqMeta *seqs;
   RowMeta rm;               // seq and pos of every row
+  const DecItem *items;     // one per workgroup
   int n_q, n_kv, n_q_heads, n_kv_heads;
-  int n_splits;
+  int n_parts;              // partial records per (row, head)
   float sm_scale;
-  float *partials;          // [rows, n_q_heads, n_splits, head_dim + 2]
+  float *partials;          // [rows, n_q_heads, n_parts, head_dim + 2]
 };
 bool attn_decode_mfma_supported(const LayerDims &L);
-void launch_attn_decode_mfma(const DecodeArgs &a, int n_rows, hipStream_t s);
+void launch_attn_decode_mfma(const DecodeArgs &a, int n_items, hipStream_t s);
 
 // Measured ceilings: kind 0 = bf16 MFMA TFLOP/s (register-only loop), kind 1 = HBM read GB/s (4 GiB stream).
 double measure_ceiling(int kind, int n_cu, hipStream_t s);

@@ -213,6 +213,17 @@ def config4() -> Batch:
                  adapter=[b % 4 for b in range(n)], name="c4", seed=BASE_SEED + 4)
 
 
+def regime3(n_contexts: int = 16, per_context: int = 4, context: int = 16384, own: int = 64):
+    """Third cache-reuse regime of Section 3 (N adapters on one context, Proposition 2's N-adapter
+    clause) as a decode step: the c4 batch regrouped into 16 contexts of 16384 base tokens, each
+    read by 4 sequences with different adapters that hold 64 adapted rows of their own.  Returns
+    the batch and, per sequence, the index of its context."""
+    n = n_contexts * per_context
+    batch = Batch(SHAPE_8B_4AD, P=[context + own] * n, S=[1] * n, k=[context] * n,
+                  adapter=[b % per_context % 4 for b in range(n)], name="r3", seed=BASE_SEED + 7)
+    return batch, [b // per_context for b in range(n)], context
+
+
 def config5(full_lora: bool = False) -> Batch:
     """32-layer stack shape: 32768 cached tokens + 128 adapted tokens (aLoRA), or the same
     32896 tokens recomputed from scratch with the adapter on everywhere (k = 0)."""

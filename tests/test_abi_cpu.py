@@ -35,7 +35,7 @@ def test_struct_layout_matches_header(ab):
     # natural alignment, no packing: 8 int32, then pointers / floats as declared
     assert C.sizeof(ab.LayerDesc) == 8 * 4 + 7 * 8 + 2 * 4 + 5 * 8
     assert ab.LayerDesc.W_qkv.offset == 32 and ab.LayerDesc.rms_eps.offset == 88 and ab.LayerDesc.W_o.offset == 96
-    assert C.sizeof(ab.KVCacheDesc) == 48
+    assert C.sizeof(ab.KVCacheDesc) == 64
 
 
 def test_status_strings(ab):
@@ -155,3 +155,31 @@ def test_decode_steps_validation(ab, vctx):
     assert steps(81) == ("ALORA_ECAPACITY", [10, 20])
     assert steps(80) == ("ALORA_EHIP", [10, 20])
     assert steps(2, seq_len=[99, 20]) == ("ALORA_ECAPACITY", [99, 20])
+
+
+def test_shared_prefix_validation(ab, vctx):
+    """Shared-prefix fields of the cache descriptor: bounds, and the capacity counts own rows only."""
+    p = C.POINTER(C.c_int32)
+    p64 = C.POINTER(C.c_int64)
+
+    def go(prefix_len, prefix_off, seq_len=(10, 20), cap=(100, 100), give_off=True):
+        desc, cache, cu, k, a, B, keep, ln = make_args(ab, seq_len=list(seq_len), seq_capacity=list(cap))
+        pl = np.asarray(prefix_len, dtype=np.int32)
+        po = np.asarray(prefix_off, dtype=np.int64)
+        cache.prefix_len = pl.ctypes.data_as(p)
+        if give_off:
+            cache.prefix_offset = po.ctypes.data_as(p64)
+        st = call(ab, vctx, desc, cache, cu, k, a, B)
+        return ab._lib.alora_status_string(st).decode(), list(ln)
+
+    ok = "ALORA_EHIP"       # validation passed; the validation-only context then declines to launch
+    assert go([0, 0], [0, 0]) == (ok, [10, 20])
+    assert go([10, 5], [150, 150]) == (ok, [10, 20])
+    assert go([11, 5], [150, 150])[0] == "ALORA_EINVAL"          # longer than what is cached
+    assert go([-1, 5], [150, 150])[0] == "ALORA_EINVAL"
+    assert go([10, 5], [195, 150])[0] == "ALORA_ECAPACITY"       # rows 195..204 leave the pool of 200
+    assert go([10, 5], [-1, 150])[0] == "ALORA_ECAPACITY"
+    assert go([10, 5], [0, 0], give_off=False)[0] == "ALORA_EINVAL"
+    # 90 cached rows of which 80 are shared: 10 own + 3 new fit a capacity of 13, not of 12
+    assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(13, 100)) == (ok, [90, 20])
+    assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(12, 100))[0] == "ALORA_ECAPACITY"

@@ -1,0 +1,204 @@
+"""Shared-prefix batching (Section 3, third cache-reuse regime; Proposition 2 for N adapters on one
+context): several sequences read ONE physical copy of the base model's prefix rows and keep only
+their own suffix rows.  The oracle knows nothing of sharing -- every sequence is computed on its own
+with its own copy of the prefix -- so agreement with it proves that sharing changes nothing."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import alora_oracle as orc
+from paper_2504_12397_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ab():
+    from paper_2504_12397_amd import binding
+    return binding
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+def shared_case(shape, C0, S, k, adapter, seed, own_prefix=()):
+    """N sequences over one base context of C0 tokens; `own_prefix[b]` = extra cached rows of
+    sequence b beyond the shared ones (e.g. an invocation already prefilled)."""
+    n = len(S)
+    own = list(own_prefix) or [0] * n
+    base = H.make_case(shape, [C0 + max(own)], [1], [10 ** 6], [-1], seed=seed)       # base-model rows for the context
+    rng = wl.Rng(seed + 1)
+    xn = [wl.make_hidden(rng, f"shared.x_new{b}", S[b], shape) for b in range(n)]
+    cK, cV, P = [], [], []
+    for b in range(n):
+        # own cached rows: taken from the same base pass (values do not matter for the comparison,
+        # only that the GPU and the oracle hold the same ones)
+        cK.append(base.cache_K[0][:C0 + own[b]])
+        cV.append(base.cache_V[0][:C0 + own[b]])
+        P.append(C0 + own[b])
+    return H.Case(shape, base.tensors, base.layer, P, list(S), list(k), list(adapter), [None] * n, xn, cK, cV), own
+
+
+def build_cache(ab, case, own, C0, shared_mask, extra=4, guard=3):
+    """Own regions for the N sequences, then one region that holds the shared context rows."""
+    n = len(case.P)
+    shape = case.shape
+    caps = [(own[b] if shared_mask[b] else case.P[b]) + case.S[b] + extra for b in range(n)] + [C0]
+    cache = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY, guard_rows=guard)
+    ctx_off = int(cache.seq_offset[n])
+    nkv = shape.n_kv_heads
+    k0 = torch.from_numpy(case.cache_K[0][:C0]).to(shape.torch_dtype).view(C0, nkv, -1).cuda()
+    v0 = torch.from_numpy(case.cache_V[0][:C0]).to(shape.torch_dtype).view(C0, nkv, -1).cuda()
+    cache.k[ctx_off:ctx_off + C0] = k0
+    cache.v[ctx_off:ctx_off + C0] = v0
+    for b in range(n):
+        o = int(cache.seq_offset[b])
+        lo = C0 if shared_mask[b] else 0
+        rows = case.P[b] - lo
+        if rows:
+            cache.k[o:o + rows] = torch.from_numpy(case.cache_K[b][lo:]).to(shape.torch_dtype).view(rows, nkv, -1).cuda()
+            cache.v[o:o + rows] = torch.from_numpy(case.cache_V[b][lo:]).to(shape.torch_dtype).view(rows, nkv, -1).cuda()
+        cache.seq_len[b] = case.P[b]
+        if shared_mask[b]:
+            cache.share_prefix(b, ctx_off, C0)
+    if not any(shared_mask):
+        cache._refresh()
+    return cache, ctx_off
+
+
+def check_shared(ab, ctx, case, own, C0, shared_mask, decode=False):
+    tol = H.TOL[case.shape.dtype]
+    n = len(case.P)
+    cache, ctx_off = build_cache(ab, case, own, C0, shared_mask)
+    layer = H.gpu_layer(case, case.shape)
+    before_k, before_v = cache.k.clone(), cache.v.clone()
+    x = case.x_packed.cuda().contiguous()
+    if decode:
+        out = ab.alora_decode(ctx, layer, cache, x, case.k, case.adapter)
+    else:
+        out = ab.alora_prefill(ctx, layer, cache, x, case.cu, case.k, case.adapter)
+    torch.cuda.synchronize()
+    ref_o, new_rows = H.oracle_prefill(case)
+    err = H.rel_err(H.f64(out), ref_o)
+    assert err <= tol, f"attention output off by {err:.3e}"
+    written = torch.zeros(cache.pool_tokens, dtype=torch.bool)
+    for b in range(n):
+        lo = C0 if shared_mask[b] else 0
+        o = int(cache.seq_offset[b]) + case.P[b] - lo
+        written[o:o + case.S[b]] = True
+        assert int(cache.seq_len[b]) == case.P[b] + case.S[b]
+        if case.S[b]:
+            gk = H.f64(cache.k[o:o + case.S[b]]).reshape(case.S[b], -1)
+            gv = H.f64(cache.v[o:o + case.S[b]]).reshape(case.S[b], -1)
+            assert H.rel_err(gk, new_rows[b][0]) <= tol and H.rel_err(gv, new_rows[b][1]) <= tol
+    keep = ~written.cuda()
+    assert torch.equal(bits(cache.k[keep]), bits(before_k[keep])), "rows outside the new ones changed (shared prefix included)"
+    assert torch.equal(bits(cache.v[keep]), bits(before_v[keep]))
+    return out
+
+
+SHAPES = {
+    "G4": wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, n_adapters=3),
+    "G1": wl.LayerShape(d=512, n_q_heads=4, n_kv_heads=4, head_dim=128, rank=16, n_adapters=3),
+    "G8": wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=1, head_dim=128, rank=16, n_adapters=3),
+    "f32": dataclasses.replace(wl.SHAPE_TINY, n_adapters=3, rmsnorm=True, n_kv_heads=2),
+}
+
+
+@pytest.mark.parametrize("name", ["G4", "G1", "G8", "f32"])
+def test_prefill_over_one_shared_context(ab, name):
+    """Five adapter invocations (three adapters, one base-only turn) on one cached context."""
+    shape = SHAPES[name]
+    ctx = ab.Context(0)
+    try:
+        C0 = 333
+        S = [70, 33, 129, 1, 64]
+        case, own = shared_case(shape, C0, S, [C0, C0, C0 + 5, C0, 0], [0, 1, 2, 1, -1], seed=900)
+        check_shared(ab, ctx, case, own, C0, [True] * 5)
+        # the same call with private copies of the context gives the same bits (one kernel path)
+        ctx.set_option("kv_splits", 1)
+        out_sh = check_shared(ab, ctx, case, own, C0, [True] * 5)
+        out_pr = check_shared(ab, ctx, case, own, C0, [False] * 5)
+        assert torch.equal(bits(out_sh), bits(out_pr))
+    finally:
+        ctx.close()
+
+
+@pytest.mark.parametrize("name,opts", [("G4", {}), ("G4", {"kv_splits": 3}), ("G1", {}), ("G8", {}), ("f32", {}),
+                                       ("G4", {"kernels": 1})])
+def test_decode_over_shared_contexts(ab, name, opts):
+    """Decode steps of sequences that name shared prefixes: packed several to a workgroup for the
+    prefix part (MFMA kernel), own rows separately; mixed with sequences that share nothing."""
+    shape = SHAPES[name]
+    ctx = ab.Context(0)
+    try:
+        for k_, v in opts.items():
+            ctx.set_option(k_, v)
+        C0 = 1100
+        own = [40, 0, 17, 64, 5, 0, 33]            # rows each sequence already holds beyond the context
+        n = len(own)
+        case, own = shared_case(shape, C0, [1] * n, [C0, C0 + 1, C0, 0, C0 + 50, C0, 10], [0, 1, 2, -1, 1, 0, 2],
+                                seed=910, own_prefix=own)
+        check_shared(ab, ctx, case, own, C0, [True] * n, decode=True)
+        # sequences 1, 4 and 6 keep private copies, the others share
+        check_shared(ab, ctx, case, own, C0, [True, False, True, True, False, True, False], decode=True)
+        check_shared(ab, ctx, case, own, C0, [True, False, True, True, False, True, False], decode=False)
+    finally:
+        ctx.close()
+
+
+def test_two_different_shared_contexts_and_decode_steps(ab):
+    """Two groups of sequences, each over its own shared context, through a run of decode steps."""
+    shape = SHAPES["G4"]
+    ctx = ab.Context(0)
+    try:
+        n_steps = 4
+        C = [700, 260]
+        group = [0, 0, 0, 1, 1, 0, 0, 0]           # six sequences on context 0 (two packs), two on context 1
+        n = len(group)
+        k = [700, 0, 702, 260, 100, 700, 700, 701]
+        a = [0, 1, 2, 1, -1, 2, 0, 1]
+        bases = [H.make_case(shape, [C[i]], [1], [10 ** 6], [-1], seed=920 + i) for i in range(2)]
+        # both contexts must come from the same layer weights: reuse the first case's tensors
+        lay, tensors = bases[0].layer, bases[0].tensors
+        rng = wl.Rng(930)
+        ctxK, ctxV = [], []
+        for i in range(2):
+            xb = wl.make_hidden(rng, f"ctx{i}", C[i], shape)
+            pos = np.arange(C[i])
+            xh = orc._normed(lay, H.f64(xb), shape.dtype)
+            _, kk, vv = orc.project_qkv(lay, xh, pos, 10 ** 6, -1)
+            ctxK.append(orc._store(orc.rope(kk, pos, lay.n_kv_heads, lay.head_dim, lay.rope_theta), shape.dtype))
+            ctxV.append(orc._store(vv, shape.dtype))
+        xn = [wl.make_hidden(rng, f"steps{b}", n_steps, shape) for b in range(n)]
+        case = H.Case(shape, tensors, lay, [C[g] for g in group], [n_steps] * n, k, a, [None] * n, xn,
+                      [ctxK[g] for g in group], [ctxV[g] for g in group])
+        ref_o, new_rows = H.oracle_prefill(case)
+
+        caps = [n_steps] * n + C
+        cache = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY, guard_rows=2)
+        for i in range(2):
+            o = int(cache.seq_offset[n + i])
+            cache.k[o:o + C[i]] = torch.from_numpy(ctxK[i]).to(shape.torch_dtype).view(C[i], shape.n_kv_heads, -1).cuda()
+            cache.v[o:o + C[i]] = torch.from_numpy(ctxV[i]).to(shape.torch_dtype).view(C[i], shape.n_kv_heads, -1).cuda()
+        for b in range(n):
+            cache.share_prefix(b, int(cache.seq_offset[n + group[b]]), C[group[b]])
+        layer = H.gpu_layer(tensors, shape)
+        x_steps = torch.stack([torch.stack([xn[b][t] for b in range(n)]) for t in range(n_steps)]).cuda().contiguous()
+        out = ab.alora_decode_steps(ctx, layer, cache, x_steps, k, a)
+        torch.cuda.synchronize()
+        got = torch.cat([out[:, b] for b in range(n)])
+        assert H.rel_err(H.f64(got), ref_o) <= H.TOL["bf16"]
+        for b in range(n):
+            assert int(cache.seq_len[b]) == C[group[b]] + n_steps
+            o = int(cache.seq_offset[b])
+            assert H.rel_err(H.f64(cache.k[o:o + n_steps]).reshape(n_steps, -1), new_rows[b][0]) <= H.TOL["bf16"]
+        # one more step does not fit the own rows
+        with pytest.raises(ab.AloraError):
+            ab.alora_decode(ctx, layer, cache, x_steps[0], k, a)
+    finally:
+        ctx.close()
