@@ -449,6 +449,7 @@ def regime3(args, ab, wl, torch, np, dev):
 
     sec, prof = run(True)
     sec_private, prof_private = run(False)
+
     esz = 2
     alg_bytes = (n_ctx * C0 + n * (own + 1)) * 2 * shape.n_kv * esz
     avg = prof["attn_decode"]["ms"] / prof["attn_decode"]["launches"]

@@ -636,10 +636,26 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
     std::vector<Item> per_xcd_items[8];
     int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // sequences that name the same shared prefix stream the same rows for most of their length:
+    // their groups of one (kv head, split) follow the first of them to its XCD
+    std::vector<std::pair<Group, int>> placed;
     for (const Group &gr : groups) {
-      int x = 0;
-      for (int i = 1; i < 8; ++i)
-        if (load[i] < load[x]) x = i;
+      int x = -1;
+      const SeqMeta &m = pl.seqs[gr.b];
+      if (m.prefix_len > 0)
+        for (const auto &pr : placed) {
+          const SeqMeta &o = pl.seqs[pr.first.b];
+          if (pr.first.g == gr.g && pr.first.sp == gr.sp && o.prefix_len == m.prefix_len && o.prefix_off == m.prefix_off) {
+            x = pr.second;
+            break;
+          }
+        }
+      if (x < 0) {
+        x = 0;
+        for (int i = 1; i < 8; ++i)
+          if (load[i] < load[x]) x = i;
+      }
+      if (m.prefix_len > 0) placed.emplace_back(gr, x);
       load[x] += gr.cost;
       const int last = ((pl.seqs[gr.b].n_new - 1) / tq) * tq;
       for (int q0 = last; q0 >= 0; q0 -= tq)
