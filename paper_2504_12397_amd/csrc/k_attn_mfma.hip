@@ -64,6 +64,13 @@ __device__ __forceinline__ float sum_bf16x2(uint32_t pair, float acc) {
                                          false);
 }
 
+// Waits for every outstanding global load (s_waitcnt vmcnt(0); the other counters left alone).
+// Used once before the key loops: the query fragments are loaded before a conditional prologue,
+// and unless their loads are known to be complete on every path into the loop the compiler guards
+// each use of them inside the loop with a vmcnt wait -- which, the counter being in-order, also
+// drains the K/V prefetches that are supposed to stay in flight.
+__device__ __forceinline__ void wait_all_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 constexpr int ATT_BN = 64;        // keys per tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -293,6 +300,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     store_tile(0, rk0, rv0);
   }
   __syncthreads();
+  wait_all_global_loads();
   for (int t = 0; t < ntiles; t += 2) {
     load_tile(min(t + 2, ntiles - 1), rk0, rv0);
     compute_tile(0, t);
@@ -608,6 +616,7 @@ __global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
   int t_mask = min(ntiles, max(0, (first_pos + 1 - kbeg) / ATT_BN));
   if (kbeg + t_mask * ATT_BN > kend) --t_mask;
   t_mask = max(t_mask, 0);
+  wait_all_global_loads();
   for (int t = 0; t < t_mask; ++t) tile_steps(std::false_type{}, t);
   for (int t = t_mask; t < ntiles; ++t) tile_steps(std::true_type{}, t);
   // drain: the last block's probabilities still wait for their V
