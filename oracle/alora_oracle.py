@@ -306,3 +306,23 @@ def ref_stack_cached(layers: List[Layer], caches: List[Tuple[np.ndarray, np.ndar
         new_rows.append((kn, vn))
         x = layer_tail(layer, x, o, cache_dtype)
     return x, new_rows
+
+
+# --------------------------------------------------------------------------------------
+# the first token itself (Section 3 measures the time to it): final norm, vocabulary
+# projection, greedy choice
+# --------------------------------------------------------------------------------------
+def lm_head_logits(x_last: np.ndarray, final_gain: Optional[np.ndarray], eps: float, W_vocab: np.ndarray,
+                   act_dtype: str = "f64") -> np.ndarray:
+    """logits[b, v] = <RMSNorm(x_last[b]; final_gain), W_vocab[v]> -- the standard output head of
+    the decoder the paper adapts (its Background section; the head itself is never adapted)."""
+    xn = np.asarray(x_last, dtype=F64)
+    if final_gain is not None:
+        xn = rmsnorm(xn, np.asarray(final_gain, dtype=F64), eps)
+    xn = _store(xn, act_dtype)
+    return xn @ np.asarray(W_vocab, dtype=F64).T
+
+
+def greedy_token(logits: np.ndarray) -> np.ndarray:
+    """Index of the largest logit of every row, the lowest index among equals."""
+    return np.argmax(np.asarray(logits, dtype=F64), axis=-1).astype(np.int64)

@@ -405,3 +405,37 @@ def test_stack_cache_reuse_equals_recompute():
     got, rows = orc.ref_stack_cached(layers, base_caches, P, x[P:], k, a)
     assert np.allclose(got, full[P:], rtol=1e-10, atol=1e-11)
     assert all(kn.shape[0] == S for kn, _ in rows)
+
+
+# ------------------------------------------------------------------ output head (first token)
+def test_lm_head_worked_by_hand():
+    """x = (3, 4): mean square 12.5, so RMSNorm gives (3, 4)/sqrt(12.5); against the rows (1,0), (0,1), (1,1),
+    (-1,-1) the logits are 3/s, 4/s, 7/s, -7/s with s = sqrt(12.5): token 2."""
+    x = np.array([[3.0, 4.0]])
+    W = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0], [-1.0, -1.0]])
+    lg = orc.lm_head_logits(x, np.ones(2), 0.0, W)
+    s = np.sqrt(12.5)
+    np.testing.assert_allclose(lg, [[3 / s, 4 / s, 7 / s, -7 / s]], rtol=1e-15)
+    assert orc.greedy_token(lg).tolist() == [2]
+    # the gain multiplies per feature: gain (2, 0) leaves only the first coordinate
+    lg2 = orc.lm_head_logits(x, np.array([2.0, 0.0]), 0.0, W)
+    np.testing.assert_allclose(lg2, [[6 / s, 0.0, 6 / s, -6 / s]], rtol=1e-15, atol=1e-15)
+    assert orc.greedy_token(lg2).tolist() == [0]          # first of the equal maxima
+    # no final norm: plain projection
+    np.testing.assert_allclose(orc.lm_head_logits(x, None, 0.0, W), [[3.0, 4.0, 7.0, -7.0]])
+
+
+def test_lm_head_against_scalar_loops():
+    rng = np.random.default_rng(5)
+    x, g, W = rng.standard_normal((3, 7)), rng.standard_normal(7), rng.standard_normal((11, 7))
+    lg = orc.lm_head_logits(x, g, 1e-5, W)
+    for b in range(3):
+        ms = sum(float(v) ** 2 for v in x[b]) / 7
+        xn = [float(x[b, c]) / np.sqrt(ms + 1e-5) * float(g[c]) for c in range(7)]
+        for v in range(11):
+            assert abs(lg[b, v] - sum(xn[c] * float(W[v, c]) for c in range(7))) < 1e-12
+        assert orc.greedy_token(lg)[b] == max(range(11), key=lambda v: (lg[b, v], -v))
+    # rounding the normalised row to bf16 is the only difference of the bf16 reading
+    lg16 = orc.lm_head_logits(x, g, 1e-5, W, "bf16")
+    xn16 = orc.round_to_bf16(orc.rmsnorm(x, g, 1e-5))
+    np.testing.assert_allclose(lg16, xn16 @ W.T, rtol=1e-15)
