@@ -303,6 +303,25 @@ def main():
         result["full_lora_ttft_ms"] = full_ms
         result["ttft_speedup_vs_full_lora"] = full_ms / ms_per_step
 
+    # ---- first token id: final norm + vocabulary projection + greedy choice on the last row -----
+    if name == "c5":
+        V = 128256
+        Wv = rng.normal("lm_head.W", (V, shape.d), 1.0 / np.sqrt(shape.d), dtype=shape.torch_dtype)
+        gf = rng.normal("lm_head.gain", (shape.d,), 0.1, 1.0, dtype=shape.torch_dtype)
+        last = out[-1:].contiguous()
+        for _ in range(3):
+            ab.alora_lm_head(ctx, last, gf, shape.rms_eps, Wv)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            ab.alora_lm_head(ctx, last, gf, shape.rms_eps, Wv)
+        torch.cuda.synchronize()
+        head_ms = (time.perf_counter() - t0) / 20 * 1e3
+        result["lm_head_ms"] = head_ms
+        result["lm_head_GBps"] = V * shape.d * 2 / (head_ms * 1e-3) / 1e9
+        result["ttft_to_token_id_ms"] = ms_per_step + head_ms
+        del Wv
+
     # ---- the CPU oracle on the same workload, timed on the host cores -------------------------
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(name, batch, shape, sets[0], x_new, n_layers)

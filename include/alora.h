@@ -139,7 +139,8 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
  * with HIP events on the call's stream.  alora_profile_read waits for the pending events and
  * returns the accumulated time and launch count of one kernel family: "prep_rows",
  * "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
- * "mlp_norm", "gate_up", "silu_mul", "down_proj".  alora_profile_reset clears the totals. */
+ * "mlp_norm", "gate_up", "silu_mul", "down_proj", "lm_head", "lm_argmax".  alora_profile_reset
+ * clears the totals. */
 alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 alora_status alora_profile_reset(alora_ctx *ctx);
 
@@ -196,6 +197,21 @@ alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers,
                                  alora_kv_cache *caches, const void *x, const int32_t *cu_seqlens,
                                  const int32_t *k_per_seq, const int32_t *adapter_per_seq,
                                  int32_t B, void *out, void *stream);
+
+/* The first token itself (Section 3 times the adapter up to its first generated token): final
+ * RMSNorm, projection on the vocabulary with the base model's (never adapted) output matrix, and
+ * the greedy choice.  logits[b, v] = < RMSNorm(x_last[b]; final_gain), W_vocab[v] >, accumulated
+ * in fp32; token[b] = the index of the largest logit, the lowest index among equals.
+ *   x_last     DEVICE [B, d]      hidden state of the last new token of every sequence (dtype)
+ *   final_gain DEVICE [d] or NULL (no normalisation)
+ *   W_vocab    DEVICE [vocab, d]  (dtype)
+ *   logits     DEVICE [B, vocab] fp32, or NULL: kept in the context workspace
+ *   token      DEVICE [B] int32, or NULL: logits only
+ * Sampling other than greedy is the caller's (from logits).  Same error behaviour as the calls
+ * above: arguments are checked first, nothing is launched on error. */
+alora_status alora_lm_head(alora_ctx *ctx, alora_dtype dtype, int32_t d, int32_t vocab, const void *x_last,
+                           const void *final_gain, float rms_eps, const void *W_vocab, int32_t B,
+                           float *logits, int32_t *token, void *stream);
 
 #ifdef __cplusplus
 }

@@ -18,8 +18,8 @@ ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDT
 ALORA_F32, ALORA_BF16 = 0, 1
 
 EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
-           "alora_profile_read", "alora_profile_reset", "alora_measure_ceiling", "alora_prefill", "alora_decode", "alora_decode_steps", "alora_stack_prefill"]
-KERNELS = ["prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
+           "alora_profile_read", "alora_profile_reset", "alora_measure_ceiling", "alora_prefill", "alora_decode", "alora_decode_steps", "alora_stack_prefill", "alora_lm_head"]
+KERNELS = ["lm_head", "lm_argmax", "prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
            "mlp_norm", "gate_up", "silu_mul", "down_proj"]
 
 
@@ -71,6 +71,9 @@ def load_library() -> C.CDLL:
     lib.alora_decode_steps.restype = C.c_int
     lib.alora_decode_steps.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
                                        C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.alora_lm_head.restype = C.c_int
+    lib.alora_lm_head.argtypes = [C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
+                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.alora_stack_prefill.restype = C.c_int
     lib.alora_stack_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int32, C.POINTER(KVCacheDesc),
                                         C.c_void_p, i32p, i32p, i32p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -275,6 +278,21 @@ def alora_decode_steps(ctx: Context, layer: Layer, cache: KVCache, x_steps: torc
                                  ad.ctypes.data_as(p), B, n_steps, _ptr(attn_out), _stream_ptr(stream))
     ctx._check(st)
     return attn_out
+
+
+def alora_lm_head(ctx: Context, x_last: torch.Tensor, final_gain: Optional[torch.Tensor], rms_eps: float,
+                  W_vocab: torch.Tensor, want_logits: bool = False, stream=None):
+    """x_last [B, d], W_vocab [V, d] -> greedy token ids [B] (int32), and the fp32 logits [B, V] if asked for."""
+    B, d = int(x_last.shape[0]), int(x_last.shape[1])
+    V = int(W_vocab.shape[0])
+    dt = ALORA_BF16 if x_last.dtype == torch.bfloat16 else ALORA_F32
+    token = torch.empty((B,), dtype=torch.int32, device=x_last.device)
+    logits = torch.empty((B, V), dtype=torch.float32, device=x_last.device) if want_logits else None
+    st = _lib.alora_lm_head(ctx._h, dt, d, V, _ptr(x_last), _ptr(final_gain) if final_gain is not None else None,
+                            float(rms_eps), _ptr(W_vocab), B, _ptr(logits) if logits is not None else None, _ptr(token),
+                            _stream_ptr(stream))
+    ctx._check(st)
+    return (token, logits) if want_logits else token
 
 
 def alora_stack_prefill(ctx: Context, layers: List[Layer], caches: List[KVCache], x: torch.Tensor,

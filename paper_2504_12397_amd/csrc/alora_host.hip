@@ -36,9 +36,10 @@ struct ProfEvent {
 };
 
 static const char *const KERNEL_NAMES[] = {"prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode",
-                                           "attn_merge", "o_proj", "mlp_norm", "gate_up", "silu_mul", "down_proj"};
+                                           "attn_merge", "o_proj", "mlp_norm", "gate_up", "silu_mul", "down_proj",
+                                           "lm_head", "lm_argmax"};
 enum KernelId { K_PREP = 0, K_QKV, K_ROPE, K_ATTN_PREFILL, K_ATTN_DECODE, K_ATTN_MERGE, K_OPROJ, K_MLPNORM,
-                K_GATEUP, K_SILU, K_DOWN, K_COUNT };
+                K_GATEUP, K_SILU, K_DOWN, K_LMHEAD, K_ARGMAX, K_COUNT };
 
 struct alora_ctx {
   int opt_profile = 0;
@@ -856,6 +857,80 @@ alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *tota
       return ALORA_OK;
     }
   return fail(ctx, ALORA_EINVAL, "unknown kernel name '%s'", kernel);
+}
+
+alora_status alora_lm_head(alora_ctx *ctx, alora_dtype dtype, int32_t d, int32_t vocab, const void *x_last,
+                           const void *final_gain, float rms_eps, const void *W_vocab, int32_t B, float *logits,
+                           int32_t *token, void *stream) {
+  if (!ctx) return ALORA_EINVAL;
+  ctx->err.clear();
+  if (dtype != ALORA_F32 && dtype != ALORA_BF16)
+    return fail(ctx, ALORA_EDTYPE, "dtype %d is neither ALORA_F32 nor ALORA_BF16", (int)dtype);
+  if (d < 1 || d > 16000) return fail(ctx, ALORA_ESHAPE, "d = %d outside [1, 16000]", d);
+  if (vocab < 1) return fail(ctx, ALORA_ESHAPE, "vocab = %d must be positive", vocab);
+  if (B < 1 || B > 4096) return fail(ctx, ALORA_EINVAL, "B = %d outside [1, 4096]", B);
+  if (!x_last || !W_vocab) return fail(ctx, ALORA_EINVAL, "x_last / W_vocab is NULL");
+  if (!logits && !token) return fail(ctx, ALORA_EINVAL, "logits and token are both NULL: nothing to compute");
+  if (ctx->device < 0) return fail(ctx, ALORA_EHIP, "validation-only context (device -1)");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t s = (hipStream_t)stream;
+  const bool bf = dtype == ALORA_BF16;
+  const size_t esz = bf ? 2 : 4;
+  const int n_slabs = argmax_slabs(vocab);
+  // workspace: normalised rows | logits (unless the caller keeps them) | per-slab maxima
+  Bump probe(nullptr);
+  probe.take<char>((size_t)B * d * esz);
+  if (!logits) probe.take<float>((size_t)B * vocab);
+  probe.take<float>((size_t)B * n_slabs);
+  probe.take<int>((size_t)B * n_slabs);
+  alora_status st = ensure_workspace(ctx, probe.off);
+  if (st != ALORA_OK) return st;
+  Bump b(ctx->ws);
+  char *xh = b.take<char>((size_t)B * d * esz);
+  float *lg = logits ? logits : b.take<float>((size_t)B * vocab);
+  float *pv = b.take<float>((size_t)B * n_slabs);
+  int *pi = b.take<int>((size_t)B * n_slabs);
+  const bool mfma = bf && ctx->opt_kernels == 0 && gemm_mfma_supported(B, vocab, d);
+  RowMeta none{};
+  const void *rows = x_last;
+  if (final_gain) {
+    ProfScope p(ctx, K_MLPNORM, s);
+    if (mfma && prep_rows_mfma_supported(d, 0)) {
+      PrepArgs pa{};
+      pa.x = (const bf16 *)x_last; pa.gain = (const bf16 *)final_gain; pa.eps = rms_eps;
+      pa.T = B; pa.d = d; pa.xh = (bf16 *)xh; pa.rm = none;
+      launch_prep_rows_mfma(pa, s);
+    } else if (bf) {
+      launch_prep_rows<bf16>((const bf16 *)x_last, (const bf16 *)final_gain, rms_eps, B, d, nullptr, 0, 0, nullptr, 0,
+                             false, (bf16 *)xh, nullptr, nullptr, none, s);
+    } else {
+      launch_prep_rows<float>((const float *)x_last, (const float *)final_gain, rms_eps, B, d, nullptr, 0, 0, nullptr,
+                              0, false, (float *)xh, nullptr, nullptr, none, s);
+    }
+    rows = xh;
+  }
+  {
+    ProfScope p(ctx, K_LMHEAD, s);
+    if (mfma) {
+      GemmArgs g{};
+      g.A = (const bf16 *)rows; g.lda = d;
+      g.B = (const bf16 *)W_vocab; g.ldb = d;
+      g.M = B; g.N = vocab; g.K = d;
+      g.k_splits = 1;
+      g.Cpart = lg;
+      launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+    } else if (bf) {
+      launch_lm_logits_plain<bf16>((const bf16 *)rows, (const bf16 *)W_vocab, B, vocab, d, lg, s);
+    } else {
+      launch_lm_logits_plain<float>((const float *)rows, (const float *)W_vocab, B, vocab, d, lg, s);
+    }
+  }
+  if (token) {
+    ProfScope p(ctx, K_ARGMAX, s);
+    launch_argmax(lg, B, vocab, pv, pi, token, s);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return ALORA_OK;
 }
 
 alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value) {

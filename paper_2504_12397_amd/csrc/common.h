@@ -82,6 +82,12 @@ template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
                         const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s);
 
+// output head: fp32 logits[B, V] = xh[B, d] W[V, d]^T (any shape), and the greedy token of every row
+template <typename T>
+void launch_lm_logits_plain(const T *xh, const T *W, int B, int V, int d, float *logits, hipStream_t s);
+int argmax_slabs(int V);
+void launch_argmax(const float *logits, int B, int V, float *pv, int *pi, int32_t *token, hipStream_t s);
+
 // split-KV attention with plain fp32 arithmetic: partial pass + merge
 template <typename T>
 void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,

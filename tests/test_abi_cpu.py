@@ -183,3 +183,22 @@ def test_shared_prefix_validation(ab, vctx):
     # 90 cached rows of which 80 are shared: 10 own + 3 new fit a capacity of 13, not of 12
     assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(13, 100)) == (ok, [90, 20])
     assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(12, 100))[0] == "ALORA_ECAPACITY"
+
+
+def test_lm_head_validation(ab, vctx):
+    f = ab._lib.alora_lm_head
+    P = FakeBuf.PTR
+
+    def go(dtype=ab.ALORA_BF16, d=64, vocab=1000, x=P, W=P, B=2, logits=P, token=P):
+        return ab._lib.alora_status_string(f(vctx, dtype, d, vocab, x, P, 1e-5, W, B, logits, token, None)).decode()
+
+    assert go() == "ALORA_EHIP"                      # everything checked out; a validation-only context cannot launch
+    assert go(dtype=9) == "ALORA_EDTYPE"
+    assert go(d=0) == "ALORA_ESHAPE"
+    assert go(vocab=0) == "ALORA_ESHAPE"
+    assert go(B=0) == "ALORA_EINVAL"
+    assert go(x=None) == "ALORA_EINVAL"
+    assert go(W=None) == "ALORA_EINVAL"
+    assert go(logits=None, token=None) == "ALORA_EINVAL"
+    assert go(logits=None) == "ALORA_EHIP" and go(token=None) == "ALORA_EHIP"
+    assert f(None, ab.ALORA_BF16, 64, 1000, P, P, 1e-5, P, 2, P, P, None) == ab.ALORA_EINVAL
