@@ -442,11 +442,29 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       launch_gemm_plain<T>((const T *)A, (const T *)W, (const T *)R, (T *)C, T_rows, N, K, s);
     }
   };
-  {   // h1 = x + attn W_o^T
-    ProfScope p(ctx, K_OPROJ, s);
-    dense(w.attn, ly->W_o, x, w.h1, L.d, L.n_q);
-  }
+  // h1 = x + attn W_o^T, hn = RMSNorm(h1).  When the projection is split over the reduction axis anyway, the
+  // kernel that adds the partial sums also normalises the row (from its fp32 value) -- one launch less.
+  bool normed = false;
   {
+    ProfScope p(ctx, K_OPROJ, s);
+    const int splits = mfma ? gemm_mfma_pick_splits(T_rows, L.d, L.n_q, ctx->n_cu) : 1;
+    if (mfma && splits > 1 && (size_t)splits * T_rows * L.d <= w.y_floats && splitk_reduce_norm_supported(L.d)) {
+      GemmArgs g{};
+      g.A = (const bf16 *)w.attn; g.lda = L.n_q;
+      g.B = (const bf16 *)ly->W_o; g.ldb = L.n_q;
+      g.M = T_rows; g.N = L.d; g.K = L.n_q;
+      g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+      g.k_splits = splits;
+      g.Cpart = w.Y;
+      launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+      launch_splitk_reduce_norm(w.Y, splits, T_rows, L.d, (const bf16 *)x, (const bf16 *)ly->rms2_gain, ly->rms_eps,
+                                (bf16 *)w.h1, (bf16 *)w.hn, s);
+      normed = true;
+    } else {
+      dense(w.attn, ly->W_o, x, w.h1, L.d, L.n_q);
+    }
+  }
+  if (!normed) {
     ProfScope p(ctx, K_MLPNORM, s);
     if (mfma && prep_rows_mfma_supported(L.d, 0)) {
       PrepArgs pa{};

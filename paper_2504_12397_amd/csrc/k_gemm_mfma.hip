@@ -328,6 +328,60 @@ void launch_splitk_reduce(const float *part, int splits, int64_t mn, const bf16 
                      R, C);
 }
 
+// The same sum for whole rows, followed by the RMSNorm of the row (h = sum + residual is normalised from its
+// fp32 value): C = bf16(h), Cn = bf16(h * gain / rms(h)).  One workgroup per row, N <= 16384, N % 4 == 0.
+__global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(const float *__restrict__ part, int splits, int M,
+                                                                 int N, const bf16 *__restrict__ R,
+                                                                 const bf16 *__restrict__ gain, float eps,
+                                                                 bf16 *__restrict__ C, bf16 *__restrict__ Cn) {
+  __shared__ float s_red[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int64_t mn = (int64_t)M * N, ro = (int64_t)row * N;
+  float4 h[16];
+  float ssq = 0.f;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int c = (u * 256 + tid) * 4;
+    h[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < N) {
+      float4 acc = *reinterpret_cast<const float4 *>(part + ro + c);
+      for (int sp = 1; sp < splits; ++sp) {
+        const float4 v = *reinterpret_cast<const float4 *>(part + (int64_t)sp * mn + ro + c);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
+      if (R != nullptr) {
+        acc.x += (float)R[ro + c]; acc.y += (float)R[ro + c + 1]; acc.z += (float)R[ro + c + 2]; acc.w += (float)R[ro + c + 3];
+      }
+      h[u] = acc;
+      ssq += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
+    }
+  }
+  ssq = wave_sum(ssq);
+  if ((tid & 63) == 0) s_red[tid >> 6] = ssq;
+  __syncthreads();
+  const float rinv = 1.0f / sqrtf((s_red[0] + s_red[1] + s_red[2] + s_red[3]) / (float)N + eps);
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int c = (u * 256 + tid) * 4;
+    if (c < N) {
+      const float v[4] = {h[u].x, h[u].y, h[u].z, h[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        C[ro + c + e] = (bf16)v[e];
+        Cn[ro + c + e] = (bf16)(v[e] * (float)gain[c + e] * rinv);
+      }
+    }
+  }
+}
+
+bool splitk_reduce_norm_supported(int N) { return N % 4 == 0 && N <= 16384; }
+
+void launch_splitk_reduce_norm(const float *part, int splits, int M, int N, const bf16 *R, const bf16 *gain, float eps,
+                               bf16 *C, bf16 *Cn, hipStream_t s) {
+  if (M == 0) return;
+  hipLaunchKernelGGL(splitk_reduce_norm_kernel, dim3(M), dim3(256), 0, s, part, splits, M, N, R, gain, eps, C, Cn);
+}
+
 bool gemm_mfma_supported(int M, int N, int K) { return M > 0 && N > 0 && K >= 64 && K % 64 == 0; }
 
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {

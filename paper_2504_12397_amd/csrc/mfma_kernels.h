@@ -98,5 +98,9 @@ int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s);
 // C[mn] = bf16(sum_s part[s][mn] + R[mn]); mn must be a multiple of 4
 void launch_splitk_reduce(const float *part, int splits, int64_t mn, const bf16 *R, bf16 *C, hipStream_t s);
+// the same for whole rows plus the RMSNorm of the summed row: C = bf16(h), Cn = bf16(RMSNorm(h; gain))
+bool splitk_reduce_norm_supported(int N);
+void launch_splitk_reduce_norm(const float *part, int splits, int M, int N, const bf16 *R, const bf16 *gain, float eps,
+                               bf16 *C, bf16 *Cn, hipStream_t s);
 
 }  // namespace alora
