@@ -94,6 +94,17 @@ class Layer:
     W_gate: Optional[np.ndarray] = None
     W_up: Optional[np.ndarray] = None
     W_down: Optional[np.ndarray] = None
+    # optional adapters of the other linears (Section 2: "adaptations for the MLP blocks ... via
+    # directly corresponding equations"), same rank and scales as A / B_q.. above:
+    # A_o [n_ad, r, N_q], B_o [n_ad, d, r]; A_gu [n_ad, 2, r, d] (gate, up), B_gate, B_up [n_ad, I, r];
+    # A_down [n_ad, r, I], B_down [n_ad, d, r]
+    A_o: Optional[np.ndarray] = None
+    B_o: Optional[np.ndarray] = None
+    A_gu: Optional[np.ndarray] = None
+    B_gate: Optional[np.ndarray] = None
+    B_up: Optional[np.ndarray] = None
+    A_down: Optional[np.ndarray] = None
+    B_down: Optional[np.ndarray] = None
 
     @property
     def n_q(self) -> int:
@@ -117,7 +128,8 @@ def layer_from_tensors(t: dict, n_q_heads: int, n_kv_heads: int, head_dim: int,
     return Layer(n_q_heads, n_kv_heads, head_dim, f(t["W_qkv"]), f(t["A"]), f(t["B_q"]), f(t["B_k"]),
                  f(t["B_v"]), [float(s) for s in t["scale"]], f(t.get("rms_gain")), rms_eps, rope_theta,
                  f(t.get("W_o")), f(t.get("rms2_gain")), f(t.get("W_gate")), f(t.get("W_up")),
-                 f(t.get("W_down")))
+                 f(t.get("W_down")), f(t.get("A_o")), f(t.get("B_o")), f(t.get("A_gu")), f(t.get("B_gate")),
+                 f(t.get("B_up")), f(t.get("A_down")), f(t.get("B_down")))
 
 
 # --------------------------------------------------------------------------------------
@@ -274,13 +286,33 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
-def layer_tail(layer: Layer, x: np.ndarray, attn: np.ndarray, act_dtype: str = "f64") -> np.ndarray:
-    """Output projection + residual, then RMSNorm + SwiGLU MLP + residual, all per token and
-    with the base weights (the MLP blocks are not adapted)."""
-    h = x + attn @ layer.W_o.T
+def gated_linear(z: np.ndarray, W: np.ndarray, A: Optional[np.ndarray], B: Optional[np.ndarray], s: float,
+                 m: Optional[np.ndarray]) -> np.ndarray:
+    """Eq.6 for any linear of the layer: row i gets W z_i, plus s * B (A z_i) where m_i = 1."""
+    y = z @ W.T
+    if A is not None and m is not None and m.any():
+        y = y + m[:, None] * (s * ((z @ A.T) @ B.T))
+    return y
+
+
+def layer_tail(layer: Layer, x: np.ndarray, attn: np.ndarray, act_dtype: str = "f64",
+               pos: Optional[np.ndarray] = None, k: int = 0, adapter: int = -1) -> np.ndarray:
+    """Output projection + residual, then RMSNorm + SwiGLU MLP + residual, all per token.  With
+    the base weights, unless the layer carries adapters for these linears: then rows at positions
+    >= k (pos given) of a sequence with an adapter use W + Delta exactly as the q/k/v projections
+    do (Section 2, the remark after Eq.6 on MLP blocks)."""
+    m = None
+    a = adapter
+    if a >= 0 and pos is not None:
+        m = (np.asarray(pos) >= k).astype(F64)
+    s = float(layer.scale[a]) if a >= 0 else 0.0
+    pick = lambda t, *idx: None if (t is None or a < 0) else t[(a,) + idx]
+    h = x + gated_linear(attn, layer.W_o, pick(layer.A_o), pick(layer.B_o), s, m)
     hn = _store(rmsnorm(h, layer.rms2_gain, layer.rms_eps), act_dtype)
-    m = silu(hn @ layer.W_gate.T) * (hn @ layer.W_up.T)
-    return h + m @ layer.W_down.T
+    gate = gated_linear(hn, layer.W_gate, pick(layer.A_gu, 0), pick(layer.B_gate), s, m)
+    up = gated_linear(hn, layer.W_up, pick(layer.A_gu, 1), pick(layer.B_up), s, m)
+    act = silu(gate) * up
+    return h + gated_linear(act, layer.W_down, pick(layer.A_down), pick(layer.B_down), s, m)
 
 
 def ref_stack_full(layers: List[Layer], x_all: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64"):
@@ -291,7 +323,7 @@ def ref_stack_full(layers: List[Layer], x_all: np.ndarray, k: int, adapter: int,
     for layer in layers:
         o, Kc, Vc = ref_full(layer, x, k, adapter, cache_dtype)
         caches.append((Kc, Vc))
-        x = layer_tail(layer, x, o, cache_dtype)
+        x = layer_tail(layer, x, o, cache_dtype, np.arange(x.shape[0]), k, adapter)
     return x, caches
 
 
@@ -304,7 +336,7 @@ def ref_stack_cached(layers: List[Layer], caches: List[Tuple[np.ndarray, np.ndar
     for layer, (cK, cV) in zip(layers, caches):
         o, kn, vn = ref_cached(layer, cK, cV, P, x, k, adapter, cache_dtype)
         new_rows.append((kn, vn))
-        x = layer_tail(layer, x, o, cache_dtype)
+        x = layer_tail(layer, x, o, cache_dtype, P + np.arange(x.shape[0]), k, adapter)
     return x, new_rows
 
 

@@ -2,6 +2,7 @@
 than itself -- a closed form, a library routine on a special case, a separately written
 pure-loop brute force, or an invariant the paper proves (Proposition 1) -- chosen so that a
 dropped term, a wrong sign or index, or a transposed operand fails at least one of them."""
+import dataclasses
 import math
 import os
 
@@ -14,7 +15,7 @@ from oracle import alora_oracle as orc
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def rand_layer(seed, d=24, hq=4, hkv=2, h=6, r=3, n_ad=2, rms=True, scale=(2.0, 0.5), mlp=0):
+def rand_layer(seed, d=24, hq=4, hkv=2, h=6, r=3, n_ad=2, rms=True, scale=(2.0, 0.5), mlp=0, adapt_rest=False):
     g = np.random.default_rng(seed)
     nq, nkv = hq * h, hkv * h
     kw = {}
@@ -22,6 +23,12 @@ def rand_layer(seed, d=24, hq=4, hkv=2, h=6, r=3, n_ad=2, rms=True, scale=(2.0, 
         kw = dict(W_o=g.normal(size=(d, nq)) / math.sqrt(nq), rms2_gain=g.normal(1, 0.1, size=d),
                   W_gate=g.normal(size=(mlp, d)) / math.sqrt(d), W_up=g.normal(size=(mlp, d)) / math.sqrt(d),
                   W_down=g.normal(size=(d, mlp)) / math.sqrt(mlp))
+    if adapt_rest:
+        g2 = np.random.default_rng(seed + 1000)
+        kw.update(A_o=g2.normal(size=(n_ad, r, nq)) / math.sqrt(nq), B_o=g2.normal(size=(n_ad, d, r)) * 0.3,
+                  A_gu=g2.normal(size=(n_ad, 2, r, d)) / math.sqrt(d), B_gate=g2.normal(size=(n_ad, mlp, r)) * 0.3,
+                  B_up=g2.normal(size=(n_ad, mlp, r)) * 0.3, A_down=g2.normal(size=(n_ad, r, mlp)) / math.sqrt(mlp),
+                  B_down=g2.normal(size=(n_ad, d, r)) * 0.3)
     return orc.Layer(hq, hkv, h,
                      W_qkv=g.normal(size=(nq + 2 * nkv, d)) / math.sqrt(d),
                      A=g.normal(size=(n_ad, 3, r, d)) / math.sqrt(d),
@@ -405,6 +412,82 @@ def test_stack_cache_reuse_equals_recompute():
     got, rows = orc.ref_stack_cached(layers, base_caches, P, x[P:], k, a)
     assert np.allclose(got, full[P:], rtol=1e-10, atol=1e-11)
     assert all(kn.shape[0] == S for kn, _ in rows)
+
+
+# ------------------------------------------------------------------ adapters on the other linears
+def _merged_tail_layer(L, a):
+    """The same layer with Delta folded into the weights of adapter a: W + s B A (Eq.5 for every linear)."""
+    s = L.scale[a]
+    return dataclasses.replace(
+        L, W_o=L.W_o + s * L.B_o[a] @ L.A_o[a], W_gate=L.W_gate + s * L.B_gate[a] @ L.A_gu[a, 0],
+        W_up=L.W_up + s * L.B_up[a] @ L.A_gu[a, 1], W_down=L.W_down + s * L.B_down[a] @ L.A_down[a],
+        A_o=None, B_o=None, A_gu=None, B_gate=None, B_up=None, A_down=None, B_down=None)
+
+
+def test_adapted_tail_rows_after_k_use_merged_weights_rows_before_k_the_base():
+    L = rand_layer(40, mlp=40, adapt_rest=True)
+    g = np.random.default_rng(41)
+    x, attn = g.normal(size=(6, 24)), g.normal(size=(6, L.n_q))
+    pos, k, a = 10 + np.arange(6), 13, 1
+    got = orc.layer_tail(L, x, attn, "f64", pos, k, a)
+    base = orc.layer_tail(dataclasses.replace(L, A_o=None, A_gu=None, A_down=None), x, attn)
+    merged = orc.layer_tail(_merged_tail_layer(L, a), x, attn)
+    assert np.allclose(got[:3], base[:3], rtol=1e-13, atol=1e-14)            # positions 10, 11, 12 < k
+    assert np.allclose(got[3:], merged[3:], rtol=1e-11, atol=1e-12)          # positions 13.. >= k
+    assert not np.allclose(got[3:], base[3:], atol=1e-3)                     # and the adapter does something
+    # no adapter / no positions: the base layer
+    assert np.array_equal(orc.layer_tail(L, x, attn, "f64", pos, k, -1), base)
+    assert np.array_equal(orc.layer_tail(L, x, attn), base)
+    # only one of the linears adapted: the others stay base (each term is separate)
+    only_o = dataclasses.replace(L, A_gu=None, A_down=None)
+    h_diff = orc.layer_tail(only_o, x, attn, "f64", pos, 0, a) - orc.layer_tail(_merged_tail_layer(
+        dataclasses.replace(L, B_gate=L.B_gate * 0, B_up=L.B_up * 0, B_down=L.B_down * 0), a), x, attn)
+    assert np.abs(h_diff).max() < 1e-11
+
+
+def test_adapted_tail_against_scalar_loops():
+    L = rand_layer(42, d=6, hq=2, hkv=1, h=4, r=2, mlp=5, adapt_rest=True)
+    g = np.random.default_rng(43)
+    x, attn = g.normal(size=(2, 6)), g.normal(size=(2, L.n_q))
+    a, s = 0, L.scale[0]
+    got = orc.layer_tail(L, x, attn, "f64", np.array([4, 5]), 5, a)
+
+    def lin(z, W, A, B, on):
+        out = []
+        for o in range(W.shape[0]):
+            v = sum(W[o, c] * z[c] for c in range(len(z)))
+            if on:
+                v += s * sum(B[o, j] * sum(A[j, c] * z[c] for c in range(len(z))) for j in range(A.shape[0]))
+            out.append(v)
+        return out
+
+    for i, on in enumerate([False, True]):
+        h = [x[i, c] + v for c, v in enumerate(lin(list(attn[i]), L.W_o, L.A_o[a], L.B_o[a], on))]
+        ms = sum(v * v for v in h) / len(h)
+        hn = [h[c] / math.sqrt(ms + L.rms_eps) * L.rms2_gain[c] for c in range(len(h))]
+        gate = lin(hn, L.W_gate, L.A_gu[a, 0], L.B_gate[a], on)
+        up = lin(hn, L.W_up, L.A_gu[a, 1], L.B_up[a], on)
+        act = [gv / (1 + math.exp(-gv)) * uv for gv, uv in zip(gate, up)]
+        want = [h[c] + v for c, v in enumerate(lin(act, L.W_down, L.A_down[a], L.B_down[a], on))]
+        assert np.allclose(got[i], want, rtol=1e-12, atol=1e-13)
+
+
+def test_stack_with_adapted_tail_cache_reuse_equals_recompute():
+    """Proposition 1 with adapters on every linear: rows before k are the base model's in every layer, so the
+    base caches can be reused."""
+    layers = [rand_layer(50 + i, mlp=32, adapt_rest=True) for i in range(3)]
+    P, S, k, a = 5, 4, 5, 1
+    x = _x(53, P + S, 24)
+    full, caches = orc.ref_stack_full(layers, x, k, a)
+    base_out, base_caches = orc.ref_stack_full(layers, x[:P], 0, -1)
+    for (Kf, Vf), (Kb, Vb) in zip(caches, base_caches):
+        assert np.allclose(Kf[:P], Kb, rtol=1e-12, atol=1e-13) and np.allclose(Vf[:P], Vb, rtol=1e-12, atol=1e-13)
+    got, _ = orc.ref_stack_cached(layers, base_caches, P, x[P:], k, a)
+    assert np.allclose(got, full[P:], rtol=1e-10, atol=1e-11)
+    # and the tail adapters matter: stripping them changes the adapted rows
+    stripped = [dataclasses.replace(L, A_o=None, A_gu=None, A_down=None) for L in layers]
+    plain, _ = orc.ref_stack_cached(stripped, base_caches, P, x[P:], k, a)
+    assert not np.allclose(plain, got, atol=1e-3)
 
 
 # ------------------------------------------------------------------ output head (first token)
