@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-lora", action="store_true", help="c5 only: skip the k=0 recompute baseline")
     ap.add_argument("--plain", action="store_true", help="force the plain fp32-FMA kernels")
+    ap.add_argument("--adapt-rest", action="store_true",
+                    help="c5 only: adapters on W_o and the MLP linears too (Eq.6 on every linear of the layer)")
     ap.add_argument("--opt", action="append", default=[], help="library option key=value (repeatable)")
     return ap.parse_args()
 
@@ -147,6 +149,9 @@ def main():
     n_layers = 1
     if name == "c5":
         n_layers = args.layers or wl.N_LAYERS_STACK
+        if args.adapt_rest:
+            import dataclasses
+            shape = dataclasses.replace(shape, adapt_rest=True)
     steps = args.steps or {"c2": 200, "c3": 20, "c4": 50, "c5": 5}[name]
     warmup = args.warmup or {"c2": 20, "c3": 3, "c4": 5, "c5": 1}[name]
     rotate = args.rotate if args.rotate >= 0 else {"c2": 8, "c3": 2, "c4": 1, "c5": 1}[name]
@@ -256,7 +261,8 @@ def main():
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": f"{name}: " + (batch.__doc__ or ""), "sequences": batch.n_seqs, "suffix_tokens": batch.T,
                    "prefix_tokens": int(sum(batch.P)), "rank": shape.rank, "layers": n_layers,
-                   "rotating_buffer_sets": rotate, "kernels": "plain" if args.plain else "auto"},
+                   "rotating_buffer_sets": rotate, "kernels": "plain" if args.plain else "auto",
+                   "adapted_linears": "q,k,v,o,gate,up,down" if getattr(shape, "adapt_rest", False) else "q,k,v"},
         "ttft_ms": ms_per_step,
         "roofline": roof,
         "kernels": kernels,

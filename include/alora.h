@@ -83,6 +83,17 @@ typedef struct {
   const void *W_gate;   /* DEVICE [I, d]                                               */
   const void *W_up;     /* DEVICE [I, d]                                               */
   const void *W_down;   /* DEVICE [d, I]                                               */
+  /* Optional adapters of those linears (Section 2, remark after Eq.6: MLP blocks can be adapted
+   * "via directly corresponding equations"; Proposition 1's proof covers them): the same rank,
+   * scales and per-row gating (adapter >= 0 and position >= k) as q, k, v.  Each group is either
+   * given completely or NULL (that linear stays the base model's).  alora_stack_prefill only. */
+  const void *A_o;      /* DEVICE [n_adapters, rank, N_q]                               */
+  const void *B_o;      /* DEVICE [n_adapters, d, rank]                                 */
+  const void *A_gu;     /* DEVICE [n_adapters, 2, rank, d]   (order gate, up)           */
+  const void *B_gate;   /* DEVICE [n_adapters, I, rank]                                 */
+  const void *B_up;     /* DEVICE [n_adapters, I, rank]                                 */
+  const void *A_down;   /* DEVICE [n_adapters, rank, I]                                 */
+  const void *B_down;   /* DEVICE [n_adapters, d, rank]                                 */
 } alora_layer_desc;
 
 /* KV cache of one layer (Eq.3: the stored K_{1:t}, V_{1:t}).  A flat pool of token rows;

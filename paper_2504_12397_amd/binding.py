@@ -30,7 +30,9 @@ class LayerDesc(C.Structure):
                 ("B_v", C.c_void_p), ("scale", C.POINTER(C.c_float)), ("rms_gain", C.c_void_p),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float),
                 ("W_o", C.c_void_p), ("rms2_gain", C.c_void_p), ("W_gate", C.c_void_p), ("W_up", C.c_void_p),
-                ("W_down", C.c_void_p)]
+                ("W_down", C.c_void_p),
+                ("A_o", C.c_void_p), ("B_o", C.c_void_p), ("A_gu", C.c_void_p), ("B_gate", C.c_void_p),
+                ("B_up", C.c_void_p), ("A_down", C.c_void_p), ("B_down", C.c_void_p)]
 
 
 class KVCacheDesc(C.Structure):
@@ -119,7 +121,8 @@ class Layer:
                               self.scale.ctypes.data_as(C.POINTER(C.c_float)) if n_ad else None,
                               _ptr(g("rms_gain")), float(rms_eps), float(rope_theta),
                               _ptr(g("W_o")), _ptr(g("rms2_gain")), _ptr(g("W_gate")), _ptr(g("W_up")),
-                              _ptr(g("W_down")))
+                              _ptr(g("W_down")), _ptr(g("A_o")), _ptr(g("B_o")), _ptr(g("A_gu")), _ptr(g("B_gate")),
+                              _ptr(g("B_up")), _ptr(g("A_down")), _ptr(g("B_down")))
         self.n_q = n_q_heads * head_dim
         self.d = int(W.shape[1])
         self.dtype = W.dtype

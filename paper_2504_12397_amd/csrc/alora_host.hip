@@ -198,6 +198,13 @@ alora_status check_layer(alora_ctx *ctx, const alora_layer_desc *ly, bool need_t
     if (ly->intermediate < 1) return fail(ctx, ALORA_ESHAPE, "intermediate = %d must be positive", ly->intermediate);
     if (!ly->W_o || !ly->rms2_gain || !ly->W_gate || !ly->W_up || !ly->W_down)
       return fail(ctx, ALORA_EINVAL, "W_o, rms2_gain, W_gate, W_up and W_down are required for a layer stack");
+    const bool any_rest = ly->A_o || ly->B_o || ly->A_gu || ly->B_gate || ly->B_up || ly->A_down || ly->B_down;
+    if (any_rest && ly->n_adapters < 1)
+      return fail(ctx, ALORA_EINVAL, "adapters of W_o / the MLP are given but n_adapters = 0");
+    if ((ly->A_o != nullptr) != (ly->B_o != nullptr)) return fail(ctx, ALORA_EINVAL, "A_o and B_o go together");
+    if ((ly->A_down != nullptr) != (ly->B_down != nullptr)) return fail(ctx, ALORA_EINVAL, "A_down and B_down go together");
+    if ((ly->A_gu != nullptr) != (ly->B_gate != nullptr) || (ly->A_gu != nullptr) != (ly->B_up != nullptr))
+      return fail(ctx, ALORA_EINVAL, "A_gu, B_gate and B_up go together");
   }
   L->d = ly->d; L->n_q_heads = ly->n_q_heads; L->n_kv_heads = ly->n_kv_heads; L->head_dim = ly->head_dim;
   L->rank = ly->rank; L->n_adapters = ly->n_adapters;
@@ -291,6 +298,8 @@ struct Workspace {
   int n_qtiles = 0;
   const DecItem *ditems = nullptr;   // work list of the MFMA decode kernel
   int n_ditems = 0;
+  const float *scale_dev = nullptr;  // [n_adapters] s_a on the device (adapters of W_o / the MLP)
+  bool any_adapter = false;
 };
 
 int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
@@ -313,7 +322,10 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
   w.xh = b.take<char>((size_t)T * L.d * esz);
   w.tlow = b.take<float>((size_t)T * 3 * std::max(L.rank, 1));
   w.y_floats = (size_t)T * L.n_qkv * std::max(k_splits, 1);
-  if (stack) w.y_floats = std::max(w.y_floats, (size_t)8 * T * L.d);      // split-K partials of W_o / W_down
+  if (stack) {      // split-K partials of W_o / W_down and of the down-projections of their adapters
+    w.y_floats = std::max(w.y_floats, (size_t)8 * T * L.d);
+    w.y_floats = std::max(w.y_floats, (size_t)8 * T * std::max(L.n_adapters, 1) * 2 * std::max(L.rank, 1));
+  }
   w.Y = b.take<float>(w.y_floats);
   w.Q = b.take<char>((size_t)T * L.n_q * esz);
   w.partials = b.take<float>(attn_plain_partial_floats(L, T, n_splits));
@@ -365,6 +377,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.Cpart = w.Y;
       g.tlow = pl.any_adapter ? (const bf16 *)w.tlow : nullptr;
       g.rank = L.rank;
+      g.lr_parts = 3;
       g.Bq = (const bf16 *)ly->B_q; g.Bk = (const bf16 *)ly->B_k; g.Bv = (const bf16 *)ly->B_v;
       g.n_q = L.n_q; g.n_kv = L.n_kv;
       g.row_adapter = w.rm.adapter;
@@ -419,15 +432,43 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
                 int T_rows, T *out, hipStream_t s) {
   RowMeta none{};
   const bool mfma = w.mfma && std::is_same<T, bf16>::value;
-  auto dense = [&](const void *A, const void *W, const void *R, void *C, int N, int K) {
+  const int r = L.rank, n_ad = L.n_adapters;
+  // Adapters of these linears (Eq.6 applied to them): on the MFMA path t = s_a A_a z is computed for all
+  // adapters at once as a skinny GEMM against the stacked down-matrices [n_ad * parts * r, K] (exactly how
+  // they are stored), each adapted row then picks its adapter's slice as a bf16 (hi, lo) pair, and the
+  // up-projection runs as extra k-steps of the base GEMM; on the plain path the term is added afterwards.
+  auto lowrank_t = [&](const void *z, int K, const void *A_all, int parts) {
+    GemmArgs g{};
+    g.A = (const bf16 *)z; g.lda = K;
+    g.B = (const bf16 *)A_all; g.ldb = K;
+    g.M = T_rows; g.N = n_ad * parts * r; g.K = K;
+    int splits = gemm_mfma_pick_splits(T_rows, g.N, K, ctx->n_cu);
+    while (splits > 1 && (size_t)splits * T_rows * g.N > w.y_floats) splits /= 2;
+    g.k_splits = splits;
+    g.Cpart = w.Y;
+    launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+    launch_tlow_select(w.Y, splits, T_rows, n_ad, parts, r, w.rm.adapter, w.scale_dev, (bf16 *)w.tlow, s);
+  };
+  auto set_lowrank = [&](GemmArgs &g, const void *B0, const void *B1, int parts, int width) {
+    g.tlow = (const bf16 *)w.tlow; g.rank = r; g.lr_parts = parts;
+    g.Bq = (const bf16 *)B0; g.Bk = (const bf16 *)B1; g.Bv = nullptr;
+    g.n_q = width; g.n_kv = parts == 1 ? 0 : width;
+    g.row_adapter = w.rm.adapter;
+  };
+  // C = A W^T (+ R), with the gated low-rank term of (Al, Bl) when given
+  auto dense = [&](const void *A, const void *W, const void *R, void *C, int N, int K, const void *Al, const void *Bl,
+                   int parts = 1, int part = 0) {
+    const bool lr = Al != nullptr && w.any_adapter;
     if (mfma) {
+      if (lr) lowrank_t(A, K, Al, 1);
       GemmArgs g{};
       g.A = (const bf16 *)A; g.lda = K;
       g.B = (const bf16 *)W; g.ldb = K;
       g.M = T_rows; g.N = N; g.K = K;
       g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+      if (lr) set_lowrank(g, Bl, nullptr, 1, N);
       // few row tiles: split the reduction to fill the chip, partial sums go through the Y buffer
-      const int splits = gemm_mfma_pick_splits(T_rows, N, K, ctx->n_cu);
+      const int splits = ctx->opt_gemm_splits == 1 ? 1 : gemm_mfma_pick_splits(T_rows, N, K, ctx->n_cu);
       if (splits > 1 && (size_t)splits * T_rows * N <= w.y_floats && ((int64_t)T_rows * N) % 4 == 0) {
         g.k_splits = splits;
         g.Cpart = w.Y;
@@ -440,6 +481,9 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       }
     } else {
       launch_gemm_plain<T>((const T *)A, (const T *)W, (const T *)R, (T *)C, T_rows, N, K, s);
+      if (lr)
+        launch_lowrank_add_plain<T>((const T *)A, K, (const T *)Al, parts, part, (const T *)Bl, N, r, w.rm.adapter,
+                                    w.scale_dev, (T *)C, T_rows, s);
     }
   };
   // h1 = x + attn W_o^T, hn = RMSNorm(h1).  When the projection is split over the reduction axis anyway, the
@@ -447,13 +491,17 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
   bool normed = false;
   {
     ProfScope p(ctx, K_OPROJ, s);
-    const int splits = mfma ? gemm_mfma_pick_splits(T_rows, L.d, L.n_q, ctx->n_cu) : 1;
+    const int splits = mfma && ctx->opt_gemm_splits != 1 ? gemm_mfma_pick_splits(T_rows, L.d, L.n_q, ctx->n_cu) : 1;
     if (mfma && splits > 1 && (size_t)splits * T_rows * L.d <= w.y_floats && splitk_reduce_norm_supported(L.d)) {
       GemmArgs g{};
       g.A = (const bf16 *)w.attn; g.lda = L.n_q;
       g.B = (const bf16 *)ly->W_o; g.ldb = L.n_q;
       g.M = T_rows; g.N = L.d; g.K = L.n_q;
       g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+      if (ly->A_o && w.any_adapter) {
+        lowrank_t(w.attn, L.n_q, ly->A_o, 1);
+        set_lowrank(g, ly->B_o, nullptr, 1, L.d);
+      }
       g.k_splits = splits;
       g.Cpart = w.Y;
       launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
@@ -461,7 +509,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
                                 (bf16 *)w.h1, (bf16 *)w.hn, s);
       normed = true;
     } else {
-      dense(w.attn, ly->W_o, x, w.h1, L.d, L.n_q);
+      dense(w.attn, ly->W_o, x, w.h1, L.d, L.n_q, ly->A_o, ly->B_o);
     }
   }
   if (!normed) {
@@ -483,13 +531,17 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     g.B = (const bf16 *)ly->W_gate; g.B2 = (const bf16 *)ly->W_up; g.ldb = L.d;
     g.M = T_rows; g.N = 2 * ly->intermediate; g.K = L.d; g.k_splits = 1;
     g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+    if (ly->A_gu && w.any_adapter) {
+      lowrank_t(w.hn, L.d, ly->A_gu, 2);
+      set_lowrank(g, ly->B_gate, ly->B_up, 2, ly->intermediate);
+    }
     g.C = (bf16 *)w.gate; g.ldc = ly->intermediate;
     launch_gemm_mfma(g, GEMM_EPI_SWIGLU, s);
   } else {
     {
       ProfScope p(ctx, K_GATEUP, s);
-      dense(w.hn, ly->W_gate, nullptr, w.gate, ly->intermediate, L.d);
-      dense(w.hn, ly->W_up, nullptr, w.up, ly->intermediate, L.d);
+      dense(w.hn, ly->W_gate, nullptr, w.gate, ly->intermediate, L.d, ly->A_gu, ly->B_gate, 2, 0);
+      dense(w.hn, ly->W_up, nullptr, w.up, ly->intermediate, L.d, ly->A_gu, ly->B_up, 2, 1);
     }
     {
       ProfScope p(ctx, K_SILU, s);
@@ -498,7 +550,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
   }
   {
     ProfScope p(ctx, K_DOWN, s);
-    dense(w.gate, ly->W_down, w.h1, out, L.d, ly->intermediate);
+    dense(w.gate, ly->W_down, w.h1, out, L.d, ly->intermediate, ly->A_down, ly->B_down);
   }
 }
 
@@ -694,14 +746,16 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
         qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : make_int4(-1, 0, 0, 0));
   }
   const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
-  const size_t work_bytes = qtiles.size() * sizeof(int4) + ditems.size() * sizeof(DecItem);   // one of the two lists
-  const size_t meta_bytes = seq_bytes + work_bytes;
+  const size_t work_bytes = (qtiles.size() * sizeof(int4) + ditems.size() * sizeof(DecItem) + 15) & ~(size_t)15;   // one of the two lists
+  const size_t scale_bytes = stack ? (size_t)L.n_adapters * sizeof(float) : 0;
+  const size_t meta_bytes = seq_bytes + work_bytes + scale_bytes;
   MetaSlot *slot = nullptr;
   st = acquire_slot(ctx, meta_bytes, &slot);
   if (st != ALORA_OK) return st;
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
   if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(int4));
   if (!ditems.empty()) memcpy(slot->host + seq_bytes, ditems.data(), ditems.size() * sizeof(DecItem));
+  if (scale_bytes) memcpy(slot->host + seq_bytes + work_bytes, layers[0].scale, scale_bytes);
   HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
   const SeqMeta *seqs_dev = (const SeqMeta *)slot->dev;
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
@@ -714,6 +768,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.n_qtiles = (int)qtiles.size();
   w.ditems = (const DecItem *)(slot->dev + seq_bytes);
   w.n_ditems = (int)ditems.size();
+  w.scale_dev = (const float *)(slot->dev + seq_bytes + work_bytes);
+  w.any_adapter = pl.any_adapter;
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {

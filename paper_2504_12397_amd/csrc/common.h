@@ -82,6 +82,11 @@ template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
                         const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s);
 
+// C[M, N] += gated low-rank term (Eq.6) of one linear: s_a B_a (A_{a,part} x) for rows with row_adapter >= 0
+template <typename T>
+void launch_lowrank_add_plain(const T *x, int K, const T *A, int parts, int part, const T *B, int N, int rank,
+                              const int32_t *row_adapter, const float *scale, T *C, int M, hipStream_t s);
+
 // output head: fp32 logits[B, V] = xh[B, d] W[V, d]^T (any shape), and the greedy token of every row
 template <typename T>
 void launch_lm_logits_plain(const T *xh, const T *W, int B, int V, int d, float *logits, hipStream_t s);

@@ -175,19 +175,33 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
       int row = m0 + wm0 + mi * 32 + l32;
       a_row[mi] = row < M ? g.row_adapter[row] : -1;
     }
-    // per 32-column block: which of q / k / v it belongs to, and the row of B it reads
+    // per 32-column block: which part (q / k / v; gate / up; the only one) it belongs to, the row of the
+    // up-matrix B it reads, and the distance between adapters in that matrix
+    const int parts = g.lr_parts;
     int p_of[TN];
     const bf16 *brow[TN];
+    int64_t a_stride[TN];
     bool col_ok[TN];
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni) {
-      const int colb = n0 + wn0 + ni * 32, col = colb + l32;
-      p_of[ni] = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
-      col_ok[ni] = col < N;
-      const int cc = col < N ? col : N - 1;
-      if (cc < g.n_q) brow[ni] = g.Bq + (int64_t)cc * r;
-      else if (cc < g.n_q + g.n_kv) brow[ni] = g.Bk + (int64_t)(cc - g.n_q) * r;
-      else brow[ni] = g.Bv + (int64_t)(cc - g.n_q - g.n_kv) * r;
+      if (EPI == GEMM_EPI_SWIGLU) {
+        // accumulator blocks alternate gate, up; both belong to column (n0 + wn0) / 2 + 32 (ni / 2) + l32 of act
+        const int col = (n0 >> 1) + (wn0 >> 1) + (ni >> 1) * 32 + l32;
+        p_of[ni] = ni & 1;
+        col_ok[ni] = col < (N >> 1);
+        const int cc = col_ok[ni] ? col : (N >> 1) - 1;
+        brow[ni] = ((ni & 1) ? g.Bk : g.Bq) + (int64_t)cc * r;
+        a_stride[ni] = (int64_t)(N >> 1) * r;
+      } else {
+        const int colb = n0 + wn0 + ni * 32, col = colb + l32;
+        p_of[ni] = colb < g.n_q ? 0 : (colb < g.n_q + g.n_kv ? 1 : 2);
+        col_ok[ni] = col < N;
+        const int cc = col < N ? col : N - 1;
+        if (cc < g.n_q) brow[ni] = g.Bq + (int64_t)cc * r;
+        else if (cc < g.n_q + g.n_kv) brow[ni] = g.Bk + (int64_t)(cc - g.n_q) * r;
+        else brow[ni] = g.Bv + (int64_t)(cc - g.n_q - g.n_kv) * r;
+        a_stride[ni] = (int64_t)(p_of[ni] == 0 ? g.n_q : g.n_kv) * r;
+      }
     }
     while (present) {
       const int a = __builtin_ctzll(present);
@@ -203,10 +217,8 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
 #pragma unroll
           for (int ni = 0; ni < TN; ++ni) {
             bu[h2][ni] = u32x4{0, 0, 0, 0};
-            if (live && col_ok[ni]) {
-              const int64_t stride = (int64_t)(p_of[ni] == 0 ? g.n_q : g.n_kv) * r;
-              bu[h2][ni] = *reinterpret_cast<const u32x4 *>(brow[ni] + (int64_t)a * stride + ks + lhi * 8);
-            }
+            if (live && col_ok[ni])
+              bu[h2][ni] = *reinterpret_cast<const u32x4 *>(brow[ni] + (int64_t)a * a_stride[ni] + ks + lhi * 8);
           }
 #pragma unroll
           for (int mi = 0; mi < TM; ++mi) {
@@ -216,7 +228,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
               au[h2][mi][ni] = u32x4{0, 0, 0, 0};
               if (live && a_row[mi] == a)
                 au[h2][mi][ni] =
-                    *reinterpret_cast<const u32x4 *>(g.tlow + ((int64_t)row * 3 + p_of[ni]) * 2 * r + ks2 + lhi * 8);
+                    *reinterpret_cast<const u32x4 *>(g.tlow + ((int64_t)row * parts + p_of[ni]) * 2 * r + ks2 + lhi * 8);
             }
           }
         }
@@ -372,6 +384,33 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(const float *__
       }
     }
   }
+}
+
+__global__ __launch_bounds__(256) void tlow_select_kernel(const float *__restrict__ Y, int splits, int M, int n_adapters,
+                                                          int parts, int rank, const int32_t *__restrict__ row_adapter,
+                                                          const float *__restrict__ scale, bf16 *__restrict__ tlow) {
+  const int row = blockIdx.x;
+  const int a = row_adapter[row];
+  if (a < 0) return;
+  const int N = n_adapters * parts * rank;
+  const float sc = scale[a];
+  for (int i = threadIdx.x; i < parts * rank; i += 256) {
+    const int p = i / rank, j = i - p * rank;
+    float t = 0.f;
+    for (int sp = 0; sp < splits; ++sp) t += Y[((int64_t)sp * M + row) * N + (a * parts + p) * rank + j];
+    t *= sc;
+    const bf16 hi = (bf16)t;
+    bf16 *dst = tlow + (((int64_t)row * parts + p) * 2) * rank + j;
+    dst[0] = hi;
+    dst[rank] = (bf16)(t - (float)hi);
+  }
+}
+
+void launch_tlow_select(const float *Y, int splits, int M, int n_adapters, int parts, int rank,
+                        const int32_t *row_adapter, const float *scale, bf16 *tlow, hipStream_t s) {
+  if (M == 0) return;
+  hipLaunchKernelGGL(tlow_select_kernel, dim3(M), dim3(256), 0, s, Y, splits, M, n_adapters, parts, rank, row_adapter,
+                     scale, tlow);
 }
 
 bool splitk_reduce_norm_supported(int N) { return N % 4 == 0 && N <= 16384; }

@@ -486,4 +486,46 @@ void launch_silu_mul(const T *gate, const T *up, T *out, int64_t n, hipStream_t 
 template void launch_silu_mul<float>(const float *, const float *, float *, int64_t, hipStream_t);
 template void launch_silu_mul<bf16>(const bf16 *, const bf16 *, bf16 *, int64_t, hipStream_t);
 
+// Gated low-rank term of Eq.6 added to an already computed linear, any shape and dtype:
+// C[row, :] += s_a * B_a (A_{a,part} x[row]) for adapted rows (a = row_adapter[row] >= 0).  One workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(256) void lowrank_add_plain_kernel(const T *__restrict__ x, int K, const T *__restrict__ A,
+                                                                int parts, int part, const T *__restrict__ B, int N,
+                                                                int rank, const int32_t *__restrict__ row_adapter,
+                                                                const float *__restrict__ scale, T *__restrict__ C) {
+  __shared__ float t[256];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int a = row_adapter[row];
+  if (a < 0) return;
+  const T *xr = x + (int64_t)row * K;
+  const float sc = scale[a];
+  for (int j = wave; j < rank; j += 4) {
+    const T *ar = A + (((int64_t)a * parts + part) * rank + j) * K;
+    float acc = 0.f;
+    for (int c = lane; c < K; c += 64) acc += to_f32<T>(ar[c]) * to_f32<T>(xr[c]);
+    acc = wave_sum(acc);
+    if (lane == 0) t[j] = acc * sc;
+  }
+  __syncthreads();
+  for (int col = tid; col < N; col += 256) {
+    const T *br = B + ((int64_t)a * N + col) * rank;
+    float acc = 0.f;
+    for (int j = 0; j < rank; ++j) acc += to_f32<T>(br[j]) * t[j];
+    const int64_t o = (int64_t)row * N + col;
+    C[o] = from_f32<T>(to_f32<T>(C[o]) + acc);
+  }
+}
+
+template <typename T>
+void launch_lowrank_add_plain(const T *x, int K, const T *A, int parts, int part, const T *B, int N, int rank,
+                              const int32_t *row_adapter, const float *scale, T *C, int M, hipStream_t s) {
+  if (M == 0) return;
+  hipLaunchKernelGGL(lowrank_add_plain_kernel<T>, dim3(M), dim3(256), 0, s, x, K, A, parts, part, B, N, rank, row_adapter,
+                     scale, C);
+}
+template void launch_lowrank_add_plain<float>(const float *, int, const float *, int, int, const float *, int, int,
+                                              const int32_t *, const float *, float *, int, hipStream_t);
+template void launch_lowrank_add_plain<bf16>(const bf16 *, int, const bf16 *, int, int, const bf16 *, int, int,
+                                             const int32_t *, const float *, bf16 *, int, hipStream_t);
+
 }  // namespace alora

@@ -18,8 +18,11 @@ struct GemmArgs {
   bf16 *C; int ldc;            // BF16 / SWIGLU output
   const bf16 *R;               // BF16: optional residual [M, ldc]
   // gated low-rank term (Eq.6); tlow == nullptr switches it off
-  const bf16 *tlow;            // [M, 3, 2, rank]: s_a * A_{a,p} x for adapted rows as bf16 (hi, lo) pairs
+  const bf16 *tlow;            // [M, lr_parts, 2, rank]: s_a * A_{a,p} x for adapted rows as bf16 (hi, lo) pairs
   int rank;
+  int lr_parts;                // 3: parts are the column ranges q | k | v (widths n_q, n_kv, n_kv; up-matrices Bq,
+                               // Bk, Bv); 1: every column is part 0 (n_q = N, Bq); SwiGLU, 2: gate (Bq) and up
+                               // (Bk) columns, n_q = I
   const bf16 *Bq, *Bk, *Bv;
   int n_q, n_kv;
   const int32_t *row_adapter;  // [M]: adapter id of adapted rows, -1 otherwise
@@ -96,6 +99,10 @@ double measure_ceiling(int kind, int n_cu, hipStream_t s);
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s);
+// tlow[row, p, {hi, lo}, j] = s_a * sum over splits of Y[split, row, (a * parts + p) * rank + j] for adapted rows
+// (a = row_adapter[row] >= 0): picks each row's adapter out of a projection on all adapters' down-matrices
+void launch_tlow_select(const float *Y, int splits, int M, int n_adapters, int parts, int rank,
+                        const int32_t *row_adapter, const float *scale, bf16 *tlow, hipStream_t s);
 // C[mn] = bf16(sum_s part[s][mn] + R[mn]); mn must be a multiple of 4
 void launch_splitk_reduce(const float *part, int splits, int64_t mn, const bf16 *R, bf16 *C, hipStream_t s);
 // the same for whole rows plus the RMSNorm of the summed row: C = bf16(h), Cn = bf16(RMSNorm(h; gain))

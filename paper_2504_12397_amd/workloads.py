@@ -34,6 +34,7 @@ class LayerShape:
     dtype: str = "bf16"          # "bf16" or "f32": storage type of x, W, A, B, cache, outputs
     rmsnorm: bool = True
     intermediate: int = 0        # SwiGLU width; 0 = attention block only
+    adapt_rest: bool = False     # adapters on W_o and the MLP linears too (needs intermediate > 0)
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     scale: float = 2.0
@@ -112,7 +113,8 @@ def make_layer(shape: LayerShape, rng: Rng, tag: str = "L0") -> Dict[str, Option
     W_qkv [N_q+2N_kv, d] (rows: q | k | v); A [n_ad, 3, r, d]; B_q [n_ad, N_q, r];
     B_k, B_v [n_ad, N_kv, r]; scale: python list [n_ad]; rms_gain [d] or None.
     With shape.intermediate > 0 also W_o [d, N_q], rms2_gain [d], W_gate, W_up [I, d],
-    W_down [d, I]."""
+    W_down [d, I]; with shape.adapt_rest their adapters A_o [n_ad, r, N_q], B_o [n_ad, d, r],
+    A_gu [n_ad, 2, r, d], B_gate, B_up [n_ad, I, r], A_down [n_ad, r, I], B_down [n_ad, d, r]."""
     dt = shape.torch_dtype
     d, r, na = shape.d, shape.rank, shape.n_adapters
     sd = 1.0 / np.sqrt(d)
@@ -131,6 +133,14 @@ def make_layer(shape: LayerShape, rng: Rng, tag: str = "L0") -> Dict[str, Option
         L["W_gate"] = rng.normal(f"{tag}.W_gate", (I, d), sd, dtype=dt)
         L["W_up"] = rng.normal(f"{tag}.W_up", (I, d), sd, dtype=dt)
         L["W_down"] = rng.normal(f"{tag}.W_down", (d, I), 1.0 / np.sqrt(I), dtype=dt)
+        if shape.adapt_rest:
+            L["A_o"] = rng.normal(f"{tag}.A_o", (na, r, shape.n_q), 1.0 / np.sqrt(shape.n_q), dtype=dt)
+            L["B_o"] = rng.normal(f"{tag}.B_o", (na, d, r), 0.02, dtype=dt)
+            L["A_gu"] = rng.normal(f"{tag}.A_gu", (na, 2, r, d), sd, dtype=dt)
+            L["B_gate"] = rng.normal(f"{tag}.B_gate", (na, I, r), 0.02, dtype=dt)
+            L["B_up"] = rng.normal(f"{tag}.B_up", (na, I, r), 0.02, dtype=dt)
+            L["A_down"] = rng.normal(f"{tag}.A_down", (na, r, I), 1.0 / np.sqrt(I), dtype=dt)
+            L["B_down"] = rng.normal(f"{tag}.B_down", (na, d, r), 0.02, dtype=dt)
     return L
 
 

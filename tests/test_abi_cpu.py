@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(ab):
 
 def test_struct_layout_matches_header(ab):
     # natural alignment, no packing: 8 int32, then pointers / floats as declared
-    assert C.sizeof(ab.LayerDesc) == 8 * 4 + 7 * 8 + 2 * 4 + 5 * 8
+    assert C.sizeof(ab.LayerDesc) == 8 * 4 + 7 * 8 + 2 * 4 + 5 * 8 + 7 * 8
     assert ab.LayerDesc.W_qkv.offset == 32 and ab.LayerDesc.rms_eps.offset == 88 and ab.LayerDesc.W_o.offset == 96
     assert C.sizeof(ab.KVCacheDesc) == 64
 
@@ -202,3 +202,26 @@ def test_lm_head_validation(ab, vctx):
     assert go(logits=None, token=None) == "ALORA_EINVAL"
     assert go(logits=None) == "ALORA_EHIP" and go(token=None) == "ALORA_EHIP"
     assert f(None, ab.ALORA_BF16, 64, 1000, P, P, 1e-5, P, 2, P, P, None) == ab.ALORA_EINVAL
+
+
+def test_tail_adapter_groups_are_checked_as_a_whole(ab, vctx):
+    """Adapters of W_o / the MLP linears (layer stack only): each group is complete or absent."""
+    p32 = C.POINTER(C.c_int32)
+
+    def go(**fields):
+        desc, cache, cu, k, a, B, keep, ln = make_args(ab, intermediate=128)
+        for f in ("W_o", "rms2_gain", "W_gate", "W_up", "W_down"):
+            setattr(desc, f, FakeBuf.PTR)
+        for f, v in fields.items():
+            setattr(desc, f, v)
+        st = ab._lib.alora_stack_prefill(vctx, C.byref(desc), 1, C.byref(cache), FakeBuf.PTR, cu.ctypes.data_as(p32),
+                                         k.ctypes.data_as(p32), a.ctypes.data_as(p32), B, FakeBuf.PTR, None)
+        return ab._lib.alora_status_string(st).decode()
+
+    P = FakeBuf.PTR
+    assert go() == "ALORA_EHIP"                                     # valid, nothing to launch on
+    assert go(A_o=P, B_o=P, A_gu=P, B_gate=P, B_up=P, A_down=P, B_down=P) == "ALORA_EHIP"
+    assert go(A_o=P) == "ALORA_EINVAL"
+    assert go(B_down=P) == "ALORA_EINVAL"
+    assert go(A_gu=P, B_gate=P) == "ALORA_EINVAL"
+    assert go(A_o=P, B_o=P, n_adapters=0, rank=0) == "ALORA_EINVAL"

@@ -359,6 +359,50 @@ def test_stack_cache_reuse_against_oracle_recompute(ab, ctx, shape):
     assert H.rel_err(H.f64(got), want[P:]) <= tol
 
 
+REST_BF16 = dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=True)
+REST_F32 = dataclasses.replace(SMALL_F32, intermediate=320, adapt_rest=True)
+
+
+@pytest.mark.parametrize("shape,opts", [(REST_BF16, {}), (REST_BF16, {"gemm_splits": 1}), (REST_BF16, {"kernels": 1}),
+                                        (REST_F32, {})], ids=["bf16", "bf16-unsplit", "bf16-plain", "fp32"])
+def test_stack_with_adapters_on_every_linear(ab, shape, opts):
+    """Eq.6 applied to W_o and the MLP linears as well (Section 2's remark on MLP blocks): cache reuse
+    over a base prefix, then a mixed batch whose sequences straddle their invocation points."""
+    c = ab.Context(0)
+    try:
+        for k_, v in opts.items():
+            c.set_option(k_, v)
+        n_layers, P, S, a = 2, 150, 45, 1
+        tensors, layers, x_all = make_stack_case(shape, n_layers, P, S, seed=410)
+        want, _ = orc.ref_stack_full(layers, H.f64(x_all), P, a, shape.dtype)
+        stripped = [dataclasses.replace(L, A_o=None, A_gu=None, A_down=None) for L in layers]
+        without, _ = orc.ref_stack_full(stripped, H.f64(x_all), P, a, shape.dtype)
+        assert H.rel_err(without[P:], want[P:]) > 0.05          # the adapters of the tail matter in this case
+        glayers = [H.gpu_layer(t, shape) for t in tensors]
+        tol = H.TOL[shape.dtype] * (2 if shape.dtype == "bf16" else 1)
+        caches = [ab.KVCache([P + S], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda") for _ in range(n_layers)]
+        xg = x_all.cuda().contiguous()
+        base_out = ab.alora_stack_prefill(c, glayers, caches, xg[:P].contiguous(), [0, P], [0], [-1])
+        got = ab.alora_stack_prefill(c, glayers, caches, xg[P:].contiguous(), [0, S], [P], [a])
+        torch.cuda.synchronize()
+        assert H.rel_err(H.f64(base_out), want[:P]) <= tol
+        assert H.rel_err(H.f64(got), want[P:]) <= tol
+
+        # mixed batch from empty caches: adapter 0 from position 40 on, a base-only sequence, the last adapter from the start
+        lens, ks, ads = [90, 33, 140], [40, 0, 0], [0, -1, shape.n_adapters - 1]
+        rng = wl.Rng(411)
+        xs = [wl.make_hidden(rng, f"mix{b}", lens[b], shape) for b in range(3)]
+        caches = [ab.KVCache(lens, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda") for _ in range(n_layers)]
+        cu = [0, lens[0], lens[0] + lens[1], sum(lens)]
+        out = ab.alora_stack_prefill(c, glayers, caches, torch.cat(xs).cuda().contiguous(), cu, ks, ads)
+        torch.cuda.synchronize()
+        for b in range(3):
+            ref, _ = orc.ref_stack_full(layers, H.f64(xs[b]), ks[b], ads[b], shape.dtype)
+            assert H.rel_err(H.f64(out[cu[b]:cu[b + 1]]), ref) <= tol, f"sequence {b}"
+    finally:
+        c.close()
+
+
 # ------------------------------------------------------------------ full-size configurations
 def test_config2_full_size(ab, ctx):
     """One 8B-class layer: 4096 cached base tokens (cache from the oracle's base pass), 256 adapted tokens."""
