@@ -197,11 +197,12 @@ alora_status alora_decode_steps(alora_ctx *ctx, const alora_layer_desc *layer, a
                                 void *attn_out, void *stream);
 
 /* First-token pass through a stack of decoder layers (Proposition 2: the attention block as
- * in alora_prefill, then the per-token unadapted output projection and SwiGLU MLP with
- * residuals, layer after layer).  layers[l] must all have the same shape and dtype and
- * carry W_o / rms2_gain / W_gate / W_up / W_down.  caches[l] is layer l's cache; the
- * sequence layout (seq_offset, seq_capacity, seq_len) is read from caches[0] and applies
- * to every layer; only caches[0].seq_len is updated.
+ * in alora_prefill, then the per-token output projection and SwiGLU MLP with residuals -- with
+ * the base weights, or gated like q, k, v where the layer carries adapters for them -- layer
+ * after layer).  layers[l] must all have the same shape and dtype and carry W_o / rms2_gain /
+ * W_gate / W_up / W_down.  The adapter scales s_a are taken from layers[0].scale for the whole
+ * stack.  caches[l] is layer l's cache; the sequence layout (seq_offset, seq_capacity, seq_len,
+ * prefixes) is read from caches[0] and applies to every layer; only caches[0].seq_len is updated.
  *   x        DEVICE [T, d]  input hidden states of the new tokens (not modified)
  *   out      DEVICE [T, d]  hidden states after the last layer                         */
 alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers,
