@@ -61,6 +61,7 @@ struct alora_ctx {
   int opt_gemm_splits = 0;
   int opt_gemm_tile = 0;
   int opt_attn_waves = 0;
+  int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
   int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
   int opt_attn_pipeline = 1;     // 0 = software-pipelined attention kernel, 1 = the unpipelined one
   int n_cu = 256;
@@ -291,6 +292,7 @@ struct Workspace {
   size_t bytes;
   bool mfma = false;
   int k_splits = 1;
+  int lora_split = 0;                // the low-rank term of the QKV projection has a partial of its own
   bool attn_mfma = false;
   bool decode_mfma = false;
   int attn_waves = 8;
@@ -321,7 +323,7 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
   w.rm.slot = b.take<int64_t>(T);
   w.xh = b.take<char>((size_t)T * L.d * esz);
   w.tlow = b.take<float>((size_t)T * 3 * std::max(L.rank, 1));
-  w.y_floats = (size_t)T * L.n_qkv * std::max(k_splits, 1);
+  w.y_floats = (size_t)T * L.n_qkv * (std::max(k_splits, 1) + 1);
   if (stack) {      // split-K partials of W_o / W_down and of the down-projections of their adapters
     w.y_floats = std::max(w.y_floats, (size_t)8 * T * L.d);
     w.y_floats = std::max(w.y_floats, (size_t)8 * T * std::max(L.n_adapters, 1) * 2 * std::max(L.rank, 1));
@@ -373,6 +375,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.B = (const bf16 *)ly->W_qkv; g.ldb = L.d;
       g.M = pl.T; g.N = L.n_qkv; g.K = L.d;
       g.k_splits = w.k_splits;
+      g.lora_split = (pl.any_adapter && w.lora_split) ? 1 : 0;
       g.tile_hint = ctx->opt_gemm_tile;
       g.Cpart = w.Y;
       g.tlow = pl.any_adapter ? (const bf16 *)w.tlow : nullptr;
@@ -389,7 +392,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
   }
   {
     ProfScope p(ctx, K_ROPE, s);
-    launch_rope_append<T>(w.Y, mfma ? w.k_splits : 1, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k,
+    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k,
                           (T *)cache->v, s);
   }
   const bool direct = w.attn_mfma && std::is_same<T, bf16>::value && n_splits == 1;
@@ -761,6 +764,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
   w.mfma = mfma;
   w.k_splits = k_splits;
+  // few row tiles and a split reduction: the workgroups are short and the prologue of split 0 would stick out
+  w.lora_split = (k_splits > 1 && ctx->opt_lora_split != 2) || ctx->opt_lora_split == 1 ? 1 : 0;
   w.attn_mfma = attn_mfma;
   w.decode_mfma = decode_mfma;
   w.attn_waves = attn_waves;
@@ -888,6 +893,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "gemm_splits")) {
     if (value < 0 || value > 64) return fail(ctx, ALORA_EINVAL, "gemm_splits must be in [0, 64]");
     ctx->opt_gemm_splits = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "lora_split")) {
+    if (value < 0 || value > 2) return fail(ctx, ALORA_EINVAL, "lora_split must be 0, 1 or 2");
+    ctx->opt_lora_split = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "attn_lazy")) {

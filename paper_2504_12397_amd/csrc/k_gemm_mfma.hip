@@ -9,7 +9,9 @@
 //   (8 chunks of 16 B); chunk c of row r sits at position c ^ ((r >> 1) & 7): LDS serves a
 //   16-byte-per-lane access 16 lanes at a time over 64 banks, and with this swizzle 16 consecutive
 //   rows of one chunk (operand reads) as well as 2 rows x 8 chunks (stores) hit 64 distinct banks.
-// * Gated low-rank term of Eq.6 as extra k-steps BEFORE the main loop: for every adapter present
+// * Gated low-rank term of Eq.6 as extra k-steps BEFORE the main loop (or, when the reduction is split anyway, in
+//   workgroups of its own that hold one more partial sum: its loads are two dependent round trips that would
+//   otherwise make the workgroups of split 0 the last to finish): for every adapter present
 //   in the row tile, A-operand = t = s*A_a x (as a bf16 pair hi + lo, zero for rows that are not
 //   adapted by a), B-operand = B_{a,p} (twice).  Rows that are not adapted accumulate exact zeros into zero
 //   accumulators, so their results are bitwise what a base-only call gives.
@@ -58,7 +60,9 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   const int tn = xcd + 8 * nl;
   if (tn >= tiles_n) return;
   const int m0 = tm * BM, n0 = tn * BN;
-  const int k_len = K / g.k_splits, k_beg = split * k_len, nk = k_len / BK;
+  // with lora_split the workgroups of split number k_splits carry only the low-rank term (no k-tiles)
+  const bool lora_only = g.lora_split && split == g.k_splits;
+  const int k_len = K / g.k_splits, k_beg = split * k_len, nk = lora_only ? 0 : k_len / BK;
   const int l32 = lane & 31, lhi = lane >> 5;
 
   f32x16 acc[TM][TN];
@@ -156,7 +160,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   // ---- gated low-rank extension (Eq.6), split 0 only --------------------------------------
   // (runs while the first two main-loop tiles are already on their way from memory; its own loads
   // are issued two k-steps at a time before the MFMAs that use them)
-  if (g.tlow != nullptr && split == 0) {
+  if (g.tlow != nullptr && (g.lora_split ? lora_only : split == 0)) {
     if (tid == 0) s_present = 0ull;
     __syncthreads();
     for (int r = tid; r < BM; r += NT) {
@@ -305,7 +309,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
 template <int BM, int BN, int WM, int WN, int EPI, int PF = 2>
 static void launch_cfg(const GemmArgs &g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  dim3 grid(8 * ((tiles_n + 7) / 8) * tiles_m * g.k_splits);
+  dim3 grid(8 * ((tiles_n + 7) / 8) * tiles_m * (g.k_splits + (g.lora_split ? 1 : 0)));
   size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(u32x4);
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, PF>;
   constexpr int NT = 64 * (BM / WM) * (BN / WN);
@@ -441,11 +445,13 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
+    g.lora_split = 0;
     if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     else if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
   } else {
     g.k_splits = 1;
+    g.lora_split = 0;
     if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_BF16>(g, s);
     else if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_BF16>(g, s);

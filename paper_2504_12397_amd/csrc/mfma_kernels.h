@@ -13,7 +13,9 @@ struct GemmArgs {
   const bf16 *B2;              // SwiGLU only: the "up" weights; B holds the "gate" weights, N = 2 * I
   int M, N, K;
   int tile_hint;               // 0 = automatic, 1 = 128x128 blocks, 2 = 256x128 blocks
-  int k_splits;                // PARTIAL only: grid.z; K / k_splits must be a multiple of 64
+  int k_splits;                // PARTIAL only: splits of the reduction axis; K / k_splits must be a multiple of 64
+  int lora_split;              // PARTIAL only, 1: the low-rank term gets workgroups of its own that write partial
+                               // number k_splits (Cpart then holds k_splits + 1 partials), instead of riding on split 0
   float *Cpart;                // PARTIAL: [k_splits, M, N] fp32 partial sums
   bf16 *C; int ldc;            // BF16 / SWIGLU output
   const bf16 *R;               // BF16: optional residual [M, ldc]
