@@ -358,6 +358,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       PrepArgs pa{};
       pa.x = (const bf16 *)x; pa.gain = (const bf16 *)ly->rms_gain; pa.eps = ly->rms_eps;
       pa.T = pl.T; pa.d = L.d; pa.seqs = seqs_dev; pa.n_seqs = pl.B; pa.pos_shift = pos_shift;
+      pa.one = pl.seqs[0];
       pa.A = rank_used ? (const bf16 *)ly->A : nullptr; pa.rank = rank_used;
       pa.write_meta = write_meta ? 1 : 0;
       pa.xh = (bf16 *)w.xh; pa.tlow16 = (bf16 *)w.tlow; pa.rm = w.rm;

@@ -23,12 +23,17 @@ constexpr int PREP_WAVES = 8;
 // holds.  x is read from memory once: the chunks stay in registers from the sum of squares to the
 // normalised store and the MFMAs, and every phase issues all its loads before the first use, so
 // the kernel pays about three memory round trips in total.
-template <int NF, int CH>
+// EARLY (single-sequence batches with NF == 1): the sequence record comes with the kernel arguments, so the
+// adapter of the tile is known at once and its A fragments are requested together with x instead of after
+// the metadata and normalisation phases -- one dependent memory round trip less on a kernel that is nothing
+// but round trips at these sizes.
+template <int NF, int CH, bool EARLY = false>
 __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   __shared__ float s_ssq[PREP_WAVES][PREP_ROWS];
   __shared__ int s_adapter[PREP_ROWS];
   __shared__ float s_scale[PREP_ROWS];
   __shared__ unsigned long long s_present;
+  __shared__ u32x4 s_gain[CH * 32];          // d / 8 chunks of the gain
   extern __shared__ float s_part[];          // [PREP_WAVES][PREP_ROWS][16 * NF]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -42,13 +47,27 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   const int k_lo = wave * (CH * 32) + kg * 8;  // this lane's first element; chunk u is at k_lo + 32 u
 
   // ---- all of this lane's x (and gain) chunks, issued at once ----------------------------------
-  u32x4 xr[CH], gr[CH];
+  // (the gain goes through LDS: one 16-byte chunk per thread instead of CH of them in every lane's registers)
+  u32x4 xr[CH], gown = u32x4{0, 0, 0, 0};
   const bf16 *xrow = a.x + (int64_t)row * d + k_lo;
 #pragma unroll
   for (int u = 0; u < CH; ++u) xr[u] = *reinterpret_cast<const u32x4 *>(xrow + 32 * u);
-  if (a.gain != nullptr) {
+  if (a.gain != nullptr && tid < d / 8) gown = *reinterpret_cast<const u32x4 *>(a.gain + tid * 8);
+
+  // EARLY: A fragments of the sequence's adapter, if any row of the tile is adapted
+  u32x4 bpre[EARLY ? CH : 1][EARLY && NF > 0 ? NF : 1];
+  bool pre_loaded = false;
+  if constexpr (EARLY && NF > 0) {
+    const SeqMeta &o = a.one;
+    const int last = min(row0 + PREP_ROWS, a.T) - 1;
+    pre_loaded = o.adapter >= 0 && o.P + a.pos_shift + (last - o.row_start) >= o.k;
+    if (pre_loaded) {
+      const bf16 *Ab = a.A + ((int64_t)o.adapter * 3 * a.rank + col0 + r16) * d + k_lo;
 #pragma unroll
-    for (int u = 0; u < CH; ++u) gr[u] = *reinterpret_cast<const u32x4 *>(a.gain + k_lo + 32 * u);
+      for (int u = 0; u < CH; ++u)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) bpre[u][j] = *reinterpret_cast<const u32x4 *>(Ab + (int64_t)j * 16 * d + 32 * u);
+    }
   }
 
   if (tid == 0) s_present = 0ull;
@@ -59,11 +78,13 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
     float scale = 0.f;
     if (mrow < a.T && a.seqs != nullptr) {
       int lo = 0, hi = a.n_seqs - 1;           // last sequence whose first row is <= mrow
-      while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
-        if (a.seqs[mid].row_start <= mrow) lo = mid; else hi = mid - 1;
+      if constexpr (!EARLY) {
+        while (lo < hi) {
+          int mid = (lo + hi + 1) >> 1;
+          if (a.seqs[mid].row_start <= mrow) lo = mid; else hi = mid - 1;
+        }
       }
-      const SeqMeta sm = a.seqs[lo];
+      const SeqMeta sm = EARLY ? a.one : a.seqs[lo];
       const int pos = sm.P + a.pos_shift + (mrow - sm.row_start);
       if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
       if (a.write_meta && lead) {
@@ -91,6 +112,7 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
     ssq += __shfl_xor(ssq, 16, 64);
     ssq += __shfl_xor(ssq, 32, 64);
     if (kg == 0) s_ssq[wave][r16] = ssq;
+    if (tid < d / 8) s_gain[tid] = gown;
   }
   __syncthreads();
   if (a.gain != nullptr) {
@@ -101,7 +123,7 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
     // normalise in place: x_hat = bf16(x * g * rinv)
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-      const bf16x8 xv = __builtin_bit_cast(bf16x8, xr[u]), gv = __builtin_bit_cast(bf16x8, gr[u]);
+      const bf16x8 xv = __builtin_bit_cast(bf16x8, xr[u]), gv = __builtin_bit_cast(bf16x8, s_gain[(k_lo >> 3) + 4 * u]);
       bf16x8 xh;
 #pragma unroll
       for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
@@ -124,7 +146,20 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   if (NF > 0) {
     constexpr int NFX = NF > 0 ? NF : 1;
     constexpr int UB = (16 / NFX) < 1 ? 1 : ((16 / NFX) > CH ? CH : (16 / NFX));     // k-steps per load batch
-    unsigned long long todo = present;
+    if constexpr (EARLY) {
+      if (pre_loaded) {
+        const bool mine = my_adapter == a.one.adapter;
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+          const u32x4 au = mine ? xr[u] : u32x4{0, 0, 0, 0};
+#pragma unroll
+          for (int j = 0; j < NFX; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, au),
+                                                             __builtin_bit_cast(bf16x8, bpre[u][j]), acc[j], 0, 0, 0);
+        }
+      }
+    }
+    unsigned long long todo = EARLY ? 0ull : present;
     while (todo) {
       const int ad = __builtin_ctzll(todo);
       todo &= todo - 1;
@@ -180,11 +215,11 @@ bool prep_rows_mfma_supported(int d, int rank) {
   return (d == 4096 || d == 2048 || d == 1024 || d == 512) && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
 }
 
-template <int NF, int CH>
+template <int NF, int CH, bool EARLY = false>
 static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
   const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
-  auto kern = prep_rows_mfma_kernel<NF, CH>;
+  auto kern = prep_rows_mfma_kernel<NF, CH, EARLY>;
   static bool configured = false;
   if (!configured && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -195,6 +230,15 @@ static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
 
 template <int NF>
 static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
+  if (NF == 1 && a.seqs != nullptr && a.n_seqs == 1) {
+    switch (a.d) {
+      case 4096: launch_prep_cfg<1, 16, true>(a, groups, s); return;
+      case 2048: launch_prep_cfg<1, 8, true>(a, groups, s); return;
+      case 1024: launch_prep_cfg<1, 4, true>(a, groups, s); return;
+      case 512: launch_prep_cfg<1, 2, true>(a, groups, s); return;
+      default: break;
+    }
+  }
   switch (a.d) {
     case 4096: launch_prep_cfg<NF, 16>(a, groups, s); break;
     case 2048: launch_prep_cfg<NF, 8>(a, groups, s); break;

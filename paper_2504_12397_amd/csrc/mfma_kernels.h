@@ -38,6 +38,8 @@ struct PrepArgs {
   int T, d;
   const SeqMeta *seqs;      // nullptr: no metadata / adapters (plain RMSNorm)
   int n_seqs;
+  SeqMeta one;              // a copy of seqs[0] when n_seqs == 1: the kernel then needs no memory round trip
+                            // to know its rows' positions and adapter, and fetches A together with x
   int pos_shift;            // added to every position (step index of a multi-step decode)
   const bf16 *A;            // [n_adapters, 3, rank, d] or nullptr
   int rank;
