@@ -17,6 +17,8 @@
 //   accumulators, so their results are bitwise what a base-only call gives.
 // * Epilogues: fp32 partial sums (split-K capable, summed later in a fixed order), bf16 store
 //   (+ residual), SwiGLU (gate and up columns interleaved in 32-column blocks inside the tile).
+#include <type_traits>
+
 #include "mfma_kernels.h"
 
 namespace alora {
@@ -30,7 +32,10 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast
 
 // PF = tiles kept in flight in registers (2: for the weight-streaming shapes; 1: for the large
 // tiles whose accumulators leave no room for a second one).
-template <int BM, int BN, int WM, int WN, int EPI, int PF>
+// WEAVE: tile loads and LDS stores issued between the k-steps of the running tile (pays with many row tiles:
+// operands come from L2 and two workgroups share a compute unit) instead of in blocks around them (better
+// for weight streaming, where the loads want the longest time in flight).
+template <int BM, int BN, int WM, int WN, int EPI, int PF, bool WEAVE = false>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int BK = 64;
   constexpr int WAVES_N = BN / WN;
@@ -86,10 +91,13 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
     int src = n0 + j;
     return src < N ? src : N - 1;
   };
-  auto load_tiles = [&](int kt, u32x4 (&ra)[A_CHUNKS], u32x4 (&rb)[B_CHUNKS]) {
+  // loads / stores of a tile, chunk by chunk: part p of 4 takes the chunks i with i % 4 == p, so that the work
+  // can be spread over the four k-steps of the tile being multiplied
+  auto load_part = [&](int kt, int p, u32x4 (&ra)[A_CHUNKS], u32x4 (&rb)[B_CHUNKS]) {
     const int k0 = k_beg + kt * BK;
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
+      if ((i & 3) != p) continue;
       int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       int gr = m0 + row;
       gr = gr < M ? gr : M - 1;
@@ -97,23 +105,34 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
+      if (((i + A_CHUNKS) & 3) != p) continue;
       int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       const bf16 *base = g.B;
       if (EPI == GEMM_EPI_SWIGLU && ((row >> 5) & 1)) base = g.B2;
       rb[i] = *reinterpret_cast<const u32x4 *>(base + (int64_t)b_src_row(row) * g.ldb + k0 + c * 8);
     }
   };
-  auto store_tiles = [&](u32x4 *As, u32x4 *Bs, const u32x4 (&ra)[A_CHUNKS], const u32x4 (&rb)[B_CHUNKS]) {
+  auto store_part = [&](u32x4 *As, u32x4 *Bs, int p, const u32x4 (&ra)[A_CHUNKS], const u32x4 (&rb)[B_CHUNKS]) {
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
+      if ((i & 3) != p) continue;
       int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       As[row * 8 + (c ^ ((row >> 1) & 7))] = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
+      if (((i + A_CHUNKS) & 3) != p) continue;
       int q2 = tid + i * NT, row = q2 >> 3, c = q2 & 7;
       Bs[row * 8 + (c ^ ((row >> 1) & 7))] = rb[i];
     }
+  };
+  auto load_tiles = [&](int kt, u32x4 (&ra)[A_CHUNKS], u32x4 (&rb)[B_CHUNKS]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) load_part(kt, p, ra, rb);
+  };
+  auto store_tiles = [&](u32x4 *As, u32x4 *Bs, const u32x4 (&ra)[A_CHUNKS], const u32x4 (&rb)[B_CHUNKS]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) store_part(As, Bs, p, ra, rb);
   };
   // One k-tile = four k-steps of 16.  The fragments of step ks+1 are read from LDS before the
   // MFMAs of step ks are issued, so the LDS latency hides behind matrix work.
@@ -147,6 +166,40 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
     read_frags(As, Bs, 3, a1, b1);
     mma(a0, b0);
     mma(a1, b1);
+  };
+  // The same with the tile traffic woven in: the loads of the tile two ahead (kt_load -> rl) and the LDS
+  // stores of the next tile (rs -> An, Bn) are issued a quarter at a time between the four k-steps, fenced so
+  // that the compiler keeps them there.  A workgroup often has a compute unit to itself (weight streaming,
+  // one wave per SIMD): issued in a block before or after the MFMAs these instructions would leave the
+  // matrix unit idle, here they run under it.
+  auto compute_weave = [&](auto early, const u32x4 *As, const u32x4 *Bs, int kt_load, u32x4 (&rla)[A_CHUNKS],
+                           u32x4 (&rlb)[B_CHUNKS], u32x4 *An, u32x4 *Bn, const u32x4 (&rsa)[A_CHUNKS],
+                           const u32x4 (&rsb)[B_CHUNKS]) {
+    // early: all loads of the tile two ahead go out before the first MFMA (weights streamed from HBM want the
+    // longest possible time in flight), only the LDS stores are woven in; otherwise both are
+    constexpr bool EARLY = decltype(early)::value;
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+    if (EARLY) load_tiles(kt_load, rla, rlb);
+    read_frags(As, Bs, 0, a0, b0);
+    read_frags(As, Bs, 1, a1, b1);
+    if (!EARLY) load_part(kt_load, 0, rla, rlb);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b0);
+    read_frags(As, Bs, 2, a0, b0);
+    if (!EARLY) load_part(kt_load, 1, rla, rlb);
+    store_part(An, Bn, 0, rsa, rsb);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a1, b1);
+    read_frags(As, Bs, 3, a1, b1);
+    if (!EARLY) load_part(kt_load, 2, rla, rlb);
+    store_part(An, Bn, 1, rsa, rsb);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b0);
+    if (!EARLY) load_part(kt_load, 3, rla, rlb);
+    store_part(An, Bn, 2, rsa, rsb);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a1, b1);
+    store_part(An, Bn, 3, rsa, rsb);
   };
 
   // The loop is free of conditional loads and stores (tile indices are clamped instead: the last
@@ -251,15 +304,29 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   if (nk > 0) store_tiles(As0, Bs0, ra0, rb0);
   __syncthreads();
   if constexpr (PF == 2) {
-    for (int kt = 0; kt < nk; kt += 2) {
-      load_tiles(min(kt + 2, nk - 1), ra0, rb0);
-      compute(As0, Bs0);
-      store_tiles(As1, Bs1, ra1, rb1);
-      __syncthreads();
-      load_tiles(min(kt + 3, nk - 1), ra1, rb1);
-      if (kt + 1 < nk) compute(As1, Bs1);
-      store_tiles(As0, Bs0, ra0, rb0);
-      __syncthreads();
+    if constexpr (WEAVE) {
+      for (int kt = 0; kt < nk; kt += 2) {
+        compute_weave(std::false_type{}, As0, Bs0, min(kt + 2, nk - 1), ra0, rb0, As1, Bs1, ra1, rb1);
+        __syncthreads();
+        if (kt + 1 < nk) {
+          compute_weave(std::false_type{}, As1, Bs1, min(kt + 3, nk - 1), ra1, rb1, As0, Bs0, ra0, rb0);
+        } else {
+          load_tiles(nk - 1, ra1, rb1);
+          store_tiles(As0, Bs0, ra0, rb0);
+        }
+        __syncthreads();
+      }
+    } else {
+      for (int kt = 0; kt < nk; kt += 2) {
+        load_tiles(min(kt + 2, nk - 1), ra0, rb0);
+        compute(As0, Bs0);
+        store_tiles(As1, Bs1, ra1, rb1);
+        __syncthreads();
+        load_tiles(min(kt + 3, nk - 1), ra1, rb1);
+        if (kt + 1 < nk) compute(As1, Bs1);
+        store_tiles(As0, Bs0, ra0, rb0);
+        __syncthreads();
+      }
     }
   } else {
     for (int kt = 0; kt < nk; ++kt) {
@@ -306,12 +373,12 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int PF = 2>
+template <int BM, int BN, int WM, int WN, int EPI, int PF = 2, bool WEAVE = false>
 static void launch_cfg(const GemmArgs &g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(8 * ((tiles_n + 7) / 8) * tiles_m * (g.k_splits + (g.lora_split ? 1 : 0)));
   size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(u32x4);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, PF>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, PF, WEAVE>;
   constexpr int NT = 64 * (BM / WM) * (BN / WN);
   static bool configured = false;
   if (!configured) {
@@ -442,6 +509,7 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     if (g.tile_hint == 2) launch_cfg<256, 128, 128, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (g.tile_hint == 3) launch_cfg<256, 256, 64, 128, GEMM_EPI_PARTIAL, 1>(g, s);
     else if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_PARTIAL>(g, s);
+    else if (g.M > 4 * 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true>(g, s);
     else launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
