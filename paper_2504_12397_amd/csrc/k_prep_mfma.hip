@@ -27,8 +27,9 @@ constexpr int PREP_WAVES = 8;
 // adapter of the tile is known at once and its A fragments are requested together with x instead of after
 // the metadata and normalisation phases -- one dependent memory round trip less on a kernel that is nothing
 // but round trips at these sizes.
-template <int NF, int CH, bool EARLY = false>
-__global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
+// DENSE (many row tiles): registers capped so that two workgroups share a compute unit, loads in smaller batches.
+template <int NF, int CH, bool EARLY = false, bool DENSE = false>
+__global__ __launch_bounds__(512, DENSE ? 4 : 2) void prep_rows_mfma_kernel(PrepArgs a) {
   __shared__ float s_ssq[PREP_WAVES][PREP_ROWS];
   __shared__ int s_adapter[PREP_ROWS];
   __shared__ float s_scale[PREP_ROWS];
@@ -145,7 +146,8 @@ __global__ __launch_bounds__(512) void prep_rows_mfma_kernel(PrepArgs a) {
   for (int j = 0; j < (NF > 0 ? NF : 1); ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   if (NF > 0) {
     constexpr int NFX = NF > 0 ? NF : 1;
-    constexpr int UB = (16 / NFX) < 1 ? 1 : ((16 / NFX) > CH ? CH : (16 / NFX));     // k-steps per load batch
+    constexpr int UB0 = (16 / NFX) < 1 ? 1 : ((16 / NFX) > CH ? CH : (16 / NFX));     // k-steps per load batch
+    constexpr int UB = DENSE ? (UB0 > 1 ? UB0 / 2 : 1) : UB0;
     if constexpr (EARLY) {
       if (pre_loaded) {
         const bool mine = my_adapter == a.one.adapter;
@@ -215,11 +217,11 @@ bool prep_rows_mfma_supported(int d, int rank) {
   return (d == 4096 || d == 2048 || d == 1024 || d == 512) && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
 }
 
-template <int NF, int CH, bool EARLY = false>
+template <int NF, int CH, bool EARLY = false, bool DENSE = false>
 static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
   const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
-  auto kern = prep_rows_mfma_kernel<NF, CH, EARLY>;
+  auto kern = prep_rows_mfma_kernel<NF, CH, EARLY, DENSE>;
   static bool configured = false;
   if (!configured && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -238,6 +240,10 @@ static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
       case 512: launch_prep_cfg<1, 2, true>(a, groups, s); return;
       default: break;
     }
+  }
+  if (a.d == 4096 && NF >= 3 && (a.T + PREP_ROWS - 1) / PREP_ROWS * groups > 256) {
+    launch_prep_cfg<NF, 16, false, true>(a, groups, s);
+    return;
   }
   switch (a.d) {
     case 4096: launch_prep_cfg<NF, 16>(a, groups, s); break;
