@@ -64,6 +64,7 @@ struct alora_ctx {
   int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
   int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
   int opt_attn_pipeline = 1;     // 0 = software-pipelined attention kernel, 1 = the unpipelined one
+  int opt_attn_fold = 0;         // 1 = unpipelined kernel takes prescaled queries and starts its score accumulators at -m_ref
   int n_cu = 256;
 };
 
@@ -391,10 +392,15 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
                                (const T *)ly->B_k, (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
     }
   }
+  // the folded-softmax attention kernel takes its queries premultiplied by sm_scale * log2(e)
+  const bool attn_pipelined = ctx->opt_attn_pipeline == 0;
+  const float q_scale = (w.attn_mfma && std::is_same<T, bf16>::value)
+                            ? attn_prefill_mfma_q_scale(L, w.attn_waves, attn_pipelined, ctx->opt_attn_fold != 0)
+                            : 1.0f;
   {
     ProfScope p(ctx, K_ROPE, s);
-    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, (T *)w.Q, (T *)cache->k,
-                          (T *)cache->v, s);
+    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, q_scale, (T *)w.Q,
+                          (T *)cache->k, (T *)cache->v, s);
   }
   const bool direct = w.attn_mfma && std::is_same<T, bf16>::value && n_splits == 1;
   {
@@ -407,9 +413,10 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.n_splits = n_splits;
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
       a.lazy = (float)ctx->opt_attn_lazy;
+      a.q_prescaled = q_scale != 1.0f;
       a.partials = direct ? nullptr : w.partials;
       a.out = direct ? (bf16 *)out : nullptr;
-      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, ctx->opt_attn_pipeline == 0, pl.any_prefix, s);
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, attn_pipelined, pl.any_prefix, s);
     } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
       DecodeArgs a{};
       a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
@@ -904,6 +911,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "attn_lazy")) {
     if (value < 0 || value > 16) return fail(ctx, ALORA_EINVAL, "attn_lazy must be in [0, 16]");
     ctx->opt_attn_lazy = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "attn_fold")) {
+    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "attn_fold must be 0 or 1");
+    ctx->opt_attn_fold = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "attn_pipeline")) {

@@ -80,7 +80,7 @@ void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, i
 
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
-                        const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s);
+                        const float2 *rope_table, float q_scale, T *Q, T *cacheK, T *cacheV, hipStream_t s);
 
 // C[M, N] += gated low-rank term (Eq.6) of one linear: s_a B_a (A_{a,part} x) for rows with row_adapter >= 0
 template <typename T>

@@ -48,13 +48,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // spreads the transposing 8-byte stores (columns 4 apart) to a 2-way conflict at worst.
 __device__ __forceinline__ int v_swz(int col) { return ((col >> 1) ^ (col >> 4)) & 7; }
 
-// max of a value with the one held by the lane 32 away (v_permlane32_swap: lanes 32..63 of the
-// first operand trade places with lanes 0..31 of the second)
+// max of a value with the one held by the lane 32 away.  v_permlane32_swap trades lanes 32..63 of its
+// first register with lanes 0..31 of its second; given two copies of x, the first then holds the low
+// half's values in both halves and the second the high half's.  Written as inline assembly because
+// the compiler builtin hands back its first result for both (the maximum then silently covers one
+// half only); the s_nop's are the wait states between a vector write and this instruction's read.
 __device__ __forceinline__ float max_with_other_half(float x) {
-  typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
-  const uint32_t u = __builtin_bit_cast(uint32_t, x);
-  const u32x2v r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__builtin_bit_cast(float, r.x), __builtin_bit_cast(float, r.y));
+  float lo = x, hi = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1" : "+v"(lo), "+v"(hi));
+  return lo;
 }
 
 // acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
@@ -77,7 +79,18 @@ constexpr float LN2 = 0.6931471805599453f;
 
 // PFX: some sequence of the call reads a shared prefix (cached position j < prefix_len lives in
 // another place of the pool than the sequence's own rows)
-template <int G, int NW, bool PFX>      // NW waves per workgroup (8 or 4), 32 packed rows each
+//
+// FOLD: the queries arrive premultiplied by sm_scale * log2(e) (the rotation kernel does it while it
+// rounds them), and the softmax bookkeeping moves onto the matrix unit:
+//   * the accumulator of the first K Q^T product starts at -m_ref (the row's reference exponent,
+//     replicated over the lane's 16 registers), so the scores come out as s - m_ref, ready for exp2;
+//   * the row sums are two more MFMAs per 32-key block, an all-ones A operand against the rounded
+//     probabilities, which leave the sum over all 32 keys in every register of `lacc` (no
+//     cross-half exchange, and numerator and denominator see the same rounded values);
+//   * m_ref is set to the exact maximum of the first block in which the row sees a key, and later moves
+//     only when a block's maximum exceeds it by more than `lazy`, in a branch that is rare.
+// The softmax is the same function: numerator and denominator share the reference exponent.
+template <int G, int NW, bool PFX, bool FOLD>      // NW waves per workgroup (8 or 4), 32 packed rows each
 __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) {
   constexpr int H = 128;
   constexpr int NT = 64 * NW;
@@ -131,10 +144,14 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[cb][nb][v] = 0.f;
-  float m_run[NB], l_run[NB];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
   const float c_scale = a.sm_scale * LOG2E;
+  // softmax state of the lane's query row: the reference exponent m_ref (exp2 domain), the row sum in
+  // every register of lacc (it is the accumulator of an MFMA), and for FOLD -m_ref in every register of negm
+  f32x16 negm, lacc;
+  float m_ref = FOLD ? 0.f : -INFINITY;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { negm[v] = 0.f; lacc[v] = 0.f; }
+  const bf16x8 ones = u4_as_bf16x8(u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 
   // ---- tile loader: K rows as they are, V transposed in registers -------------------------
   // 512 threads: K = 1024 chunks of 16 B, two per thread; V = 16 key quads x 32 column groups of
@@ -213,7 +230,8 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
-            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], u4_as_bf16x8(qf[nb][ks]), s[nb], 0, 0, 0);
+            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], u4_as_bf16x8(qf[nb][ks]),
+                                                            (FOLD && ks == 0) ? negm : s[nb], 0, 0, 0);
       }
 
       // ---- causal mask: only tiles that reach past the first query position or the split end --
@@ -229,45 +247,58 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 
       // ---- online softmax (log2 domain), one query row per lane -------------------------------
       u32x4 pf[2][NB];     // [half][nb]: 8 probabilities as bf16
+      f32x16 &sv = s[0];
+      float mx = sv[0];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        float mx = -INFINITY;
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sv[v]);
+      mx = max_with_other_half(mx);
+      // The reference exponent of a row moves (and its 64 output accumulators and row sum are rescaled)
+      // only in blocks where some row of the wave needs it -- a wave-uniform, rare branch: with random
+      // scores a third of all blocks would otherwise move the maximum of some row.  The softmax is
+      // mathematically unchanged (numerator and denominator share the reference); probabilities reach
+      // 2^lazy instead of 1, with the same relative bf16 rounding.
+      if constexpr (FOLD) {
+        // sv holds s - m_ref.  A row's first keys set the reference to their exact maximum (the largest
+        // probability is then exactly 1, which matters most for rows that see few keys).
+        const bool fresh = lacc[0] == 0.f;       // nothing accumulated for this row yet
+        const bool want = mx > a.lazy || (fresh && mx > -INFINITY);
+        if (__any(want)) {
+          const float delta = want ? mx : 0.f;
+          const float alpha = fresh ? 1.0f : __builtin_amdgcn_exp2f(-delta);
+          m_ref += delta;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // The reference exponent m_run moves (and the 64 output accumulators are rescaled) only in
-        // blocks where some row of the wave exceeds it by more than a.lazy powers of two -- a
-        // wave-uniform decision.  The softmax is mathematically unchanged (numerator and
-        // denominator share the reference); probabilities reach 2^lazy instead of 1, with the same
-        // relative bf16 rounding.  With random scores a third of all blocks would otherwise move
-        // the maximum of some row and pay 64 multiplications per lane.
-        const float m_blk = mx * c_scale;
-        const bool move = __any(m_blk > m_run[nb] + a.lazy);
-        const float m_new = move ? fmaxf(m_run[nb], m_blk) : m_run[nb];
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = move ? __builtin_amdgcn_exp2f(m_run[nb] - m_safe) : 1.0f;
-        m_run[nb] = m_new;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[nb][v] = __builtin_amdgcn_exp2f(fmaf(s[nb][v], c_scale, -m_safe));
-        if (move) {
-          l_run[nb] *= alpha;
+          for (int v = 0; v < 16; ++v) { sv[v] -= delta; negm[v] -= delta; lacc[v] *= alpha; }
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[cb][nb][v] *= alpha;
+            for (int v = 0; v < 16; ++v) o[cb][0][v] *= alpha;
         }
-        // probabilities as bf16 pairs; the row sum is taken from the ROUNDED values (one dot2 per
-        // pair), so numerator and denominator of the softmax carry the same rounding
-        float rs = 0.f;
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          const int e = 8 * hf;
-          pf[hf][nb] = u32x4{pack_bf16x2(s[nb][e], s[nb][e + 1]), pack_bf16x2(s[nb][e + 2], s[nb][e + 3]),
-                             pack_bf16x2(s[nb][e + 4], s[nb][e + 5]), pack_bf16x2(s[nb][e + 6], s[nb][e + 7])};
+        for (int v = 0; v < 16; ++v) sv[v] = __builtin_amdgcn_exp2f(sv[v]);
+      } else {
+        // sv holds raw scores; m_ref is in the exp2 domain (score * sm_scale * log2 e)
+        const float m_blk = mx * c_scale;
+        const bool move = __any(m_blk > m_ref + a.lazy);
+        const float m_new = move ? fmaxf(m_ref, m_blk) : m_ref;
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        if (move) {
+          const float alpha = __builtin_amdgcn_exp2f(m_ref - m_safe);
 #pragma unroll
-          for (int w = 0; w < 4; ++w) rs = sum_bf16x2(pf[hf][nb][w], rs);
+          for (int v = 0; v < 16; ++v) lacc[v] *= alpha;
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[cb][0][v] *= alpha;
         }
-        l_run[nb] += rs;
+        m_ref = m_new;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sv[v] = __builtin_amdgcn_exp2f(fmaf(sv[v], c_scale, -m_safe));
+      }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int e = 8 * hf;
+        pf[hf][0] = u32x4{pack_bf16x2(sv[e], sv[e + 1]), pack_bf16x2(sv[e + 2], sv[e + 3]), pack_bf16x2(sv[e + 4], sv[e + 5]),
+                          pack_bf16x2(sv[e + 6], sv[e + 7])};
       }
 
       // ---- O^T += V^T P^T ---------------------------------------------------------------------
@@ -287,6 +318,12 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
               o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][cb], u4_as_bf16x8(pf[hf][nb]), o[cb][nb], 0, 0, 0);
+        // row sums of the ROUNDED probabilities (the values the products above use, so numerator and
+        // denominator of the softmax carry the same rounding): an all-ones A operand leaves the sum over
+        // the block's 32 keys in every register of lacc
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+          lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, u4_as_bf16x8(pf[hf][0]), lacc, 0, 0, 0);
       }
     }
 
@@ -315,7 +352,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
   // ---- write the partial (or final) result ----------------------------------------------------
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 32, 64);
+    const float l_tot = lacc[0];
     if (tok[nb] >= ntok) continue;
     const int64_t row = row0 + tok[nb];
     if (a.out != nullptr) {
@@ -343,7 +380,8 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
           *reinterpret_cast<float2 *>(pp + col + 2) = make_float2(o[cb][nb][4 * v4 + 2], o[cb][nb][4 * v4 + 3]);
         }
       if (kh == 0) {
-        pp[H] = m_run[nb] == -INFINITY ? -INFINITY : m_run[nb] * LN2;    // natural-log domain
+        // natural-log domain; a row that saw no key keeps -inf so that the merge gives it no weight
+        pp[H] = (l_tot == 0.f || m_ref == -INFINITY) ? -INFINITY : m_ref * LN2;
         pp[H + 1] = l_tot;
       }
     }
@@ -664,15 +702,26 @@ int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves) {
   return 32 * waves / (L.n_q_heads / L.n_kv_heads);
 }
 
-template <int NW, bool PFX>
+template <int NW, bool PFX, bool FOLD>
 static void launch_attn_nw(const AttnArgs &a, int n_work, int G, hipStream_t s) {
   dim3 grid(n_work);
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_prefill_mfma_kernel<1, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((attn_prefill_mfma_kernel<2, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((attn_prefill_mfma_kernel<4, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((attn_prefill_mfma_kernel<8, NW, PFX>), grid, dim3(64 * NW), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((attn_prefill_mfma_kernel<1, NW, PFX, FOLD>), grid, dim3(64 * NW), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((attn_prefill_mfma_kernel<2, NW, PFX, FOLD>), grid, dim3(64 * NW), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((attn_prefill_mfma_kernel<4, NW, PFX, FOLD>), grid, dim3(64 * NW), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((attn_prefill_mfma_kernel<8, NW, PFX, FOLD>), grid, dim3(64 * NW), 0, s, a); break;
     default: break;
+  }
+}
+
+template <int NW>
+static void launch_attn_nw_any(const AttnArgs &a, int n_work, int G, bool prefix, hipStream_t s) {
+  if (a.q_prescaled) {
+    if (prefix) launch_attn_nw<NW, true, true>(a, n_work, G, s);
+    else launch_attn_nw<NW, false, true>(a, n_work, G, s);
+  } else {
+    if (prefix) launch_attn_nw<NW, true, false>(a, n_work, G, s);
+    else launch_attn_nw<NW, false, false>(a, n_work, G, s);
   }
 }
 
@@ -695,12 +744,17 @@ void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, b
     if (prefix) launch_attn_pipe<true>(a, n_work, G, s);
     else launch_attn_pipe<false>(a, n_work, G, s);
   } else if (waves == 4) {
-    if (prefix) launch_attn_nw<4, true>(a, n_work, G, s);
-    else launch_attn_nw<4, false>(a, n_work, G, s);
+    launch_attn_nw_any<4>(a, n_work, G, prefix, s);
   } else {
-    if (prefix) launch_attn_nw<8, true>(a, n_work, G, s);
-    else launch_attn_nw<8, false>(a, n_work, G, s);
+    launch_attn_nw_any<8>(a, n_work, G, prefix, s);
   }
+}
+
+// What the rotation kernel multiplies the queries by for the variant the arguments select: the folded
+// softmax wants them in the exp2 domain, every other kernel applies sm_scale itself.
+float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, bool pipelined, bool fold) {
+  if (!fold || (pipelined && waves == 8)) return 1.0f;
+  return LOG2E / sqrtf((float)L.head_dim);
 }
 
 }  // namespace alora

@@ -243,8 +243,9 @@ template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, 
 template <typename T>
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, int n_parts,
                                                          int64_t part_stride, LayerDims L, RowMeta rm,
-                                                         const float2 *__restrict__ table, T *__restrict__ Q,
-                                                         T *__restrict__ cacheK, T *__restrict__ cacheV) {
+                                                         const float2 *__restrict__ table, float q_scale,
+                                                         T *__restrict__ Q, T *__restrict__ cacheK,
+                                                         T *__restrict__ cacheV) {
   const int row = blockIdx.x, slot_id = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int h = L.head_dim, h2 = h >> 1;
   if (slot_id >= L.n_q_heads + 2 * L.n_kv_heads) return;
@@ -261,11 +262,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     const int base = (is_q ? 0 : L.n_q) + head * h;
     const float2 *tab = table + (int64_t)rm.pos[row] * h2;
     T *dst = is_q ? Q + (int64_t)row * L.n_q + head * h : cacheK + rm.slot[row] * L.n_kv + head * h;
+    // q_scale: the attention kernel that follows may want its queries premultiplied (softmax scale and
+    // log2 e, so that its scores come out of the MFMA ready for exp2); keys are never scaled
+    const float qs = is_q ? q_scale : 1.0f;
     for (int c = lane; c < h2; c += 64) {
       const float u = ysum(y + base + c), w = ysum(y + base + c + h2);
       const float2 cs = tab[c];
-      dst[c] = from_f32<T>(u * cs.x - w * cs.y);
-      dst[c + h2] = from_f32<T>(w * cs.x + u * cs.y);
+      dst[c] = from_f32<T>((u * cs.x - w * cs.y) * qs);
+      dst[c + h2] = from_f32<T>((w * cs.x + u * cs.y) * qs);
     }
   } else {
     const int head = slot_id - L.n_q_heads - L.n_kv_heads;
@@ -277,16 +281,16 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
 
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
-                        const float2 *rope_table, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
+                        const float2 *rope_table, float q_scale, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
   if (T_rows == 0) return;
   dim3 grid(T_rows, (L.n_q_heads + 2 * L.n_kv_heads + 3) / 4);
   hipLaunchKernelGGL((rope_append_kernel<T>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
-                     rope_table, Q, cacheK, cacheV);
+                     rope_table, q_scale, Q, cacheK, cacheV);
 }
-template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *,
+template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float,
                                         float *, float *, float *, hipStream_t);
-template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, bf16 *,
-                                       bf16 *, bf16 *, hipStream_t);
+template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float,
+                                       bf16 *, bf16 *, bf16 *, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // plain split-KV attention (Eq.1 / Eq.4, causal, GQA).  One wave per (row, kv head, chunk of

@@ -60,14 +60,18 @@ struct AttnArgs {
   int n_q, n_kv, n_q_heads, n_kv_heads;
   int n_splits;             // key splits (grid.z)
   float sm_scale;           // 1 / sqrt(head_dim)
+  int q_prescaled;          // Q already carries sm_scale * log2(e): scores leave the MFMA in the exp2 domain
   float lazy;               // the running maximum moves only when a block exceeds it by more than this (log2 units)
   float *partials;          // [T, n_q_heads, n_splits, head_dim + 2] (acc, max, sum), used when out == nullptr
   bf16 *out;                // [T, n_q] final output, only with n_splits == 1
 };
 bool attn_prefill_mfma_supported(const LayerDims &L);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
+// with a.q_prescaled the unpipelined kernels run their folded-softmax form; the pipelined variant needs
+// unscaled queries (attn_prefill_mfma_q_scale tells the rotation kernel which it is)
 void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, bool prefix,
                               hipStream_t s);
+float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, bool pipelined, bool fold);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
 // One workgroup of the decode kernel: the query heads (of one GQA group) of up to 16 / G rows

@@ -128,6 +128,20 @@ def test_prefill_over_one_shared_context(ab, name):
         ctx.close()
 
 
+def test_prefill_over_shared_context_with_folded_softmax(ab):
+    """The attention variant that takes prescaled queries (option attn_fold) over a shared context."""
+    ctx = ab.Context(0)
+    try:
+        ctx.set_option("attn_fold", 1)
+        C0 = 333
+        S = [70, 33, 129, 1, 64]
+        case, own = shared_case(SHAPES["G4"], C0, S, [C0, C0, C0 + 5, C0, 0], [0, 1, 2, 1, -1], seed=900)
+        check_shared(ab, ctx, case, own, C0, [True] * 5)
+        check_shared(ab, ctx, case, own, C0, [True, False, True, False, True])
+    finally:
+        ctx.close()
+
+
 @pytest.mark.parametrize("name,opts", [("G4", {}), ("G4", {"kv_splits": 3}), ("G1", {}), ("G8", {}), ("f32", {}),
                                        ("G4", {"kernels": 1})])
 def test_decode_over_shared_contexts(ab, name, opts):
