@@ -393,9 +393,9 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
     }
   }
   // the folded-softmax attention kernel takes its queries premultiplied by sm_scale * log2(e)
-  const bool attn_pipelined = ctx->opt_attn_pipeline == 0;
+  const int attn_schedule = ctx->opt_attn_pipeline;
   const float q_scale = (w.attn_mfma && std::is_same<T, bf16>::value)
-                            ? attn_prefill_mfma_q_scale(L, w.attn_waves, attn_pipelined, ctx->opt_attn_fold != 0)
+                            ? attn_prefill_mfma_q_scale(L, w.attn_waves, attn_schedule, ctx->opt_attn_fold != 0)
                             : 1.0f;
   {
     ProfScope p(ctx, K_ROPE, s);
@@ -416,7 +416,12 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.q_prescaled = q_scale != 1.0f;
       a.partials = direct ? nullptr : w.partials;
       a.out = direct ? (bf16 *)out : nullptr;
-      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, attn_pipelined, pl.any_prefix, s);
+      // the kernels' fast tile loads use 32-bit byte offsets inside one sequence's rows; shared prefixes and
+      // (absurdly) long sequences take the variant with full address arithmetic
+      bool generic_addr = pl.any_prefix;
+      for (const SeqMeta &q : pl.seqs)
+        if ((uint64_t)(q.P + q.n_new) * (uint64_t)L.n_kv * 2u >= (1ull << 31)) generic_addr = true;
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, attn_schedule, generic_addr, s);
     } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
       DecodeArgs a{};
       a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;

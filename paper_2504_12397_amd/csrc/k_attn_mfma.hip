@@ -165,28 +165,62 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
   u32x4 rk0[KC], rk1[KC];
   vword rv0[4], rv1[4];
   const int v_qd = tid / (H / CW), v_cg = tid % (H / CW);
-  auto load_tile = [&](int t, u32x4 (&rk)[KC], vword (&rv)[4]) {
-    const int k0 = kbeg + t * ATT_BN;
+  // Without shared prefixes the tile loads are buffer loads: a resource that covers exactly the rows
+  // [0, n_visible) of this sequence and kv head, per-lane byte offsets that never change, and the tile's
+  // first row as the scalar offset -- no address arithmetic per load, and rows past the end read as zero
+  // (the range check of the buffer resource) instead of needing a clamp.  (The host takes the other path
+  // when a sequence is too long for 32-bit byte offsets.)
+  const uint32_t row_bytes = (uint32_t)a.n_kv * 2u;
+  __amdgpu_buffer_rsrc_t k_rsrc, v_rsrc;
+  uint32_t k_off[KC], v_off[4];
+  if constexpr (!PFX) {
+    const int n_rec = (int)(((uint32_t)max(n_visible, 1) - 1u) * row_bytes + H * 2u);
+    k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Kp, 0, n_rec, 0x00020000);
+    v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)Vp, 0, n_rec, 0x00020000);
 #pragma unroll
     for (int i = 0; i < KC; ++i) {
-      const int q = tid + i * NT, key = q >> 4, c = q & 15;
-      const int kidx = min(k0 + key, n_visible - 1);
-      const int64_t e = (int64_t)kidx * a.n_kv + c * 8 + (PFX && kidx < pfx_len ? pfx_delta : 0);
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + e);
+      const int q = tid + i * NT;
+      k_off[i] = (uint32_t)(q >> 4) * row_bytes + (q & 15) * 16u;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-      const int64_t e = (int64_t)kidx * a.n_kv + v_cg * CW + (PFX && kidx < pfx_len ? pfx_delta : 0);
-      rv[i] = *reinterpret_cast<const vword *>(Vp + e);
+    for (int i = 0; i < 4; ++i) v_off[i] = (uint32_t)(v_qd * 4 + i) * row_bytes + v_cg * (CW * 2u);
+  }
+  auto load_tile = [&](int t, u32x4 (&rk)[KC], vword (&rv)[4]) {
+    const int k0 = kbeg + t * ATT_BN;
+    if constexpr (!PFX) {
+      const int s_off = __builtin_amdgcn_readfirstlane((int)((uint32_t)k0 * row_bytes));
+#pragma unroll
+      for (int i = 0; i < KC; ++i)
+        rk[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)k_off[i], s_off, 0));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (VW == 2) rv[i] = __builtin_bit_cast(vword, __builtin_amdgcn_raw_buffer_load_b64(v_rsrc, (int)v_off[i], s_off, 0));
+        else rv[i] = __builtin_bit_cast(vword, __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)v_off[i], s_off, 0));
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < KC; ++i) {
+        const int q = tid + i * NT, key = q >> 4, c = q & 15;
+        const int kidx = min(k0 + key, n_visible - 1);
+        const int64_t e = (int64_t)kidx * a.n_kv + c * 8 + (kidx < pfx_len ? pfx_delta : 0);
+        rk[i] = *reinterpret_cast<const u32x4 *>(Kp + e);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
+        const int64_t e = (int64_t)kidx * a.n_kv + v_cg * CW + (kidx < pfx_len ? pfx_delta : 0);
+        rv[i] = *reinterpret_cast<const vword *>(Vp + e);
+      }
     }
   };
-  auto store_tile = [&](int buf, const u32x4 (&rk)[KC], const vword (&rv)[4]) {
+  auto store_k = [&](int buf, const u32x4 (&rk)[KC]) {
 #pragma unroll
     for (int i = 0; i < KC; ++i) {
       const int q = tid + i * NT, key = q >> 4, c = q & 15;
       Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
     }
+  };
+  auto store_v = [&](int buf, const vword (&rv)[4]) {
     // V: this thread holds keys 4*v_qd..+3 for columns CW*v_cg..+CW-1
     const int grp16 = v_qd >> 2, qi = v_qd & 3;
     const int vkh = qi & 1, halfpos = qi >> 1;
@@ -206,147 +240,145 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     }
   };
 
-  auto compute_tile = [&](int buf, int t) {
+  // A 64-key tile is consumed as two 32-key blocks, each with its own softmax update, so that only one
+  // block of scores and probabilities is live at a time.  The three steps of a block:
+  f32x16 sv;            // scores of the block in flight, then its probabilities
+  u32x4 pf[2];          // the probabilities as bf16: [half of the block's keys] x 8
+  // ---- S^T = K Q^T ------------------------------------------------------------------------------
+  auto qk = [&](int buf, int kb) {
+    // all eight K fragments of this key block are fetched from LDS first: with one MFMA per
+    // fragment there is nothing else to hide the LDS latency behind
+    bf16x8 kf[8];
+    const int key = kb * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kf[ks] = u4_as_bf16x8(Ks[buf][key * 16 + ((2 * ks + kh) ^ (key & 15))]);
+    if constexpr (FOLD) {
+      sv = negm;
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[v] = 0.f;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], u4_as_bf16x8(qf[0][ks]), sv, 0, 0, 0);
+  };
+  // ---- causal mask and online softmax (log2 domain), one query row per lane -----------------------
+  auto softmax = [&](int t, int kb) {
     const int k0 = kbeg + t * ATT_BN;
-    const bool need_mask = (k0 + ATT_BN - 1 > first_pos) || (k0 + ATT_BN > kend);
-    // the 64-key tile is consumed as two 32-key blocks, each with its own softmax update, so that
-    // only one block of scores and probabilities is live at a time
+    // only tiles that reach past the first query position or the split end need the mask
+    if ((k0 + ATT_BN - 1 > first_pos) || (k0 + ATT_BN > kend)) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      // ---- S^T = K Q^T ----------------------------------------------------------------------
-      f32x16 s[NB];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
-      {
-        // all eight K fragments of this key block are fetched from LDS first: with one MFMA per
-        // fragment there is nothing else to hide the LDS latency behind
-        bf16x8 kf[8];
-        const int key = kb * 32 + l32;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[ks] = u4_as_bf16x8(Ks[buf][key * 16 + ((2 * ks + kh) ^ (key & 15))]);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], u4_as_bf16x8(qf[nb][ks]),
-                                                            (FOLD && ks == 0) ? negm : s[nb], 0, 0, 0);
-      }
-
-      // ---- causal mask: only tiles that reach past the first query position or the split end --
-      if (need_mask) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = k0 + kb * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
-            if (key > pos[nb] || key >= kend) s[nb][v] = -INFINITY;
-          }
-      }
-
-      // ---- online softmax (log2 domain), one query row per lane -------------------------------
-      u32x4 pf[2][NB];     // [half][nb]: 8 probabilities as bf16
-      f32x16 &sv = s[0];
-      float mx = sv[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sv[v]);
-      mx = max_with_other_half(mx);
-      // The reference exponent of a row moves (and its 64 output accumulators and row sum are rescaled)
-      // only in blocks where some row of the wave needs it -- a wave-uniform, rare branch: with random
-      // scores a third of all blocks would otherwise move the maximum of some row.  The softmax is
-      // mathematically unchanged (numerator and denominator share the reference); probabilities reach
-      // 2^lazy instead of 1, with the same relative bf16 rounding.
-      if constexpr (FOLD) {
-        // sv holds s - m_ref.  A row's first keys set the reference to their exact maximum (the largest
-        // probability is then exactly 1, which matters most for rows that see few keys).
-        const bool fresh = lacc[0] == 0.f;       // nothing accumulated for this row yet
-        const bool want = mx > a.lazy || (fresh && mx > -INFINITY);
-        if (__any(want)) {
-          const float delta = want ? mx : 0.f;
-          const float alpha = fresh ? 1.0f : __builtin_amdgcn_exp2f(-delta);
-          m_ref += delta;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) { sv[v] -= delta; negm[v] -= delta; lacc[v] *= alpha; }
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[cb][0][v] *= alpha;
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sv[v] = __builtin_amdgcn_exp2f(sv[v]);
-      } else {
-        // sv holds raw scores; m_ref is in the exp2 domain (score * sm_scale * log2 e)
-        const float m_blk = mx * c_scale;
-        const bool move = __any(m_blk > m_ref + a.lazy);
-        const float m_new = move ? fmaxf(m_ref, m_blk) : m_ref;
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        if (move) {
-          const float alpha = __builtin_amdgcn_exp2f(m_ref - m_safe);
-#pragma unroll
-          for (int v = 0; v < 16; ++v) lacc[v] *= alpha;
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[cb][0][v] *= alpha;
-        }
-        m_ref = m_new;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sv[v] = __builtin_amdgcn_exp2f(fmaf(sv[v], c_scale, -m_safe));
-      }
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        const int e = 8 * hf;
-        pf[hf][0] = u32x4{pack_bf16x2(sv[e], sv[e + 1]), pack_bf16x2(sv[e + 2], sv[e + 3]), pack_bf16x2(sv[e + 4], sv[e + 5]),
-                          pack_bf16x2(sv[e + 6], sv[e + 7])};
-      }
-
-      // ---- O^T += V^T P^T ---------------------------------------------------------------------
-      {
-        bf16x8 vf[2][4];
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb) {
-            const int col = cb * 32 + l32, c = 2 * (kb * 2 + hf) + kh;
-            vf[hf][cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
-          }
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-              o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][cb], u4_as_bf16x8(pf[hf][nb]), o[cb][nb], 0, 0, 0);
-        // row sums of the ROUNDED probabilities (the values the products above use, so numerator and
-        // denominator of the softmax carry the same rounding): an all-ones A operand leaves the sum over
-        // the block's 32 keys in every register of lacc
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-          lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, u4_as_bf16x8(pf[hf][0]), lacc, 0, 0, 0);
+      for (int v = 0; v < 16; ++v) {
+        const int key = k0 + kb * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
+        if (key > pos[0] || key >= kend) sv[v] = -INFINITY;
       }
     }
-
+    float mx = sv[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sv[v]);
+    mx = max_with_other_half(mx);
+    // The reference exponent of a row moves (and its 64 output accumulators and row sum are rescaled)
+    // only in blocks where some row of the wave needs it -- a wave-uniform, rare branch: with random
+    // scores a third of all blocks would otherwise move the maximum of some row.  The softmax is
+    // mathematically unchanged (numerator and denominator share the reference); probabilities reach
+    // 2^lazy instead of 1, with the same relative bf16 rounding.
+    if constexpr (FOLD) {
+      // sv holds s - m_ref.  A row's first keys set the reference to their exact maximum (the largest
+      // probability is then exactly 1, which matters most for rows that see few keys).
+      const bool fresh = lacc[0] == 0.f;       // nothing accumulated for this row yet
+      const bool want = mx > a.lazy || (fresh && mx > -INFINITY);
+      if (__any(want)) {
+        const float delta = want ? mx : 0.f;
+        const float alpha = fresh ? 1.0f : __builtin_amdgcn_exp2f(-delta);
+        m_ref += delta;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sv[v] -= delta; negm[v] -= delta; lacc[v] *= alpha; }
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[cb][0][v] *= alpha;
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[v] = __builtin_amdgcn_exp2f(sv[v]);
+    } else {
+      // sv holds raw scores; m_ref is in the exp2 domain (score * sm_scale * log2 e)
+      const float m_blk = mx * c_scale;
+      const bool move = __any(m_blk > m_ref + a.lazy);
+      const float m_new = move ? fmaxf(m_ref, m_blk) : m_ref;
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      if (move) {
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_safe);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) lacc[v] *= alpha;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[cb][0][v] *= alpha;
+      }
+      m_ref = m_new;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[v] = __builtin_amdgcn_exp2f(fmaf(sv[v], c_scale, -m_safe));
+    }
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int e = 8 * hf;
+      pf[hf] = u32x4{pack_bf16x2(sv[e], sv[e + 1]), pack_bf16x2(sv[e + 2], sv[e + 3]), pack_bf16x2(sv[e + 4], sv[e + 5]),
+                     pack_bf16x2(sv[e + 6], sv[e + 7])};
+    }
+  };
+  // ---- O^T += V^T P^T and the row sums ----------------------------------------------------------------
+  auto pv = [&](int buf, int kb) {
+    bf16x8 vf[2][4];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const int col = cb * 32 + l32, c = 2 * (kb * 2 + hf) + kh;
+        vf[hf][cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
+      }
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+        o[cb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][cb], u4_as_bf16x8(pf[hf]), o[cb][0], 0, 0, 0);
+    // row sums of the ROUNDED probabilities (the values the products above use, so numerator and
+    // denominator of the softmax carry the same rounding): an all-ones A operand leaves the sum over
+    // the block's 32 keys in every register of lacc
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+      lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, u4_as_bf16x8(pf[hf]), lacc, 0, 0, 0);
   };
 
-  // Loads and stores in the loop are unconditional (tile indices clamped) so that the compiler's
-  // count of outstanding loads is exact and it waits only for the tile it is about to store.
-  if (ntiles > 0) {
-    load_tile(0, rk0, rv0);
-    load_tile(min(1, ntiles - 1), rk1, rv1);
-    store_tile(0, rk0, rv0);
-  }
-  __syncthreads();
-  wait_all_global_loads();
-  for (int t = 0; t < ntiles; t += 2) {
-    load_tile(min(t + 2, ntiles - 1), rk0, rv0);
-    compute_tile(0, t);
-    store_tile(1, rk1, rv1);
+  {
+    auto compute_tile = [&](int buf, int t) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        qk(buf, kb);
+        softmax(t, kb);
+        pv(buf, kb);
+      }
+    };
+    // Loads and stores in the loop are unconditional (tile indices clamped) so that the compiler's
+    // count of outstanding loads is exact and it waits only for the tile it is about to store.
+    if (ntiles > 0) {
+      load_tile(0, rk0, rv0);
+      load_tile(min(1, ntiles - 1), rk1, rv1);
+      store_k(0, rk0);
+      store_v(0, rv0);
+    }
     __syncthreads();
-    load_tile(min(t + 3, ntiles - 1), rk1, rv1);
-    if (t + 1 < ntiles) compute_tile(1, t + 1);
-    store_tile(0, rk0, rv0);
-    __syncthreads();
+    wait_all_global_loads();
+    for (int t = 0; t < ntiles; t += 2) {
+      load_tile(min(t + 2, ntiles - 1), rk0, rv0);
+      compute_tile(0, t);
+      store_k(1, rk1);
+      store_v(1, rv1);
+      __syncthreads();
+      load_tile(min(t + 3, ntiles - 1), rk1, rv1);
+      if (t + 1 < ntiles) compute_tile(1, t + 1);
+      store_k(0, rk0);
+      store_v(0, rv0);
+      __syncthreads();
+    }
   }
 
   // ---- write the partial (or final) result ----------------------------------------------------
@@ -737,10 +769,10 @@ static void launch_attn_pipe(const AttnArgs &a, int n_work, int G, hipStream_t s
   }
 }
 
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, bool prefix,
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, int schedule, bool prefix,
                               hipStream_t s) {
   if (n_work == 0) return;
-  if (pipelined && waves == 8) {
+  if (schedule == ATTN_SCHED_PIPELINED && waves == 8) {
     if (prefix) launch_attn_pipe<true>(a, n_work, G, s);
     else launch_attn_pipe<false>(a, n_work, G, s);
   } else if (waves == 4) {
@@ -752,8 +784,8 @@ void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, b
 
 // What the rotation kernel multiplies the queries by for the variant the arguments select: the folded
 // softmax wants them in the exp2 domain, every other kernel applies sm_scale itself.
-float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, bool pipelined, bool fold) {
-  if (!fold || (pipelined && waves == 8)) return 1.0f;
+float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, int schedule, bool fold) {
+  if (!fold || (schedule == ATTN_SCHED_PIPELINED && waves == 8)) return 1.0f;
   return LOG2E / sqrtf((float)L.head_dim);
 }
 

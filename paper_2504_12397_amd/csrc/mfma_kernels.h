@@ -67,11 +67,15 @@ struct AttnArgs {
 };
 bool attn_prefill_mfma_supported(const LayerDims &L);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
-// with a.q_prescaled the unpipelined kernels run their folded-softmax form; the pipelined variant needs
-// unscaled queries (attn_prefill_mfma_q_scale tells the rotation kernel which it is)
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool pipelined, bool prefix,
+// How one workgroup orders its work: every wave runs K Q^T, softmax, P V one after the other and the
+// overlap of matrix and vector work is left to the two waves that share a SIMD (SIMPLE), or each wave
+// interleaves the three instruction streams of neighbouring blocks itself (PIPELINED, 8 waves).
+enum { ATTN_SCHED_PIPELINED = 0, ATTN_SCHED_SIMPLE = 1 };
+// with a.q_prescaled the SIMPLE kernels run their folded-softmax form; the PIPELINED variant
+// needs unscaled queries (attn_prefill_mfma_q_scale tells the rotation kernel which it is)
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, int schedule, bool prefix,
                               hipStream_t s);
-float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, bool pipelined, bool fold);
+float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, int schedule, bool fold);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
 // One workgroup of the decode kernel: the query heads (of one GQA group) of up to 16 / G rows
