@@ -136,7 +136,8 @@ const char *alora_status_string(alora_status s);
  * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
  * of attention into n chunks.  "gemm_splits": 0 = automatic, n > 0 = split the reduction axis
  * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128,
- * 3 = 256x256 block tiles for the QKV projection.  "lora_split": 0 = automatic, 1 = always, 2 = never give the low-rank term of
+ * 3 = 256x256, 4 = 128x64 block tiles (four waves), 5 / 6 = 128x128 with eight waves of 32x64 / 64x32 (the automatic
+ * choice up to 512 / 128 rows; 1 and 4..6 also apply to the other linears of a stack).  "lora_split": 0 = automatic, 1 = always, 2 = never give the low-rank term of
  * the QKV projection workgroups (and a partial sum) of its own.  "attn_waves": 0 = automatic, 4 or 8 waves per workgroup
  * in the prefill attention kernel.  "attn_pipeline": 1 (default) = prefill attention kernel that
  * leaves the overlap of softmax and matrix work to the waves sharing a SIMD, 0 = the variant that

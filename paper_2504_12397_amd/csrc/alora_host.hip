@@ -481,7 +481,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       g.A = (const bf16 *)A; g.lda = K;
       g.B = (const bf16 *)W; g.ldb = K;
       g.M = T_rows; g.N = N; g.K = K;
-      g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+      g.tile_hint = (ctx->opt_gemm_tile >= 4 || ctx->opt_gemm_tile == 1) ? ctx->opt_gemm_tile : 0;
       if (lr) set_lowrank(g, Bl, nullptr, 1, N);
       // few row tiles: split the reduction to fill the chip, partial sums go through the Y buffer
       const int splits = ctx->opt_gemm_splits == 1 ? 1 : gemm_mfma_pick_splits(T_rows, N, K, ctx->n_cu);
@@ -513,7 +513,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       g.A = (const bf16 *)w.attn; g.lda = L.n_q;
       g.B = (const bf16 *)ly->W_o; g.ldb = L.n_q;
       g.M = T_rows; g.N = L.d; g.K = L.n_q;
-      g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+      g.tile_hint = (ctx->opt_gemm_tile >= 4 || ctx->opt_gemm_tile == 1) ? ctx->opt_gemm_tile : 0;
       if (ly->A_o && w.any_adapter) {
         lowrank_t(w.attn, L.n_q, ly->A_o, 1);
         set_lowrank(g, ly->B_o, nullptr, 1, L.d);
@@ -546,7 +546,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     g.A = (const bf16 *)w.hn; g.lda = L.d;
     g.B = (const bf16 *)ly->W_gate; g.B2 = (const bf16 *)ly->W_up; g.ldb = L.d;
     g.M = T_rows; g.N = 2 * ly->intermediate; g.K = L.d; g.k_splits = 1;
-    g.tile_hint = ctx->opt_gemm_tile == 4 ? 4 : 0;
+    g.tile_hint = (ctx->opt_gemm_tile >= 4 || ctx->opt_gemm_tile == 1) ? ctx->opt_gemm_tile : 0;
     if (ly->A_gu && w.any_adapter) {
       lowrank_t(w.hn, L.d, ly->A_gu, 2);
       set_lowrank(g, ly->B_gate, ly->B_up, 2, ly->intermediate);
@@ -934,7 +934,7 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
     return ALORA_OK;
   }
   if (!strcmp(key, "gemm_tile")) {
-    if (value < 0 || value > 4) return fail(ctx, ALORA_EINVAL, "gemm_tile must be in [0, 4]");
+    if (value < 0 || value > 6) return fail(ctx, ALORA_EINVAL, "gemm_tile must be in [0, 6]");
     ctx->opt_gemm_tile = value;
     return ALORA_OK;
   }

@@ -42,6 +42,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   constexpr int NT = 64 * (BM / WM) * WAVES_N;
   static_assert(NT == 256 || NT == 512, "four or eight waves per block");
   constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(EPI != GEMM_EPI_SWIGLU || TN % 2 == 0, "the SwiGLU epilogue pairs the 32-column blocks of a wave");
   constexpr int A_CHUNKS = BM * 8 / NT, B_CHUNKS = BN * 8 / NT;
   extern __shared__ u32x4 smem[];
   __shared__ unsigned long long s_present;
@@ -509,19 +510,31 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     if (g.tile_hint == 2) launch_cfg<256, 128, 128, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (g.tile_hint == 3) launch_cfg<256, 256, 64, 128, GEMM_EPI_PARTIAL, 1>(g, s);
     else if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_PARTIAL>(g, s);
+    else if (g.tile_hint == 5) launch_cfg<128, 128, 32, 64, GEMM_EPI_PARTIAL>(g, s);
+    else if (g.tile_hint == 6) launch_cfg<128, 128, 64, 32, GEMM_EPI_PARTIAL>(g, s);
+    else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (g.M > 4 * 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true>(g, s);
-    else launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
+    // few row tiles: the kernel streams weights and eight waves (two per SIMD) hide its LDS and barrier
+    // latencies better than four; which way the 128x128 block is cut among them matters by a few percent
+    else if (g.M > 128) launch_cfg<128, 128, 32, 64, GEMM_EPI_PARTIAL>(g, s);
+    else launch_cfg<128, 128, 64, 32, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
     g.lora_split = 0;
     if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_SWIGLU>(g, s);
-    else if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
+    // (a wave needs a gate block and its up block: at least two 32-column blocks, so no 64x32 wave tiles here)
+    else if (g.tile_hint == 5 || g.tile_hint == 6) launch_cfg<128, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
+    else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
+    else if (g.M <= 128) launch_cfg<128, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
   } else {
     g.k_splits = 1;
     g.lora_split = 0;
     if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_BF16>(g, s);
-    else if (g.M <= 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
+    else if (g.tile_hint == 5) launch_cfg<128, 128, 32, 64, GEMM_EPI_BF16>(g, s);
+    else if (g.tile_hint == 6) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
+    else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
+    else if (g.M <= 128) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_BF16>(g, s);
   }
 }

@@ -12,7 +12,7 @@ struct GemmArgs {
   const bf16 *B; int ldb;      // [N, K]
   const bf16 *B2;              // SwiGLU only: the "up" weights; B holds the "gate" weights, N = 2 * I
   int M, N, K;
-  int tile_hint;               // 0 = automatic, 1 = 128x128 blocks, 2 = 256x128 blocks
+  int tile_hint;               // 0 = automatic; 1 = 128x128 (4 waves), 2 = 256x128, 3 = 256x256, 4 = 128x64, 5/6 = 128x128 with 8 waves of 32x64 / 64x32
   int k_splits;                // PARTIAL only: splits of the reduction axis; K / k_splits must be a multiple of 64
   int lora_split;              // PARTIAL only, 1: the low-rank term gets workgroups of its own that write partial
                                // number k_splits (Cpart then holds k_splits + 1 partials), instead of riding on split 0

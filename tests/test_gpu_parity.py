@@ -487,7 +487,7 @@ def test_bf16_head_layouts(ab, ctx, hq, hkv, h, r):
 
 
 @pytest.mark.parametrize("opts", [{"kernels": 1}, {"kv_splits": 1}, {"kv_splits": 5}, {"gemm_splits": 1}, {"gemm_splits": 4},
-                                  {"gemm_tile": 2}, {"gemm_tile": 3}, {"attn_waves": 4}, {"attn_lazy": 0}, {"attn_lazy": 8},
+                                  {"gemm_tile": 1}, {"gemm_tile": 2}, {"gemm_tile": 3}, {"gemm_tile": 4}, {"gemm_tile": 5}, {"gemm_tile": 6}, {"attn_waves": 4}, {"attn_lazy": 0}, {"attn_lazy": 8},
                                   {"attn_pipeline": 0}, {"attn_pipeline": 0, "attn_lazy": 0},
                                   {"attn_pipeline": 0, "kv_splits": 3},
                                   {"attn_fold": 1}, {"attn_fold": 1, "kv_splits": 3}, {"attn_fold": 1, "attn_waves": 4},
