@@ -84,10 +84,10 @@ def algorithmic_work(batch, shape, n_layers=1):
 # profiles/*.md.  bench.py cannot read hardware counters itself, so these are the recorded values for the
 # kernels as committed; a workload/kernel pair that has not been profiled reports null.
 MEASURED_TRAFFIC_KIB = {
-    ("c2", "qkv_gemm"): 66972 + 18432, ("c2", "attn_prefill"): 33994 + 35499, ("c2", "prep_rows"): 8387 + 2149,
-    ("c3", "qkv_gemm"): 669792 + 106992, ("c3", "attn_prefill"): 375153 + 35664,
-    ("c4", "attn_decode"): 4337116 + 4353, ("c4", "qkv_gemm"): 55198 + 7680,
-    ("c5", "attn_prefill"): 139979 + 35623, ("c5", "gate_up"): 237760 + 3584,
+    ("c2", "qkv_gemm"): 66861 + 18432, ("c2", "attn_prefill"): 33994 + 35513, ("c2", "prep_rows"): 8387 + 2149,
+    ("c3", "qkv_gemm"): 668440 + 106992, ("c3", "attn_prefill"): 375153 + 35664,
+    ("c4", "attn_decode"): 4337132 + 4353, ("c4", "qkv_gemm"): 55114 + 7680,
+    ("c5", "attn_prefill"): 139978 + 35617, ("c5", "gate_up"): 237689 + 3584,
 }
 
 

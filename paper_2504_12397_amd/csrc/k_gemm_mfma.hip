@@ -389,20 +389,45 @@ static void launch_cfg(const GemmArgs &g, hipStream_t s) {
   hipLaunchKernelGGL(kern, grid, dim3(NT), smem, s, g);
 }
 
+// Sum of the partial sums of one group of four columns, in split order.  The first eight partials are requested
+// together before any is added (a loop over a run-time count would take one memory round trip per split).
+__device__ __forceinline__ float4 sum_partials(const float *__restrict__ p, int splits, int64_t stride) {
+  float4 v[8];
+#pragma unroll
+  for (int sp = 0; sp < 8; ++sp)
+    if (sp < splits) v[sp] = *reinterpret_cast<const float4 *>(p + (int64_t)sp * stride);
+  float4 acc = v[0];
+#pragma unroll
+  for (int sp = 1; sp < 8; ++sp)
+    if (sp < splits) { acc.x += v[sp].x; acc.y += v[sp].y; acc.z += v[sp].z; acc.w += v[sp].w; }
+  for (int sp = 8; sp < splits; ++sp) {
+    const float4 w = *reinterpret_cast<const float4 *>(p + (int64_t)sp * stride);
+    acc.x += w.x; acc.y += w.y; acc.z += w.z; acc.w += w.w;
+  }
+  return acc;
+}
+
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+__device__ __forceinline__ float4 load_bf16x4(const bf16 *p) {
+  const bf16x4_t r = *reinterpret_cast<const bf16x4_t *>(p);
+  return make_float4((float)r[0], (float)r[1], (float)r[2], (float)r[3]);
+}
+__device__ __forceinline__ void store_bf16x4(bf16 *p, float a, float b, float c, float d) {
+  bf16x4_t o;
+  o[0] = (bf16)a; o[1] = (bf16)b; o[2] = (bf16)c; o[3] = (bf16)d;
+  *reinterpret_cast<bf16x4_t *>(p) = o;
+}
+
 // C = bf16( sum over splits of partial sums (fixed order) + residual )
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int splits, int64_t mn,
                                                             const bf16 *__restrict__ R, bf16 *__restrict__ C) {
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= mn) return;
-  float4 acc = *reinterpret_cast<const float4 *>(part + i);
-  for (int s = 1; s < splits; ++s) {
-    const float4 v = *reinterpret_cast<const float4 *>(part + (int64_t)s * mn + i);
-    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-  }
-  if (R != nullptr) {
-    acc.x += (float)R[i]; acc.y += (float)R[i + 1]; acc.z += (float)R[i + 2]; acc.w += (float)R[i + 3];
-  }
-  C[i] = (bf16)acc.x; C[i + 1] = (bf16)acc.y; C[i + 2] = (bf16)acc.z; C[i + 3] = (bf16)acc.w;
+  float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (R != nullptr) res = load_bf16x4(R + i);
+  float4 acc = sum_partials(part + i, splits, mn);
+  acc.x += res.x; acc.y += res.y; acc.z += res.z; acc.w += res.w;
+  store_bf16x4(C + i, acc.x, acc.y, acc.z, acc.w);
 }
 
 void launch_splitk_reduce(const float *part, int splits, int64_t mn, const bf16 *R, bf16 *C, hipStream_t s) {
@@ -421,21 +446,21 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(const float *__
   __shared__ float s_red[4];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int64_t mn = (int64_t)M * N, ro = (int64_t)row * N;
-  float4 h[16];
+  float4 h[16], res[16];
   float ssq = 0.f;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int c = (u * 256 + tid) * 4;
+    res[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < N && R != nullptr) res[u] = load_bf16x4(R + ro + c);
+  }
 #pragma unroll
   for (int u = 0; u < 16; ++u) {
     const int c = (u * 256 + tid) * 4;
     h[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (c < N) {
-      float4 acc = *reinterpret_cast<const float4 *>(part + ro + c);
-      for (int sp = 1; sp < splits; ++sp) {
-        const float4 v = *reinterpret_cast<const float4 *>(part + (int64_t)sp * mn + ro + c);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-      }
-      if (R != nullptr) {
-        acc.x += (float)R[ro + c]; acc.y += (float)R[ro + c + 1]; acc.z += (float)R[ro + c + 2]; acc.w += (float)R[ro + c + 3];
-      }
+      float4 acc = sum_partials(part + ro + c, splits, mn);
+      acc.x += res[u].x; acc.y += res[u].y; acc.z += res[u].z; acc.w += res[u].w;
       h[u] = acc;
       ssq += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
     }
@@ -448,12 +473,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(const float *__
   for (int u = 0; u < 16; ++u) {
     const int c = (u * 256 + tid) * 4;
     if (c < N) {
-      const float v[4] = {h[u].x, h[u].y, h[u].z, h[u].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        C[ro + c + e] = (bf16)v[e];
-        Cn[ro + c + e] = (bf16)(v[e] * (float)gain[c + e] * rinv);
-      }
+      const float4 gn = load_bf16x4(gain + c);
+      store_bf16x4(C + ro + c, h[u].x, h[u].y, h[u].z, h[u].w);
+      store_bf16x4(Cn + ro + c, h[u].x * gn.x * rinv, h[u].y * gn.y * rinv, h[u].z * gn.z * rinv, h[u].w * gn.w * rinv);
     }
   }
 }

@@ -240,7 +240,7 @@ template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, 
 // One wave per (row, head slot), four slots per workgroup: slots 0..Hq-1 are query heads, then the
 // key heads, then the value heads.  Every lane handles whole rotation pairs, all loads are
 // independent.
-template <typename T>
+template <typename T, bool MULTI>      // MULTI: Y arrives as several partial sums
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, int n_parts,
                                                          int64_t part_stride, LayerDims L, RowMeta rm,
                                                          const float2 *__restrict__ table, float q_scale,
@@ -251,9 +251,18 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
   if (slot_id >= L.n_q_heads + 2 * L.n_kv_heads) return;
   const float *y = Y + (int64_t)row * L.n_qkv;
   // Y may arrive as n_parts partial sums over the reduction axis: add them in a fixed order
+  // (the first eight are requested together: a loop over the run-time count costs a memory round trip per part)
   auto ysum = [&](const float *p) {
-    float v = p[0];
-    for (int s = 1; s < n_parts; ++s) v += p[(int64_t)s * part_stride];
+    if constexpr (!MULTI) return p[0];
+    float t[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      if (s < n_parts) t[s] = p[(int64_t)s * part_stride];
+    float v = t[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s)
+      if (s < n_parts) v += t[s];
+    for (int s = 8; s < n_parts; ++s) v += p[(int64_t)s * part_stride];
     return v;
   };
   if (slot_id < L.n_q_heads + L.n_kv_heads) {
@@ -284,8 +293,12 @@ void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta
                         const float2 *rope_table, float q_scale, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
   if (T_rows == 0) return;
   dim3 grid(T_rows, (L.n_q_heads + 2 * L.n_kv_heads + 3) / 4);
-  hipLaunchKernelGGL((rope_append_kernel<T>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
-                     rope_table, q_scale, Q, cacheK, cacheV);
+  if (n_parts > 1)
+    hipLaunchKernelGGL((rope_append_kernel<T, true>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
+                       rope_table, q_scale, Q, cacheK, cacheV);
+  else
+    hipLaunchKernelGGL((rope_append_kernel<T, false>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
+                       rope_table, q_scale, Q, cacheK, cacheV);
 }
 template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float,
                                         float *, float *, float *, hipStream_t);
