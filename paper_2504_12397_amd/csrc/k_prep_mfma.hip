@@ -27,9 +27,8 @@ constexpr int PREP_WAVES = 8;
 // adapter of the tile is known at once and its A fragments are requested together with x instead of after
 // the metadata and normalisation phases -- one dependent memory round trip less on a kernel that is nothing
 // but round trips at these sizes.
-// DENSE (many row tiles): registers capped so that two workgroups share a compute unit, loads in smaller batches.
-template <int NF, int CH, bool EARLY = false, bool DENSE = false>
-__global__ __launch_bounds__(512, DENSE ? 4 : 2) void prep_rows_mfma_kernel(PrepArgs a) {
+template <int NF, int CH, bool EARLY = false>
+__global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
   __shared__ float s_ssq[PREP_WAVES][PREP_ROWS];
   __shared__ int s_adapter[PREP_ROWS];
   __shared__ float s_scale[PREP_ROWS];
@@ -72,32 +71,36 @@ __global__ __launch_bounds__(512, DENSE ? 4 : 2) void prep_rows_mfma_kernel(Prep
   }
 
   if (tid == 0) s_present = 0ull;
+  if (tid < PREP_ROWS) { s_adapter[tid] = -1; s_scale[tid] = 0.f; }
   __syncthreads();
-  if (tid < PREP_ROWS) {
-    const int mrow = row0 + tid;
+  // Row metadata.  With one sequence (EARLY: its record came with the arguments) a thread takes a row.
+  // Otherwise a thread takes a sequence: it fetches the sequence record once and fills in the rows of this
+  // tile that belong to it -- one memory round trip, where a search over the sequence table per row costs
+  // log2(n_seqs) dependent ones.
+  const int tile_end = min(row0 + PREP_ROWS, a.T);
+  auto fill_row = [&](const SeqMeta &sm, int sq, int mrow) {
+    const int pos = sm.P + a.pos_shift + (mrow - sm.row_start);
     int adapter = -1;
     float scale = 0.f;
-    if (mrow < a.T && a.seqs != nullptr) {
-      int lo = 0, hi = a.n_seqs - 1;           // last sequence whose first row is <= mrow
-      if constexpr (!EARLY) {
-        while (lo < hi) {
-          int mid = (lo + hi + 1) >> 1;
-          if (a.seqs[mid].row_start <= mrow) lo = mid; else hi = mid - 1;
-        }
-      }
-      const SeqMeta sm = EARLY ? a.one : a.seqs[lo];
-      const int pos = sm.P + a.pos_shift + (mrow - sm.row_start);
-      if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
-      if (a.write_meta && lead) {
-        a.rm.seq[mrow] = lo;
-        a.rm.pos[mrow] = pos;
-        a.rm.adapter[mrow] = adapter;
-        a.rm.slot[mrow] = sm.pool_off + pos;
-      }
+    if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
+    if (a.write_meta && lead) {
+      a.rm.seq[mrow] = sq;
+      a.rm.pos[mrow] = pos;
+      a.rm.adapter[mrow] = adapter;
+      a.rm.slot[mrow] = sm.pool_off + pos;
     }
-    s_adapter[tid] = adapter;
-    s_scale[tid] = scale;
+    s_adapter[mrow - row0] = adapter;
+    s_scale[mrow - row0] = scale;
     if (adapter >= 0) atomicOr(&s_present, 1ull << adapter);
+  };
+  if constexpr (EARLY) {
+    if (tid < PREP_ROWS && row0 + tid < tile_end) fill_row(a.one, 0, row0 + tid);
+  } else {
+    for (int sq = tid; sq < (a.seqs != nullptr ? a.n_seqs : 0); sq += 512) {
+      const SeqMeta sm = a.seqs[sq];
+      const int lo = max(sm.row_start, row0), hi = min(sm.row_start + sm.n_new, tile_end);
+      for (int mrow = lo; mrow < hi; ++mrow) fill_row(sm, sq, mrow);
+    }
   }
 
   // ---- sum of squares: lane -> the 4 lanes of a row -> the 8 waves (fixed order) ------------------
@@ -146,8 +149,10 @@ __global__ __launch_bounds__(512, DENSE ? 4 : 2) void prep_rows_mfma_kernel(Prep
   for (int j = 0; j < (NF > 0 ? NF : 1); ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   if (NF > 0) {
     constexpr int NFX = NF > 0 ? NF : 1;
-    constexpr int UB0 = (16 / NFX) < 1 ? 1 : ((16 / NFX) > CH ? CH : (16 / NFX));     // k-steps per load batch
-    constexpr int UB = DENSE ? (UB0 > 1 ? UB0 / 2 : 1) : UB0;
+    // chunks per load batch: about 16 fragments, a power of two so that it divides CH
+    constexpr int UBN = NFX >= 9 ? 1 : NFX >= 5 ? 2 : NFX >= 3 ? 4 : NFX == 2 ? 8 : 16;
+    constexpr int UB0 = UBN > CH ? CH : UBN;
+    constexpr int UB = UB0;
     if constexpr (EARLY) {
       if (pre_loaded) {
         const bool mine = my_adapter == a.one.adapter;
@@ -161,28 +166,66 @@ __global__ __launch_bounds__(512, DENSE ? 4 : 2) void prep_rows_mfma_kernel(Prep
         }
       }
     }
+    // One pass over the lane's chunks per adapter present in the tile, in batches of UB chunks.  Every batch
+    // of A fragments is a memory round trip, so two register buffers alternate: the next batch -- the next
+    // adapter's first one at the end of a pass -- is requested before the current one is multiplied.
     unsigned long long todo = EARLY ? 0ull : present;
-    while (todo) {
+    auto next_adapter = [&]() {
+      if (!todo) return -1;
       const int ad = __builtin_ctzll(todo);
       todo &= todo - 1;
-      const bool mine = my_adapter == ad;
+      return ad;
+    };
+    auto load_batch = [&](int ad, int u0, u32x4 (&br)[UB][NFX]) {
       const bf16 *Ab = a.A + ((int64_t)ad * 3 * rank + col0 + r16) * d + k_lo;     // row col0 + 16 j + r16
 #pragma unroll
-      for (int u0 = 0; u0 < CH; u0 += UB) {
-        u32x4 br[UB][NFX];
+      for (int u = 0; u < UB; ++u)
 #pragma unroll
-        for (int u = 0; u < UB; ++u)
+        for (int j = 0; j < NFX; ++j)
+          br[u][j] = *reinterpret_cast<const u32x4 *>(Ab + (int64_t)j * 16 * d + 32 * (u0 + u));
+    };
+    auto mma_batch = [&](int ad, int u0, const u32x4 (&br)[UB][NFX]) {
+      const bool mine = my_adapter == ad;
 #pragma unroll
-          for (int j = 0; j < NFX; ++j)
-            br[u][j] = *reinterpret_cast<const u32x4 *>(Ab + (int64_t)j * 16 * d + 32 * (u0 + u));
+      for (int u = 0; u < UB; ++u) {
+        const u32x4 au = mine ? xr[u0 + u] : u32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int u = 0; u < UB; ++u) {
-          const u32x4 au = mine ? xr[u0 + u] : u32x4{0, 0, 0, 0};
+        for (int j = 0; j < NFX; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, au),
+                                                           __builtin_bit_cast(bf16x8, br[u][j]), acc[j], 0, 0, 0);
+      }
+    };
+    constexpr int NB = CH / UB;        // batches per pass
+    static_assert(CH % UB == 0, "batches cover the lane's chunks exactly");
+    if constexpr (NB % 2 == 0) {
+      u32x4 br0[UB][NFX], br1[UB][NFX];
+      int ad = next_adapter();
+      if (ad >= 0) load_batch(ad, 0, br0);
+      while (ad >= 0) {
+        const int nx = next_adapter();
 #pragma unroll
-          for (int j = 0; j < NFX; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, au),
-                                                             __builtin_bit_cast(bf16x8, br[u][j]), acc[j], 0, 0, 0);
+        for (int u0 = 0; u0 < CH; u0 += 2 * UB) {
+          load_batch(ad, u0 + UB, br1);
+          mma_batch(ad, u0, br0);
+          if (u0 + 2 * UB < CH) load_batch(ad, u0 + 2 * UB, br0);
+          else if (nx >= 0) load_batch(nx, 0, br0);
+          mma_batch(ad, u0 + UB, br1);
         }
+        ad = nx;
+      }
+    } else {
+      static_assert(NB == 1, "batches per pass: one or an even number");
+      u32x4 br0[UB][NFX], br1[UB][NFX];      // one batch per pass: adapters alternate between the buffers
+      int ad = next_adapter();
+      if (ad >= 0) load_batch(ad, 0, br0);
+      while (ad >= 0) {
+        const int nx = next_adapter();
+        if (nx >= 0) load_batch(nx, 0, br1);
+        mma_batch(ad, 0, br0);
+        if (nx < 0) break;
+        ad = next_adapter();
+        if (ad >= 0) load_batch(ad, 0, br0);
+        mma_batch(nx, 0, br1);
       }
     }
   }
@@ -217,11 +260,11 @@ bool prep_rows_mfma_supported(int d, int rank) {
   return (d == 4096 || d == 2048 || d == 1024 || d == 512) && (rank == 0 || rank == 16 || rank == 32 || rank == 64);
 }
 
-template <int NF, int CH, bool EARLY = false, bool DENSE = false>
+template <int NF, int CH, bool EARLY = false>
 static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
   const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
-  auto kern = prep_rows_mfma_kernel<NF, CH, EARLY, DENSE>;
+  auto kern = prep_rows_mfma_kernel<NF, CH, EARLY>;
   static bool configured = false;
   if (!configured && smem > 48 * 1024) {
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -240,10 +283,6 @@ static void launch_prep_nf(const PrepArgs &a, int groups, hipStream_t s) {
       case 512: launch_prep_cfg<1, 2, true>(a, groups, s); return;
       default: break;
     }
-  }
-  if (a.d == 4096 && NF >= 3 && (a.T + PREP_ROWS - 1) / PREP_ROWS * groups > 256) {
-    launch_prep_cfg<NF, 16, false, true>(a, groups, s);
-    return;
   }
   switch (a.d) {
     case 4096: launch_prep_cfg<NF, 16>(a, groups, s); break;

@@ -486,6 +486,17 @@ def test_bf16_head_layouts(ab, ctx, hq, hkv, h, r):
     check_case(ab, ctx, dcase, decode=True)
 
 
+@pytest.mark.parametrize("rank", [16, 32, 64])
+def test_full_width_rows_mixed_adapters(ab, ctx, rank):
+    """Hidden size 4096 (the widest row-preparation variant) with every supported rank, several adapters
+    and base-only rows inside one 16-row tile."""
+    shape = wl.LayerShape(d=4096, n_q_heads=4, n_kv_heads=1, head_dim=128, rank=rank, n_adapters=3)
+    case = H.make_case(shape, [40, 0, 9, 17], [21, 13, 7, 30], [40, 5, 0, 30], [2, 0, -1, 1], seed=520 + rank)
+    check_case(ab, ctx, case)
+    dcase = H.make_case(shape, [33, 5, 12, 20, 8], [1, 1, 1, 1, 1], [30, 5, 20, 0, 8], [0, 1, 2, -1, 1], seed=530 + rank)
+    check_case(ab, ctx, dcase, decode=True)
+
+
 @pytest.mark.parametrize("opts", [{"kernels": 1}, {"kv_splits": 1}, {"kv_splits": 5}, {"gemm_splits": 1}, {"gemm_splits": 4},
                                   {"gemm_tile": 1}, {"gemm_tile": 2}, {"gemm_tile": 3}, {"gemm_tile": 4}, {"gemm_tile": 5}, {"gemm_tile": 6}, {"attn_waves": 4}, {"attn_lazy": 0}, {"attn_lazy": 8},
                                   {"attn_pipeline": 0}, {"attn_pipeline": 0, "attn_lazy": 0},
