@@ -4,9 +4,10 @@
 // Work item: one workgroup = (q-tile of 256/G tokens of one sequence, kv head, key split).
 // The G query heads of the kv group are packed next to the tokens into 256 "packed rows"
 // (packed row = token * G + head), 32 per wave and eight waves per workgroup, so every K/V tile
-// fetched from HBM serves all heads of the group.  Two waves share a SIMD: the softmax of one
-// (exponentials and rescaling on the vector ALU -- as many cycles per tile as the MFMAs take on
-// this chip) overlaps the matrix work of the other.
+// fetched from HBM serves all heads of the group.  Two waves share a SIMD, so the softmax of one
+// (exponentials and rescaling on the vector ALU) can in principle run under the matrix work of the
+// other; measured, the tile time is close to the sum of its parts (MFMAs 1.59 us, softmax 0.35,
+// tile loads 0.27, LDS reads 0.17, LDS stores 0.14 of 2.37 us per 256 x 64 tile).
 //
 // Per 64-key tile, each wave computes S^T = K Q^T (keys are MFMA rows, packed query rows are
 // MFMA columns).  In that orientation a lane owns one query row (column l%32) in every
