@@ -364,7 +364,9 @@ REST_F32 = dataclasses.replace(SMALL_F32, intermediate=320, adapt_rest=True)
 
 
 @pytest.mark.parametrize("shape,opts", [(REST_BF16, {}), (REST_BF16, {"gemm_splits": 1}), (REST_BF16, {"kernels": 1}),
-                                        (REST_F32, {})], ids=["bf16", "bf16-unsplit", "bf16-plain", "fp32"])
+                                        (REST_BF16, {"gemm_tile": 1}), (REST_BF16, {"gemm_tile": 4}),
+                                        (REST_BF16, {"gemm_tile": 5}), (REST_F32, {})],
+                         ids=["bf16", "bf16-unsplit", "bf16-plain", "bf16-4waves", "bf16-128x64", "bf16-8waves-32x64", "fp32"])
 def test_stack_with_adapters_on_every_linear(ab, shape, opts):
     """Eq.6 applied to W_o and the MLP linears as well (Section 2's remark on MLP blocks): cache reuse
     over a base prefix, then a mixed batch whose sequences straddle their invocation points."""
