@@ -64,6 +64,7 @@ struct alora_ctx {
   int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
   int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
   int opt_attn_pipeline = 1;     // 0 = software-pipelined attention kernel, 1 = the unpipelined one
+  int opt_rope_fuse = 1;         // rotation + cache append in the epilogue of the QKV projection where the shape allows
   int opt_attn_fold = 0;         // 1 = unpipelined kernel takes prescaled queries and starts its score accumulators at -m_ref
   int n_cu = 256;
 };
@@ -369,6 +370,12 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
                           (const T *)ly->A, rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
     }
   }
+  // the folded-softmax attention kernel takes its queries premultiplied by sm_scale * log2(e)
+  const int attn_schedule = ctx->opt_attn_pipeline;
+  const float q_scale = (w.attn_mfma && std::is_same<T, bf16>::value)
+                            ? attn_prefill_mfma_q_scale(L, w.attn_waves, attn_schedule, ctx->opt_attn_fold != 0)
+                            : 1.0f;
+  bool rope_fused = false;
   {
     ProfScope p(ctx, K_QKV, s);
     if (mfma) {
@@ -386,18 +393,22 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.Bq = (const bf16 *)ly->B_q; g.Bk = (const bf16 *)ly->B_k; g.Bv = (const bf16 *)ly->B_v;
       g.n_q = L.n_q; g.n_kv = L.n_kv;
       g.row_adapter = w.rm.adapter;
-      launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+      // many rows, unsplit reduction, one head per column tile: rotation and cache append happen in the
+      // projection's epilogue and the fp32 projection never goes to memory
+      if (ctx->opt_gemm_tile == 0 && ctx->opt_rope_fuse && gemm_mfma_rope_supported(g, L.head_dim)) {
+        g.rope_pos = w.rm.pos; g.rope_slot = w.rm.slot; g.rope_table = ctx->rope; g.q_scale = q_scale;
+        g.Qout = (bf16 *)w.Q; g.cacheK = (bf16 *)cache->k; g.cacheV = (bf16 *)cache->v;
+        launch_gemm_mfma(g, GEMM_EPI_ROPE, s);
+        rope_fused = true;
+      } else {
+        launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
+      }
     } else {
       launch_qkv_gemm_plain<T>((const T *)w.xh, (const T *)ly->W_qkv, w.tlow, (const T *)ly->B_q,
                                (const T *)ly->B_k, (const T *)ly->B_v, L, w.rm, pl.T, w.Y, s);
     }
   }
-  // the folded-softmax attention kernel takes its queries premultiplied by sm_scale * log2(e)
-  const int attn_schedule = ctx->opt_attn_pipeline;
-  const float q_scale = (w.attn_mfma && std::is_same<T, bf16>::value)
-                            ? attn_prefill_mfma_q_scale(L, w.attn_waves, attn_schedule, ctx->opt_attn_fold != 0)
-                            : 1.0f;
-  {
+  if (!rope_fused) {
     ProfScope p(ctx, K_ROPE, s);
     launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, q_scale, (T *)w.Q,
                           (T *)cache->k, (T *)cache->v, s);
@@ -916,6 +927,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "attn_lazy")) {
     if (value < 0 || value > 16) return fail(ctx, ALORA_EINVAL, "attn_lazy must be in [0, 16]");
     ctx->opt_attn_lazy = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "rope_fuse")) {
+    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "rope_fuse must be 0 or 1");
+    ctx->opt_rope_fuse = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "attn_fold")) {

@@ -341,6 +341,69 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   }
 
   // ---- epilogue ---------------------------------------------------------------------------
+  if constexpr (EPI == GEMM_EPI_ROPE) {
+    // The 128-column tile is one head.  The accumulators go to LDS as fp32 (the k-tiles are done with it), then
+    // each wave takes 32 rows, a lane the rotation pair (c, c + 64): the same arithmetic, in the same order,
+    // as the rotary kernel applies to the fp32 projection it reads from memory.
+    static_assert(EPI != GEMM_EPI_ROPE || (BM == 128 && BN == 128 && NT == 256), "one head per tile, four waves");
+    float *ys = reinterpret_cast<float *>(smem);       // [128][128]
+    __syncthreads();
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          ys[(wm0 + mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3)) * 128 + wn0 + ni * 32 + l32] = acc[mi][ni][v];
+    __syncthreads();
+    const int kind = n0 < g.n_q ? 0 : (n0 < g.n_q + g.n_kv ? 1 : 2);          // q, k or v head
+    const int hcol = kind == 0 ? n0 : (kind == 1 ? n0 - g.n_q : n0 - g.n_q - g.n_kv);
+    // lanes 0..31 take one row, lanes 32..63 the next; a lane the columns (2j, 2j+1) and their partners
+    // (64 + 2j, 64 + 2j + 1): 4-byte stores, and the table entries of four row pairs are requested together
+    const int my_row = m0 + wave * 32 + (lane & 31);
+    const bool my_ok = my_row < M;
+    const int my_pos = my_ok ? g.rope_pos[my_row] : 0;
+    const int64_t my_slot = (my_ok && kind != 0) ? g.rope_slot[my_row] : 0;
+    const float qs = kind == 0 ? g.q_scale : 1.0f;
+    const int j2 = 2 * (lane & 31), half = lane >> 5;
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    for (int r0 = 0; r0 < 32; r0 += 8) {
+      if (m0 + wave * 32 + r0 >= M) break;
+      float4 cs[4];
+      int pos[4];
+      int64_t slot[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int rr = r0 + 2 * i + half;
+        pos[i] = __shfl(my_pos, rr, 64);
+        slot[i] = ((int64_t)__shfl((int)(my_slot >> 32), rr, 64) << 32) | (uint32_t)__shfl((int)my_slot, rr, 64);
+        cs[i] = make_float4(1.f, 0.f, 1.f, 0.f);
+        if (kind != 2) cs[i] = *reinterpret_cast<const float4 *>(g.rope_table + (int64_t)pos[i] * 64 + j2);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int rr = r0 + 2 * i + half, row = m0 + wave * 32 + rr;
+        if (row >= M) continue;
+        const float2 u = *reinterpret_cast<const float2 *>(ys + (wave * 32 + rr) * 128 + j2);
+        const float2 w = *reinterpret_cast<const float2 *>(ys + (wave * 32 + rr) * 128 + 64 + j2);
+        bf16 *dst = kind == 0 ? g.Qout + (int64_t)row * g.n_q + hcol
+                              : (kind == 1 ? g.cacheK : g.cacheV) + slot[i] * g.n_kv + hcol;
+        bf16x2_t lo, hi;
+        if (kind == 2) {
+          lo[0] = (bf16)u.x; lo[1] = (bf16)u.y;
+          hi[0] = (bf16)w.x; hi[1] = (bf16)w.y;
+        } else {
+          lo[0] = (bf16)((u.x * cs[i].x - w.x * cs[i].y) * qs);
+          lo[1] = (bf16)((u.y * cs[i].z - w.y * cs[i].w) * qs);
+          hi[0] = (bf16)((w.x * cs[i].x + u.x * cs[i].y) * qs);
+          hi[1] = (bf16)((w.y * cs[i].z + u.y * cs[i].w) * qs);
+        }
+        *reinterpret_cast<bf16x2_t *>(dst + j2) = lo;
+        *reinterpret_cast<bf16x2_t *>(dst + 64 + j2) = hi;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mi = 0; mi < TM; ++mi) {
 #pragma unroll
@@ -526,8 +589,17 @@ int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
   return s;
 }
 
+bool gemm_mfma_rope_supported(const GemmArgs &g, int head_dim) {
+  return head_dim == 128 && g.k_splits == 1 && g.lora_split == 0 && g.n_q % 128 == 0 && g.n_kv % 128 == 0 &&
+         g.N == g.n_q + 2 * g.n_kv && g.M > 4 * 128;
+}
+
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
+  if (epi == GEMM_EPI_ROPE) {
+    launch_cfg<128, 128, 64, 64, GEMM_EPI_ROPE, 2, true>(g, s);
+    return;
+  }
   if (epi == GEMM_EPI_PARTIAL) {
     if (g.tile_hint == 2) launch_cfg<256, 128, 128, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (g.tile_hint == 3) launch_cfg<256, 256, 64, 128, GEMM_EPI_PARTIAL, 1>(g, s);

@@ -4,7 +4,7 @@
 
 namespace alora {
 
-enum GemmEpi { GEMM_EPI_PARTIAL = 0, GEMM_EPI_BF16 = 1, GEMM_EPI_SWIGLU = 2 };
+enum GemmEpi { GEMM_EPI_PARTIAL = 0, GEMM_EPI_BF16 = 1, GEMM_EPI_SWIGLU = 2, GEMM_EPI_ROPE = 3 };
 
 // C[M,N] = A[M,K] B[N,K]^T, bf16 operands, fp32 accumulation.
 struct GemmArgs {
@@ -28,7 +28,16 @@ struct GemmArgs {
   const bf16 *Bq, *Bk, *Bv;
   int n_q, n_kv;
   const int32_t *row_adapter;  // [M]: adapter id of adapted rows, -1 otherwise
+  // ROPE epilogue (the QKV projection with an unsplit reduction and head_dim = 128 = the column tile): q and k
+  // heads are rotated (Eq.3's K_t before it is appended) and every head goes where the rotary kernel would have
+  // put it -- Q [M, n_q], the cache rows rope_slot[row] of K and V -- without the fp32 round trip through memory
+  const int32_t *rope_pos;     // [M] absolute positions
+  const int64_t *rope_slot;    // [M] pool rows
+  const float2 *rope_table;    // [positions, 64] (cos, sin)
+  float q_scale;               // multiplies the rotated queries
+  bf16 *Qout, *cacheK, *cacheV;
 };
+bool gemm_mfma_rope_supported(const GemmArgs &g, int head_dim);
 
 // Row preparation: metadata, RMSNorm, t = s_a * A_a x_hat as bf16 (hi, lo) pairs.
 struct PrepArgs {
