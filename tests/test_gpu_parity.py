@@ -526,14 +526,17 @@ def test_kernel_options_do_not_change_results(ab, opts):
         c.close()
 
 
-def test_rotation_in_the_projection_epilogue_gives_the_same_bits(ab):
+@pytest.mark.parametrize("fold", [0, 1])
+def test_rotation_in_the_projection_epilogue_gives_the_same_bits(ab, fold):
     """With many rows the QKV projection rotates and appends in its own epilogue (option rope_fuse, default
-    on); the separate rotary kernel must produce the same Q, cache rows and outputs bit for bit."""
+    on); the separate rotary kernel must produce the same Q, cache rows and outputs bit for bit (also when
+    the queries are premultiplied for the folded softmax)."""
     case = H.make_case(SMALL_BF16, [300, 0, 64], [330, 290, 77], [310, 0, 100], [1, 2, -1], seed=708)
     res = []
     for fuse in (1, 0):
         c = ab.Context(0)
         try:
+            c.set_option("attn_fold", fold)
             c.set_option("rope_fuse", fuse)
             out, cache = check_case(ab, c, case)
             res.append((out.clone(), cache.k.clone(), cache.v.clone()))
