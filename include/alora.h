@@ -149,7 +149,10 @@ const char *alora_status_string(alora_status s);
  * bf16 and the score accumulators start at minus the row's reference exponent, which takes the
  * scaling and the subtraction off the vector ALU (about 15 % less kernel time on long uniform
  * batches).  The same softmax of Eq.1; the queries are rounded at a different point, so single
- * elements differ from attn_fold = 0 within the bf16 tolerance.  "rope_fuse": 1 (default) / 0: with more than 512 rows, an unsplit reduction and
+ * elements differ from attn_fold = 0 within the bf16 tolerance.  "attn_partials16": 1 (default) / 0: when prefill attention is split over
+ * the keys, the partial results travel as compact records (accumulators scaled to [-1, 1] as fp16 plus three fp32
+ * scalars, 272 bytes) instead of fp32 records (520 bytes); they are most of what a short call writes and reads.
+ * "rope_fuse": 1 (default) / 0: with more than 512 rows, an unsplit reduction and
  * head size 128 the QKV projection rotates q and k and appends k and v in its own epilogue instead
  * of handing the fp32 projection to a separate kernel (same bits either way).  "profile": 0/1, see alora_profile_read.  Unknown key or bad
  * value: ALORA_EINVAL. */

@@ -64,6 +64,7 @@ struct alora_ctx {
   int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
   int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
   int opt_attn_pipeline = 1;     // 0 = software-pipelined attention kernel, 1 = the unpipelined one
+  int opt_attn_partials16 = 1;   // split prefill attention (MFMA path): compact partial records
   int opt_rope_fuse = 1;         // rotation + cache append in the epilogue of the QKV projection where the shape allows
   int opt_attn_fold = 0;         // 1 = unpipelined kernel takes prescaled queries and starts its score accumulators at -m_ref
   int n_cu = 256;
@@ -414,6 +415,9 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
                           (T *)cache->k, (T *)cache->v, s);
   }
   const bool direct = w.attn_mfma && std::is_same<T, bf16>::value && n_splits == 1;
+  // split prefill attention on the MFMA path: partial results travel in the compact record
+  const bool compact16 = w.attn_mfma && std::is_same<T, bf16>::value && !direct && ctx->opt_attn_partials16 &&
+                         attn_prefill_mfma_compact(w.attn_waves, attn_schedule);
   {
     ProfScope p(ctx, decode ? K_ATTN_DECODE : K_ATTN_PREFILL, s);
     if (w.attn_mfma && std::is_same<T, bf16>::value) {
@@ -426,6 +430,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.lazy = (float)ctx->opt_attn_lazy;
       a.q_prescaled = q_scale != 1.0f;
       a.partials = direct ? nullptr : w.partials;
+      a.compact = compact16 ? 1 : 0;
       a.out = direct ? (bf16 *)out : nullptr;
       // the kernels' fast tile loads use 32-bit byte offsets inside one sequence's rows; shared prefixes and
       // (absurdly) long sequences take the variant with full address arithmetic
@@ -450,7 +455,8 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
   }
   if (!direct) {
     ProfScope p(ctx, K_ATTN_MERGE, s);
-    launch_attn_merge<T>(w.partials, L, pl.T, n_splits, out, s);
+    if (compact16) launch_attn_merge16(w.partials, L, pl.T, n_splits, (bf16 *)out, s);
+    else launch_attn_merge<T>(w.partials, L, pl.T, n_splits, out, s);
   }
 }
 
@@ -927,6 +933,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "attn_lazy")) {
     if (value < 0 || value > 16) return fail(ctx, ALORA_EINVAL, "attn_lazy must be in [0, 16]");
     ctx->opt_attn_lazy = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "attn_partials16")) {
+    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "attn_partials16 must be 0 or 1");
+    ctx->opt_attn_partials16 = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "rope_fuse")) {

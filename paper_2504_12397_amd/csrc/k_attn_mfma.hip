@@ -401,6 +401,37 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
           w.y = pack_bf16x2(o[cb][nb][4 * v4 + 2] * inv, o[cb][nb][4 * v4 + 3] * inv);
           *reinterpret_cast<uint2 *>(op + col) = w;
         }
+    } else if (a.compact) {
+      // compact partial record (ATTN_REC16 bytes): the unnormalised accumulators of the row divided by their
+      // largest magnitude, as 128 fp16 values (relative precision 2^-11, finer than the bf16 the merged result
+      // is rounded to; no overflow whatever the values), then that magnitude, the reference and the row sum.
+      // Half the bytes of the fp32 record -- and these records are most of what a short call writes and reads.
+      float amax = 0.f;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) amax = fmaxf(amax, fabsf(o[cb][nb][v]));
+      amax = max_with_other_half(amax);
+      const float rs = amax > 0.f ? 1.0f / amax : 0.f;
+      char *rec = reinterpret_cast<char *>(a.partials) +
+                  ((row * a.n_q_heads + head[nb]) * a.n_splits + split) * (int64_t)ATTN_REC16;
+      typedef __attribute__((__vector_size__(4 * sizeof(_Float16)))) _Float16 half4_t;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const int col = cb * 32 + 8 * v4 + 4 * kh;
+          half4_t hv;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) hv[i] = (_Float16)(o[cb][nb][4 * v4 + i] * rs);
+          *reinterpret_cast<half4_t *>(rec + col * 2) = hv;
+        }
+      if (kh == 0) {
+        float *tail = reinterpret_cast<float *>(rec + 2 * H);
+        tail[0] = (l_tot == 0.f || m_ref == -INFINITY) ? -INFINITY : m_ref * LN2;
+        tail[1] = l_tot;
+        tail[2] = amax;
+      }
     } else {
       float *pp = a.partials + ((row * a.n_q_heads + head[nb]) * a.n_splits + split) * (H + 2);
 #pragma unroll
@@ -769,6 +800,59 @@ static void launch_attn_pipe(const AttnArgs &a, int n_work, int G, hipStream_t s
     default: break;
   }
 }
+
+// Log-sum-exp merge of the compact partial records (Eq.1 over the union of the key splits): one wave per
+// (row, head), a lane two columns.  out = sum_i w_i amax_i u_i / sum_i w_i l_i with w_i = exp(m_i - max m).
+__global__ __launch_bounds__(256) void attn_merge16_kernel(const char *__restrict__ part, int n_splits, int64_t n_rh,
+                                                           bf16 *__restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t rh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (rh >= n_rh) return;
+  const char *p = part + rh * n_splits * (int64_t)ATTN_REC16;
+  typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 half2_t;
+  float M = -INFINITY;
+  for (int s0 = 0; s0 < n_splits; s0 += 64) {
+    const int sp = s0 + lane;
+    M = fmaxf(M, sp < n_splits ? *reinterpret_cast<const float *>(p + sp * (int64_t)ATTN_REC16 + 256) : -INFINITY);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+  float denom = 0.f, a0 = 0.f, a1 = 0.f;
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {       // eight records requested together
+    float ms[8], ls[8], am[8];
+    half2_t u[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const char *r = p + min(s0 + i, n_splits - 1) * (int64_t)ATTN_REC16;
+      const float *tail = reinterpret_cast<const float *>(r + 256);
+      ms[i] = tail[0]; ls[i] = tail[1]; am[i] = tail[2];
+      u[i] = *reinterpret_cast<const half2_t *>(r + lane * 4);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float w = (s0 + i >= n_splits || ms[i] == -INFINITY) ? 0.f : __expf(ms[i] - M);
+      denom += w * ls[i];
+      a0 += w * am[i] * (float)u[i][0];
+      a1 += w * am[i] * (float)u[i][1];
+    }
+  }
+  const float inv = 1.0f / denom;
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+  bf16x2_t ov;
+  ov[0] = (bf16)(a0 * inv);
+  ov[1] = (bf16)(a1 * inv);
+  *reinterpret_cast<bf16x2_t *>(out + rh * 128 + lane * 2) = ov;
+}
+
+void launch_attn_merge16(const float *partials, const LayerDims &L, int T_rows, int n_splits, bf16 *out, hipStream_t s) {
+  if (T_rows == 0) return;
+  const int64_t n_rh = (int64_t)T_rows * L.n_q_heads;
+  hipLaunchKernelGGL(attn_merge16_kernel, dim3((unsigned)((n_rh + 3) / 4)), dim3(256), 0, s, (const char *)partials,
+                     n_splits, n_rh, out);
+}
+
+// compact records are written by the unpipelined kernels only
+bool attn_prefill_mfma_compact(int waves, int schedule) { return !(schedule == ATTN_SCHED_PIPELINED && waves == 8); }
 
 void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, int schedule, bool prefix,
                               hipStream_t s) {

@@ -72,9 +72,13 @@ struct AttnArgs {
   int q_prescaled;          // Q already carries sm_scale * log2(e): scores leave the MFMA in the exp2 domain
   float lazy;               // the running maximum moves only when a block exceeds it by more than this (log2 units)
   float *partials;          // [T, n_q_heads, n_splits, head_dim + 2] (acc, max, sum), used when out == nullptr
+  int compact;              // partial records in the compact form (ATTN_REC16 bytes each) that launch_attn_merge16 reads
   bf16 *out;                // [T, n_q] final output, only with n_splits == 1
 };
+constexpr int ATTN_REC16 = 272;      // 128 fp16 + (reference, row sum, scale) as fp32 + 4 bytes of padding
 bool attn_prefill_mfma_supported(const LayerDims &L);
+bool attn_prefill_mfma_compact(int waves, int schedule);
+void launch_attn_merge16(const float *partials, const LayerDims &L, int T_rows, int n_splits, bf16 *out, hipStream_t s);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
 // How one workgroup orders its work: every wave runs K Q^T, softmax, P V one after the other and the
 // overlap of matrix and vector work is left to the two waves that share a SIMD (SIMPLE), or each wave
