@@ -84,10 +84,10 @@ def algorithmic_work(batch, shape, n_layers=1):
 # profiles/*.md.  bench.py cannot read hardware counters itself, so these are the recorded values for the
 # kernels as committed; a workload/kernel pair that has not been profiled reports null.
 MEASURED_TRAFFIC_KIB = {
-    ("c2", "qkv_gemm"): 66847 + 18432, ("c2", "attn_prefill"): 33994 + 35511, ("c2", "prep_rows"): 8386 + 2149,
-    ("c3", "qkv_gemm"): 706482 + 53496, ("c3", "attn_prefill"): 375153 + 35664,
-    ("c4", "attn_decode"): 4337126 + 4352, ("c4", "qkv_gemm"): 55116 + 7680,
-    ("c5", "attn_prefill"): 139979 + 35624, ("c5", "gate_up"): 237696 + 3584,
+    ("c2", "qkv_gemm"): 66849 + 18432, ("c2", "attn_prefill"): 34001 + 18435, ("c2", "prep_rows"): 8386 + 2149,
+    ("c3", "qkv_gemm"): 691256 + 53496, ("c3", "attn_prefill"): 375336 + 35666,
+    ("c4", "attn_decode"): 4337111 + 4352, ("c4", "qkv_gemm"): 55118 + 7680,
+    ("c5", "attn_prefill"): 139985 + 18440, ("c5", "gate_up"): 237711 + 3584,
 }
 
 
