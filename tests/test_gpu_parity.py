@@ -547,6 +547,23 @@ def test_rotation_in_the_projection_epilogue_gives_the_same_bits(ab, fold):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
+def test_many_short_sequences(ab, ctx):
+    """More sequences than a workgroup has threads (600): the per-sequence loops of the metadata and work-list
+    code wrap around; prefill with one to three new tokens each, then a decode step for all of them."""
+    rs = np.random.RandomState(77)
+    n = 600
+    P = [int(v) for v in rs.randint(0, 40, n)]
+    S = [int(v) for v in rs.randint(1, 4, n)]
+    k = [int(P[i] + rs.randint(-3, 3)) if rs.rand() < 0.7 else 0 for i in range(n)]
+    k = [max(0, v) for v in k]
+    a = [int(v) for v in rs.randint(-1, 3, n)]
+    case = H.make_case(SMALL_BF16, P, S, k, a, seed=709, prefix="random")
+    check_case(ab, ctx, case)
+    Pd = [max(1, p) for p in P]
+    dcase = H.make_case(SMALL_BF16, Pd, [1] * n, k, a, seed=710, prefix="random")
+    check_case(ab, ctx, dcase, decode=True)
+
+
 def test_long_positions_rotary_accuracy(ab, ctx):
     """Positions near 33k: the rotary table is evaluated in double, so late positions stay accurate."""
     shape = SMALL_BF16
