@@ -26,8 +26,12 @@ state and the cached keys/values -- are rounded to that dtype here; every produc
 is exact float64 and the attention output is left unrounded.
 
 Pins: every function here is pinned by tests/test_oracle_pins.py (closed forms, library
-special cases, a pure-loop brute force written separately, Proposition-1 invariants, a
-hand-worked two-token example under tests/golden/).  No function is "parity unpinned".
+special cases, a pure-loop brute force written separately, Proposition-1 invariants, two
+hand-worked examples under tests/golden/: a two-token attention block, and the storage
+points -- which tensor is rounded to bf16, and where -- of the block, the layer tail and the
+output head).  `act_dtype="f64"` switches the activation rounding off (the cache keeps its
+own dtype); the parity tests report the GPU's error against that reading as well.  No
+function is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -267,13 +271,13 @@ def ref_cached(layer: Layer, cache_K: np.ndarray, cache_V: np.ndarray, P: int, x
 
 def ref_prefill_batch(layer: Layer, caches: List[Tuple[np.ndarray, np.ndarray]], P: Sequence[int],
                       x_packed: np.ndarray, cu_seqlens: Sequence[int], k: Sequence[int],
-                      adapter: Sequence[int], cache_dtype: str = "f64"):
+                      adapter: Sequence[int], cache_dtype: str = "f64", act_dtype: Optional[str] = None):
     """A packed batch is a loop over its sequences: they do not interact.  Returns the packed
     O [T, N_q] and, per sequence, its new cache rows."""
     outs, new_rows = [], []
     for b in range(len(P)):
         xs = x_packed[cu_seqlens[b]:cu_seqlens[b + 1]]
-        o, kn, vn = ref_cached(layer, caches[b][0], caches[b][1], P[b], xs, k[b], adapter[b], cache_dtype)
+        o, kn, vn = ref_cached(layer, caches[b][0], caches[b][1], P[b], xs, k[b], adapter[b], cache_dtype, act_dtype)
         outs.append(o)
         new_rows.append((kn, vn))
     return np.concatenate(outs, axis=0), new_rows
@@ -315,28 +319,30 @@ def layer_tail(layer: Layer, x: np.ndarray, attn: np.ndarray, act_dtype: str = "
     return h + gated_linear(act, layer.W_down, pick(layer.A_down), pick(layer.B_down), s, m)
 
 
-def ref_stack_full(layers: List[Layer], x_all: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64"):
+def ref_stack_full(layers: List[Layer], x_all: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64",
+                   act_dtype: Optional[str] = None):
     """All layers on a whole sequence.  Returns the final hidden states [L, d] and the list of
     per-layer caches (K, V)."""
     x = np.asarray(x_all, dtype=F64)
     caches = []
     for layer in layers:
-        o, Kc, Vc = ref_full(layer, x, k, adapter, cache_dtype)
+        o, Kc, Vc = ref_full(layer, x, k, adapter, cache_dtype, act_dtype)
         caches.append((Kc, Vc))
-        x = layer_tail(layer, x, o, cache_dtype, np.arange(x.shape[0]), k, adapter)
+        x = layer_tail(layer, x, o, act_dtype or cache_dtype, np.arange(x.shape[0]), k, adapter)
     return x, caches
 
 
 def ref_stack_cached(layers: List[Layer], caches: List[Tuple[np.ndarray, np.ndarray]], P: int,
-                     x_suffix: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64"):
+                     x_suffix: np.ndarray, k: int, adapter: int, cache_dtype: str = "f64",
+                     act_dtype: Optional[str] = None):
     """All layers on the new rows only, each layer reading its own prefix cache.  Returns the
     final hidden states of the new rows [S, d] and the new cache rows per layer."""
     x = np.asarray(x_suffix, dtype=F64)
     new_rows = []
     for layer, (cK, cV) in zip(layers, caches):
-        o, kn, vn = ref_cached(layer, cK, cV, P, x, k, adapter, cache_dtype)
+        o, kn, vn = ref_cached(layer, cK, cV, P, x, k, adapter, cache_dtype, act_dtype)
         new_rows.append((kn, vn))
-        x = layer_tail(layer, x, o, cache_dtype, P + np.arange(x.shape[0]), k, adapter)
+        x = layer_tail(layer, x, o, act_dtype or cache_dtype, P + np.arange(x.shape[0]), k, adapter)
     return x, new_rows
 
 

@@ -382,6 +382,95 @@ def test_two_token_example_worked_by_hand():
     assert np.allclose(K, [[1.0, 0.0], [-s, c]], rtol=1e-14, atol=1e-15)
 
 
+# ---------------------------------------------------------------------------- storage points (bf16 activations)
+A_BF16, B_BF16 = 0.84765625, 1.1328125          # (3, 4)/sqrt(12.5) rounded to bf16 by hand, see the golden file
+
+
+def _storage_layer():
+    """d = 2, one head of width 2, W_q = I, W_k = 2 I, W_v = [[1, 1], [1, -1]], unit gains, eps = 0, and a
+    one-unit MLP; tests/golden/bf16_storage_points.txt works the numbers by hand."""
+    return orc.Layer(1, 1, 2,
+                     W_qkv=np.array([[1.0, 0.0], [0.0, 1.0], [2.0, 0.0], [0.0, 2.0], [1.0, 1.0], [1.0, -1.0]]),
+                     A=np.zeros((1, 3, 1, 2)), B_q=np.zeros((1, 2, 1)), B_k=np.zeros((1, 2, 1)), B_v=np.zeros((1, 2, 1)),
+                     scale=[1.0], rms_gain=np.ones(2), rms_eps=0.0,
+                     W_o=np.zeros((2, 2)), rms2_gain=np.ones(2), W_gate=np.array([[1.0, 1.0]]),
+                     W_up=np.array([[1.0, 0.0]]), W_down=np.array([[1.0], [0.0]]))
+
+
+def _two_token_closed_form(a, b):
+    c, s, r2 = math.cos(1.0), math.sin(1.0), math.sqrt(2.0)
+    e0 = 2 * (2 * a * b * c + (b * b - a * a) * s) / r2
+    e1 = 2 * (a * a + b * b) / r2
+    p1 = 1 / (1 + math.exp(e0 - e1))
+    K = np.array([[2 * a, 2 * b], [2 * (b * c - a * s), 2 * (a * c + b * s)]])
+    V = np.array([[a + b, a - b], [a + b, b - a]])
+    o = np.array([[a + b, a - b], [a + b, (a - b) * (1 - 2 * p1)]])
+    return o, K, V
+
+
+def test_normalised_rows_are_rounded_to_bf16_before_the_projections():
+    """tests/golden/bf16_storage_points.txt.  Fails if the rounding of the normalised hidden state is
+    dropped, applied to x instead, or applied to the projections instead."""
+    assert "0.84765625" in open(os.path.join(GOLDEN, "bf16_storage_points.txt")).read()
+    L = _storage_layer()
+    x = np.array([[3.0, 4.0], [4.0, 3.0]])
+    # activations bf16, cache unrounded: q, k and v are exact products of the ROUNDED normalised rows
+    o, K, V = orc.ref_full(L, x, 0, -1, cache_dtype="f64", act_dtype="bf16")
+    wo, wK, wV = _two_token_closed_form(A_BF16, B_BF16)
+    assert np.allclose(o, wo, rtol=1e-13, atol=1e-15) and np.array_equal(K[0], wK[0]) and np.array_equal(V, wV)
+    assert np.allclose(K[1], wK[1], rtol=1e-14)
+    # no rounding anywhere: the closed forms in (3, 4)/sqrt(12.5)
+    r = math.sqrt(12.5)
+    o64, K64, V64 = orc.ref_full(L, x, 0, -1, cache_dtype="f64", act_dtype="f64")
+    wo, wK, wV = _two_token_closed_form(3 / r, 4 / r)
+    assert np.allclose(o64, wo, rtol=1e-13) and np.allclose(K64, wK, rtol=1e-14) and np.allclose(V64, wV, rtol=1e-13)
+    assert abs(o64[1, 1] - o[1, 1]) > 1e-4 and abs(V64[0, 0] - V[0, 0]) > 5e-4      # the two readings differ
+    # bf16 cache on top: a + b = 1.98046875 is a tie and is stored as 254/128; without the rounding of the
+    # normalised row (or with the projections rounded instead) the cache would hold 253/128
+    _, Kc, Vc = orc.ref_full(L, x, 0, -1, cache_dtype="bf16")
+    assert Vc[0, 0] == 1.984375 and Vc[1, 0] == 1.984375 and Kc[0, 0] == 1.6953125 and Kc[0, 1] == 2.265625
+    _, _, Vu = orc.ref_full(L, x, 0, -1, cache_dtype="bf16", act_dtype="f64")
+    assert Vu[0, 0] == 1.9765625
+    # the cached method and the base-prefix helper round at the same point
+    oc, kn, vn = orc.ref_cached(L, Kc[:1], Vc[:1], 1, x[1:], 0, -1, "bf16")
+    assert vn[0, 0] == 1.984375 and np.array_equal(kn[0], Kc[1])
+    Kb, Vb = orc.base_kv(L, x, "bf16")
+    assert np.array_equal(Kb, Kc) and np.array_equal(Vb, Vc)
+    ob, _ = orc.ref_prefill_batch(L, [(Kc[:1], Vc[:1])], [1], x[1:], [0, 1], [0], [-1], "bf16")
+    assert np.array_equal(ob, oc)
+    ob64, _ = orc.ref_prefill_batch(L, [(Kc[:1], Vc[:1])], [1], x[1:], [0, 1], [0], [-1], "bf16", act_dtype="f64")
+    assert not np.array_equal(ob64, oc)
+
+
+def test_layer_tail_rounds_the_normalised_row_and_nothing_else():
+    """h = x = (3, 4) (W_o = 0): out = (3 + silu(g) u, 4) with g = a + b, u = a of the rounded normalised row.
+    Fails if layer_tail drops the rounding, rounds h instead of its normalised value, or rounds more."""
+    L = _storage_layer()
+    x, attn = np.array([[3.0, 4.0]]), np.array([[0.5, -2.0]])
+    silu = lambda z: z / (1 + math.exp(-z))
+    got = orc.layer_tail(L, x, attn, "bf16")
+    g, u = A_BF16 + B_BF16, A_BF16
+    assert g == 1.98046875
+    assert np.allclose(got, [[3 + silu(g) * u, 4.0]], rtol=1e-15)
+    r = math.sqrt(12.5)
+    got64 = orc.layer_tail(L, x, attn, "f64")
+    assert np.allclose(got64, [[3 + silu(7 / r) * 3 / r, 4.0]], rtol=1e-15)
+    assert abs(got64[0, 0] - got[0, 0]) > 5e-4
+    # through the stack functions: the activation dtype reaches the tail (one layer, one token: h = x)
+    out, caches = orc.ref_stack_full([L], x, 0, -1, "bf16")
+    assert np.allclose(out, [[3 + silu(g) * u, 4.0]], rtol=1e-15) and caches[0][1][0, 0] == 1.984375
+    out2, _ = orc.ref_stack_cached([L], [(np.zeros((0, 2)), np.zeros((0, 2)))], 0, x, 0, -1, "bf16")
+    assert np.array_equal(out2, out)
+    out64, _ = orc.ref_stack_full([L], x, 0, -1, "f64")
+    assert np.allclose(out64, [[3 + silu(7 / r) * 3 / r, 4.0]], rtol=1e-15)
+
+
+def test_lm_head_rounds_the_normalised_row():
+    x, W = np.array([[3.0, 4.0]]), np.array([[1.0, 1.0]])
+    assert orc.lm_head_logits(x, np.ones(2), 0.0, W, "bf16")[0, 0] == 1.98046875
+    assert math.isclose(orc.lm_head_logits(x, np.ones(2), 0.0, W, "f64")[0, 0], 7 / math.sqrt(12.5), rel_tol=1e-15)
+
+
 # ---------------------------------------------------------------------------- decoder-layer tail
 def test_layer_tail_against_library_ops():
     L = rand_layer(25, mlp=40)
