@@ -28,7 +28,10 @@
  *   - Calls are asynchronous on the given stream.  The library owns only its context
  *     (a workspace that grows on demand, staged copies of the small HOST arrays, a rotary
  *     table); it never frees or keeps caller memory.  One context per stream; a context
- *     is not thread-safe.
+ *     is not thread-safe.  When a call needs a larger workspace or a longer rotary table than
+ *     the context holds, the context synchronises the DEVICE, frees the old block and allocates
+ *     a new one before it enqueues anything (the first call of a given size, typically); calls
+ *     that fit are enqueued without any synchronisation or allocation.
  *   - Every argument is validated on the host before anything is launched.  On any error
  *     nothing has been enqueued, the cache and seq_len are untouched, and
  *     alora_last_error() describes the problem.
@@ -98,9 +101,11 @@ typedef struct {
 
 /* KV cache of one layer (Eq.3: the stored K_{1:t}, V_{1:t}).  A flat pool of token rows;
  * sequence b owns rows [seq_offset[b], seq_offset[b] + seq_capacity[b]); its row j holds
- * the key / value of absolute position j.  Keys are stored after rotation.
+ * the key / value of absolute position j.  Keys are stored after rotation.  The regions of the
+ * sequences of one call must not overlap, and no sequence may write into rows that any sequence of
+ * the call reads as its shared prefix (ALORA_ECAPACITY otherwise).
  *
- * Shared prefix (Section 3, third cache-reuse regime; Proposition 2 for N adapters on one
+ * Shared prefix (Section 2, "Cache reuse patterns", third regime; Proposition 2 for N adapters on one
  * context): when prefix_len is given, positions [0, prefix_len[b]) of sequence b are READ from
  * pool rows prefix_offset[b] + j -- one physical copy that any number of sequences may name, for
  * instance the rows of the base model's own sequence -- and only positions >= prefix_len[b] live
@@ -131,31 +136,51 @@ void alora_destroy(alora_ctx *ctx);
 const char *alora_last_error(const alora_ctx *ctx);
 const char *alora_status_string(alora_status s);
 
-/* Kernel selection and tuning knobs, by name.  "kernels": 0 = automatic (MFMA kernels
- * for bf16 where the shape allows, plain fp32-FMA kernels otherwise), 1 = force the plain
- * kernels (any dtype, any shape).  "kv_splits": 0 = automatic, n > 0 = split the key axis
- * of attention into n chunks.  "gemm_splits": 0 = automatic, n > 0 = split the reduction axis
- * of the QKV projection into n chunks (partial sums are added in a fixed order).  "gemm_tile": 0 = automatic, 1 = 128x128, 2 = 256x128,
- * 3 = 256x256, 4 = 128x64 block tiles (four waves), 5 / 6 = 128x128 with eight waves of 32x64 / 64x32 (the automatic
- * choice up to 512 / 128 rows; 1 and 4..6 also apply to the other linears of a stack).  "lora_split": 0 = automatic, 1 = always, 2 = never give the low-rank term of
- * the QKV projection workgroups (and a partial sum) of its own.  "attn_waves": 0 = automatic, 4 or 8 waves per workgroup
- * in the prefill attention kernel.  "attn_pipeline": 1 (default) = prefill attention kernel that
- * leaves the overlap of softmax and matrix work to the waves sharing a SIMD, 0 = the variant that
- * software-pipelines the two inside each wave.  "attn_lazy": 0..16 (default 3), the running row
- * maximum of the prefill attention kernels moves only when a block of scores exceeds it by more
- * than this many powers of two (0 = exact maximum; the softmax is the same either way, only the
- * scale of the intermediate probabilities changes).  "attn_fold": 0 (default) / 1, with
- * attn_pipeline = 1 only: the queries are multiplied by log2(e)/sqrt(h) before they are rounded to
- * bf16 and the score accumulators start at minus the row's reference exponent, which takes the
- * scaling and the subtraction off the vector ALU (about 15 % less kernel time on long uniform
- * batches).  The same softmax of Eq.1; the queries are rounded at a different point, so single
- * elements differ from attn_fold = 0 within the bf16 tolerance.  "attn_partials16": 1 (default) / 0: when prefill attention is split over
- * the keys, the partial results travel as compact records (accumulators scaled to [-1, 1] as fp16 plus three fp32
- * scalars, 272 bytes) instead of fp32 records (520 bytes); they are most of what a short call writes and reads.
- * "rope_fuse": 1 (default) / 0: with more than 512 rows, an unsplit reduction and
- * head size 128 the QKV projection rotates q and k and appends k and v in its own epilogue instead
- * of handing the fp32 projection to a separate kernel (same bits either way).  "profile": 0/1, see alora_profile_read.  Unknown key or bad
- * value: ALORA_EINVAL. */
+/* Kernel selection and tuning knobs, by name.  Unknown key or value out of range: ALORA_EINVAL.
+ * Every setting computes the same operation; defaults are what the benchmarks run.
+ *
+ *   "kernels"         0 (default): MFMA kernels for bf16 where the shape allows, plain fp32-FMA kernels
+ *                     otherwise.  1: force the plain kernels (any dtype, any shape).
+ *   "kv_splits"       0 (default): automatic.  n in 1..256: split the key axis of attention into n chunks
+ *                     (partial results are merged by log-sum-exp weights).
+ *   "gemm_splits"     0 (default): the reduction axis of every linear is cut into a number of equal segments
+ *                     fixed by the shape of its weight matrix.  n in 1..64: into n segments (where the
+ *                     reduction length allows; 1 = a single running sum).  See "Summation order" below.
+ *   "gemm_tile"       0 (default): automatic block shape.  1: 128x128, 2: 256x128, 3: 256x256, 4: 128x64
+ *                     (four waves); 5 / 6: 128x128 on eight waves of 32x64 / 64x32.  1 and 4..6 also apply to
+ *                     the other linears of a stack.  A tuning experiment: with a value other than 0 the
+ *                     summation-order guarantee below does not hold.
+ *   "lora_split"      0 (default): automatic.  1: always, 2: never give the low-rank term of the QKV
+ *                     projection workgroups (and a partial sum) of its own.
+ *   "rope_fuse"       1 (default): where the shape allows (more than 256 rows, head size 128) the QKV
+ *                     projection rotates q and k and appends k and v in its own epilogue.  0: a separate
+ *                     kernel does, from the fp32 projection.  Same bits either way.
+ *   "attn_waves"      0 (default) / 8: eight waves per workgroup in the prefill attention kernel.  4: four.
+ *   "attn_pipeline"   1 (default): prefill attention kernel that leaves the overlap of softmax and matrix
+ *                     work to the waves sharing a SIMD.  0: the variant that software-pipelines the two
+ *                     inside each wave.
+ *   "attn_lazy"       0..16 (default 3): the running row maximum of the prefill attention kernels moves only
+ *                     when a block of scores exceeds it by more than this many powers of two (0 = exact
+ *                     maximum).  The softmax is the same; only the scale of the intermediate probabilities
+ *                     changes.
+ *   "attn_fold"       0 (default) / 1, with attn_pipeline = 1 only: the queries are multiplied by
+ *                     log2(e)/sqrt(h) before they are rounded to bf16 and the score accumulators start at
+ *                     minus the row's reference exponent.  The same softmax of Eq.1; the queries are rounded
+ *                     at a different point, so single elements differ within the bf16 tolerance.
+ *   "attn_partials16" 1 (default): when prefill attention is split over the keys, the partial results travel
+ *                     as compact records (accumulators scaled to [-1, 1] as fp16 plus three fp32 scalars,
+ *                     272 bytes).  0: fp32 records (520 bytes).
+ *   "profile"         0 (default) / 1: see alora_profile_read.
+ *
+ * Summation order (Proposition 1 in its strong form: rows before the invocation index are the base model's
+ * rows).  With "gemm_tile" = 0 the key and value rows a call appends are a function of the row's own input and
+ * position alone: bit-identical whether the row came in a long prefill, a short one, a decode step, alone or
+ * in a mixed batch, with or without an adapter active on OTHER rows -- every linear adds the products of a row
+ * in one fixed order (segments fixed by the weight shape, each summed from zero, the sums added in ascending
+ * order).  Rows before k_b of an adapter call are therefore bitwise the rows a base-only call writes.  What
+ * is NOT bit-stable across differently shaped calls: attention outputs (the key axis is split by a heuristic
+ * that looks at the whole batch, and prefill and decode attention are different kernels), and with them the
+ * hidden states and cache rows of layers after the first in alora_stack_prefill; those agree to rounding. */
 alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
 
 /* Per-kernel timing.  With option "profile" = 1 the library brackets every kernel it launches
@@ -166,13 +191,6 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value);
  * clears the totals. */
 alora_status alora_profile_read(alora_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 alora_status alora_profile_reset(alora_ctx *ctx);
-
-/* Measured ceilings of this machine, to price the kernels next to the published peaks (for the
- * callers that report roofline fractions): kind 0 = bf16 MFMA TFLOP/s of a register-only loop on
- * constant operands, kind 1 = HBM read GB/s of a 4 GiB stream (allocated and freed inside the
- * call), kind 2 = the MFMA loop on pseudo-random operands (the sustained clock depends on how much
- * the operand bits toggle, so this is what a kernel on real data can reach).  Synchronous. */
-alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value);
 
 /* Adapter-activated prefill (Section 2, Eq.6; cost model of Proposition 2: only the T new
  * rows are projected, and each attends over its sequence's cached-plus-new rows).
@@ -211,8 +229,8 @@ alora_status alora_decode_steps(alora_ctx *ctx, const alora_layer_desc *layer, a
 /* First-token pass through a stack of decoder layers (Proposition 2: the attention block as
  * in alora_prefill, then the per-token output projection and SwiGLU MLP with residuals -- with
  * the base weights, or gated like q, k, v where the layer carries adapters for them -- layer
- * after layer).  layers[l] must all have the same shape and dtype and carry W_o / rms2_gain /
- * W_gate / W_up / W_down.  The adapter scales s_a are taken from layers[0].scale for the whole
+ * after layer).  layers[l] must all have the same shape, dtype, rms_eps and rope_theta and carry
+ * W_o / rms2_gain / W_gate / W_up / W_down.  The adapter scales s_a are taken from layers[0].scale for the whole
  * stack.  caches[l] is layer l's cache; the sequence layout (seq_offset, seq_capacity, seq_len,
  * prefixes) is read from caches[0] and applies to every layer; only caches[0].seq_len is updated.
  *   x        DEVICE [T, d]  input hidden states of the new tokens (not modified)

@@ -18,7 +18,7 @@ ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDT
 ALORA_F32, ALORA_BF16 = 0, 1
 
 EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
-           "alora_profile_read", "alora_profile_reset", "alora_measure_ceiling", "alora_prefill", "alora_decode", "alora_decode_steps", "alora_stack_prefill", "alora_lm_head"]
+           "alora_profile_read", "alora_profile_reset", "alora_prefill", "alora_decode", "alora_decode_steps", "alora_stack_prefill", "alora_lm_head"]
 KERNELS = ["lm_head", "lm_argmax", "prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
            "mlp_norm", "gate_up", "silu_mul", "down_proj"]
 
@@ -61,8 +61,6 @@ def load_library() -> C.CDLL:
     lib.alora_profile_read.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.alora_profile_reset.restype = C.c_int
     lib.alora_profile_reset.argtypes = [C.c_void_p]
-    lib.alora_measure_ceiling.restype = C.c_int
-    lib.alora_measure_ceiling.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
     i32p = C.POINTER(C.c_int32)
     lib.alora_prefill.restype = C.c_int
     lib.alora_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
@@ -213,12 +211,6 @@ class Context:
 
     def set_option(self, key: str, value: int):
         self._check(_lib.alora_set_option(self._h, key.encode(), int(value)))
-
-    def measure_ceiling(self, kind: int) -> float:
-        """kind 0: bf16 MFMA TFLOP/s of a register-only loop; kind 1: HBM read GB/s of a 4 GiB stream."""
-        v = C.c_double()
-        self._check(_lib.alora_measure_ceiling(self._h, int(kind), C.byref(v)))
-        return v.value
 
     def profile_reset(self):
         self._check(_lib.alora_profile_reset(self._h))

@@ -272,6 +272,41 @@ alora_status check_batch(alora_ctx *ctx, const alora_layer_desc *ly, const alora
     pl->max_len = std::max(pl->max_len, (int)grown);
   }
   pl->T = cu[B];
+  // The regions the sequences own must be disjoint, and nobody may write where somebody reads a shared prefix:
+  // the kernels would write those cache rows concurrently, silently.
+  {
+    struct Iv { int64_t lo, hi; int b; };
+    std::vector<Iv> own, wr, pf;
+    for (int b = 0; b < B; ++b) {
+      const SeqMeta &m = pl->seqs[b];
+      const int64_t off = cache->seq_offset[b];
+      if (cache->seq_capacity[b] > 0) own.push_back(Iv{off, off + cache->seq_capacity[b], b});
+      if (m.n_new > 0) {
+        const int64_t w0 = off + (m.P - m.prefix_len);
+        wr.push_back(Iv{w0, w0 + (int64_t)m.n_new * n_steps, b});
+      }
+      if (m.prefix_len > 0) pf.push_back(Iv{m.prefix_off, m.prefix_off + m.prefix_len, b});
+    }
+    auto by_lo = [](const Iv &x, const Iv &y) { return x.lo < y.lo; };
+    std::sort(own.begin(), own.end(), by_lo);
+    for (size_t i = 1; i < own.size(); ++i)
+      if (own[i].lo < own[i - 1].hi)
+        return fail(ctx, ALORA_ECAPACITY, "sequences %d and %d own overlapping cache rows [%lld, %lld) and [%lld, %lld)",
+                    own[i - 1].b, own[i].b, (long long)own[i - 1].lo, (long long)own[i - 1].hi, (long long)own[i].lo,
+                    (long long)own[i].hi);
+    if (!pf.empty() && !wr.empty()) {
+      std::sort(wr.begin(), wr.end(), by_lo);       // disjoint (inside disjoint regions), so sorted by hi as well
+      std::sort(pf.begin(), pf.end(), by_lo);
+      size_t j = 0;
+      for (const Iv &p : pf) {
+        while (j < wr.size() && wr[j].hi <= p.lo) ++j;     // prefixes come in ascending lo: skipped writes end before all later ones too
+        for (size_t q = j; q < wr.size() && wr[q].lo < p.hi; ++q)
+          if (wr[q].hi > p.lo)
+            return fail(ctx, ALORA_ECAPACITY, "sequence %d would write rows [%lld, %lld) that sequence %d reads as its shared prefix",
+                        wr[q].b, (long long)wr[q].lo, (long long)wr[q].hi, p.b);
+      }
+    }
+  }
   return ALORA_OK;
 }
 
@@ -294,7 +329,8 @@ struct Workspace {
   void *attn, *h1, *hn, *gate, *up, *xa, *xb;
   size_t bytes;
   bool mfma = false;
-  int k_splits = 1;
+  int k_splits = 1;                  // workgroups per output tile along the reduction axis of the QKV projection
+  int k_segments = 1;                // its fixed reduction segments (from the weight shape alone)
   int lora_split = 0;                // the low-rank term of the QKV projection has a partial of its own
   bool attn_mfma = false;
   bool decode_mfma = false;
@@ -385,6 +421,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.B = (const bf16 *)ly->W_qkv; g.ldb = L.d;
       g.M = pl.T; g.N = L.n_qkv; g.K = L.d;
       g.k_splits = w.k_splits;
+      g.k_segments = w.k_segments;
       g.lora_split = (pl.any_adapter && w.lora_split) ? 1 : 0;
       g.tile_hint = ctx->opt_gemm_tile;
       g.Cpart = w.Y;
@@ -478,6 +515,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     int splits = gemm_mfma_pick_splits(T_rows, g.N, K, ctx->n_cu);
     while (splits > 1 && (size_t)splits * T_rows * g.N > w.y_floats) splits /= 2;
     g.k_splits = splits;
+    g.k_segments = splits;
     g.Cpart = w.Y;
     launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
     launch_tlow_select(w.Y, splits, T_rows, n_ad, parts, r, w.rm.adapter, w.scale_dev, (bf16 *)w.tlow, s);
@@ -487,6 +525,12 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     g.Bq = (const bf16 *)B0; g.Bk = (const bf16 *)B1; g.Bv = nullptr;
     g.n_q = width; g.n_kv = parts == 1 ? 0 : width;
     g.row_adapter = w.rm.adapter;
+  };
+  // reduction segments of a linear [N, K]: fixed by the weight shape (or by the gemm_splits option), so that a
+  // row's result does not depend on the number of rows in the call
+  auto segments_of = [&](int N, int K) {
+    if (ctx->opt_gemm_splits > 0) return K % (64 * ctx->opt_gemm_splits) == 0 ? ctx->opt_gemm_splits : 1;
+    return gemm_mfma_fixed_segments(N, K, ctx->n_cu);
   };
   // C = A W^T (+ R), with the gated low-rank term of (Al, Bl) when given
   auto dense = [&](const void *A, const void *W, const void *R, void *C, int N, int K, const void *Al, const void *Bl,
@@ -500,13 +544,16 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
       g.M = T_rows; g.N = N; g.K = K;
       g.tile_hint = (ctx->opt_gemm_tile >= 4 || ctx->opt_gemm_tile == 1) ? ctx->opt_gemm_tile : 0;
       if (lr) set_lowrank(g, Bl, nullptr, 1, N);
-      // few row tiles: split the reduction to fill the chip, partial sums go through the Y buffer
-      const int splits = ctx->opt_gemm_splits == 1 ? 1 : gemm_mfma_pick_splits(T_rows, N, K, ctx->n_cu);
-      if (splits > 1 && (size_t)splits * T_rows * N <= w.y_floats && ((int64_t)T_rows * N) % 4 == 0) {
-        g.k_splits = splits;
+      // few row tiles: every segment gets workgroups of its own to fill the chip, the segment sums go through
+      // the Y buffer; otherwise one workgroup adds them itself, in the same order
+      const int segs = segments_of(N, K);
+      g.k_segments = segs;
+      if (segs > 1 && gemm_mfma_split_segments(T_rows, N, ctx->n_cu) && (size_t)segs * T_rows * N <= w.y_floats &&
+          ((int64_t)T_rows * N) % 4 == 0) {
+        g.k_splits = segs;
         g.Cpart = w.Y;
         launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
-        launch_splitk_reduce(w.Y, splits, (int64_t)T_rows * N, (const bf16 *)R, (bf16 *)C, s);
+        launch_splitk_reduce(w.Y, segs, (int64_t)T_rows * N, (const bf16 *)R, (bf16 *)C, s);
       } else {
         g.k_splits = 1;
         g.C = (bf16 *)C; g.ldc = N; g.R = (const bf16 *)R;
@@ -524,8 +571,9 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
   bool normed = false;
   {
     ProfScope p(ctx, K_OPROJ, s);
-    const int splits = mfma && ctx->opt_gemm_splits != 1 ? gemm_mfma_pick_splits(T_rows, L.d, L.n_q, ctx->n_cu) : 1;
-    if (mfma && splits > 1 && (size_t)splits * T_rows * L.d <= w.y_floats && splitk_reduce_norm_supported(L.d)) {
+    const int splits = mfma ? segments_of(L.d, L.n_q) : 1;
+    if (mfma && splits > 1 && gemm_mfma_split_segments(T_rows, L.d, ctx->n_cu) &&
+        (size_t)splits * T_rows * L.d <= w.y_floats && splitk_reduce_norm_supported(L.d)) {
       GemmArgs g{};
       g.A = (const bf16 *)w.attn; g.lda = L.n_q;
       g.B = (const bf16 *)ly->W_o; g.ldb = L.n_q;
@@ -536,6 +584,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
         set_lowrank(g, ly->B_o, nullptr, 1, L.d);
       }
       g.k_splits = splits;
+      g.k_segments = splits;
       g.Cpart = w.Y;
       launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
       launch_splitk_reduce_norm(w.Y, splits, T_rows, L.d, (const bf16 *)x, (const bf16 *)ly->rms2_gain, ly->rms_eps,
@@ -562,7 +611,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     GemmArgs g{};
     g.A = (const bf16 *)w.hn; g.lda = L.d;
     g.B = (const bf16 *)ly->W_gate; g.B2 = (const bf16 *)ly->W_up; g.ldb = L.d;
-    g.M = T_rows; g.N = 2 * ly->intermediate; g.K = L.d; g.k_splits = 1;
+    g.M = T_rows; g.N = 2 * ly->intermediate; g.K = L.d; g.k_splits = 1; g.k_segments = 1;
     g.tile_hint = (ctx->opt_gemm_tile >= 4 || ctx->opt_gemm_tile == 1) ? ctx->opt_gemm_tile : 0;
     if (ly->A_gu && w.any_adapter) {
       lowrank_t(w.hn, L.d, ly->A_gu, 2);
@@ -604,6 +653,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     if (memcmp(&Ll, &L, sizeof L) != 0 || layers[l].dtype != layers[0].dtype ||
         layers[l].intermediate != layers[0].intermediate)
       return fail(ctx, ALORA_ESHAPE, "layer %d differs in shape or dtype from layer 0", l);
+    if (layers[l].rope_theta != layers[0].rope_theta || layers[l].rms_eps != layers[0].rms_eps)
+      return fail(ctx, ALORA_ESHAPE, "layer %d differs in rope_theta or rms_eps from layer 0 (one rotary table per call)", l);
     if (!caches[l].k || !caches[l].v) return fail(ctx, ALORA_EINVAL, "caches[%d] k / v is NULL", l);
     if (caches[l].pool_tokens != caches[0].pool_tokens)
       return fail(ctx, ALORA_ECAPACITY, "caches[%d] pool size differs from caches[0]", l);
@@ -707,8 +758,12 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   const bool mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && L.d % 64 == 0 &&
                     (L.n_adapters == 0 || (L.rank % 16 == 0 && L.n_adapters <= 64)) && L.n_q % 32 == 0 &&
                     L.n_kv % 32 == 0 && (!stack || (layers[0].intermediate % 64 == 0 && L.n_q % 64 == 0));
-  int k_splits = mfma ? gemm_mfma_pick_splits(pl.T, L.n_qkv, L.d, ctx->n_cu) : 1;
-  if (mfma && ctx->opt_gemm_splits > 0 && L.d % (64 * ctx->opt_gemm_splits) == 0) k_splits = ctx->opt_gemm_splits;
+  // The reduction axis of the QKV projection is cut into segments fixed by the weight shape (or by the
+  // gemm_splits option); whether they run in workgroups of their own or one after the other inside one
+  // is a scheduling choice that does not change a single bit of the result.
+  int k_segments = mfma ? gemm_mfma_fixed_segments(L.n_qkv, L.d, ctx->n_cu) : 1;
+  if (mfma && ctx->opt_gemm_splits > 0) k_segments = L.d % (64 * ctx->opt_gemm_splits) == 0 ? ctx->opt_gemm_splits : 1;
+  const int k_splits = (k_segments > 1 && gemm_mfma_split_segments(pl.T, L.n_qkv, ctx->n_cu)) ? k_segments : 1;
   Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
   st = ensure_workspace(ctx, probe.bytes);
   if (st != ALORA_OK) return st;
@@ -794,6 +849,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
   w.mfma = mfma;
   w.k_splits = k_splits;
+  w.k_segments = k_segments;
   // few row tiles and a split reduction: the workgroups are short and the prologue of split 0 would stick out
   w.lora_split = (k_splits > 1 && ctx->opt_lora_split != 2) || ctx->opt_lora_split == 1 ? 1 : 0;
   w.attn_mfma = attn_mfma;
@@ -1046,6 +1102,7 @@ alora_status alora_lm_head(alora_ctx *ctx, alora_dtype dtype, int32_t d, int32_t
       g.B = (const bf16 *)W_vocab; g.ldb = d;
       g.M = B; g.N = vocab; g.K = d;
       g.k_splits = 1;
+      g.k_segments = 1;
       g.Cpart = lg;
       launch_gemm_mfma(g, GEMM_EPI_PARTIAL, s);
     } else if (bf) {
@@ -1059,18 +1116,6 @@ alora_status alora_lm_head(alora_ctx *ctx, alora_dtype dtype, int32_t d, int32_t
     launch_argmax(lg, B, vocab, pv, pi, token, s);
   }
   HIP_TRY(ctx, hipGetLastError());
-  return ALORA_OK;
-}
-
-alora_status alora_measure_ceiling(alora_ctx *ctx, int32_t kind, double *value) {
-  if (!ctx) return ALORA_EINVAL;
-  ctx->err.clear();
-  if (!value || kind < 0 || kind > 2) return fail(ctx, ALORA_EINVAL, "kind must be 0, 1 or 2 and value non-NULL");
-  if (ctx->device < 0) return fail(ctx, ALORA_EHIP, "validation-only context (device -1)");
-  HIP_TRY(ctx, hipSetDevice(ctx->device));
-  const double v = measure_ceiling(kind, ctx->n_cu, nullptr);
-  if (v < 0.0) return fail(ctx, ALORA_EHIP, "ceiling measurement failed");
-  *value = v;
   return ALORA_OK;
 }
 

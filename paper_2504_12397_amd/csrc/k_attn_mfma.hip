@@ -454,7 +454,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 
 
 // ------------------------------------------------------------------------------------------------
-// Software-pipelined variant (the default).  Same work item, layouts and arithmetic as the kernel
+// Software-pipelined variant (option attn_pipeline = 0; the default is the kernel above).  Same work item, layouts and arithmetic as the kernel
 // above; what changes is the order in which one wave issues its work.  The loop advances in
 // 32-key blocks, and in step j a wave issues, as three independent instruction streams,
 //     matrix unit:  S(j+1) = K(j+1) Q^T   and   O^T += V(j-1)^T P(j-1)^T        (16 MFMAs)

@@ -4,7 +4,7 @@
 // Work item: one workgroup = (rows, kv head, key split), listed by the host; its four waves take
 // disjoint key ranges and never synchronise until the final merge.  Normally an item is one row
 // (one sequence's new token) over that sequence's own cache rows.  Sequences that name the same
-// shared prefix (Section 3, several adapters on one context) are packed 16 / G to an item for the
+// shared prefix (Section 2, "Cache reuse patterns": several adapters on one context) are packed 16 / G to an item for the
 // prefix part: their heads fill the MFMA columns a single sequence leaves empty, and the prefix
 // is read from memory once for all of them.  A wave consumes 32 keys per step:
 //   * K rows go from global memory straight into the A operand of v_mfma_f32_16x16x32_bf16

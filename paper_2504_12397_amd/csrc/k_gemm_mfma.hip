@@ -35,8 +35,15 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast
 // WEAVE: tile loads and LDS stores issued between the k-steps of the running tile (pays with many row tiles:
 // operands come from L2 and two workgroups share a compute unit) instead of in blocks around them (better
 // for weight streaming, where the loads want the longest time in flight).
-template <int BM, int BN, int WM, int WN, int EPI, int PF, bool WEAVE = false>
-__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(GemmArgs g) {
+// SEG: the reduction axis is cut into g.k_segments equal segments; the workgroup accumulates each from zero
+// and adds the segment sums in ascending order in fp32 -- bit for bit what the split-reduction path
+// (one segment per workgroup, partial sums added in the same order by the kernel that consumes them)
+// produces, so a row's result does not depend on how many rows share the call.
+template <int BM, int BN, int WM, int WN, int EPI, int PF, bool WEAVE = false, bool SEG = false>
+__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN))
+// the woven 128x128 kernel is built for two workgroups per compute unit (two waves per SIMD): hold the
+// register allocator to that also when the segment sums take 64 more registers
+__attribute__((amdgpu_waves_per_eu((WEAVE && SEG) ? 2 : 1))) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int BK = 64;
   constexpr int WAVES_N = BN / WN;
   constexpr int NT = 64 * (BM / WM) * WAVES_N;
@@ -78,6 +85,35 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // running sum of the finished segments (SEG only)
+  // (starts at +0: an accumulator that began at +0 is never -0, so 0 + p0 is p0 bit for bit)
+  f32x16 tot[SEG ? TM : 1][SEG ? TN : 1];
+  if constexpr (SEG) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[i][j][v] = 0.f;
+  }
+  const int seg_tiles = SEG ? nk / g.k_segments : 0;
+  int seg_left = seg_tiles;       // k-tiles until the running segment ends
+  // called after every k-tile: at a segment end the accumulators join the running sum and restart from zero
+  auto segment_end = [&](int) {
+    if constexpr (SEG) {
+      if (--seg_left != 0) return;
+      seg_left = seg_tiles;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            tot[i][j][v] += acc[i][j][v];
+            acc[i][j][v] = 0.f;
+          }
+    }
+  };
 
   // ---- main loop --------------------------------------------------------------------------
   // Two tiles are kept in flight in registers (R0, R1) on top of the one being consumed from
@@ -308,9 +344,11 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
     if constexpr (WEAVE) {
       for (int kt = 0; kt < nk; kt += 2) {
         compute_weave(std::false_type{}, As0, Bs0, min(kt + 2, nk - 1), ra0, rb0, As1, Bs1, ra1, rb1);
+        segment_end(kt + 1);
         __syncthreads();
         if (kt + 1 < nk) {
           compute_weave(std::false_type{}, As1, Bs1, min(kt + 3, nk - 1), ra1, rb1, As0, Bs0, ra0, rb0);
+          segment_end(kt + 2);
         } else {
           load_tiles(nk - 1, ra1, rb1);
           store_tiles(As0, Bs0, ra0, rb0);
@@ -321,10 +359,14 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
       for (int kt = 0; kt < nk; kt += 2) {
         load_tiles(min(kt + 2, nk - 1), ra0, rb0);
         compute(As0, Bs0);
+        segment_end(kt + 1);
         store_tiles(As1, Bs1, ra1, rb1);
         __syncthreads();
         load_tiles(min(kt + 3, nk - 1), ra1, rb1);
-        if (kt + 1 < nk) compute(As1, Bs1);
+        if (kt + 1 < nk) {
+          compute(As1, Bs1);
+          segment_end(kt + 2);
+        }
         store_tiles(As0, Bs0, ra0, rb0);
         __syncthreads();
       }
@@ -335,9 +377,16 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
       u32x4 *An = (kt & 1) ? As0 : As1, *Bn = (kt & 1) ? Bs0 : Bs1;
       load_tiles(min(kt + 1, nk - 1), ra0, rb0);
       compute(Ac, Bc);
+      segment_end(kt + 1);
       store_tiles(An, Bn, ra0, rb0);
       __syncthreads();
     }
+  }
+  if constexpr (SEG) {      // the last segment has joined the sum: the epilogues read acc
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
   }
 
   // ---- epilogue ---------------------------------------------------------------------------
@@ -437,18 +486,15 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_mfma_kernel(G
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int PF = 2, bool WEAVE = false>
+template <int BM, int BN, int WM, int WN, int EPI, int PF = 2, bool WEAVE = false, bool SEG = false>
 static void launch_cfg(const GemmArgs &g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   dim3 grid(8 * ((tiles_n + 7) / 8) * tiles_m * (g.k_splits + (g.lora_split ? 1 : 0)));
   size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(u32x4);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, PF, WEAVE>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, PF, WEAVE, SEG>;
   constexpr int NT = 64 * (BM / WM) * (BN / WN);
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    configured = true;
-  }
+  // set on every launch: a host-side attribute write, safe from any thread and on any device
+  (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   hipLaunchKernelGGL(kern, grid, dim3(NT), smem, s, g);
 }
 
@@ -589,15 +635,41 @@ int gemm_mfma_pick_splits(int M, int N, int K, int n_cu) {
   return s;
 }
 
+// The number of equal segments the reduction axis of a linear with weights [N, K] is ALWAYS cut in: a function
+// of the weight shape (and the chip) alone, never of the number of rows, so that a row's result has one
+// summation order whatever else is in the call (Proposition 1 in its strong form: the rows before the
+// invocation point come out bit-identical from a long prefill, a short one and a decode step).  Enough
+// segments that a call with one row tile fills the chip when every segment gets a workgroup of its own.
+int gemm_mfma_fixed_segments(int N, int K, int n_cu) {
+  const int tiles_n = (N + 127) / 128;
+  int s = 1;
+  while (4 * tiles_n * s < 3 * n_cu && s < 8 && K % (s * 2 * 64) == 0 && K / (s * 2) >= 512) s *= 2;
+  return s;
+}
+
+// Whether the segments go to workgroups of their own (their sums travel as fp32 partials and are added in
+// order by the consumer) or one workgroup walks through all of them (and adds them in the same order).
+// Only a scheduling choice: few row tiles underfill the chip, many make the partials expensive.
+bool gemm_mfma_split_segments(int M, int N, int n_cu) {
+  const int tiles_m = (M + 127) / 128, tiles_n = (N + 127) / 128;
+  return tiles_m <= 2 && 2 * tiles_m * tiles_n <= n_cu;
+}
+
 bool gemm_mfma_rope_supported(const GemmArgs &g, int head_dim) {
   return head_dim == 128 && g.k_splits == 1 && g.lora_split == 0 && g.n_q % 128 == 0 && g.n_kv % 128 == 0 &&
-         g.N == g.n_q + 2 * g.n_kv && g.M > 4 * 128;
+         g.N == g.n_q + 2 * g.n_kv && g.M > 2 * 128;
 }
 
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
+  if (g.k_segments < 1) g.k_segments = 1;
+  // one workgroup per output tile and a segmented reduction: the kernel adds the segment sums itself.  (The
+  // tile shapes behind tile_hint are tuning experiments and do not carry that code.)
+  const bool seg = g.k_splits == 1 && g.k_segments > 1 && g.tile_hint == 0 && (g.K / 64) % g.k_segments == 0;
+  if (!seg && g.k_splits == 1) g.k_segments = 1;
   if (epi == GEMM_EPI_ROPE) {
-    launch_cfg<128, 128, 64, 64, GEMM_EPI_ROPE, 2, true>(g, s);
+    if (seg) launch_cfg<128, 128, 64, 64, GEMM_EPI_ROPE, 2, true, true>(g, s);
+    else launch_cfg<128, 128, 64, 64, GEMM_EPI_ROPE, 2, true>(g, s);
     return;
   }
   if (epi == GEMM_EPI_PARTIAL) {
@@ -607,6 +679,7 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else if (g.tile_hint == 5) launch_cfg<128, 128, 32, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (g.tile_hint == 6) launch_cfg<128, 128, 64, 32, GEMM_EPI_PARTIAL>(g, s);
     else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
+    else if (seg) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true, true>(g, s);
     else if (g.M > 4 * 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true>(g, s);
     // few row tiles: the kernel streams weights and eight waves (two per SIMD) hide its LDS and barrier
     // latencies better than four; which way the 128x128 block is cut among them matters by a few percent
@@ -615,6 +688,7 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
     g.lora_split = 0;
+    g.k_segments = 1;
     if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     // (a wave needs a gate block and its up block: at least two 32-column blocks, so no 64x32 wave tiles here)
     else if (g.tile_hint == 5 || g.tile_hint == 6) launch_cfg<128, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
@@ -628,8 +702,13 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else if (g.tile_hint == 5) launch_cfg<128, 128, 32, 64, GEMM_EPI_BF16>(g, s);
     else if (g.tile_hint == 6) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
     else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
-    else if (g.M <= 128) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
-    else launch_cfg<256, 128, 128, 64, GEMM_EPI_BF16>(g, s);
+    else if (g.M <= 128) {
+      if (seg) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16, 2, false, true>(g, s);
+      else launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
+    } else {
+      if (seg) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16, 2, true, true>(g, s);
+      else launch_cfg<256, 128, 128, 64, GEMM_EPI_BF16>(g, s);
+    }
   }
 }
 

@@ -13,7 +13,10 @@ struct GemmArgs {
   const bf16 *B2;              // SwiGLU only: the "up" weights; B holds the "gate" weights, N = 2 * I
   int M, N, K;
   int tile_hint;               // 0 = automatic; 1 = 128x128 (4 waves), 2 = 256x128, 3 = 256x256, 4 = 128x64, 5/6 = 128x128 with 8 waves of 32x64 / 64x32
-  int k_splits;                // PARTIAL only: splits of the reduction axis; K / k_splits must be a multiple of 64
+  int k_splits;                // PARTIAL only: workgroups per output tile along the reduction axis, 1 or k_segments
+  int k_segments;              // equal segments the reduction axis is cut in, each summed from zero and the sums added
+                               // in ascending order (by the consumer of the partials when k_splits == k_segments, by
+                               // the kernel itself when k_splits == 1); K / k_segments must be a multiple of 64
   int lora_split;              // PARTIAL only, 1: the low-rank term gets workgroups of its own that write partial
                                // number k_splits (Cpart then holds k_splits + 1 partials), instead of riding on split 0
   float *Cpart;                // PARTIAL: [k_splits, M, N] fp32 partial sums
@@ -118,11 +121,10 @@ struct DecodeArgs {
 bool attn_decode_mfma_supported(const LayerDims &L);
 void launch_attn_decode_mfma(const DecodeArgs &a, int n_items, hipStream_t s);
 
-// Measured ceilings: kind 0 = bf16 MFMA TFLOP/s (register-only loop), kind 1 = HBM read GB/s (4 GiB stream).
-double measure_ceiling(int kind, int n_cu, hipStream_t s);
-
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
+int gemm_mfma_fixed_segments(int N, int K, int n_cu);      // reduction segments of a linear: from the weight shape alone
+bool gemm_mfma_split_segments(int M, int N, int n_cu);     // one workgroup per segment (few row tiles) or one for all
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s);
 // tlow[row, p, {hi, lo}, j] = s_a * sum over splits of Y[split, row, (a * parts + p) * rank + j] for adapted rows
 // (a = row_adapter[row] >= 0): picks each row's adapter out of a projection on all adapters' down-matrices

@@ -195,7 +195,7 @@ def config2() -> Batch:
 
 
 def regime2():
-    """Second cache-reuse regime of Section 3: an adapter call over 4096 tokens of context that the
+    """Second cache-reuse regime of Section 2 ("Cache reuse patterns"): an adapter call over 4096 tokens of context that the
     base model has not cached (k = 4096 > P = 0) plus 256 adapted tokens, then a base-model turn of
     256 tokens that reuses the 4096 base rows the adapter call left behind."""
     seed = BASE_SEED + 6
@@ -224,7 +224,7 @@ def config4() -> Batch:
 
 
 def regime3(n_contexts: int = 16, per_context: int = 4, context: int = 16384, own: int = 64):
-    """Third cache-reuse regime of Section 3 (N adapters on one context, Proposition 2's N-adapter
+    """Third cache-reuse regime of Section 2, "Cache reuse patterns" (N adapters on one context, Proposition 2's N-adapter
     clause) as a decode step: the c4 batch regrouped into 16 contexts of 16384 base tokens, each
     read by 4 sequences with different adapters that hold 64 adapted rows of their own.  Returns
     the batch and, per sequence, the index of its context."""

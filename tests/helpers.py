@@ -3,6 +3,8 @@ Holds no arithmetic of the method: expected values always come from oracle/."""
 from __future__ import annotations
 
 import dataclasses
+import json
+import os
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -12,6 +14,24 @@ from oracle import alora_oracle as orc
 from paper_2504_12397_amd import workloads as wl
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+# where the parity tests record their measured errors (one JSON object per line)
+REPORT_PATH = os.environ.get("ALORA_PARITY_REPORT", os.path.join(ROOT, "gpurun_out", "parity_report.jsonl"))
+
+
+def report(**vals):
+    """Prints and records measured errors of the running test: the asserted one (against the oracle as it
+    stands, activations stored in bf16) next to the error against the oracle with unrounded activations."""
+    rec = {"test": os.environ.get("PYTEST_CURRENT_TEST", "").split(" ")[0]}
+    rec.update({k_: (float(v) if isinstance(v, (float, np.floating)) else v) for k_, v in vals.items()})
+    print("parity:", json.dumps(rec))
+    try:
+        os.makedirs(os.path.dirname(REPORT_PATH), exist_ok=True)
+        with open(REPORT_PATH, "a") as f:
+            f.write(json.dumps(rec) + "\n")
+    except OSError:
+        pass
 
 
 def rel_err(got, ref) -> float:
@@ -93,10 +113,12 @@ def make_case(shape: wl.LayerShape, P: Sequence[int], S: Sequence[int], k: Seque
     return Case(shape, tensors, layer, list(P), list(S), list(k), list(adapter), xp, xn, cK, cV)
 
 
-def oracle_prefill(case: Case):
+def oracle_prefill(case: Case, act_dtype: Optional[str] = None):
+    """act_dtype = "f64": the reading in which the normalised hidden state is NOT rounded to the storage
+    dtype before the projections (the cache keeps its dtype); used to report, never to assert."""
     caches = list(zip(case.cache_K, case.cache_V))
     return orc.ref_prefill_batch(case.layer, caches, case.P, f64(case.x_packed), case.cu, case.k, case.adapter,
-                                 case.shape.dtype)
+                                 case.shape.dtype, act_dtype)
 
 
 # ------------------------------------------------------------------------------ GPU side

@@ -181,8 +181,27 @@ def test_shared_prefix_validation(ab, vctx):
     assert go([10, 5], [-1, 150])[0] == "ALORA_ECAPACITY"
     assert go([10, 5], [0, 0], give_off=False)[0] == "ALORA_EINVAL"
     # 90 cached rows of which 80 are shared: 10 own + 3 new fit a capacity of 13, not of 12
-    assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(13, 100)) == (ok, [90, 20])
-    assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(12, 100))[0] == "ALORA_ECAPACITY"
+    assert go([80, 0], [20, 0], seq_len=(90, 20), cap=(13, 100)) == (ok, [90, 20])
+    assert go([80, 0], [20, 0], seq_len=(90, 20), cap=(12, 100))[0] == "ALORA_ECAPACITY"
+    # the shared rows [100, 180) are rows sequence 1 is about to write ([120, 125)): rejected
+    assert go([80, 0], [100, 0], seq_len=(90, 20), cap=(13, 100))[0] == "ALORA_ECAPACITY"
+    # reading another sequence's already valid rows as a prefix is fine (the base model's own sequence in the batch)
+    assert go([15, 0], [100, 0], seq_len=(18, 20), cap=(13, 100)) == (ok, [18, 20])
+
+
+def test_overlapping_sequence_regions_are_rejected(ab, vctx):
+    """Two sequences of one call may not own the same pool rows: both would write them."""
+    for off, cap, want in (([0, 100], [100, 100], "ALORA_EHIP"), ([0, 99], [100, 100], "ALORA_ECAPACITY"),
+                           ([100, 0], [100, 100], "ALORA_EHIP"), ([50, 0], [100, 100], "ALORA_ECAPACITY"),
+                           ([0, 0], [100, 100], "ALORA_ECAPACITY"), ([0, 0], [100, 0], "ALORA_ECAPACITY")):
+        desc, cache, cu, k, a, B, keep, ln = make_args(ab, seq_offset=off, seq_capacity=cap,
+                                                       seq_len=[10, 0] if cap[1] == 0 else [10, 20],
+                                                       cu=[0, 3, 3] if cap[1] == 0 else [0, 3, 8])
+        st = ab._lib.alora_status_string(call(ab, vctx, desc, cache, cu, k, a, B)).decode()
+        if cap[1] == 0:
+            want = "ALORA_EHIP"          # an empty region overlaps nothing
+        assert st == want, (off, cap, st)
+        assert list(ln) == ([10, 0] if cap[1] == 0 else [10, 20])
 
 
 def test_lm_head_validation(ab, vctx):

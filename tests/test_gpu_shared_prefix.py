@@ -1,4 +1,4 @@
-"""Shared-prefix batching (Section 3, third cache-reuse regime; Proposition 2 for N adapters on one
+"""Shared-prefix batching (Section 2, "Cache reuse patterns", third regime; Proposition 2 for N adapters on one
 context): several sequences read ONE physical copy of the base model's prefix rows and keep only
 their own suffix rows.  The oracle knows nothing of sharing -- every sequence is computed on its own
 with its own copy of the prefix -- so agreement with it proves that sharing changes nothing."""
