@@ -156,17 +156,14 @@ const char *alora_status_string(alora_status s);
  *                     projection rotates q and k and appends k and v in its own epilogue.  0: a separate
  *                     kernel does, from the fp32 projection.  Same bits either way.
  *   "attn_waves"      0 (default) / 8: eight waves per workgroup in the prefill attention kernel.  4: four.
- *   "attn_pipeline"   1 (default): prefill attention kernel that leaves the overlap of softmax and matrix
- *                     work to the waves sharing a SIMD.  0: the variant that software-pipelines the two
- *                     inside each wave.
  *   "attn_lazy"       0..16 (default 3): the running row maximum of the prefill attention kernels moves only
  *                     when a block of scores exceeds it by more than this many powers of two (0 = exact
  *                     maximum).  The softmax is the same; only the scale of the intermediate probabilities
  *                     changes.
- *   "attn_fold"       0 (default) / 1, with attn_pipeline = 1 only: the queries are multiplied by
- *                     log2(e)/sqrt(h) before they are rounded to bf16 and the score accumulators start at
- *                     minus the row's reference exponent.  The same softmax of Eq.1; the queries are rounded
- *                     at a different point, so single elements differ within the bf16 tolerance.
+ *   "attn_fold"       1 (default): the queries are multiplied by log2(e)/sqrt(h) when they are written and the
+ *                     score accumulators of the prefill attention kernel start at minus the row's reference
+ *                     exponent, so the scores leave the matrix unit ready for exp2.  0: the kernel scales and
+ *                     subtracts on the vector ALU.  The same softmax of Eq.1 either way.
  *   "attn_partials16" 1 (default): when prefill attention is split over the keys, the partial results travel
  *                     as compact records (accumulators scaled to [-1, 1] as fp16 plus three fp32 scalars,
  *                     272 bytes).  0: fp32 records (520 bytes).

@@ -63,10 +63,9 @@ struct alora_ctx {
   int opt_attn_waves = 0;
   int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
   int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
-  int opt_attn_pipeline = 1;     // 0 = software-pipelined attention kernel, 1 = the unpipelined one
   int opt_attn_partials16 = 1;   // split prefill attention (MFMA path): compact partial records
   int opt_rope_fuse = 1;         // rotation + cache append in the epilogue of the QKV projection where the shape allows
-  int opt_attn_fold = 0;         // 1 = unpipelined kernel takes prescaled queries and starts its score accumulators at -m_ref
+  int opt_attn_fold = 1;         // 1 = prefill attention takes prescaled queries and starts its score accumulators at -m_ref
   int n_cu = 256;
 };
 
@@ -368,7 +367,7 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
     w.y_floats = std::max(w.y_floats, (size_t)8 * T * std::max(L.n_adapters, 1) * 2 * std::max(L.rank, 1));
   }
   w.Y = b.take<float>(w.y_floats);
-  w.Q = b.take<char>((size_t)T * L.n_q * esz);
+  w.Q = b.take<char>((size_t)T * L.n_q * 4);      // fp16 for the MFMA attention kernels, fp32 for the plain one
   w.partials = b.take<float>(attn_plain_partial_floats(L, T, n_splits));
   if (stack) {
     w.attn = b.take<char>((size_t)T * L.n_q * esz);
@@ -407,11 +406,12 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
                           (const T *)ly->A, rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
     }
   }
-  // the folded-softmax attention kernel takes its queries premultiplied by sm_scale * log2(e)
-  const int attn_schedule = ctx->opt_attn_pipeline;
-  const float q_scale = (w.attn_mfma && std::is_same<T, bf16>::value)
-                            ? attn_prefill_mfma_q_scale(L, w.attn_waves, attn_schedule, ctx->opt_attn_fold != 0)
-                            : 1.0f;
+  // the MFMA attention kernels (prefill and decode) take their queries as fp16 (every operand of its matrix products is fp16),
+  // in its folded-softmax form premultiplied by sm_scale * log2(e)
+  // (the plain attention kernel reads them as fp32: the Q buffer holds four bytes per element)
+  const bool q_half = (w.attn_mfma || w.decode_mfma) && std::is_same<T, bf16>::value;
+  const int q_mode = q_half ? 1 : 2;
+  const float q_scale = (w.attn_mfma && q_half) ? attn_prefill_mfma_q_scale(L, ctx->opt_attn_fold != 0) : 1.0f;
   bool rope_fused = false;
   {
     ProfScope p(ctx, K_QKV, s);
@@ -433,9 +433,10 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.row_adapter = w.rm.adapter;
       // many rows, unsplit reduction, one head per column tile: rotation and cache append happen in the
       // projection's epilogue and the fp32 projection never goes to memory
-      if (ctx->opt_gemm_tile == 0 && ctx->opt_rope_fuse && gemm_mfma_rope_supported(g, L.head_dim)) {
+      if (ctx->opt_gemm_tile == 0 && ctx->opt_rope_fuse && q_half && gemm_mfma_rope_supported(g, L.head_dim)) {
         g.rope_pos = w.rm.pos; g.rope_slot = w.rm.slot; g.rope_table = ctx->rope; g.q_scale = q_scale;
         g.Qout = (bf16 *)w.Q; g.cacheK = (bf16 *)cache->k; g.cacheV = (bf16 *)cache->v;
+        g.q_half = q_half ? 1 : 0;
         launch_gemm_mfma(g, GEMM_EPI_ROPE, s);
         rope_fused = true;
       } else {
@@ -448,18 +449,17 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
   }
   if (!rope_fused) {
     ProfScope p(ctx, K_ROPE, s);
-    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, q_scale, (T *)w.Q,
+    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, q_scale, q_mode, w.Q,
                           (T *)cache->k, (T *)cache->v, s);
   }
   const bool direct = w.attn_mfma && std::is_same<T, bf16>::value && n_splits == 1;
   // split prefill attention on the MFMA path: partial results travel in the compact record
-  const bool compact16 = w.attn_mfma && std::is_same<T, bf16>::value && !direct && ctx->opt_attn_partials16 &&
-                         attn_prefill_mfma_compact(w.attn_waves, attn_schedule);
+  const bool compact16 = w.attn_mfma && std::is_same<T, bf16>::value && !direct && ctx->opt_attn_partials16;
   {
     ProfScope p(ctx, decode ? K_ATTN_DECODE : K_ATTN_PREFILL, s);
     if (w.attn_mfma && std::is_same<T, bf16>::value) {
       AttnArgs a{};
-      a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
+      a.Q = (const _Float16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
       a.seqs = seqs_dev; a.work = w.qtiles;
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
       a.n_splits = n_splits;
@@ -474,10 +474,10 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       bool generic_addr = pl.any_prefix;
       for (const SeqMeta &q : pl.seqs)
         if ((uint64_t)(q.P + q.n_new) * (uint64_t)L.n_kv * 2u >= (1ull << 31)) generic_addr = true;
-      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, attn_schedule, generic_addr, s);
+      launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, generic_addr, s);
     } else if (w.decode_mfma && std::is_same<T, bf16>::value) {
       DecodeArgs a{};
-      a.Q = (const bf16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
+      a.Q = (const _Float16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
       a.seqs = seqs_dev; a.rm = w.rm;
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
       a.items = w.ditems;
@@ -486,7 +486,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.partials = w.partials;
       launch_attn_decode_mfma(a, w.n_ditems, s);
     } else {
-      launch_attn_plain<T>((const T *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
+      launch_attn_plain<T>((const float *)w.Q, (const T *)cache->k, (const T *)cache->v, seqs_dev, w.rm, L, pl.T,
                            n_splits, w.partials, s);
     }
   }
@@ -1004,11 +1004,6 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "attn_fold")) {
     if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "attn_fold must be 0 or 1");
     ctx->opt_attn_fold = value;
-    return ALORA_OK;
-  }
-  if (!strcmp(key, "attn_pipeline")) {
-    if (value != 0 && value != 1) return fail(ctx, ALORA_EINVAL, "attn_pipeline must be 0 or 1");
-    ctx->opt_attn_pipeline = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "attn_waves")) {

@@ -78,9 +78,11 @@ void launch_qkv_gemm_plain(const T *xh, const T *W, const float *tlow, const T *
 template <typename T>
 void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, int K, hipStream_t s);
 
+// q_mode: how the rotated queries are stored -- 0: as T, 1: as fp16 (operand type of the MFMA attention kernels),
+// 2: as fp32 (the plain attention kernel)
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
-                        const float2 *rope_table, float q_scale, T *Q, T *cacheK, T *cacheV, hipStream_t s);
+                        const float2 *rope_table, float q_scale, int q_mode, void *Q, T *cacheK, T *cacheV, hipStream_t s);
 
 // C[M, N] += gated low-rank term (Eq.6) of one linear: s_a B_a (A_{a,part} x) for rows with row_adapter >= 0
 template <typename T>
@@ -95,7 +97,7 @@ void launch_argmax(const float *logits, int B, int V, float *pv, int *pi, int32_
 
 // split-KV attention with plain fp32 arithmetic: partial pass + merge
 template <typename T>
-void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
+void launch_attn_plain(const float *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
                        const LayerDims &L, int T_rows, int n_splits, float *partials, hipStream_t s);
 // merge of the per-split partials (log-sum-exp weights); partial layout per (row, q head, split):
 // head_dim accumulators, running max, running sum

@@ -1,5 +1,13 @@
 // Flash-style causal attention of new queries over [cached prefix ; new suffix] (Eq.1 with the
-// causal mask, rows as in Eq.6) with bf16 MFMA on gfx950, head_dim 128, grouped-query sharing.
+// causal mask, rows as in Eq.6) on the gfx950 matrix cores, head_dim 128, grouped-query sharing.
+//
+// Operand precision.  The cache holds bf16 keys and values (storage), but inside this kernel every MFMA
+// operand is fp16: the queries arrive as fp16 from the rotation step, K/V tiles are converted bf16 -> fp16 on
+// their way into LDS (exact: 8 significant bits fit in 11; magnitudes beyond 65504 saturate, values below
+// 2^-24 vanish), and the probabilities are packed to fp16.  With bf16 operands the rounding of q (2^-9 per
+// element, amplified through the exponential) and of p dominated the error against the float64 oracle --
+// 1.5e-3 and 1.2e-3 rms of the row scale, with maxima of 1-2.3e-2 over 10^6 elements, right at the 2e-2
+// bar; fp16 operands cut both by 8x at the price of ~40 conversion instructions per thread and tile.
 //
 // Work item: one workgroup = (q-tile of 256/G tokens of one sequence, kv head, key split).
 // The G query heads of the kv group are packed next to the tokens into 256 "packed rows"
@@ -27,13 +35,13 @@
 
 namespace alora {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ bf16x8 u4_as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ f16x8 u4_as_f16x8(u32x4 u) { return __builtin_bit_cast(f16x8, u); }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -42,6 +50,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   p[1] = (bf16)b;
   return __builtin_bit_cast(uint32_t, p);
 }
+
+// two floats as an fp16 pair (v_cvt_pkrtz_f16_f32: one instruction, round toward zero, so a finite value
+// never becomes infinite).  Used for the probabilities -- numerator and denominator of the softmax are both
+// taken from the packed values, so the rounding direction cancels -- and for bf16 values, where it is exact.
+__device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+// the two bf16 halves of a word as floats
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+// a word of two bf16 -> a word of two fp16
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) { return pack_f16x2(bf16_lo(w), bf16_hi(w)); }
 
 // chunk swizzle of the V^T tile (128-byte rows).  LDS serves 16 lanes at a time over 64 banks:
 // 16 consecutive columns of one chunk (operand reads) must land on 16 distinct 16-byte slots
@@ -60,11 +80,10 @@ __device__ __forceinline__ float max_with_other_half(float x) {
   return lo;
 }
 
-// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
-__device__ __forceinline__ float sum_bf16x2(uint32_t pair, float acc) {
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
-                                         false);
+// acc + lo + hi of a packed fp16 pair (v_dot2_f32_f16 against (1, 1)): products and sum in fp32
+__device__ __forceinline__ float sum_f16x2(uint32_t pair, float acc) {
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, pair), __builtin_bit_cast(half2_t, 0x3c003c00u), acc, false);
 }
 
 // Waits for every outstanding global load (s_waitcnt vmcnt(0); the other counters left alone).
@@ -85,9 +104,9 @@ constexpr float LN2 = 0.6931471805599453f;
 // rounds them), and the softmax bookkeeping moves onto the matrix unit:
 //   * the accumulator of the first K Q^T product starts at -m_ref (the row's reference exponent,
 //     replicated over the lane's 16 registers), so the scores come out as s - m_ref, ready for exp2;
-//   * the row sums are two more MFMAs per 32-key block, an all-ones A operand against the rounded
-//     probabilities, which leave the sum over all 32 keys in every register of `lacc` (no
-//     cross-half exchange, and numerator and denominator see the same rounded values);
+//   * the row sums are taken on the vector ALU from the packed probabilities (v_dot2_f32_f16 against (1, 1)),
+//     so numerator and denominator see the same rounded values; each half of the wave sums the keys it holds and
+//     the two halves are added once, at the end (they share the reference exponent);
 //   * m_ref is set to the exact maximum of the first block in which the row sees a key, and later moves
 //     only when a block's maximum exceeds it by more than `lazy`, in a branch that is rare.
 // The softmax is the same function: numerator and denominator share the reference exponent.
@@ -133,7 +152,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     head[nb] = g * G + pr % G;
     const int tc = min(tok[nb], ntok - 1);
     pos[nb] = tok[nb] < ntok ? first_pos + tok[nb] : -1;       // -1: padding row, sees nothing
-    const bf16 *qp = a.Q + (int64_t)(row0 + tc) * a.n_q + head[nb] * H + kh * 8;
+    const _Float16 *qp = a.Q + (int64_t)(row0 + tc) * a.n_q + head[nb] * H + kh * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const u32x4 *>(qp + ks * 16);
   }
@@ -146,13 +165,14 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[cb][nb][v] = 0.f;
   const float c_scale = a.sm_scale * LOG2E;
-  // softmax state of the lane's query row: the reference exponent m_ref (exp2 domain), the row sum in
-  // every register of lacc (it is the accumulator of an MFMA), and for FOLD -m_ref in every register of negm
-  f32x16 negm, lacc;
+  // softmax state of the lane's query row: the reference exponent m_ref (exp2 domain), the sum l_run of the
+  // probabilities of the keys this half of the wave holds, and for FOLD -m_ref in every register of negm
+  f32x16 negm;
   float m_ref = FOLD ? 0.f : -INFINITY;
+  float l_run = 0.f;
+  bool seen = false;        // the row has met a visible key (the same in both halves: derived from the shared maximum)
 #pragma unroll
-  for (int v = 0; v < 16; ++v) { negm[v] = 0.f; lacc[v] = 0.f; }
-  const bf16x8 ones = u4_as_bf16x8(u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+  for (int v = 0; v < 16; ++v) negm[v] = 0.f;
 
   // ---- tile loader: K rows as they are, V transposed in registers -------------------------
   // 512 threads: K = 1024 chunks of 16 B, two per thread; V = 16 key quads x 32 column groups of
@@ -218,7 +238,8 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 #pragma unroll
     for (int i = 0; i < KC; ++i) {
       const int q = tid + i * NT, key = q >> 4, c = q & 15;
-      Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
+      Ks[buf][key * 16 + (c ^ (key & 15))] = u32x4{bf16x2_to_f16x2(rk[i].x), bf16x2_to_f16x2(rk[i].y),
+                                                   bf16x2_to_f16x2(rk[i].z), bf16x2_to_f16x2(rk[i].w)};
     }
   };
   auto store_v = [&](int buf, const vword (&rv)[4]) {
@@ -229,12 +250,13 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     u32x2 *vs2 = reinterpret_cast<u32x2 *>(Vs[buf]);
 #pragma unroll
     for (int j = 0; j < VW; ++j) {
-      // even column 2j: low halves; odd column 2j+1: high halves
+      // even column 2j: low halves; odd column 2j+1: high halves.  The conversion to fp16 packs two keys of one
+      // column into a word, which is the transposition.
       u32x2 ev, od;
-      ev.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x05040100u);
-      ev.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x05040100u);
-      od.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x07060302u);
-      od.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x07060302u);
+      ev.x = pack_f16x2(bf16_lo(rv[0][j]), bf16_lo(rv[1][j]));
+      ev.y = pack_f16x2(bf16_lo(rv[2][j]), bf16_lo(rv[3][j]));
+      od.x = pack_f16x2(bf16_hi(rv[0][j]), bf16_hi(rv[1][j]));
+      od.y = pack_f16x2(bf16_hi(rv[2][j]), bf16_hi(rv[3][j]));
       const int c0 = v_cg * CW + 2 * j, c1 = c0 + 1;
       vs2[(c0 * 8 + (vchunk ^ v_swz(c0))) * 2 + halfpos] = ev;
       vs2[(c1 * 8 + (vchunk ^ v_swz(c1))) * 2 + halfpos] = od;
@@ -244,15 +266,15 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
   // A 64-key tile is consumed as two 32-key blocks, each with its own softmax update, so that only one
   // block of scores and probabilities is live at a time.  The three steps of a block:
   f32x16 sv;            // scores of the block in flight, then its probabilities
-  u32x4 pf[2];          // the probabilities as bf16: [half of the block's keys] x 8
+  u32x4 pf[2];          // the probabilities as fp16: [half of the block's keys] x 8
   // ---- S^T = K Q^T ------------------------------------------------------------------------------
   auto qk = [&](int buf, int kb) {
     // all eight K fragments of this key block are fetched from LDS first: with one MFMA per
     // fragment there is nothing else to hide the LDS latency behind
-    bf16x8 kf[8];
+    f16x8 kf[8];
     const int key = kb * 32 + l32;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) kf[ks] = u4_as_bf16x8(Ks[buf][key * 16 + ((2 * ks + kh) ^ (key & 15))]);
+    for (int ks = 0; ks < 8; ++ks) kf[ks] = u4_as_f16x8(Ks[buf][key * 16 + ((2 * ks + kh) ^ (key & 15))]);
     if constexpr (FOLD) {
       sv = negm;
     } else {
@@ -260,7 +282,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
       for (int v = 0; v < 16; ++v) sv[v] = 0.f;
     }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], u4_as_bf16x8(qf[0][ks]), sv, 0, 0, 0);
+    for (int ks = 0; ks < 8; ++ks) sv = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[ks], u4_as_f16x8(qf[0][ks]), sv, 0, 0, 0);
   };
   // ---- causal mask and online softmax (log2 domain), one query row per lane -----------------------
   auto softmax = [&](int t, int kb) {
@@ -285,14 +307,16 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     if constexpr (FOLD) {
       // sv holds s - m_ref.  A row's first keys set the reference to their exact maximum (the largest
       // probability is then exactly 1, which matters most for rows that see few keys).
-      const bool fresh = lacc[0] == 0.f;       // nothing accumulated for this row yet
+      const bool fresh = !seen;                // nothing accumulated for this row yet
       const bool want = mx > a.lazy || (fresh && mx > -INFINITY);
+      seen = seen || mx > -INFINITY;
       if (__any(want)) {
         const float delta = want ? mx : 0.f;
         const float alpha = fresh ? 1.0f : __builtin_amdgcn_exp2f(-delta);
         m_ref += delta;
+        l_run *= alpha;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sv[v] -= delta; negm[v] -= delta; lacc[v] *= alpha; }
+        for (int v = 0; v < 16; ++v) { sv[v] -= delta; negm[v] -= delta; }
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -308,8 +332,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
       if (move) {
         const float alpha = __builtin_amdgcn_exp2f(m_ref - m_safe);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) lacc[v] *= alpha;
+        l_run *= alpha;
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -322,31 +345,30 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
       const int e = 8 * hf;
-      pf[hf] = u32x4{pack_bf16x2(sv[e], sv[e + 1]), pack_bf16x2(sv[e + 2], sv[e + 3]), pack_bf16x2(sv[e + 4], sv[e + 5]),
-                     pack_bf16x2(sv[e + 6], sv[e + 7])};
+      pf[hf] = u32x4{pack_f16x2(sv[e], sv[e + 1]), pack_f16x2(sv[e + 2], sv[e + 3]), pack_f16x2(sv[e + 4], sv[e + 5]),
+                     pack_f16x2(sv[e + 6], sv[e + 7])};
+      // row sum of the PACKED probabilities (the values the products below use)
+      l_run = sum_f16x2(pf[hf].x, l_run);
+      l_run = sum_f16x2(pf[hf].y, l_run);
+      l_run = sum_f16x2(pf[hf].z, l_run);
+      l_run = sum_f16x2(pf[hf].w, l_run);
     }
   };
-  // ---- O^T += V^T P^T and the row sums ----------------------------------------------------------------
+  // ---- O^T += V^T P^T ----------------------------------------------------------------------------------
   auto pv = [&](int buf, int kb) {
-    bf16x8 vf[2][4];
+    f16x8 vf[2][4];
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb) {
         const int col = cb * 32 + l32, c = 2 * (kb * 2 + hf) + kh;
-        vf[hf][cb] = u4_as_bf16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
+        vf[hf][cb] = u4_as_f16x8(Vs[buf][col * 8 + (c ^ v_swz(col))]);
       }
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb)
-        o[cb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][cb], u4_as_bf16x8(pf[hf]), o[cb][0], 0, 0, 0);
-    // row sums of the ROUNDED probabilities (the values the products above use, so numerator and
-    // denominator of the softmax carry the same rounding): an all-ones A operand leaves the sum over
-    // the block's 32 keys in every register of lacc
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-      lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, u4_as_bf16x8(pf[hf]), lacc, 0, 0, 0);
+        o[cb][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[hf][cb], u4_as_f16x8(pf[hf]), o[cb][0], 0, 0, 0);
   };
 
   {
@@ -385,7 +407,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
   // ---- write the partial (or final) result ----------------------------------------------------
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const float l_tot = lacc[0];
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);      // the two halves of the wave hold disjoint keys
     if (tok[nb] >= ntok) continue;
     const int64_t row = row0 + tok[nb];
     if (a.out != nullptr) {
@@ -453,310 +475,6 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 }
 
 
-// ------------------------------------------------------------------------------------------------
-// Software-pipelined variant (option attn_pipeline = 0; the default is the kernel above).  Same work item, layouts and arithmetic as the kernel
-// above; what changes is the order in which one wave issues its work.  The loop advances in
-// 32-key blocks, and in step j a wave issues, as three independent instruction streams,
-//     matrix unit:  S(j+1) = K(j+1) Q^T   and   O^T += V(j-1)^T P(j-1)^T        (16 MFMAs)
-//     vector ALU :  online softmax of S(j) -> P(j)
-//     memory     :  LDS fragment reads for the MFMAs above, one half tile stored to LDS, one half
-//                   tile requested from global memory (two tiles ahead)
-// so the exponentials of one block run while the matrix unit works on its neighbours, inside the
-// wave, instead of relying on another wave being in a different phase.  The rescaling of O by
-// exp2(m_old - m_new) (Eq.1's softmax computed online) is applied after P(j-1) V(j-1) has been
-// accumulated, which is the same value: O_j = (O_{j-2} + P_{j-1} V_{j-1}) * alpha_j.
-//
-// LDS buffers are double: K(t+1) is stored during the first step of tile t (its slot was last
-// read two steps earlier), V(t+1) during the second (its slot was last read one step earlier);
-// one barrier per step orders them.
-template <int G, bool PFX>
-__global__ __launch_bounds__(512) void attn_prefill_pipe_kernel(AttnArgs a) {
-  constexpr int H = 128;
-  constexpr int NT = 512;
-  constexpr int TQ = 256 / G;
-#ifndef ATT_AHEAD
-#define ATT_AHEAD 6
-#endif
-  constexpr int AH = ATT_AHEAD;      // LDS fragment reads in flight per wave
-  __shared__ u32x4 Ks[2][ATT_BN * 16];
-  __shared__ u32x4 Vs[2][H * 8];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, kh = lane >> 5;
-  const int4 wk = a.work[blockIdx.x];
-  if (wk.x < 0) return;
-  const int g = wk.z, split = wk.w;
-  const SeqMeta sm = a.seqs[wk.x];
-  const int q0 = wk.y;
-  const int ntok = min(TQ, sm.n_new - q0);
-  const int row0 = sm.row_start + q0;
-  const int n_visible = sm.P + q0 + ntok;
-  int chunk = (n_visible + a.n_splits - 1) / a.n_splits;
-  chunk = (chunk + ATT_BN - 1) & ~(ATT_BN - 1);
-  const int kbeg = split * chunk, kend = min(n_visible, kbeg + chunk);
-  const int ntiles = kend > kbeg ? (kend - kbeg + ATT_BN - 1) / ATT_BN : 0;
-  const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
-  const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
-  // offset (in elements) that turns an own-row address into the shared-prefix address of the same position
-  const int64_t pfx_delta = PFX ? (sm.prefix_off - sm.pool_off) * a.n_kv : 0;
-  const int pfx_len = PFX ? sm.prefix_len : 0;
-  const int first_pos = sm.P + q0;
-
-  const int pr = wave * 32 + l32;
-  const int tok = pr / G, head = g * G + pr % G;
-  const int pos = tok < ntok ? first_pos + tok : -1;
-  u32x4 qf[8];
-  {
-    const bf16 *qp = a.Q + (int64_t)(row0 + min(tok, ntok - 1)) * a.n_q + head * H + kh * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const u32x4 *>(qp + ks * 16);
-  }
-  f32x16 o[4];
-#pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[cb][v] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  const float c_scale = a.sm_scale * LOG2E;
-
-  // ---- loaders: as in the kernel above, K and V handled separately ----------------------------
-  u32x4 rkA[2];
-  u32x2 rvA[4];
-  const int v_qd = tid >> 5, v_cg = tid & 31;
-  auto load_k = [&](int t, u32x4 (&rk)[2]) {
-    const int k0 = kbeg + min(t, ntiles - 1) * ATT_BN;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int q = tid + i * NT, key = q >> 4, c = q & 15;
-      const int kidx = min(k0 + key, n_visible - 1);
-      const int64_t e = (int64_t)kidx * a.n_kv + c * 8 + (PFX && kidx < pfx_len ? pfx_delta : 0);
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kp + e);
-    }
-  };
-  auto load_v = [&](int t, u32x2 (&rv)[4]) {
-    const int k0 = kbeg + min(t, ntiles - 1) * ATT_BN;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-      const int64_t e = (int64_t)kidx * a.n_kv + v_cg * 4 + (PFX && kidx < pfx_len ? pfx_delta : 0);
-      rv[i] = *reinterpret_cast<const u32x2 *>(Vp + e);
-    }
-  };
-  auto store_k = [&](int buf, const u32x4 (&rk)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int q = tid + i * NT, key = q >> 4, c = q & 15;
-      Ks[buf][key * 16 + (c ^ (key & 15))] = rk[i];
-    }
-  };
-  auto store_v = [&](int buf, const u32x2 (&rv)[4]) {
-    const int grp16 = v_qd >> 2, qi = v_qd & 3;
-    const int vkh = qi & 1, halfpos = qi >> 1;
-    const int vchunk = grp16 * 2 + vkh;
-    u32x2 *vs2 = reinterpret_cast<u32x2 *>(Vs[buf]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      u32x2 ev, od;
-      ev.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x05040100u);
-      ev.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x05040100u);
-      od.x = __builtin_amdgcn_perm(rv[1][j], rv[0][j], 0x07060302u);
-      od.y = __builtin_amdgcn_perm(rv[3][j], rv[2][j], 0x07060302u);
-      const int c0 = v_cg * 4 + 2 * j, c1 = c0 + 1;
-      vs2[(c0 * 8 + (vchunk ^ v_swz(c0))) * 2 + halfpos] = ev;
-      vs2[(c1 * 8 + (vchunk ^ v_swz(c1))) * 2 + halfpos] = od;
-    }
-  };
-
-  f32x16 s_cur;          // S of the block whose softmax is next
-  u32x4 pf[2];           // P of the previous block (two k-steps of 16 keys), zero before the first
-  pf[0] = u32x4{0, 0, 0, 0};
-  pf[1] = u32x4{0, 0, 0, 0};
-
-  // S(block kb of the K tile in buffer kbuf)
-  auto qk_block = [&](int kbuf, int kb, f32x16 &s) {
-    const int key = kb * 32 + l32;
-    const u32x4 *kp = &Ks[kbuf][key * 16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s[v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(kp[(2 * ks + kh) ^ (key & 15)]), u4_as_bf16x8(qf[ks]), s, 0, 0, 0);
-  };
-  // O^T += V^T P^T for block kb of the V tile in buffer vbuf
-  auto pv_block = [&](int vbuf, int kb) {
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        const int col = cb * 32 + l32, c = 2 * (kb * 2 + hf) + kh;
-        o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(Vs[vbuf][col * 8 + (c ^ v_swz(col))]),
-                                                        u4_as_bf16x8(pf[hf]), o[cb], 0, 0, 0);
-      }
-  };
-
-  const uint32_t k_base = (uint32_t)(l32 * 256 + ((kh ^ (l32 & 15)) << 4));
-  const uint32_t v_base = (uint32_t)(l32 * 128 + ((kh ^ v_swz(l32)) << 4));
-
-  // One pipeline step, written as 16 chunks of {one MFMA, one LDS fragment read three chunks ahead,
-  // a slice of vector work}; scheduling fences between the chunks keep the compiler from
-  // regrouping them, so the matrix unit gets a new instruction about every eight vector ones and
-  // only a few fragments are live at a time.
-  //   MFMA c < 8: O^T[cb] += V^T fragment (hf, cb) P(j-1)[hf] ; c >= 8: S(j+1) += K fragment c-8
-  //   (S(j) has been consumed by then, so S(j+1) takes over its registers)
-  //   vector slices: block maximum and rescale factor before the first MFMA (the fragment reads
-  //   are in flight meanwhile), two exponentials + pack + row-sum per chunk, then the LDS store
-  //   and the global prefetch that belong to this step (st, ld).
-  auto step_m = [&](auto need_mask, int k0, int kbuf, auto kb_c, int vbuf, auto vb_c, auto &&st, auto &&ld) {
-    constexpr int kb = decltype(kb_c)::value, vb = decltype(vb_c)::value;
-    // fragment addresses: one per-lane base each for K and V^T, the chunk swizzles are XORs with
-    // constants (bits 5..7 of the byte address) and everything else is an immediate offset
-    // (the bases pass through an empty asm so that the XORs stay inside the step, one
-    // instruction next to each read, instead of being hoisted into sixteen registers)
-    uint32_t k_bs = k_base + (uint32_t)(kbuf * (ATT_BN * 256)), v_bs = v_base + (uint32_t)(vbuf * (H * 128));
-    asm volatile("" : "+v"(k_bs), "+v"(v_bs));
-    auto rd = [&](int c) -> u32x4 {
-      const int i = c & 7;
-      if (c >= 8) {
-        // K chunk (2i + kh) ^ (key & 15) of row key = 32 kb + l32
-        const uint32_t ad = (k_bs ^ (uint32_t)(i << 5)) + (uint32_t)(kb * (32 * 256));
-        return *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(&Ks[0][0]) + ad);
-      }
-      // V^T chunk (2 (2 vb + hf) + kh) ^ v_swz(col) of row col = 32 cb + l32
-      const int hf = i >> 2, cb = i & 3;
-      const uint32_t ad = (v_bs ^ (uint32_t)(((2 * vb + hf) ^ cb) << 5)) + (uint32_t)(cb * (32 * 128));
-      return *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(&Vs[0][0]) + ad);
-    };
-    // fragments are requested AH chunks before their MFMA: with eight waves sharing the LDS a read
-    // takes a few hundred cycles to come back, so several per wave have to be in flight
-    u32x4 fr[16];
-#pragma unroll
-    for (int c = 0; c < AH; ++c) fr[c] = rd(c);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (decltype(need_mask)::value) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int kk = k0 + 8 * (v >> 2) + 4 * kh + (v & 3);
-        if (kk > pos || kk >= kend) s_cur[v] = -INFINITY;
-      }
-    }
-    float mx = s_cur[0];
-#pragma unroll
-    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_cur[v]);
-    mx = max_with_other_half(mx);
-    const float m_blk = mx * c_scale;
-    const bool move = __any(m_blk > m_run + a.lazy);
-    const float m_new = move ? fmaxf(m_run, m_blk) : m_run;
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);      // 1 exactly where the maximum stays
-    m_run = m_new;
-    asm volatile("" : "+v"(alpha));
-    __builtin_amdgcn_sched_barrier(0);
-    f32x16 s_nxt;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s_nxt[v] = 0.f;
-    uint32_t pw[8];
-    float rs = 0.f;
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-      if (c + AH < 16) fr[c + AH] = rd(c + AH);
-      const int i = c & 7;
-      if (c >= 8) {
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(fr[c]), u4_as_bf16x8(qf[i]), s_nxt, 0, 0, 0);
-      } else {
-        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u4_as_bf16x8(fr[c]), u4_as_bf16x8(pf[i >> 2]), o[i & 3], 0, 0, 0);
-      }
-      if (c < 8) {
-        // probabilities 2c, 2c+1 as a bf16 pair; the row sum is taken from the ROUNDED values so
-        // that numerator and denominator of the softmax carry the same rounding
-        const float e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * c], c_scale, -m_safe));
-        const float e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * c + 1], c_scale, -m_safe));
-        pw[c] = pack_bf16x2(e0, e1);
-        rs = sum_bf16x2(pw[c], rs);
-        asm volatile("" : "+v"(pw[c]), "+v"(rs));      // keeps this slice in this chunk
-      } else if (c == 8) {
-        l_run = l_run * alpha + rs;
-      } else if (c == 10) {
-        st();
-      } else if (c == 12) {
-        ld();
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (move) {     // after P(j-1) V(j-1) has been accumulated: O_j = (O + P V) * alpha
-#pragma unroll
-      for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[cb][v] *= alpha;
-    }
-    s_cur = s_nxt;
-    pf[0] = u32x4{pw[0], pw[1], pw[2], pw[3]};
-    pf[1] = u32x4{pw[4], pw[5], pw[6], pw[7]};
-  };
-  if (ntiles > 0) {
-    load_k(0, rkA); load_v(0, rvA);
-    store_k(0, rkA); store_v(0, rvA);
-    // the first step multiplies a zero P with whatever V buffer 1 holds: make that finite
-    for (int i = tid; i < H * 8; i += NT) Vs[1][i] = u32x4{0, 0, 0, 0};
-    load_k(1, rkA); load_v(1, rvA);
-    __syncthreads();
-    qk_block(0, 0, s_cur);
-  }
-  // Tile t sits in LDS buffer t & 1.  Its two steps: S(t, block 1) with V(t-1, block 1), then
-  // S(t+1, block 0) with V(t, block 0).  The causal / split-end mask is compiled into a second copy
-  // of the loop that takes over at the first tile that needs it (a branch inside a step would cut
-  // the region the three streams share).
-  auto tile_steps = [&](auto need_mask, int t) {
-    const int b = t & 1;
-    step_m(need_mask, kbeg + t * ATT_BN, b, std::integral_constant<int, 1>{}, b ^ 1, std::integral_constant<int, 1>{},
-           [&] { store_k(b ^ 1, rkA); }, [&] { load_k(t + 2, rkA); });
-    __syncthreads();
-    step_m(need_mask, kbeg + t * ATT_BN + 32, b ^ 1, std::integral_constant<int, 0>{}, b, std::integral_constant<int, 0>{},
-           [&] { store_v(b ^ 1, rvA); }, [&] { load_v(t + 2, rvA); });
-    __syncthreads();
-  };
-  // tiles [0, t_mask) lie entirely below the tile's first query position and inside the split
-  int t_mask = min(ntiles, max(0, (first_pos + 1 - kbeg) / ATT_BN));
-  if (kbeg + t_mask * ATT_BN > kend) --t_mask;
-  t_mask = max(t_mask, 0);
-  wait_all_global_loads();
-  for (int t = 0; t < t_mask; ++t) tile_steps(std::false_type{}, t);
-  for (int t = t_mask; t < ntiles; ++t) tile_steps(std::true_type{}, t);
-  // drain: the last block's probabilities still wait for their V
-  if (ntiles > 0) pv_block((ntiles - 1) & 1, 1);
-
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (tok >= ntok) return;
-  const int64_t row = row0 + tok;
-  if (a.out != nullptr) {
-    const float inv = 1.0f / l_tot;
-    bf16 *op = a.out + row * a.n_q + head * H;
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const int col = cb * 32 + 8 * v4 + 4 * kh;
-        uint2 w;
-        w.x = pack_bf16x2(o[cb][4 * v4] * inv, o[cb][4 * v4 + 1] * inv);
-        w.y = pack_bf16x2(o[cb][4 * v4 + 2] * inv, o[cb][4 * v4 + 3] * inv);
-        *reinterpret_cast<uint2 *>(op + col) = w;
-      }
-  } else {
-    float *pp = a.partials + ((row * a.n_q_heads + head) * a.n_splits + split) * (H + 2);
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const int col = cb * 32 + 8 * v4 + 4 * kh;
-        *reinterpret_cast<float2 *>(pp + col) = make_float2(o[cb][4 * v4], o[cb][4 * v4 + 1]);
-        *reinterpret_cast<float2 *>(pp + col + 2) = make_float2(o[cb][4 * v4 + 2], o[cb][4 * v4 + 3]);
-      }
-    if (kh == 0) {
-      pp[H] = m_run == -INFINITY ? -INFINITY : m_run * LN2;
-      pp[H + 1] = l_tot;
-    }
-  }
-}
-
 bool attn_prefill_mfma_supported(const LayerDims &L) {
   const int G = L.n_q_heads / L.n_kv_heads;
   return L.head_dim == 128 && (G == 1 || G == 2 || G == 4 || G == 8);
@@ -786,18 +504,6 @@ static void launch_attn_nw_any(const AttnArgs &a, int n_work, int G, bool prefix
   } else {
     if (prefix) launch_attn_nw<NW, true, false>(a, n_work, G, s);
     else launch_attn_nw<NW, false, false>(a, n_work, G, s);
-  }
-}
-
-template <bool PFX>
-static void launch_attn_pipe(const AttnArgs &a, int n_work, int G, hipStream_t s) {
-  dim3 grid(n_work);
-  switch (G) {
-    case 1: hipLaunchKernelGGL((attn_prefill_pipe_kernel<1, PFX>), grid, dim3(512), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((attn_prefill_pipe_kernel<2, PFX>), grid, dim3(512), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((attn_prefill_pipe_kernel<4, PFX>), grid, dim3(512), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((attn_prefill_pipe_kernel<8, PFX>), grid, dim3(512), 0, s, a); break;
-    default: break;
   }
 }
 
@@ -851,27 +557,16 @@ void launch_attn_merge16(const float *partials, const LayerDims &L, int T_rows, 
                      n_splits, n_rh, out);
 }
 
-// compact records are written by the unpipelined kernels only
-bool attn_prefill_mfma_compact(int waves, int schedule) { return !(schedule == ATTN_SCHED_PIPELINED && waves == 8); }
-
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, int schedule, bool prefix,
-                              hipStream_t s) {
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool prefix, hipStream_t s) {
   if (n_work == 0) return;
-  if (schedule == ATTN_SCHED_PIPELINED && waves == 8) {
-    if (prefix) launch_attn_pipe<true>(a, n_work, G, s);
-    else launch_attn_pipe<false>(a, n_work, G, s);
-  } else if (waves == 4) {
-    launch_attn_nw_any<4>(a, n_work, G, prefix, s);
-  } else {
-    launch_attn_nw_any<8>(a, n_work, G, prefix, s);
-  }
+  if (waves == 4) launch_attn_nw_any<4>(a, n_work, G, prefix, s);
+  else launch_attn_nw_any<8>(a, n_work, G, prefix, s);
 }
 
-// What the rotation kernel multiplies the queries by for the variant the arguments select: the folded
-// softmax wants them in the exp2 domain, every other kernel applies sm_scale itself.
-float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, int schedule, bool fold) {
-  if (!fold || (schedule == ATTN_SCHED_PIPELINED && waves == 8)) return 1.0f;
-  return LOG2E / sqrtf((float)L.head_dim);
+// What the rotation kernel multiplies the queries by: the folded softmax wants them in the exp2 domain,
+// otherwise the kernel applies sm_scale itself.
+float attn_prefill_mfma_q_scale(const LayerDims &L, bool fold) {
+  return fold ? LOG2E / sqrtf((float)L.head_dim) : 1.0f;
 }
 
 }  // namespace alora

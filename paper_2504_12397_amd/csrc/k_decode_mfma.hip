@@ -16,28 +16,34 @@
 //   * V rows are loaded as 8 columns x 1 key per lane (16 B) for exactly those 8 keys and
 //     transposed inside the lane with byte permutes: MFMA number c uses column 8*i + c of lane
 //     row i, so O^T_c[i][head] = O[column 8*i + c][head].  No LDS, no cross-lane traffic.
+// Every MFMA operand is fp16, as in the prefill kernel: the queries arrive as fp16, the bf16 cache rows are
+// converted in registers on their way into the operands (exact; the V conversion packs two keys of one column into
+// a word, which is the transposition) and the probabilities are packed to fp16.  The kernel waits for memory, the
+// vector ALU has the time, and the rounding of bf16 queries and probabilities was most of the error.
 // Partials (acc, max, sum) per (row, head, split) are merged by the log-sum-exp merge kernel.
 #include "mfma_kernels.h"
 
 namespace alora {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// two floats as an fp16 pair (round toward zero: finite stays finite; exact for bf16 values)
 __device__ __forceinline__ uint32_t dec_pack2(float a, float b) {
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-  bf16x2 p;
-  p[0] = (bf16)a;
-  p[1] = (bf16)b;
-  return __builtin_bit_cast(uint32_t, p);
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+__device__ __forceinline__ float dec_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float dec_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+__device__ __forceinline__ u32x4 dec_bf16x8_to_f16x8(u32x4 r) {
+  return u32x4{dec_pack2(dec_lo(r.x), dec_hi(r.x)), dec_pack2(dec_lo(r.y), dec_hi(r.y)),
+               dec_pack2(dec_lo(r.z), dec_hi(r.z)), dec_pack2(dec_lo(r.w), dec_hi(r.w))};
 }
 
-// acc + lo + hi of a packed bf16 pair
+// acc + lo + hi of a packed fp16 pair
 __device__ __forceinline__ float dec_sum2(uint32_t pair, float acc) {
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
-                                         false);
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, pair), __builtin_bit_cast(half2_t, 0x3c003c00u), acc, false);
 }
 
 constexpr float DEC_LOG2E = 1.4426950408889634f;
@@ -117,8 +123,8 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
       sc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[u][s]),
-                                                        __builtin_bit_cast(bf16x8, qf[s]), sc[u], 0, 0, 0);
+        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, dec_bf16x8_to_f16x8(kc[u][s])),
+                                                       __builtin_bit_cast(f16x8, qf[s]), sc[u], 0, 0, 0);
     }
     if (k0 + 32 > kend) {
 #pragma unroll
@@ -151,17 +157,15 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       // column 8*j + c of the 8 keys this lane loaded: element c of each 16-byte row
-      const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
       const int w = c >> 1;
-      const u32x4 vf = u32x4{__builtin_amdgcn_perm(vc[0][1][w], vc[0][0][w], sel),
-                             __builtin_amdgcn_perm(vc[0][3][w], vc[0][2][w], sel),
-                             __builtin_amdgcn_perm(vc[1][1][w], vc[1][0][w], sel),
-                             __builtin_amdgcn_perm(vc[1][3][w], vc[1][2][w], sel)};
+      auto el = [&](uint32_t word) { return (c & 1) ? dec_hi(word) : dec_lo(word); };
+      const u32x4 vf = u32x4{dec_pack2(el(vc[0][0][w]), el(vc[0][1][w])), dec_pack2(el(vc[0][2][w]), el(vc[0][3][w])),
+                             dec_pack2(el(vc[1][0][w]), el(vc[1][1][w])), dec_pack2(el(vc[1][2][w]), el(vc[1][3][w]))};
       f32x4 oc = o[c];
 #pragma unroll
       for (int v = 0; v < 4; ++v) oc[v] *= alpha;
-      o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf),
-                                                     oc, 0, 0, 0);
+      o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, vf), __builtin_bit_cast(f16x8, pf),
+                                                    oc, 0, 0, 0);
     }
   }
 

@@ -441,6 +441,16 @@ __attribute__((amdgpu_waves_per_eu((WEAVE && SEG) ? 2 : 1))) void gemm_mfma_kern
         if (kind == 2) {
           lo[0] = (bf16)u.x; lo[1] = (bf16)u.y;
           hi[0] = (bf16)w.x; hi[1] = (bf16)w.y;
+        } else if (kind == 0 && g.q_half) {
+          // queries as fp16 for the MFMA prefill attention kernel: same arithmetic, same two bytes per element
+          typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+          half2_t l2, h2;
+          l2[0] = (_Float16)((u.x * cs[i].x - w.x * cs[i].y) * qs);
+          l2[1] = (_Float16)((u.y * cs[i].z - w.y * cs[i].w) * qs);
+          h2[0] = (_Float16)((w.x * cs[i].x + u.x * cs[i].y) * qs);
+          h2[1] = (_Float16)((w.y * cs[i].z + u.y * cs[i].w) * qs);
+          lo = __builtin_bit_cast(bf16x2_t, l2);
+          hi = __builtin_bit_cast(bf16x2_t, h2);
         } else {
           lo[0] = (bf16)((u.x * cs[i].x - w.x * cs[i].y) * qs);
           lo[1] = (bf16)((u.y * cs[i].z - w.y * cs[i].w) * qs);

@@ -244,7 +244,7 @@ template <typename T, bool MULTI>      // MULTI: Y arrives as several partial su
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, int n_parts,
                                                          int64_t part_stride, LayerDims L, RowMeta rm,
                                                          const float2 *__restrict__ table, float q_scale,
-                                                         T *__restrict__ Q, T *__restrict__ cacheK,
+                                                         int q_half, T *__restrict__ Q, T *__restrict__ cacheK,
                                                          T *__restrict__ cacheV) {
   const int row = blockIdx.x, slot_id = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int h = L.head_dim, h2 = h >> 1;
@@ -277,8 +277,21 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     for (int c = lane; c < h2; c += 64) {
       const float u = ysum(y + base + c), w = ysum(y + base + c + h2);
       const float2 cs = tab[c];
-      dst[c] = from_f32<T>((u * cs.x - w * cs.y) * qs);
-      dst[c + h2] = from_f32<T>((w * cs.x + u * cs.y) * qs);
+      const float lo = (u * cs.x - w * cs.y) * qs, hi = (w * cs.x + u * cs.y) * qs;
+      if (is_q && q_half == 1) {
+        // the MFMA attention kernels want their queries as fp16
+        _Float16 *dq = reinterpret_cast<_Float16 *>(Q) + (int64_t)row * L.n_q + head * h;
+        dq[c] = (_Float16)lo;
+        dq[c + h2] = (_Float16)hi;
+      } else if (is_q && q_half == 2) {
+        // the plain attention kernel keeps them in fp32
+        float *dq = reinterpret_cast<float *>(Q) + (int64_t)row * L.n_q + head * h;
+        dq[c] = lo;
+        dq[c + h2] = hi;
+      } else {
+        dst[c] = from_f32<T>(lo);
+        dst[c + h2] = from_f32<T>(hi);
+      }
     }
   } else {
     const int head = slot_id - L.n_q_heads - L.n_kv_heads;
@@ -290,20 +303,20 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
 
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
-                        const float2 *rope_table, float q_scale, T *Q, T *cacheK, T *cacheV, hipStream_t s) {
+                        const float2 *rope_table, float q_scale, int q_half, void *Q, T *cacheK, T *cacheV, hipStream_t s) {
   if (T_rows == 0) return;
   dim3 grid(T_rows, (L.n_q_heads + 2 * L.n_kv_heads + 3) / 4);
   if (n_parts > 1)
     hipLaunchKernelGGL((rope_append_kernel<T, true>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
-                       rope_table, q_scale, Q, cacheK, cacheV);
+                       rope_table, q_scale, q_half, (T *)Q, cacheK, cacheV);
   else
     hipLaunchKernelGGL((rope_append_kernel<T, false>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
-                       rope_table, q_scale, Q, cacheK, cacheV);
+                       rope_table, q_scale, q_half, (T *)Q, cacheK, cacheV);
 }
-template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float,
-                                        float *, float *, float *, hipStream_t);
-template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float,
-                                       bf16 *, bf16 *, bf16 *, hipStream_t);
+template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float, int,
+                                        void *, float *, float *, hipStream_t);
+template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float, int,
+                                       void *, bf16 *, bf16 *, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // plain split-KV attention (Eq.1 / Eq.4, causal, GQA).  One wave per (row, kv head, chunk of
@@ -314,7 +327,7 @@ template void launch_rope_append<bf16>(const float *, int, const LayerDims &, Ro
 #define ATT_DMAX 4     // head_dim <= 256
 
 template <typename T>
-__global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ Q, const T *__restrict__ cacheK,
+__global__ __launch_bounds__(64) void attn_partial_kernel(const float *__restrict__ Q, const T *__restrict__ cacheK,
                                                           const T *__restrict__ cacheV,
                                                           const SeqMeta *__restrict__ seqs, RowMeta rm,
                                                           LayerDims L, int n_splits, float *__restrict__ part) {
@@ -335,7 +348,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const T *__restrict__ 
   const float sm_scale = 1.0f / sqrtf((float)h);
   for (int i = lane; i < ng * h; i += 64) {
     int gi = i / h, c = i % h;
-    qs[gi * h + c] = to_f32<T>(Q[(int64_t)row * L.n_q + (g * G + g0 + gi) * h + c]) * sm_scale;
+    qs[gi * h + c] = Q[(int64_t)row * L.n_q + (g * G + g0 + gi) * h + c] * sm_scale;
   }
   __syncthreads();
   float m[ATT_GMAX], l[ATT_GMAX], acc[ATT_GMAX][ATT_DMAX];
@@ -457,7 +470,7 @@ size_t attn_plain_partial_floats(const LayerDims &L, int T_rows, int n_splits) {
 }
 
 template <typename T>
-void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
+void launch_attn_plain(const float *Q, const T *cacheK, const T *cacheV, const SeqMeta *seqs, RowMeta rm,
                        const LayerDims &L, int T_rows, int n_splits, float *partials, hipStream_t s) {
   if (T_rows == 0) return;
   const int G = L.n_q_heads / L.n_kv_heads;
@@ -468,7 +481,7 @@ void launch_attn_plain(const T *Q, const T *cacheK, const T *cacheV, const SeqMe
 }
 template void launch_attn_plain<float>(const float *, const float *, const float *, const SeqMeta *, RowMeta,
                                        const LayerDims &, int, int, float *, hipStream_t);
-template void launch_attn_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, const SeqMeta *, RowMeta,
+template void launch_attn_plain<bf16>(const float *, const bf16 *, const bf16 *, const SeqMeta *, RowMeta,
                                       const LayerDims &, int, int, float *, hipStream_t);
 
 template <typename T>

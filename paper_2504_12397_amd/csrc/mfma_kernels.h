@@ -38,6 +38,7 @@ struct GemmArgs {
   const int64_t *rope_slot;    // [M] pool rows
   const float2 *rope_table;    // [positions, 64] (cos, sin)
   float q_scale;               // multiplies the rotated queries
+  int q_half;                  // 1: Qout receives fp16 (the MFMA prefill attention kernel's operand type) instead of bf16
   bf16 *Qout, *cacheK, *cacheV;
 };
 bool gemm_mfma_rope_supported(const GemmArgs &g, int head_dim);
@@ -65,7 +66,7 @@ void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s);
 
 // Prefill attention (Eq.1 with the causal mask) over the pool cache.
 struct AttnArgs {
-  const bf16 *Q;            // [T, n_q] rotated queries of the new rows
+  const _Float16 *Q;        // [T, n_q] rotated queries of the new rows, as fp16
   const bf16 *K, *V;        // pool [tokens, n_kv]
   const SeqMeta *seqs;
   const int4 *work;         // per workgroup: (sequence or -1, first new token of the q-tile, kv head, key split)
@@ -80,18 +81,12 @@ struct AttnArgs {
 };
 constexpr int ATTN_REC16 = 272;      // 128 fp16 + (reference, row sum, scale) as fp32 + 4 bytes of padding
 bool attn_prefill_mfma_supported(const LayerDims &L);
-bool attn_prefill_mfma_compact(int waves, int schedule);
 void launch_attn_merge16(const float *partials, const LayerDims &L, int T_rows, int n_splits, bf16 *out, hipStream_t s);
 int attn_prefill_mfma_tokens_per_tile(const LayerDims &L, int waves);      // waves per workgroup: 8 or 4
-// How one workgroup orders its work: every wave runs K Q^T, softmax, P V one after the other and the
-// overlap of matrix and vector work is left to the two waves that share a SIMD (SIMPLE), or each wave
-// interleaves the three instruction streams of neighbouring blocks itself (PIPELINED, 8 waves).
-enum { ATTN_SCHED_PIPELINED = 0, ATTN_SCHED_SIMPLE = 1 };
-// with a.q_prescaled the SIMPLE kernels run their folded-softmax form; the PIPELINED variant
-// needs unscaled queries (attn_prefill_mfma_q_scale tells the rotation kernel which it is)
-void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, int schedule, bool prefix,
-                              hipStream_t s);
-float attn_prefill_mfma_q_scale(const LayerDims &L, int waves, int schedule, bool fold);
+// with a.q_prescaled the kernels run their folded-softmax form (attn_prefill_mfma_q_scale tells the rotation
+// kernel what to multiply the queries by)
+void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, bool prefix, hipStream_t s);
+float attn_prefill_mfma_q_scale(const LayerDims &L, bool fold);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
 // One workgroup of the decode kernel: the query heads (of one GQA group) of up to 16 / G rows
@@ -108,7 +103,7 @@ struct DecItem {
   int32_t rows[16];
 };
 struct DecodeArgs {
-  const bf16 *Q;            // [rows, n_q]
+  const _Float16 *Q;        // [rows, n_q] rotated queries as fp16
   const bf16 *K, *V;        // pool [tokens, n_kv]
   const SeqMeta *seqs;
   RowMeta rm;               // seq and pos of every row
