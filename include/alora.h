@@ -211,6 +211,22 @@ alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_k
                           const void *x_tok, const int32_t *k_per_seq,
                           const int32_t *adapter_per_seq, int32_t B, void *attn_out, void *stream);
 
+/* alora_decode for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and -- bit for bit -- the same results as
+ * alora_decode, but the call allocates nothing, frees nothing, synchronises nothing and copies nothing from host
+ * memory: its workspace, the per-sequence records (passed to the device as kernel arguments), the decode work
+ * list and the rotary lines of the new rows live in one static device array of 32 MiB (33554432 bytes) that every
+ * GPU the library runs on holds until the process ends.  A call that needs more (roughly: 5 fp32 copies of the
+ * [B, N_q + 2 N_kv] projection plus B * n_q_heads * key-splits partial attention records; 64 sequences of the
+ * 8B-class shape over 16k-token caches take 14 MiB) is rejected with ALORA_ECAPACITY before anything is launched,
+ * as is B > 4096.  Shared prefixes are not taken (ALORA_EINVAL); the "profile" option is ignored.  All calls on
+ * one GPU -- from any context, stream or thread -- share that GPU's array and it keeps the last call's contents:
+ * calls that overlap in time on one GPU race, so serialise them (one stream, or events).  Nothing in the array
+ * has to start at zero, and nothing is cleared. */
+alora_status alora_decode_static(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
+                                 const void *x_tok, const int32_t *k_per_seq,
+                                 const int32_t *adapter_per_seq, int32_t B, void *attn_out, void *stream);
+
 /* A run of n_steps decode steps (the short generations of an adapter: Section 3 times 16-token
  * evaluations) with the per-sequence arrays validated and staged once: the same result as n_steps
  * alora_decode calls, step t reading x_steps[t] and writing attn_out[t], every sequence growing by

@@ -18,7 +18,7 @@ ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDT
 ALORA_F32, ALORA_BF16 = 0, 1
 
 EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
-           "alora_profile_read", "alora_profile_reset", "alora_prefill", "alora_decode", "alora_decode_steps", "alora_stack_prefill", "alora_lm_head"]
+           "alora_profile_read", "alora_profile_reset", "alora_prefill", "alora_decode", "alora_decode_static", "alora_decode_steps", "alora_stack_prefill", "alora_lm_head"]
 KERNELS = ["lm_head", "lm_argmax", "prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
            "mlp_norm", "gate_up", "silu_mul", "down_proj"]
 
@@ -68,6 +68,8 @@ def load_library() -> C.CDLL:
     lib.alora_decode.restype = C.c_int
     lib.alora_decode.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
                                  C.c_int32, C.c_void_p, C.c_void_p]
+    lib.alora_decode_static.restype = C.c_int
+    lib.alora_decode_static.argtypes = lib.alora_decode.argtypes
     lib.alora_decode_steps.restype = C.c_int
     lib.alora_decode_steps.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.POINTER(KVCacheDesc), C.c_void_p, i32p, i32p,
                                        C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -256,6 +258,17 @@ def alora_decode(ctx: Context, layer: Layer, cache: KVCache, x_tok: torch.Tensor
     p = C.POINTER(C.c_int32)
     st = _lib.alora_decode(ctx._h, C.byref(layer.desc), C.byref(cache.desc), _ptr(x_tok), kk.ctypes.data_as(p),
                            ad.ctypes.data_as(p), B, _ptr(attn_out), _stream_ptr(stream))
+    ctx._check(st)
+    return attn_out
+
+
+def alora_decode_static(ctx: Context, layer: Layer, cache: KVCache, x_tok: torch.Tensor, k_per_seq: Sequence[int],
+                        adapter_per_seq: Sequence[int], attn_out: torch.Tensor, stream=None) -> torch.Tensor:
+    """alora_decode through the entry point that allocates nothing; the caller brings the output buffer."""
+    kk, ad = _i32(k_per_seq), _i32(adapter_per_seq)
+    p = C.POINTER(C.c_int32)
+    st = _lib.alora_decode_static(ctx._h, C.byref(layer.desc), C.byref(cache.desc), _ptr(x_tok), kk.ctypes.data_as(p),
+                                  ad.ctypes.data_as(p), len(kk), _ptr(attn_out), _stream_ptr(stream))
     ctx._check(st)
     return attn_out
 

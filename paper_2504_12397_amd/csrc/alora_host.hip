@@ -16,9 +16,38 @@
 
 using namespace alora;
 
+// ---- scratch of the entry point that may not allocate (alora_decode_static) --------------------------------
+// One array per GPU the library is loaded on, alive until the process ends.  Host code never uses this name as
+// an address: alora_create asks the runtime for the array's device address once per context
+// (hipGetSymbolAddress, with the context's device current) and everything below works with that pointer.
+constexpr size_t SCRATCH_BYTES = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+
 namespace {
 
 constexpr int N_SLOTS = 8;
+
+// per-sequence records travel to the device as kernel arguments (no staging buffer, no copy from host memory)
+constexpr int STAGE_SEQS = 32;
+struct SeqChunk { SeqMeta m[STAGE_SEQS]; };
+__global__ void stage_seqs_kernel(SeqChunk c, int n, SeqMeta *dst) {
+  if ((int)threadIdx.x < n) dst[threadIdx.x] = c.m[threadIdx.x];
+}
+// the work list of the decode attention kernel for sequences without shared prefixes, in the order the host
+// builds it: item ((row * n_kv_heads) + g) * n_own + split covers split `split` of row `row`, kv head g
+__global__ void make_decode_items_kernel(DecItem *items, int n_items, int n_kv_heads, int n_own) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_items) return;
+  DecItem it{};
+  it.n_rows = 1;
+  it.split = i % n_own;
+  it.g = (i / n_own) % n_kv_heads;
+  it.n_splits = n_own;
+  it.part = it.split;
+  it.shared = 0;
+  it.rows[0] = i / (n_own * n_kv_heads);
+  items[i] = it;
+}
 
 struct MetaSlot {
   char *host = nullptr;      // pinned
@@ -51,6 +80,7 @@ struct alora_ctx {
   std::string err;
   char *ws = nullptr;
   size_t ws_cap = 0;
+  unsigned char *scratch_dev = nullptr;      // device address of the static scratch array on this context's GPU
   float2 *rope = nullptr;
   int rope_pos = 0, rope_half = 0;
   float rope_theta = 0.f;
@@ -340,6 +370,9 @@ struct Workspace {
   int n_ditems = 0;
   const float *scale_dev = nullptr;  // [n_adapters] s_a on the device (adapters of W_o / the MLP)
   bool any_adapter = false;
+  const float2 *rope = nullptr;      // rotary table: one line per position, or (rope_by_row) one per packed row
+  bool rope_by_row = false;
+  float2 *rope_rows = nullptr;       // where the per-row table is built after row preparation
 };
 
 int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
@@ -406,6 +439,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
                           (const T *)ly->A, rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
     }
   }
+  if (w.rope_by_row) launch_rope_rows(w.rope_rows, w.rm.pos, pl.T, L.head_dim / 2, ly->rope_theta, s);
   // the MFMA attention kernels (prefill and decode) take their queries as fp16 (every operand of its matrix products is fp16),
   // in its folded-softmax form premultiplied by sm_scale * log2(e)
   // (the plain attention kernel reads them as fp32: the Q buffer holds four bytes per element)
@@ -433,8 +467,9 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.row_adapter = w.rm.adapter;
       // many rows, unsplit reduction, one head per column tile: rotation and cache append happen in the
       // projection's epilogue and the fp32 projection never goes to memory
-      if (ctx->opt_gemm_tile == 0 && ctx->opt_rope_fuse && q_half && gemm_mfma_rope_supported(g, L.head_dim)) {
-        g.rope_pos = w.rm.pos; g.rope_slot = w.rm.slot; g.rope_table = ctx->rope; g.q_scale = q_scale;
+      if (ctx->opt_gemm_tile == 0 && ctx->opt_rope_fuse && q_half && !w.rope_by_row &&
+          gemm_mfma_rope_supported(g, L.head_dim)) {
+        g.rope_pos = w.rm.pos; g.rope_slot = w.rm.slot; g.rope_table = w.rope; g.q_scale = q_scale;
         g.Qout = (bf16 *)w.Q; g.cacheK = (bf16 *)cache->k; g.cacheV = (bf16 *)cache->v;
         g.q_half = q_half ? 1 : 0;
         launch_gemm_mfma(g, GEMM_EPI_ROPE, s);
@@ -449,7 +484,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
   }
   if (!rope_fused) {
     ProfScope p(ctx, K_ROPE, s);
-    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, ctx->rope, q_scale, q_mode, w.Q,
+    launch_rope_append<T>(w.Y, mfma ? w.k_splits + ((pl.any_adapter && w.lora_split) ? 1 : 0) : 1, L, w.rm, pl.T, w.rope, w.rope_by_row, q_scale, q_mode, w.Q,
                           (T *)cache->k, (T *)cache->v, s);
   }
   const bool direct = w.attn_mfma && std::is_same<T, bf16>::value && n_splits == 1;
@@ -638,7 +673,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
 
 alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, alora_kv_cache *caches,
                  const void *x, const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, void *out,
-                 void *stream, bool stack, bool decode = false, int n_steps = 1) {
+                 void *stream, bool stack, bool decode = false, int n_steps = 1, bool use_static = false) {
   if (!ctx) return ALORA_EINVAL;
   ctx->err.clear();
   if (n_layers < 1) return fail(ctx, ALORA_EINVAL, "n_layers = %d must be at least 1", n_layers);
@@ -666,8 +701,21 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (st != ALORA_OK) return st;
   if (pl.T > 0 && (!x || !out)) return fail(ctx, ALORA_EINVAL, "x / out is NULL");
   if (pl.T == 0) return ALORA_OK;
-  if (ctx->device < 0)
+  if (use_static && pl.any_prefix)
+    return fail(ctx, ALORA_EINVAL, "alora_decode_static does not take shared prefixes (prefix_len must be NULL or all zero)");
+  const size_t esz0 = layers[0].dtype == ALORA_BF16 ? 2 : 4;
+  if (ctx->device < 0) {
+    // a validation-only context still answers the size question of the static entry point
+    if (use_static) {
+      const int ns = std::max(1, std::min(64, pl.max_len / 1024));      // upper bound on the key splits
+      const size_t need = layout_workspace(nullptr, L, pl.T, esz0, ns, 8, 0, false).bytes + (size_t)B * sizeof(SeqMeta) +
+                          (size_t)pl.T * L.n_kv_heads * ns * sizeof(DecItem) + (size_t)pl.T * (L.head_dim / 2) * sizeof(float2) + 1024;
+      if (need > SCRATCH_BYTES)
+        return fail(ctx, ALORA_ECAPACITY, "alora_decode_static: this call needs up to %zu bytes of scratch, the static buffer holds %zu",
+                    need, SCRATCH_BYTES);
+    }
     return fail(ctx, ALORA_EHIP, "arguments are valid, but this is a validation-only context (device -1)");
+  }
 
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   hipStream_t s = (hipStream_t)stream;
@@ -682,6 +730,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   // sequences name shared prefixes -- per (group of up to 16 / G rows with the same prefix, kv head)
   // n_shared items over that prefix.  Every (row, head) ends up with n_own + n_shared partial records.
   std::vector<DecItem> ditems;
+  int n_static_items = 0, n_static_n_own = 1;
   if (decode_mfma) {
     const int G = L.n_q_heads / L.n_kv_heads;
     const int pack = std::max(1, 16 / G);
@@ -727,6 +776,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     }
     n_splits = n_own + n_shared;
     DecItem it{};
+    n_static_items = pl.T * L.n_kv_heads * n_own;     // (static entry point: the same list, built on the device)
+    if (!use_static) {
     for (const auto &rows : chunks)
       for (int g = 0; g < L.n_kv_heads; ++g)
         for (int sp = 0; sp < n_shared; ++sp) {
@@ -743,6 +794,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
           it.rows[0] = row;
           ditems.push_back(it);
         }
+    }
+    n_static_n_own = n_own;
   }
   if (attn_mfma && ctx->opt_splits == 0) {
     // one workgroup per (q-tile, kv head, split): aim at one full wave of workgroups over the chip,
@@ -765,6 +818,58 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (mfma && ctx->opt_gemm_splits > 0) k_segments = L.d % (64 * ctx->opt_gemm_splits) == 0 ? ctx->opt_gemm_splits : 1;
   const int k_splits = (k_segments > 1 && gemm_mfma_split_segments(pl.T, L.n_qkv, ctx->n_cu)) ? k_segments : 1;
   Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
+  if (use_static) {
+    // Everything the call needs beyond its inputs and outputs lives in the static scratch array of this GPU:
+    //   [ workspace | per-sequence records | decode work list | rotary lines, one per row ]
+    // No allocation, no staging copy: the records travel as kernel arguments, the work list and the rotary lines
+    // are computed on the device.  Nothing in there has to start at zero (every byte a kernel reads was written
+    // by a kernel of this call), so nothing is cleared.
+    const size_t ws_bytes = (probe.bytes + 255) & ~(size_t)255;
+    const size_t seq_b = ((size_t)B * sizeof(SeqMeta) + 255) & ~(size_t)255;
+    const size_t item_b = ((size_t)n_static_items * sizeof(DecItem) + 255) & ~(size_t)255;
+    const size_t rope_b = (size_t)pl.T * (L.head_dim / 2) * sizeof(float2);
+    const size_t need = ws_bytes + seq_b + item_b + rope_b;
+    if (need > SCRATCH_BYTES)
+      return fail(ctx, ALORA_ECAPACITY, "alora_decode_static: this call needs %zu bytes of scratch, the static buffer holds %zu",
+                  need, SCRATCH_BYTES);
+    if (!ctx->scratch_dev) return fail(ctx, ALORA_EHIP, "the static scratch array has no device address on this context");
+    char *base = (char *)ctx->scratch_dev;
+    SeqMeta *seqs_dev = (SeqMeta *)(base + ws_bytes);
+    DecItem *items_dev = (DecItem *)(base + ws_bytes + seq_b);
+    for (int b0 = 0; b0 < B; b0 += STAGE_SEQS) {
+      SeqChunk c;
+      const int n = std::min(STAGE_SEQS, B - b0);
+      memcpy(c.m, pl.seqs.data() + b0, (size_t)n * sizeof(SeqMeta));
+      hipLaunchKernelGGL(stage_seqs_kernel, dim3(1), dim3(64), 0, s, c, n, seqs_dev + b0);
+    }
+    if (decode_mfma && n_static_items > 0)
+      hipLaunchKernelGGL(make_decode_items_kernel, dim3((n_static_items + 255) / 256), dim3(256), 0, s, items_dev,
+                         n_static_items, L.n_kv_heads, n_static_n_own);
+    Workspace w = layout_workspace(base, L, pl.T, esz, n_splits, k_splits, 0, false);
+    w.mfma = mfma;
+    w.k_splits = k_splits;
+    w.k_segments = k_segments;
+    w.lora_split = (k_splits > 1 && ctx->opt_lora_split != 2) || ctx->opt_lora_split == 1 ? 1 : 0;
+    w.attn_mfma = false;
+    w.decode_mfma = decode_mfma;
+    w.attn_waves = attn_waves;
+    w.ditems = items_dev;
+    w.n_ditems = decode_mfma ? n_static_items : 0;
+    w.any_adapter = pl.any_adapter;
+    w.rope_by_row = true;
+    w.rope_rows = (float2 *)(base + ws_bytes + seq_b + item_b);
+    w.rope = w.rope_rows;
+    const int saved_profile = ctx->opt_profile;
+    ctx->opt_profile = 0;             // the event brackets of the profiling option create events: not here
+    if (layers[0].dtype == ALORA_BF16)
+      attention_block<bf16>(ctx, &layers[0], L, &caches[0], (const bf16 *)x, pl, seqs_dev, w, true, n_splits, true, 0, (bf16 *)out, s);
+    else
+      attention_block<float>(ctx, &layers[0], L, &caches[0], (const float *)x, pl, seqs_dev, w, true, n_splits, true, 0, (float *)out, s);
+    ctx->opt_profile = saved_profile;
+    HIP_TRY(ctx, hipGetLastError());
+    for (int b = 0; b < B; ++b) caches[0].seq_len[b] += 1;
+    return ALORA_OK;
+  }
   st = ensure_workspace(ctx, probe.bytes);
   if (st != ALORA_OK) return st;
   st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
@@ -861,6 +966,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.n_ditems = (int)ditems.size();
   w.scale_dev = (const float *)(slot->dev + seq_bytes + work_bytes);
   w.any_adapter = pl.any_adapter;
+  w.rope = ctx->rope;
 
   const bool bf = layers[0].dtype == ALORA_BF16;
   if (!stack) {
@@ -924,6 +1030,13 @@ alora_status alora_create(alora_ctx **out, int device) {
   if (hipSetDevice(device) != hipSuccess) return ALORA_EHIP;
   alora_ctx *ctx = new alora_ctx();
   ctx->device = device;
+  // the device address of this GPU's copy of the static scratch array (the array's name is not one)
+  void *sp = nullptr;
+  if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || sp == nullptr) {
+    delete ctx;
+    return ALORA_EHIP;
+  }
+  ctx->scratch_dev = (unsigned char *)sp;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->n_cu = prop.multiProcessorCount;
   *out = ctx;
@@ -1137,6 +1250,17 @@ alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_k
   std::vector<int32_t> cu(B + 1);
   for (int b = 0; b <= B; ++b) cu[b] = b;
   return run(ctx, layer, 1, cache, x_tok, cu.data(), k_per_seq, adapter_per_seq, B, attn_out, stream, false, true);
+}
+
+alora_status alora_decode_static(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache, const void *x_tok,
+                                 const int32_t *k_per_seq, const int32_t *adapter_per_seq, int32_t B, void *attn_out,
+                                 void *stream) {
+  if (!ctx) return ALORA_EINVAL;
+  if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
+  if (B > 4096) return fail(ctx, ALORA_ECAPACITY, "alora_decode_static takes at most 4096 sequences per call (B = %d)", B);
+  int32_t cu[4097];
+  for (int b = 0; b <= B; ++b) cu[b] = b;
+  return run(ctx, layer, 1, cache, x_tok, cu, k_per_seq, adapter_per_seq, B, attn_out, stream, false, true, 1, true);
 }
 
 alora_status alora_decode_steps(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,

@@ -62,6 +62,8 @@ __device__ __forceinline__ float wave_max(float v) {
 enum GemmEpilogue { EPI_F32_LORA = 0, EPI_STORE = 1, EPI_STORE_RESIDUAL = 2 };
 
 void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipStream_t s);
+// one table line per row (entry row * half_dim + c belongs to position pos[row])
+void launch_rope_rows(float2 *table, const int32_t *pos, int n_rows, int half_dim, float theta, hipStream_t s);
 
 template <typename T>
 void launch_prep_rows(const T *x, const T *gain, float eps, int T_rows, int d, const SeqMeta *seqs,
@@ -82,7 +84,8 @@ void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, i
 // 2: as fp32 (the plain attention kernel)
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
-                        const float2 *rope_table, float q_scale, int q_mode, void *Q, T *cacheK, T *cacheV, hipStream_t s);
+                        const float2 *rope_table, bool table_by_row, float q_scale, int q_mode, void *Q, T *cacheK,
+                        T *cacheV, hipStream_t s);
 
 // C[M, N] += gated low-rank term (Eq.6) of one linear: s_a B_a (A_{a,part} x) for rows with row_adapter >= 0
 template <typename T>

@@ -20,6 +20,26 @@ __global__ void rope_table_kernel(float2 *table, int n_pos, int half, double log
   table[i] = make_float2((float)cs, (float)sn);
 }
 
+// The same entries for the positions of given rows only: table[row * half + c] for position pos[row] (callers
+// that may not allocate a table of all positions keep one line per row).  Same arithmetic, same bits.
+__global__ void rope_rows_kernel(float2 *table, const int32_t *__restrict__ pos, int n_rows, int half, double log2_theta) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n_rows * half) return;
+  int row = (int)(i / half), c = (int)(i % half);
+  double inv = exp2(-(double)c / (double)half * log2_theta);
+  double ang = (double)pos[row] * inv;
+  double sn, cs;
+  sincos(ang, &sn, &cs);
+  table[i] = make_float2((float)cs, (float)sn);
+}
+
+void launch_rope_rows(float2 *table, const int32_t *pos, int n_rows, int half_dim, float theta, hipStream_t s) {
+  int64_t n = (int64_t)n_rows * half_dim;
+  if (n == 0) return;
+  hipLaunchKernelGGL(rope_rows_kernel, dim3((int)((n + 255) / 256)), dim3(256), 0, s, table, pos, n_rows, half_dim,
+                     log2((double)theta));
+}
+
 void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipStream_t s) {
   int64_t n = (int64_t)n_pos * half_dim;
   if (n == 0) return;
@@ -243,8 +263,9 @@ template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, 
 template <typename T, bool MULTI>      // MULTI: Y arrives as several partial sums
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ Y, int n_parts,
                                                          int64_t part_stride, LayerDims L, RowMeta rm,
-                                                         const float2 *__restrict__ table, float q_scale,
-                                                         int q_half, T *__restrict__ Q, T *__restrict__ cacheK,
+                                                         const float2 *__restrict__ table, int table_by_row,
+                                                         float q_scale, int q_half, T *__restrict__ Q,
+                                                         T *__restrict__ cacheK,
                                                          T *__restrict__ cacheV) {
   const int row = blockIdx.x, slot_id = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int h = L.head_dim, h2 = h >> 1;
@@ -269,7 +290,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     const bool is_q = slot_id < L.n_q_heads;
     const int head = is_q ? slot_id : slot_id - L.n_q_heads;
     const int base = (is_q ? 0 : L.n_q) + head * h;
-    const float2 *tab = table + (int64_t)rm.pos[row] * h2;
+    const float2 *tab = table + (int64_t)(table_by_row ? row : rm.pos[row]) * h2;
     T *dst = is_q ? Q + (int64_t)row * L.n_q + head * h : cacheK + rm.slot[row] * L.n_kv + head * h;
     // q_scale: the attention kernel that follows may want its queries premultiplied (softmax scale and
     // log2 e, so that its scores come out of the MFMA ready for exp2); keys are never scaled
@@ -303,19 +324,20 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
 
 template <typename T>
 void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta rm, int T_rows,
-                        const float2 *rope_table, float q_scale, int q_half, void *Q, T *cacheK, T *cacheV, hipStream_t s) {
+                        const float2 *rope_table, bool table_by_row, float q_scale, int q_half, void *Q, T *cacheK,
+                        T *cacheV, hipStream_t s) {
   if (T_rows == 0) return;
   dim3 grid(T_rows, (L.n_q_heads + 2 * L.n_kv_heads + 3) / 4);
   if (n_parts > 1)
     hipLaunchKernelGGL((rope_append_kernel<T, true>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
-                       rope_table, q_scale, q_half, (T *)Q, cacheK, cacheV);
+                       rope_table, table_by_row ? 1 : 0, q_scale, q_half, (T *)Q, cacheK, cacheV);
   else
     hipLaunchKernelGGL((rope_append_kernel<T, false>), grid, dim3(256), 0, s, Y, n_parts, (int64_t)T_rows * L.n_qkv, L, rm,
-                       rope_table, q_scale, q_half, (T *)Q, cacheK, cacheV);
+                       rope_table, table_by_row ? 1 : 0, q_scale, q_half, (T *)Q, cacheK, cacheV);
 }
-template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float, int,
+template void launch_rope_append<float>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, bool, float, int,
                                         void *, float *, float *, hipStream_t);
-template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, float, int,
+template void launch_rope_append<bf16>(const float *, int, const LayerDims &, RowMeta, int, const float2 *, bool, float, int,
                                        void *, bf16 *, bf16 *, hipStream_t);
 
 // ---------------------------------------------------------------------------------------

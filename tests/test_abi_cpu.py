@@ -244,3 +244,24 @@ def test_tail_adapter_groups_are_checked_as_a_whole(ab, vctx):
     assert go(B_down=P) == "ALORA_EINVAL"
     assert go(A_gu=P, B_gate=P) == "ALORA_EINVAL"
     assert go(A_o=P, B_o=P, n_adapters=0, rank=0) == "ALORA_EINVAL"
+
+
+def test_static_decode_rejects_what_its_scratch_cannot_hold(ab, vctx):
+    """alora_decode_static checks its arguments like alora_decode and, on top, that the call fits the static
+    scratch array (32 MiB); both before anything would be launched."""
+    p = C.POINTER(C.c_int32)
+
+    def go(B, **over):
+        off = [100 * b for b in range(B)]
+        desc, cache, cu, k, a, _, keep, ln = make_args(ab, B=B, seq_offset=off, seq_capacity=[100] * B, seq_len=[10] * B,
+                                                       pool_tokens=100 * B, k=[0] * B, a=[0] * B, **over)
+        st = ab._lib.alora_decode_static(vctx, C.byref(desc), C.byref(cache), FakeBuf.PTR, k.ctypes.data_as(p),
+                                         a.ctypes.data_as(p), B, FakeBuf.PTR, None)
+        return ab._lib.alora_status_string(st).decode(), ab._lib.alora_last_error(vctx).decode(), list(ln)
+
+    assert go(2)[0] == "ALORA_EHIP"                       # valid; a validation-only context cannot launch
+    st, msg, ln = go(3000, d=4096, n_q_heads=32, n_kv_heads=8, head_dim=128)
+    assert st == "ALORA_ECAPACITY" and "scratch" in msg and ln == [10] * 3000
+    assert go(5000)[0] == "ALORA_ECAPACITY"               # more than 4096 sequences
+    assert go(0)[0] == "ALORA_EINVAL"
+    assert go(2, dtype=9)[0] == "ALORA_EDTYPE"
