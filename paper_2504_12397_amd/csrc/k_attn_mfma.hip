@@ -475,6 +475,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 }
 
 
+
 bool attn_prefill_mfma_supported(const LayerDims &L) {
   const int G = L.n_q_heads / L.n_kv_heads;
   return L.head_dim == 128 && (G == 1 || G == 2 || G == 4 || G == 8);
