@@ -5,7 +5,7 @@ A step is one pass of the whole hot path (row preparation, fused base + gated lo
 projection, rotary embedding + cache append, attention over [base prefix ; adapted suffix])
 over one batch of seeded synthetic input that is already resident in HBM.
 
-    python bench.py [--workload c5|c2|c3|c4|c4x16|r2|r3] [--steps K] [--warmup W]
+    python bench.py [--workload c5|c2|c3|c4|c4x16|r2|r3|r3p] [--steps K] [--warmup W]
 
 prints ONE JSON line: suffix tokens/s, ms per step, the roofline of the dominant kernel
 (per-kernel durations from HIP events recorded by the library on the launch stream) and the
@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c4x16", "c5", "r2", "r3", "copy"],
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c4x16", "c5", "r2", "r3", "r3p", "copy"],
                     help="c5 (default): the first-token workload the metric is quoted on, with the c3 and c4 records "
                          "alongside; copy: a plain 1 GiB device copy, the known-size kernel that calibrates the HBM counters")
     ap.add_argument("--only", action="store_true", help="c5 only: leave out the c3 and c4 records")
@@ -143,8 +143,8 @@ def main():
         return
     if name == "r2":
         return regime2(args, ab, wl, torch, np, dev)
-    if name == "r3":
-        return regime3(args, ab, wl, torch, np, dev)
+    if name in ("r3", "r3p"):
+        return regime3(args, ab, wl, torch, np, dev, prefill=name == "r3p")
     result = run_workload(name, args, ab, wl, torch, np, dev, cpu=not args.no_cpu_baseline)
     if name == "c5" and not args.only:
         # The metric is quoted on c5 (first-token latency against the k = 0 recompute); its two roofline claims
@@ -454,15 +454,18 @@ def regime2(args, ab, wl, torch, np, dev):
     ctx.close()
 
 
-def regime3(args, ab, wl, torch, np, dev):
-    """Section 2 ("Cache reuse patterns"), third regime, as a decode step: sequences that run different adapters over the
-    same context read one physical copy of its cache rows, packed four to a workgroup for that
-    part; compared with the same batch holding a private copy of the context per sequence."""
-    batch, ctx_of, C0 = wl.regime3()
+def regime3(args, ab, wl, torch, np, dev, prefill=False):
+    """Section 2 ("Cache reuse patterns"), third regime: sequences that run different adapters over the same context
+    read one physical copy of its cache rows, and their rows share workgroups for that part (a decode step packs
+    four sequences to a workgroup; a prefill of invocation sequences packs the rows of neighbouring sequences up
+    to a full query tile); compared with the same batch holding a private copy of the context per sequence."""
+    batch, ctx_of, C0 = wl.regime3_prefill() if prefill else wl.regime3()
     shape = batch.shape
     n = batch.n_seqs
     n_ctx = max(ctx_of) + 1
     own = batch.P[0] - C0
+    S = batch.S[0]
+    kname = "attn_prefill" if prefill else "attn_decode"
     steps, warmup = args.steps or 30, args.warmup or 5
     ctx = ab.Context(0)
     for kv in args.opt:
@@ -471,11 +474,12 @@ def regime3(args, ab, wl, torch, np, dev):
     rng = wl.Rng(batch.seed, dev)
     layer = ab.Layer(wl.make_layer(shape, rng, "r3.L0"), shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                      shape.rms_eps, shape.rope_theta, shape.intermediate)
-    x = wl.make_hidden(rng, "r3.x", n, shape)
-    out = torch.empty((n, shape.n_q), dtype=shape.torch_dtype, device=dev)
+    x = wl.make_hidden(rng, "r3.x", n * S, shape)
+    out = torch.empty((n * S, shape.n_q), dtype=shape.torch_dtype, device=dev)
+    cu = [b * S for b in range(n + 1)]
 
     def make_cache(shared):
-        caps = [(own if shared else batch.P[b]) + 1 for b in range(n)] + ([C0] * n_ctx if shared else [])
+        caps = [(own if shared else batch.P[b]) + S for b in range(n)] + ([C0] * n_ctx if shared else [])
         c = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, dev)
         c.k.normal_()
         c.v.normal_()
@@ -490,7 +494,10 @@ def regime3(args, ab, wl, torch, np, dev):
 
         def step():
             c.seq_len[:n] = np.asarray(batch.P, dtype=np.int32)
-            ab.alora_decode(ctx, layer, c, x, batch.k, batch.adapter, out)
+            if prefill:
+                ab.alora_prefill(ctx, layer, c, x, cu, batch.k, batch.adapter, out)
+            else:
+                ab.alora_decode(ctx, layer, c, x, batch.k, batch.adapter, out)
 
         for _ in range(warmup):
             step()
@@ -514,22 +521,36 @@ def regime3(args, ab, wl, torch, np, dev):
     sec_private, prof_private = run(False)
 
     esz = 2
-    alg_bytes = (n_ctx * C0 + n * (own + 1)) * 2 * shape.n_kv * esz
-    avg = prof["attn_decode"]["ms"] / prof["attn_decode"]["launches"]
-    roof = dict(kernel="attn_decode", bound="hbm", achieved=alg_bytes / (avg * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
-                frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, traffic=None, avg_ms=avg, algorithmic_bytes=alg_bytes)
+    avg = prof[kname]["ms"] / prof[kname]["launches"]
+    avg_private = prof_private[kname]["ms"] / prof_private[kname]["launches"]
+    alg_bytes = (n_ctx * C0 + n * (own + S)) * 2 * shape.n_kv * esz
+    if prefill:
+        # causal attention of S new tokens over P cached ones: 4 * head_dim flops per (query head, visible key)
+        alg = n * 4 * shape.head_dim * shape.n_q_heads * (S * batch.P[0] + S * (S + 1) // 2)
+        roof = dict(kernel=kname, bound="mfma", achieved=alg / (avg * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=alg / (avg * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                    traffic=measured_traffic("r3p", kname), avg_ms=avg, algorithmic_flops=alg,
+                    algorithmic_bytes=alg_bytes, hbm_frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS)
+        what = ("r3p: prefill of %d invocation sequences of %d tokens = %d contexts of %d cached base tokens x %d adapter "
+                "calls, the context rows stored once per context" % (n, S, n_ctx, C0, n // n_ctx))
+    else:
+        roof = dict(kernel=kname, bound="hbm", achieved=alg_bytes / (avg * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, traffic=measured_traffic("r3", kname), avg_ms=avg,
+                    algorithmic_bytes=alg_bytes)
+        what = ("r3: decode step, %d sequences = %d contexts of %d cached base tokens x %d adapters, %d own "
+                "adapted rows each, the context rows stored once per context" % (n, n_ctx, C0, n // n_ctx, own))
     result = {
-        "metric": "alora_decode_tok_per_s", "value": n / sec, "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "metric": "alora_suffix_prefill_tok_per_s" if prefill else "alora_decode_tok_per_s", "value": n * S / sec,
+        "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
         "data": "synthetic",
-        "config": {"workload": "r3: decode step, %d sequences = %d contexts of %d cached base tokens x %d adapters, %d own "
-                               "adapted rows each, the context rows stored once per context" % (n, n_ctx, C0, n // n_ctx, own),
-                   "rank": shape.rank, "layers": 1},
+        "config": {"workload": what, "rank": shape.rank, "layers": 1},
         "roofline": roof,
         "kernels": {k_: dict(avg_ms=round(r["ms"] / r["launches"], 5), launches=r["launches"]) for k_, r in prof.items()},
         "private_copies_ms_per_step": sec_private * 1e3,
-        "private_copies_attn_decode_ms": prof_private["attn_decode"]["ms"] / prof_private["attn_decode"]["launches"],
+        "private_copies_%s_ms" % kname: avg_private,
         "speedup_vs_private_copies": sec_private / sec,
+        "%s_speedup_vs_private_copies" % kname: avg_private / avg,
     }
     print(json.dumps(result))
     ctx.close()

@@ -364,7 +364,7 @@ struct Workspace {
   bool attn_mfma = false;
   bool decode_mfma = false;
   int attn_waves = 8;
-  const int4 *qtiles = nullptr;
+  const AttnItem *qtiles = nullptr;
   int n_qtiles = 0;
   const DecItem *ditems = nullptr;   // work list of the MFMA decode kernel
   int n_ditems = 0;
@@ -495,18 +495,18 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
     if (w.attn_mfma && std::is_same<T, bf16>::value) {
       AttnArgs a{};
       a.Q = (const _Float16 *)w.Q; a.K = (const bf16 *)cache->k; a.V = (const bf16 *)cache->v;
-      a.seqs = seqs_dev; a.work = w.qtiles;
+      a.work = w.qtiles;
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
-      a.n_splits = n_splits;
+      a.n_parts = n_splits;
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
       a.lazy = (float)ctx->opt_attn_lazy;
       a.q_prescaled = q_scale != 1.0f;
       a.partials = direct ? nullptr : w.partials;
       a.compact = compact16 ? 1 : 0;
       a.out = direct ? (bf16 *)out : nullptr;
-      // the kernels' fast tile loads use 32-bit byte offsets inside one sequence's rows; shared prefixes and
-      // (absurdly) long sequences take the variant with full address arithmetic
-      bool generic_addr = pl.any_prefix;
+      // the kernels' fast tile loads use 32-bit byte offsets from an item's first key row; (absurdly) long
+      // sequences take the variant with full address arithmetic
+      bool generic_addr = false;
       for (const SeqMeta &q : pl.seqs)
         if ((uint64_t)(q.P + q.n_new) * (uint64_t)L.n_kv * 2u >= (1ull << 31)) generic_addr = true;
       launch_attn_prefill_mfma(a, w.n_qtiles, L.n_q_heads / L.n_kv_heads, w.attn_waves, generic_addr, s);
@@ -797,15 +797,45 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     }
     n_static_n_own = n_own;
   }
-  if (attn_mfma && ctx->opt_splits == 0) {
-    // one workgroup per (q-tile, kv head, split): aim at one full wave of workgroups over the chip,
-    // with at least 256 keys per split
+  // Prefill work list, part 1: how the keys of a (row, head) are cut up.  Sequences that name no shared prefix cut
+  // their visible keys into n_parts ranges.  Sequences that do cut their own keys (positions from prefix_len on)
+  // into n_own ranges, and the prefix into n_sh ranges that are walked once for ALL rows of a run of consecutive
+  // sequences naming that same prefix (Section 2, "Cache reuse patterns": several adapters invoked on one context):
+  // the rows of such a run are neighbours in the packed batch, so up to 256 / G of them share a workgroup and the
+  // prefix keys and values are fetched once per run instead of once per sequence.
+  struct PrefixRun { int64_t prefix_off; int prefix_len, row0, n_rows; };
+  std::vector<PrefixRun> runs;
+  int n_own = 1, n_sh = 0;
+  if (attn_mfma) {
     const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
     int64_t tiles = 0;
-    for (int b = 0; b < B; ++b) tiles += (pl.seqs[b].n_new + tq - 1) / tq;
+    int max_own = 1, max_pfx = 0;
+    for (int b = 0; b < B; ++b) {
+      const SeqMeta &m = pl.seqs[b];
+      if (m.n_new <= 0) continue;
+      tiles += (m.n_new + tq - 1) / tq;
+      max_own = std::max(max_own, m.P + m.n_new - m.prefix_len);
+      max_pfx = std::max(max_pfx, m.prefix_len);
+      if (m.prefix_len <= 0) continue;
+      if (!runs.empty() && runs.back().prefix_off == m.prefix_off && runs.back().prefix_len == m.prefix_len &&
+          runs.back().row0 + runs.back().n_rows == m.row_start)
+        runs.back().n_rows += m.n_new;
+      else
+        runs.push_back(PrefixRun{m.prefix_off, m.prefix_len, m.row_start, m.n_new});
+    }
+    for (const PrefixRun &r : runs) tiles += (r.n_rows + tq - 1) / tq;
     tiles *= L.n_kv_heads;
-    int want = (int)std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1));
-    n_splits = std::max(1, std::min(std::min(want, 16), std::max(1, pl.max_len / 256)));
+    // aim at one full wave of workgroups over the chip, with at least 256 keys per range
+    const int want = ctx->opt_splits > 0 ? ctx->opt_splits
+                                         : (int)std::min<int64_t>(16, std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1)));
+    auto ranges = [&](int longest) { return ctx->opt_splits > 0 ? want : std::max(1, std::min(want, longest / 256)); };
+    if (runs.empty()) {
+      n_own = ranges(pl.max_len);
+    } else {
+      n_own = ranges(max_own);
+      n_sh = ranges(max_pfx);
+    }
+    n_splits = n_own + n_sh;
   }
   // kernel family: MFMA for bf16 shapes it covers, plain otherwise
   const bool mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && L.d % 64 == 0 &&
@@ -876,77 +906,97 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (st != ALORA_OK) return st;
   // staged metadata: per-sequence records, then the work list of the MFMA attention kernel.
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2, and an XCD starts them
-  // in list order as compute units become free.  All q-tiles of one (sequence, kv head, key split)
-  // read the same keys and values, so such a group goes to one XCD: groups are handed out heaviest
-  // first to the XCD with the least work so far, and inside an XCD the items run longest first
+  // in list order as compute units become free.  All q-tiles of one (sequence or prefix run, kv head,
+  // key range) read the same keys and values, so such a group goes to one XCD: groups are handed out
+  // heaviest first to the XCD with the least work so far, and inside an XCD the items run longest first
   // (which keeps the q-tiles of a group next to each other: their lengths differ least).
-  std::vector<int4> qtiles;
+  std::vector<AttnItem> qtiles;
   if (attn_mfma) {
     const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
-    struct Item { int64_t cost; int4 w; };
-    auto item_cost = [&](int b, int q0) {     // key tiles the item walks through
-      const int ntok = std::min(tq, pl.seqs[b].n_new - q0);
-      return (int64_t)((pl.seqs[b].P + q0 + ntok + 63) / 64 + n_splits - 1) / n_splits + 1;
-    };
-    struct Group { int64_t cost; int b, g, sp; };
+    struct Group { int64_t cost; std::vector<AttnItem> items; };      // the items of a group stream the same keys
     std::vector<Group> groups;
+    // range `sp` of `parts` over the key positions [lo, hi), in whole tiles of 64 keys
+    auto cut = [](int lo, int hi, int parts, int sp, AttnItem *it) {
+      int chunk = (std::max(hi - lo, 0) + parts - 1) / parts;
+      chunk = (chunk + 63) & ~63;
+      it->kbeg = (int)std::min<int64_t>(hi, lo + (int64_t)sp * chunk);
+      it->kend = (int)std::min<int64_t>(hi, (int64_t)it->kbeg + chunk);
+    };
+    auto key_tiles = [](const AttnItem &it) { return (int64_t)(it.kend - it.kbeg + 63) / 64 + 1; };
     for (int b = 0; b < B; ++b) {
-      if (pl.seqs[b].n_new <= 0) continue;
-      int64_t c = 0;
-      for (int q0 = 0; q0 < pl.seqs[b].n_new; q0 += tq) c += item_cost(b, q0);
+      const SeqMeta &m = pl.seqs[b];
+      if (m.n_new <= 0) continue;
+      const int parts = m.prefix_len > 0 ? n_own : n_splits;
+      const int last = ((m.n_new - 1) / tq) * tq;
       for (int g = 0; g < L.n_kv_heads; ++g)
-        for (int sp = 0; sp < n_splits; ++sp) groups.push_back(Group{c, b, g, sp});
-    }
-    std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
-    std::vector<Item> per_xcd_items[8];
-    int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    // sequences that name the same shared prefix stream the same rows for most of their length:
-    // their groups of one (kv head, split) follow the first of them to its XCD
-    std::vector<std::pair<Group, int>> placed;
-    for (const Group &gr : groups) {
-      int x = -1;
-      const SeqMeta &m = pl.seqs[gr.b];
-      if (m.prefix_len > 0)
-        for (const auto &pr : placed) {
-          const SeqMeta &o = pl.seqs[pr.first.b];
-          if (pr.first.g == gr.g && pr.first.sp == gr.sp && o.prefix_len == m.prefix_len && o.prefix_off == m.prefix_off) {
-            x = pr.second;
-            break;
+        for (int sp = 0; sp < parts; ++sp) {
+          Group gr{0, {}};
+          for (int q0 = last; q0 >= 0; q0 -= tq) {
+            AttnItem it{};
+            it.ntok = std::min(tq, m.n_new - q0);
+            it.row0 = m.row_start + q0;
+            // key positions count from the sequence's first own row (position prefix_len)
+            it.pos0 = m.P + q0 - m.prefix_len;
+            it.key_row0 = m.pool_off + m.prefix_len;
+            it.n_addr = it.pos0 + it.ntok;                  // keys visible to the item's last token
+            cut(0, it.n_addr, parts, sp, &it);
+            it.g = g;
+            it.part = sp;
+            gr.cost += key_tiles(it);
+            gr.items.push_back(it);
           }
+          groups.push_back(std::move(gr));
         }
-      if (x < 0) {
-        x = 0;
-        for (int i = 1; i < 8; ++i)
-          if (load[i] < load[x]) x = i;
-      }
-      if (m.prefix_len > 0) placed.emplace_back(gr, x);
-      load[x] += gr.cost;
-      const int last = ((pl.seqs[gr.b].n_new - 1) / tq) * tq;
-      for (int q0 = last; q0 >= 0; q0 -= tq)
-        per_xcd_items[x].push_back(Item{item_cost(gr.b, q0), make_int4(gr.b, q0, gr.g, gr.sp)});
     }
-    std::vector<int4> per_xcd[8];
-    for (int x = 0; x < 8; ++x) {
-      std::stable_sort(per_xcd_items[x].begin(), per_xcd_items[x].end(),
-                       [](const Item &p, const Item &q) { return p.cost > q.cost; });
-      for (const Item &it : per_xcd_items[x]) per_xcd[x].push_back(it.w);
+    for (const PrefixRun &r : runs)
+      for (int g = 0; g < L.n_kv_heads; ++g)
+        for (int sp = 0; sp < n_sh; ++sp) {
+          Group gr{0, {}};
+          for (int r0 = 0; r0 < r.n_rows; r0 += tq) {
+            AttnItem it{};
+            it.ntok = std::min(tq, r.n_rows - r0);
+            it.row0 = r.row0 + r0;
+            it.pos0 = 1 << 30;                              // every prefix key is visible to every row of the run
+            it.key_row0 = r.prefix_off;
+            it.n_addr = r.prefix_len;
+            cut(0, r.prefix_len, n_sh, sp, &it);
+            it.g = g;
+            it.part = n_own + sp;
+            gr.cost += key_tiles(it);
+            gr.items.push_back(it);
+          }
+          groups.push_back(std::move(gr));
+        }
+    std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
+    std::vector<AttnItem> per_xcd[8];
+    int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (const Group &gr : groups) {
+      int x = 0;
+      for (int i = 1; i < 8; ++i)
+        if (load[i] < load[x]) x = i;
+      load[x] += gr.cost;
+      per_xcd[x].insert(per_xcd[x].end(), gr.items.begin(), gr.items.end());
     }
     size_t longest = 0;
-    for (auto &v : per_xcd) longest = std::max(longest, v.size());
+    for (int x = 0; x < 8; ++x) {
+      std::stable_sort(per_xcd[x].begin(), per_xcd[x].end(),
+                       [&](const AttnItem &p, const AttnItem &q) { return key_tiles(p) > key_tiles(q); });
+      longest = std::max(longest, per_xcd[x].size());
+    }
     qtiles.reserve(longest * 8);
     for (size_t i = 0; i < longest; ++i)
       for (int x = 0; x < 8; ++x)
-        qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : make_int4(-1, 0, 0, 0));
+        qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : AttnItem{});        // ntok = 0: padding
   }
   const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
-  const size_t work_bytes = (qtiles.size() * sizeof(int4) + ditems.size() * sizeof(DecItem) + 15) & ~(size_t)15;   // one of the two lists
+  const size_t work_bytes = (qtiles.size() * sizeof(AttnItem) + ditems.size() * sizeof(DecItem) + 15) & ~(size_t)15;   // one of the two lists
   const size_t scale_bytes = stack ? (size_t)L.n_adapters * sizeof(float) : 0;
   const size_t meta_bytes = seq_bytes + work_bytes + scale_bytes;
   MetaSlot *slot = nullptr;
   st = acquire_slot(ctx, meta_bytes, &slot);
   if (st != ALORA_OK) return st;
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
-  if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(int4));
+  if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(AttnItem));
   if (!ditems.empty()) memcpy(slot->host + seq_bytes, ditems.data(), ditems.size() * sizeof(DecItem));
   if (scale_bytes) memcpy(slot->host + seq_bytes + work_bytes, layers[0].scale, scale_bytes);
   HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
@@ -960,7 +1010,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.attn_mfma = attn_mfma;
   w.decode_mfma = decode_mfma;
   w.attn_waves = attn_waves;
-  w.qtiles = (const int4 *)(slot->dev + seq_bytes);
+  w.qtiles = (const AttnItem *)(slot->dev + seq_bytes);
   w.n_qtiles = (int)qtiles.size();
   w.ditems = (const DecItem *)(slot->dev + seq_bytes);
   w.n_ditems = (int)ditems.size();

@@ -97,8 +97,8 @@ constexpr int ATT_BN = 64;        // keys per tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// PFX: some sequence of the call reads a shared prefix (cached position j < prefix_len lives in
-// another place of the pool than the sequence's own rows)
+// PFX: tile loads with full 64-bit address arithmetic (items whose keys lie beyond 2 GB from their first row)
+// instead of buffer loads with 32-bit offsets
 //
 // FOLD: the queries arrive premultiplied by sm_scale * log2(e) (the rotation kernel does it while it
 // rounds them), and the softmax bookkeeping moves onto the matrix unit:
@@ -114,33 +114,27 @@ template <int G, int NW, bool PFX, bool FOLD>      // NW waves per workgroup (8 
 __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) {
   constexpr int H = 128;
   constexpr int NT = 64 * NW;
-  constexpr int TQ = 32 * NW / G;
   constexpr int NB = 1;             // 32-row query blocks per wave
   __shared__ u32x4 Ks[2][ATT_BN * 16];
   __shared__ u32x4 Vs[2][H * 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, kh = lane >> 5;
-  // work list built by the host: (sequence, first token of the q-tile, kv head, key split), ordered
-  // so that the q-tiles that stream the same keys and values sit on one XCD (one L2) together
-  const int4 wk = a.work[blockIdx.x];
-  if (wk.x < 0) return;
-  const int g = wk.z, split = wk.w;
-  const SeqMeta sm = a.seqs[wk.x];
-  const int q0 = wk.y;
-  const int ntok = min(TQ, sm.n_new - q0);
-  const int row0 = sm.row_start + q0;
-  const int n_visible = sm.P + q0 + ntok;            // keys visible to the tile's last token
-  int chunk = (n_visible + a.n_splits - 1) / a.n_splits;
-  chunk = (chunk + ATT_BN - 1) & ~(ATT_BN - 1);
-  const int kbeg = split * chunk, kend = min(n_visible, kbeg + chunk);
+  // work list built by the host: one item per workgroup -- up to TQ consecutive packed rows against one range of
+  // key positions of one kv head -- ordered so that the items that stream the same keys and values sit on one XCD
+  // (one L2) together.  The rows of an item belong to one sequence (the causal mask uses pos0 + token), or to
+  // several consecutive sequences over the shared prefix they all name (no mask needed: pos0 is out of reach).
+  const AttnItem wk = a.work[blockIdx.x];
+  if (wk.ntok <= 0) return;
+  const int g = wk.g, split = wk.part;
+  const int ntok = wk.ntok;
+  const int row0 = wk.row0;
+  const int n_visible = wk.n_addr;                   // key positions addressable from key_row0
+  const int kbeg = wk.kbeg, kend = wk.kend;
   const int ntiles = kend > kbeg ? (kend - kbeg + ATT_BN - 1) / ATT_BN : 0;
-  const bf16 *Kp = a.K + sm.pool_off * a.n_kv + g * H;
-  const bf16 *Vp = a.V + sm.pool_off * a.n_kv + g * H;
-  // offset (in elements) that turns an own-row address into the shared-prefix address of the same position
-  const int64_t pfx_delta = PFX ? (sm.prefix_off - sm.pool_off) * a.n_kv : 0;
-  const int pfx_len = PFX ? sm.prefix_len : 0;
-  const int first_pos = sm.P + q0;                   // smallest query position in the tile
+  const bf16 *Kp = a.K + wk.key_row0 * a.n_kv + g * H;
+  const bf16 *Vp = a.V + wk.key_row0 * a.n_kv + g * H;
+  const int first_pos = wk.pos0;                     // smallest query position in the tile
 
   // ---- this wave's queries as B operands: 2 column blocks x 8 k-steps ---------------------
   u32x4 qf[NB][8];
@@ -223,13 +217,13 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
       for (int i = 0; i < KC; ++i) {
         const int q = tid + i * NT, key = q >> 4, c = q & 15;
         const int kidx = min(k0 + key, n_visible - 1);
-        const int64_t e = (int64_t)kidx * a.n_kv + c * 8 + (kidx < pfx_len ? pfx_delta : 0);
+        const int64_t e = (int64_t)kidx * a.n_kv + c * 8;
         rk[i] = *reinterpret_cast<const u32x4 *>(Kp + e);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int kidx = min(k0 + v_qd * 4 + i, n_visible - 1);
-        const int64_t e = (int64_t)kidx * a.n_kv + v_cg * CW + (kidx < pfx_len ? pfx_delta : 0);
+        const int64_t e = (int64_t)kidx * a.n_kv + v_cg * CW;
         rv[i] = *reinterpret_cast<const vword *>(Vp + e);
       }
     }
@@ -436,7 +430,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
       amax = max_with_other_half(amax);
       const float rs = amax > 0.f ? 1.0f / amax : 0.f;
       char *rec = reinterpret_cast<char *>(a.partials) +
-                  ((row * a.n_q_heads + head[nb]) * a.n_splits + split) * (int64_t)ATTN_REC16;
+                  ((row * a.n_q_heads + head[nb]) * a.n_parts + split) * (int64_t)ATTN_REC16;
       typedef __attribute__((__vector_size__(4 * sizeof(_Float16)))) _Float16 half4_t;
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb)
@@ -455,7 +449,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
         tail[2] = amax;
       }
     } else {
-      float *pp = a.partials + ((row * a.n_q_heads + head[nb]) * a.n_splits + split) * (H + 2);
+      float *pp = a.partials + ((row * a.n_q_heads + head[nb]) * a.n_parts + split) * (H + 2);
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb)
 #pragma unroll

@@ -64,20 +64,34 @@ struct PrepArgs {
 bool prep_rows_mfma_supported(int d, int rank);
 void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s);
 
+// One workgroup of the prefill attention kernel: up to 256/G consecutive packed rows (tokens) against the key
+// positions [kbeg, kend) of one kv head, counted from pool row key_row0.  Own rows of one sequence: key_row0 is
+// its first own row, pos0 the position of the first token counted from there, and the causal mask applies.  Rows of several consecutive sequences over the shared
+// prefix they all name (Section 2, "Cache reuse patterns", several adapters on one context): key_row0 is the prefix,
+// pos0 lies beyond every key, the prefix tile is fetched once for all of them.
+struct AttnItem {
+  int64_t key_row0;         // pool row that holds key position 0 of this item
+  int32_t kbeg, kend;       // key positions of this item
+  int32_t n_addr;           // key positions that may be addressed from key_row0 (loads beyond kend are clamped to it)
+  int32_t row0, ntok;       // packed rows row0 .. row0 + ntok - 1; ntok <= 0: padding item
+  int32_t pos0;             // position of row0's token (token i sits at pos0 + i)
+  int32_t g;                // kv head
+  int32_t part;             // which of the n_parts partial records of a (row, head) this item writes
+  int32_t pad_[2];
+};
 // Prefill attention (Eq.1 with the causal mask) over the pool cache.
 struct AttnArgs {
   const _Float16 *Q;        // [T, n_q] rotated queries of the new rows, as fp16
   const bf16 *K, *V;        // pool [tokens, n_kv]
-  const SeqMeta *seqs;
-  const int4 *work;         // per workgroup: (sequence or -1, first new token of the q-tile, kv head, key split)
+  const AttnItem *work;     // one item per workgroup
   int n_q, n_kv, n_q_heads, n_kv_heads;
-  int n_splits;             // key splits (grid.z)
+  int n_parts;              // partial records per (row, head); 1: the kernel writes the final output
   float sm_scale;           // 1 / sqrt(head_dim)
   int q_prescaled;          // Q already carries sm_scale * log2(e): scores leave the MFMA in the exp2 domain
   float lazy;               // the running maximum moves only when a block exceeds it by more than this (log2 units)
-  float *partials;          // [T, n_q_heads, n_splits, head_dim + 2] (acc, max, sum), used when out == nullptr
+  float *partials;          // [T, n_q_heads, n_parts, head_dim + 2] (acc, max, sum), used when out == nullptr
   int compact;              // partial records in the compact form (ATTN_REC16 bytes each) that launch_attn_merge16 reads
-  bf16 *out;                // [T, n_q] final output, only with n_splits == 1
+  bf16 *out;                // [T, n_q] final output, only with n_parts == 1
 };
 constexpr int ATTN_REC16 = 272;      // 128 fp16 + (reference, row sum, scale) as fp32 + 4 bytes of padding
 bool attn_prefill_mfma_supported(const LayerDims &L);

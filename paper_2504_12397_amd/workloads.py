@@ -234,6 +234,17 @@ def regime3(n_contexts: int = 16, per_context: int = 4, context: int = 16384, ow
     return batch, [b // per_context for b in range(n)], context
 
 
+def regime3_prefill(n_contexts: int = 4, per_context: int = 8, context: int = 16384, invocation: int = 16):
+    """The same regime at the moment the adapters are invoked (Section 2, "Cache reuse patterns"; Section 3's
+    invocation sequences are a handful of tokens): 4 contexts of 16384 base tokens, each invoked by 8 adapter calls
+    whose 16-token invocation sequences are prefilled in one call.  Returns the batch and, per sequence, the index
+    of its context."""
+    n = n_contexts * per_context
+    batch = Batch(SHAPE_8B_4AD, P=[context] * n, S=[invocation] * n, k=[context] * n,
+                  adapter=[b % per_context % 4 for b in range(n)], name="r3p", seed=BASE_SEED + 8)
+    return batch, [b // per_context for b in range(n)], context
+
+
 def config5(full_lora: bool = False) -> Batch:
     """32-layer stack shape: 32768 cached tokens + 128 adapted tokens (aLoRA), or the same
     32896 tokens recomputed from scratch with the adapter on everywhere (k = 0)."""
