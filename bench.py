@@ -44,6 +44,9 @@ def parse():
                     help="distinct weight/cache sets cycled through so the last-level cache cannot hold the working set")
     ap.add_argument("--layers", type=int, default=0, help="c5 only: number of layers (default 32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", default="both", choices=["both", "shared", "private"],
+                    help="r3 / r3p only: time the batch with shared context rows, with private copies, or both (default); "
+                         "one variant per process is what a profiler run wants")
     ap.add_argument("--no-full-lora", action="store_true", help="c5 only: skip the k=0 recompute baseline")
     ap.add_argument("--plain", action="store_true", help="force the plain fp32-FMA kernels")
     ap.add_argument("--adapt-rest", action="store_true",
@@ -517,25 +520,30 @@ def regime3(args, ab, wl, torch, np, dev, prefill=False):
         del c
         return sec, prof
 
-    sec, prof = run(True)
-    sec_private, prof_private = run(False)
+    if args.variant == "private":
+        sec, prof = run(False)
+        sec_private, prof_private = sec, prof
+    else:
+        sec, prof = run(True)
+        sec_private, prof_private = run(False) if args.variant == "both" else (None, None)
 
     esz = 2
     avg = prof[kname]["ms"] / prof[kname]["launches"]
-    avg_private = prof_private[kname]["ms"] / prof_private[kname]["launches"]
-    alg_bytes = (n_ctx * C0 + n * (own + S)) * 2 * shape.n_kv * esz
+    avg_private = prof_private[kname]["ms"] / prof_private[kname]["launches"] if prof_private else None
+    # the rows that exist: every context once (or once per sequence when each holds a private copy) + the own rows
+    alg_bytes = ((n if args.variant == "private" else n_ctx) * C0 + n * (own + S)) * 2 * shape.n_kv * esz
     if prefill:
         # causal attention of S new tokens over P cached ones: 4 * head_dim flops per (query head, visible key)
         alg = n * 4 * shape.head_dim * shape.n_q_heads * (S * batch.P[0] + S * (S + 1) // 2)
         roof = dict(kernel=kname, bound="mfma", achieved=alg / (avg * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS,
                     unit="TFLOP/s", frac=alg / (avg * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                    traffic=measured_traffic("r3p", kname), avg_ms=avg, algorithmic_flops=alg,
+                    traffic=measured_traffic("r3pp" if args.variant == "private" else "r3p", kname), avg_ms=avg, algorithmic_flops=alg,
                     algorithmic_bytes=alg_bytes, hbm_frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS)
         what = ("r3p: prefill of %d invocation sequences of %d tokens = %d contexts of %d cached base tokens x %d adapter "
                 "calls, the context rows stored once per context" % (n, S, n_ctx, C0, n // n_ctx))
     else:
         roof = dict(kernel=kname, bound="hbm", achieved=alg_bytes / (avg * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, traffic=measured_traffic("r3", kname), avg_ms=avg,
+                    frac=alg_bytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, traffic=None, avg_ms=avg,
                     algorithmic_bytes=alg_bytes)
         what = ("r3: decode step, %d sequences = %d contexts of %d cached base tokens x %d adapters, %d own "
                 "adapted rows each, the context rows stored once per context" % (n, n_ctx, C0, n // n_ctx, own))
@@ -547,11 +555,15 @@ def regime3(args, ab, wl, torch, np, dev, prefill=False):
         "config": {"workload": what, "rank": shape.rank, "layers": 1},
         "roofline": roof,
         "kernels": {k_: dict(avg_ms=round(r["ms"] / r["launches"], 5), launches=r["launches"]) for k_, r in prof.items()},
-        "private_copies_ms_per_step": sec_private * 1e3,
-        "private_copies_%s_ms" % kname: avg_private,
-        "speedup_vs_private_copies": sec_private / sec,
-        "%s_speedup_vs_private_copies" % kname: avg_private / avg,
+        "variant": args.variant,
     }
+    if args.variant == "both":
+        result.update({"private_copies_ms_per_step": sec_private * 1e3, "private_copies_%s_ms" % kname: avg_private,
+                       "speedup_vs_private_copies": sec_private / sec,
+                       "%s_speedup_vs_private_copies" % kname: avg_private / avg})
+    if args.variant == "private":
+        result["config"]["workload"] = result["config"]["workload"].replace(
+            "the context rows stored once per context", "every sequence holding a private copy of its context's rows")
     print(json.dumps(result))
     ctx.close()
 

@@ -823,15 +823,27 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
       else
         runs.push_back(PrefixRun{m.prefix_off, m.prefix_len, m.row_start, m.n_new});
     }
-    for (const PrefixRun &r : runs) tiles += (r.n_rows + tq - 1) / tq;
-    tiles *= L.n_kv_heads;
-    // aim at one full wave of workgroups over the chip, with at least 256 keys per range
-    const int want = ctx->opt_splits > 0 ? ctx->opt_splits
-                                         : (int)std::min<int64_t>(16, std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1)));
-    auto ranges = [&](int longest) { return ctx->opt_splits > 0 ? want : std::max(1, std::min(want, longest / 256)); };
     if (runs.empty()) {
-      n_own = ranges(pl.max_len);
+      // aim at one full wave of workgroups over the chip, with at least 256 keys per range
+      tiles *= L.n_kv_heads;
+      const int want = (int)std::min<int64_t>(16, std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1)));
+      n_own = ctx->opt_splits > 0 ? ctx->opt_splits : std::max(1, std::min(want, pl.max_len / 256));
     } else {
+      // The work is uneven (long contexts walked by few packed tiles, short own parts walked by many): size the
+      // ranges by work.  One unit = one 64-key tile of one workgroup; aim at two workgroups per compute unit of
+      // equal length, at least four tiles each.
+      int64_t units = 0;
+      for (int b = 0; b < B; ++b) {
+        const SeqMeta &m = pl.seqs[b];
+        for (int q0 = 0; q0 < m.n_new; q0 += tq) units += (m.P + std::min(m.n_new, q0 + tq) - m.prefix_len + 63) / 64;
+      }
+      for (const PrefixRun &r : runs) units += (int64_t)((r.n_rows + tq - 1) / tq) * ((r.prefix_len + 63) / 64);
+      units *= L.n_kv_heads;
+      const int64_t target = std::max<int64_t>(4, units / (2 * (int64_t)ctx->n_cu));
+      auto ranges = [&](int longest) {
+        if (ctx->opt_splits > 0) return ctx->opt_splits;
+        return (int)std::max<int64_t>(1, std::min<int64_t>(16, ((longest + 63) / 64 + target - 1) / target));
+      };
       n_own = ranges(max_own);
       n_sh = ranges(max_pfx);
     }

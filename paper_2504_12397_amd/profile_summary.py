@@ -2,7 +2,8 @@
 
     python -m paper_2504_12397_amd.profile_summary --in gpurun_out/prof --out profiles
 
-Expects under --in, per workload w in {c2, c3, c4, c5} (any subset):
+Expects under --in, per workload w in {c2, c3, c4, c5, r3p, r3pp} (any subset; r3p and r3pp are bench.py's r3p workload with
+--variant shared and --variant private):
     kt_<w>/<w>_kernel_stats.csv, kt_<w>.json          rocprofv3 --kernel-trace --stats, and bench.py's JSON line
     pmc_FETCH_<w>/, pmc_WRITE_<w>/                    --pmc FETCH_SIZE / WRITE_SIZE  (<w>_counter_collection.csv)
     pmc_A_<w>/, pmc_B_<w>/                            the two sets of SQ counters listed in COUNTER_SETS
@@ -31,7 +32,12 @@ TITLES = {
     "c4": ("c4_decode_step", "c4: decode step, 64 sequences x 16448 cached tokens, one new token each", ""),
     "c5": ("c5_stack_first_token", "c5: 32-layer 8B-class stack, 32768 cached base tokens + 128 adapted suffix tokens, rank 64",
            " --only --no-full-lora"),
+    "r3p": ("r3p_shared_context_prefill", "r3p: prefill of 32 invocation sequences of 16 tokens, 4 contexts of 16384 cached base "
+            "tokens x 8 adapter calls, each context's rows stored once and walked once per run of sequences", " --variant shared"),
+    "r3pp": ("r3p_private_copies_prefill", "r3p with private copies: the same 32 invocation sequences, every sequence holding "
+             "(and walking) its own copy of the 16384 context rows", " --variant private"),
 }
+BENCH_WORKLOAD = {"r3pp": "r3p"}         # summary key -> bench.py --workload, where they differ
 # kernel symbol -> the kernel family bench.py reports (only where one symbol is one family in that workload)
 FAMILY = [("attn_prefill_mfma_kernel", "attn_prefill"), ("attn_decode_mfma_kernel", "attn_decode"),
           ("prep_rows_mfma_kernel", "prep_rows"), ("rope_append_kernel", "rope_append"), ("attn_merge", "attn_merge")]
@@ -110,10 +116,11 @@ def main():
         ca = counters(f"{src}/pmc_A_{w}/{w}_counter_collection.csv")
         cb = counters(f"{src}/pmc_B_{w}/{w}_counter_collection.csv")
         pmc_extra = extra + (" --layers 4" if w == "c5" else "")
+        bw = BENCH_WORKLOAD.get(w, w)
         out = [f"# rocprofv3 summary, workload {title}", "",
                "Commands (from /tmp with TMPDIR=/tmp on one MI355X; paths relative to the repository root; every --pmc pass is a run of its own):", "",
-               f"    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt_{w} -o {w} -- python3 bench.py --workload {w} --no-cpu-baseline{extra}",
-               f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/prof/pmc_FETCH_{w} -o {w} -- python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline{pmc_extra}",
+               f"    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt_{w} -o {w} -- python3 bench.py --workload {bw} --no-cpu-baseline{extra}",
+               f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/prof/pmc_FETCH_{w} -o {w} -- python3 bench.py --workload {bw} --no-cpu-baseline --steps 3 --warmup 1{pmc_extra}",
                "    (the same with WRITE_SIZE, and with the two SQ counter sets below)",
                f"    set A: {COUNTER_SETS['A']}",
                f"    set B: {COUNTER_SETS['B']}",
