@@ -112,7 +112,13 @@ typedef struct {
  * in the sequence's own rows, position j at seq_offset[b] + (j - prefix_len[b]).  seq_len stays
  * the full cached length (prefix included); the capacity bounds the own rows.  A call never
  * writes prefix rows (new positions are >= seq_len >= prefix_len); the caller must not hand the
- * same rows to another sequence of the same call as rows to be written. */
+ * same rows to another sequence of the same call as rows to be written.
+ * The shared rows are also WALKED once: sequences of a call that name the same (prefix_offset,
+ * prefix_len) put their new rows into common workgroups for the prefix keys -- in a decode step any
+ * such sequences, up to 16 query-head rows per workgroup; in a prefill sequences that are neighbours
+ * in the batch, up to 256 query-head rows -- so a caller keeps the sequences of one context next to
+ * each other.  Results do not depend on it beyond the summation order of the attention (see
+ * "Summation order" at alora_set_option). */
 typedef struct {
   void *k;                     /* DEVICE [pool_tokens, n_kv_heads, head_dim]           */
   void *v;                     /* DEVICE [pool_tokens, n_kv_heads, head_dim]           */
