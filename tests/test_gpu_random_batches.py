@@ -1,0 +1,87 @@
+"""Randomised differential test: seeded random batch compositions -- ragged lengths, empty sequences, invocation
+points before, inside and beyond the new rows (Eq.6), base-only sequences, shared and private contexts (Section 2,
+"Cache reuse patterns"), head groupings, option settings -- through alora_prefill and alora_decode, every sequence
+compared with the oracle on its own.  The draws are fixed by the seed, so a failure names a reproducible case."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2504_12397_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, n_adapters=3),
+    wl.LayerShape(d=512, n_q_heads=4, n_kv_heads=4, head_dim=128, rank=16, n_adapters=3),
+    wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=1, head_dim=128, rank=32, n_adapters=3),
+    wl.LayerShape(d=256, n_q_heads=4, n_kv_heads=2, head_dim=128, rank=16, n_adapters=3),
+    dataclasses.replace(wl.SHAPE_TINY, n_adapters=3, rmsnorm=True, n_kv_heads=2),          # fp32, plain kernels
+]
+OPTIONS = [{}, {}, {}, {"kv_splits": 2}, {"kv_splits": 5}, {"attn_waves": 4}, {"attn_fold": 0}, {"attn_partials16": 0},
+           {"gemm_splits": 1}, {"rope_fuse": 0}, {"kernels": 1}, {"attn_lazy": 0}, {"lora_split": 1}, {"lora_split": 2}]
+
+
+def draw(seed: int, decode: bool):
+    r = np.random.default_rng(seed)
+    shape = SHAPES[int(r.integers(len(SHAPES)))]
+    opts = dict(OPTIONS[int(r.integers(len(OPTIONS)))])
+    n_ctx = int(r.integers(0, 3))
+    C = [int(r.choice([1, 17, 64, 130, 333, 700, 1100])) for _ in range(n_ctx)]
+    n = int(r.integers(1, 8))
+    group, S, own, k, adapter = [], [], [], [], []
+    g_now = -1
+    for b in range(n):
+        # neighbours tend to stay on the same context (that is what gets packed), sometimes they do not
+        if n_ctx and r.random() < 0.75:
+            g_now = g_now if (g_now >= 0 and r.random() < 0.7) else int(r.integers(n_ctx))
+            g = g_now
+        else:
+            g = -1
+        group.append(g)
+        if decode:
+            S.append(1)
+        else:
+            S.append(int(r.choice([0, 1, 2, 15, 16, 31, 33, 64, 65, 100, 150])))
+        own.append(int(r.choice([0, 0, 1, 5, 63, 64, 200, 450])))
+        P = own[-1] + (C[g] if g >= 0 else 0)
+        k.append(int(r.choice([0, P // 2, P, P + S[-1] // 2, P + S[-1], 10 ** 6])))
+        adapter.append(int(r.integers(-1, shape.n_adapters)))
+    if sum(S) == 0:
+        S[0] = 3
+    return shape, opts, C, group, S, own, k, adapter
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_prefill_batches(seed):
+    from paper_2504_12397_amd import binding as ab
+    shape, opts, C, group, S, own, k, adapter = draw(1000 + seed, decode=False)
+    print(f"seed {seed}: {shape.dtype} G={shape.n_q_heads // shape.n_kv_heads} opts={opts} C={C} group={group} S={S} "
+          f"own={own} k={k} adapter={adapter}", flush=True)
+    ctx = ab.Context(0)
+    try:
+        for key, v in opts.items():
+            ctx.set_option(key, v)
+        case, ctx_kv = H.contexts_case(shape, C, group, own, S, k, adapter, seed=2000 + seed)
+        worst = H.run_contexts(ab, ctx, case, ctx_kv, C, group, own)
+        H.report(test="random_prefill", seed=seed, dtype=shape.dtype, opts=opts, err=worst)
+    finally:
+        ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_decode_batches(seed):
+    from paper_2504_12397_amd import binding as ab
+    shape, opts, C, group, S, own, k, adapter = draw(3000 + seed, decode=True)
+    print(f"seed {seed}: {shape.dtype} G={shape.n_q_heads // shape.n_kv_heads} opts={opts} C={C} group={group} "
+          f"own={own} k={k} adapter={adapter}", flush=True)
+    ctx = ab.Context(0)
+    try:
+        for key, v in opts.items():
+            ctx.set_option(key, v)
+        case, ctx_kv = H.contexts_case(shape, C, group, own, S, k, adapter, seed=4000 + seed)
+        worst = H.run_contexts(ab, ctx, case, ctx_kv, C, group, own, decode=True)
+        H.report(test="random_decode", seed=seed, dtype=shape.dtype, opts=opts, err=worst)
+    finally:
+        ctx.close()

@@ -223,82 +223,6 @@ def test_two_different_shared_contexts_and_decode_steps(ab):
         ctx.close()
 
 
-def contexts_case(shape, C, group, own, S, k, adapter, seed):
-    """Sequences over several base contexts: sequence b reads context group[b] (C[group[b]] rows, -1: none) and
-    holds own[b] cached rows of its own behind it.  All cached values are random: the comparison needs only that
-    the GPU and the oracle hold the same ones."""
-    rng = wl.Rng(seed)
-    tensors = wl.make_layer(shape, rng)
-    layer = H.oracle_layer(tensors, shape)
-    ctx_kv = []
-    for i, c in enumerate(C):
-        K, V = wl.make_random_kv(rng, f"context{i}", c, shape)
-        ctx_kv.append((H.f64(K).reshape(c, shape.n_kv), H.f64(V).reshape(c, shape.n_kv)))
-    xn, cK, cV, P = [], [], [], []
-    for b in range(len(S)):
-        xn.append(wl.make_hidden(rng, f"x_new{b}", S[b], shape))
-        K, V = wl.make_random_kv(rng, f"own{b}", own[b], shape)
-        K, V = H.f64(K).reshape(own[b], shape.n_kv), H.f64(V).reshape(own[b], shape.n_kv)
-        if group[b] >= 0:
-            K, V = np.concatenate([ctx_kv[group[b]][0], K]), np.concatenate([ctx_kv[group[b]][1], V])
-        cK.append(K)
-        cV.append(V)
-        P.append(len(K))
-    case = H.Case(shape, tensors, layer, P, list(S), list(k), list(adapter), [None] * len(S), xn, cK, cV)
-    return case, ctx_kv
-
-
-def run_contexts(ab, ctx, case, ctx_kv, C, group, own):
-    shape = case.shape
-    n = len(case.S)
-    nkv = shape.n_kv_heads
-    caps = [own[b] + case.S[b] + 2 for b in range(n)] + list(C)
-    cache = ab.KVCache(caps, nkv, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY, guard_rows=2)
-
-    def put(o, K, V):
-        r = len(K)
-        if r:
-            cache.k[o:o + r] = torch.from_numpy(K).to(shape.torch_dtype).view(r, nkv, -1).cuda()
-            cache.v[o:o + r] = torch.from_numpy(V).to(shape.torch_dtype).view(r, nkv, -1).cuda()
-
-    for i in range(len(C)):
-        put(int(cache.seq_offset[n + i]), *ctx_kv[i])
-    for b in range(n):
-        lo = C[group[b]] if group[b] >= 0 else 0
-        put(int(cache.seq_offset[b]), case.cache_K[b][lo:], case.cache_V[b][lo:])
-        cache.seq_len[b] = case.P[b]
-        if group[b] >= 0:
-            cache.share_prefix(b, int(cache.seq_offset[n + group[b]]), lo)
-    cache._refresh()
-    before_k, before_v = cache.k.clone(), cache.v.clone()
-    layer = H.gpu_layer(case, shape)
-    out = ab.alora_prefill(ctx, layer, cache, case.x_packed.cuda().contiguous(), case.cu, case.k, case.adapter)
-    torch.cuda.synchronize()
-    ref_o, new_rows = H.oracle_prefill(case)
-    tol = H.TOL[shape.dtype]
-    # row by row, so that a row that took another sequence's context shows up under its own number
-    cu = case.cu
-    worst = 0.0
-    for b in range(n):
-        if case.S[b] == 0:
-            continue
-        e = H.rel_err(H.f64(out[cu[b]:cu[b + 1]]), ref_o[cu[b]:cu[b + 1]])
-        assert e <= tol, f"sequence {b}: attention output off by {e:.3e}"
-        worst = max(worst, e)
-    written = torch.zeros(cache.pool_tokens, dtype=torch.bool)
-    for b in range(n):
-        o = int(cache.seq_offset[b]) + own[b]
-        written[o:o + case.S[b]] = True
-        assert int(cache.seq_len[b]) == case.P[b] + case.S[b]
-        if case.S[b]:
-            assert H.rel_err(H.f64(cache.k[o:o + case.S[b]]).reshape(case.S[b], -1), new_rows[b][0]) <= tol
-            assert H.rel_err(H.f64(cache.v[o:o + case.S[b]]).reshape(case.S[b], -1), new_rows[b][1]) <= tol
-    keep = ~written.cuda()
-    assert torch.equal(bits(cache.k[keep]), bits(before_k[keep])), "rows outside the new ones changed (contexts included)"
-    assert torch.equal(bits(cache.v[keep]), bits(before_v[keep]))
-    return worst
-
-
 @pytest.mark.parametrize("name,opts", [("G4", {}), ("G4", {"kv_splits": 3}), ("G4", {"attn_waves": 4}),
                                        ("G4", {"attn_fold": 0}), ("G4", {"attn_partials16": 0}), ("G1", {}), ("G8", {}),
                                        ("G4", {"kernels": 1}), ("f32", {})])
@@ -323,8 +247,8 @@ def test_prefill_rows_of_neighbouring_sequences_walk_their_context_together(ab, 
         k[7] = 0                  # adapter rows from the start
         adapter = [b % 3 for b in range(n)]
         adapter[5] = -1
-        case, ctx_kv = contexts_case(shape, C, group, own, S, k, adapter, seed=940)
-        worst = run_contexts(ab, ctx, case, ctx_kv, C, group, own)
+        case, ctx_kv = H.contexts_case(shape, C, group, own, S, k, adapter, seed=940)
+        worst = H.run_contexts(ab, ctx, case, ctx_kv, C, group, own)
         H.report(test="prefill_shared_contexts", shape=name, opts=opts, err=worst)
     finally:
         ctx.close()
@@ -340,8 +264,8 @@ def test_prefill_of_many_short_invocations_on_one_long_context(ab):
         n = 16
         S = [12 + (b % 5) for b in range(n)]
         own = [0] * n
-        case, ctx_kv = contexts_case(shape, C, [0] * n, own, S, [C[0]] * n, list(range(n)), seed=950)
-        worst = run_contexts(ab, ctx, case, ctx_kv, C, [0] * n, own)
+        case, ctx_kv = H.contexts_case(shape, C, [0] * n, own, S, [C[0]] * n, list(range(n)), seed=950)
+        worst = H.run_contexts(ab, ctx, case, ctx_kv, C, [0] * n, own)
         H.report(test="prefill_many_invocations_one_context", err=worst)
     finally:
         ctx.close()
