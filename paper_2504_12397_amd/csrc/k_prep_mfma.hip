@@ -265,11 +265,9 @@ static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
   const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
   auto kern = prep_rows_mfma_kernel<NF, CH, EARLY>;
-  static bool configured = false;
-  if (!configured && smem > 48 * 1024) {
+  // set on every launch that needs it: a host-side attribute write, safe from any thread and on any device
+  if (smem > 48 * 1024)
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    configured = true;
-  }
   hipLaunchKernelGGL(kern, grid, dim3(512), smem, s, a);
 }
 
