@@ -356,6 +356,7 @@ struct Workspace {
   float *partials;
   // layer-stack buffers
   void *attn, *h1, *hn, *gate, *up, *xa, *xb;
+  float *f0 = nullptr, *f1 = nullptr;      // plain bf16 stack: sums of a linear before their one rounding
   size_t bytes;
   bool mfma = false;
   int k_splits = 1;                  // workgroups per output tile along the reduction axis of the QKV projection
@@ -385,7 +386,7 @@ int pick_splits(const alora_ctx *ctx, int T, int n_kv_heads, int max_len) {
 }
 
 Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, int n_splits, int k_splits,
-                           int intermediate, bool stack) {
+                           int intermediate, bool stack, bool f32_tail = false) {
   Bump b(base);
   Workspace w{};
   w.rm.seq = b.take<int32_t>(T);
@@ -410,6 +411,10 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
     w.up = b.take<char>((size_t)T * intermediate * esz);
     w.xa = b.take<char>((size_t)T * L.d * esz);
     w.xb = b.take<char>((size_t)T * L.d * esz);
+    if (f32_tail) {
+      w.f0 = b.take<float>((size_t)T * std::max(intermediate, L.d));
+      w.f1 = b.take<float>((size_t)T * std::max(intermediate, L.d));
+    }
   }
   w.bytes = b.off;
   return w;
@@ -594,11 +599,18 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
         g.C = (bf16 *)C; g.ldc = N; g.R = (const bf16 *)R;
         launch_gemm_mfma(g, GEMM_EPI_BF16, s);
       }
+    } else if (w.f0 != nullptr) {
+      // bf16 on the plain kernels: base product, low-rank term and residual are added in fp32 and rounded once
+      launch_gemm_plain_f32<T>((const T *)A, (const T *)W, w.f0, T_rows, N, K, s);
+      if (lr)
+        launch_lowrank_add_plain<T, float>((const T *)A, K, (const T *)Al, parts, part, (const T *)Bl, N, r, w.rm.adapter,
+                                           w.scale_dev, w.f0, T_rows, s);
+      launch_residual_store<T>(w.f0, (const T *)R, (T *)C, (int64_t)T_rows * N, s);
     } else {
       launch_gemm_plain<T>((const T *)A, (const T *)W, (const T *)R, (T *)C, T_rows, N, K, s);
       if (lr)
-        launch_lowrank_add_plain<T>((const T *)A, K, (const T *)Al, parts, part, (const T *)Bl, N, r, w.rm.adapter,
-                                    w.scale_dev, (T *)C, T_rows, s);
+        launch_lowrank_add_plain<T, T>((const T *)A, K, (const T *)Al, parts, part, (const T *)Bl, N, r, w.rm.adapter,
+                                       w.scale_dev, (T *)C, T_rows, s);
     }
   };
   // h1 = x + attn W_o^T, hn = RMSNorm(h1).  When the projection is split over the reduction axis anyway, the
@@ -654,6 +666,24 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     }
     g.C = (bf16 *)w.gate; g.ldc = ly->intermediate;
     launch_gemm_mfma(g, GEMM_EPI_SWIGLU, s);
+  } else if (w.f0 != nullptr) {
+    // bf16 on the plain kernels: gate and up stay in fp32 until silu(gate) * up is rounded, once
+    const bool lr = ly->A_gu != nullptr && w.any_adapter;
+    {
+      ProfScope p(ctx, K_GATEUP, s);
+      launch_gemm_plain_f32<T>((const T *)w.hn, (const T *)ly->W_gate, w.f0, T_rows, ly->intermediate, L.d, s);
+      launch_gemm_plain_f32<T>((const T *)w.hn, (const T *)ly->W_up, w.f1, T_rows, ly->intermediate, L.d, s);
+      if (lr) {
+        launch_lowrank_add_plain<T, float>((const T *)w.hn, L.d, (const T *)ly->A_gu, 2, 0, (const T *)ly->B_gate,
+                                           ly->intermediate, r, w.rm.adapter, w.scale_dev, w.f0, T_rows, s);
+        launch_lowrank_add_plain<T, float>((const T *)w.hn, L.d, (const T *)ly->A_gu, 2, 1, (const T *)ly->B_up,
+                                           ly->intermediate, r, w.rm.adapter, w.scale_dev, w.f1, T_rows, s);
+      }
+    }
+    {
+      ProfScope p(ctx, K_SILU, s);
+      launch_silu_mul_f32<T>(w.f0, w.f1, (T *)w.gate, (int64_t)T_rows * ly->intermediate, s);
+    }
   } else {
     {
       ProfScope p(ctx, K_GATEUP, s);
@@ -859,7 +889,8 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   int k_segments = mfma ? gemm_mfma_fixed_segments(L.n_qkv, L.d, ctx->n_cu) : 1;
   if (mfma && ctx->opt_gemm_splits > 0) k_segments = L.d % (64 * ctx->opt_gemm_splits) == 0 ? ctx->opt_gemm_splits : 1;
   const int k_splits = (k_segments > 1 && gemm_mfma_split_segments(pl.T, L.n_qkv, ctx->n_cu)) ? k_segments : 1;
-  Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
+  const bool f32_tail = stack && !mfma && layers[0].dtype == ALORA_BF16;
+  Workspace probe = layout_workspace(nullptr, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack, f32_tail);
   if (use_static) {
     // Everything the call needs beyond its inputs and outputs lives in the static scratch array of this GPU:
     //   [ workspace | per-sequence records | decode work list | rotary lines, one per row ]
@@ -1013,7 +1044,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (scale_bytes) memcpy(slot->host + seq_bytes + work_bytes, layers[0].scale, scale_bytes);
   HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
   const SeqMeta *seqs_dev = (const SeqMeta *)slot->dev;
-  Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack);
+  Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack, f32_tail);
   w.mfma = mfma;
   w.k_splits = k_splits;
   w.k_segments = k_segments;

@@ -59,7 +59,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- launchers: plain kernels (any dtype, any shape) ------------------------------------
-enum GemmEpilogue { EPI_F32_LORA = 0, EPI_STORE = 1, EPI_STORE_RESIDUAL = 2 };
+enum GemmEpilogue { EPI_F32_LORA = 0, EPI_STORE = 1, EPI_STORE_RESIDUAL = 2, EPI_STORE_F32 = 3 };
 
 void launch_rope_table(float2 *table, int n_pos, int half_dim, float theta, hipStream_t s);
 // one table line per row (entry row * half_dim + c belongs to position pos[row])
@@ -79,6 +79,15 @@ void launch_qkv_gemm_plain(const T *xh, const T *W, const float *tlow, const T *
 // C[M,N] (T) = A[M,K] B[N,K]^T (+ R[M,N])
 template <typename T>
 void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, int K, hipStream_t s);
+// The same product left in fp32 (no rounding to the storage type), for the callers that still add to it:
+// low-rank term, residual, SwiGLU -- so that a stored activation is rounded once, as in the fused MFMA epilogues.
+template <typename T>
+void launch_gemm_plain_f32(const T *A, const T *B, float *C, int M, int N, int K, hipStream_t s);
+// out = T(C + R) (R may be nullptr), and out = T(silu(gate) * up), from fp32 inputs
+template <typename T>
+void launch_residual_store(const float *C, const T *R, T *out, int64_t n, hipStream_t s);
+template <typename T>
+void launch_silu_mul_f32(const float *gate, const float *up, T *out, int64_t n, hipStream_t s);
 
 // q_mode: how the rotated queries are stored -- 0: as T, 1: as fp16 (operand type of the MFMA attention kernels),
 // 2: as fp32 (the plain attention kernel)
@@ -88,9 +97,10 @@ void launch_rope_append(const float *Y, int n_parts, const LayerDims &L, RowMeta
                         T *cacheV, hipStream_t s);
 
 // C[M, N] += gated low-rank term (Eq.6) of one linear: s_a B_a (A_{a,part} x) for rows with row_adapter >= 0
-template <typename T>
+// (TC: the type C is held in -- the storage type, or float for a sum that has not been rounded yet)
+template <typename T, typename TC>
 void launch_lowrank_add_plain(const T *x, int K, const T *A, int parts, int part, const T *B, int N, int rank,
-                              const int32_t *row_adapter, const float *scale, T *C, int M, hipStream_t s);
+                              const int32_t *row_adapter, const float *scale, TC *C, int M, hipStream_t s);
 
 // output head: fp32 logits[B, V] = xh[B, d] W[V, d]^T (any shape), and the greedy token of every row
 template <typename T>

@@ -212,6 +212,8 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(const T *__restrict__ A
           v += lo;
         }
         ((float *)Cv)[(int64_t)row * N + col] = v;
+      } else if (MODE == EPI_STORE_F32) {
+        ((float *)Cv)[(int64_t)row * N + col] = v;
       } else {
         if (MODE == EPI_STORE_RESIDUAL) v += to_f32<T>(R[(int64_t)row * N + col]);
         ((T *)Cv)[(int64_t)row * N + col] = from_f32<T>(v);
@@ -249,6 +251,16 @@ void launch_gemm_plain(const T *A, const T *B, const T *R, T *C, int M, int N, i
     hipLaunchKernelGGL((gemm_plain_kernel<T, EPI_STORE>), grid, dim3(256), 0, s, A, B, R, (void *)C, M, N, K,
                        epi);
 }
+template <typename T>
+void launch_gemm_plain_f32(const T *A, const T *B, float *C, int M, int N, int K, hipStream_t s) {
+  if (M == 0 || N == 0) return;
+  LoraEpi epi{};
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  hipLaunchKernelGGL((gemm_plain_kernel<T, EPI_STORE_F32>), grid, dim3(256), 0, s, A, B, (const T *)nullptr, (void *)C, M,
+                     N, K, epi);
+}
+template void launch_gemm_plain_f32<float>(const float *, const float *, float *, int, int, int, hipStream_t);
+template void launch_gemm_plain_f32<bf16>(const bf16 *, const bf16 *, float *, int, int, int, hipStream_t);
 template void launch_gemm_plain<float>(const float *, const float *, const float *, float *, int, int, int,
                                        hipStream_t);
 template void launch_gemm_plain<bf16>(const bf16 *, const bf16 *, const bf16 *, bf16 *, int, int, int,
@@ -535,16 +547,50 @@ void launch_silu_mul(const T *gate, const T *up, T *out, int64_t n, hipStream_t 
   int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
   hipLaunchKernelGGL((silu_mul_kernel<T>), dim3(grid), dim3(256), 0, s, gate, up, out, n);
 }
+template <typename T>
+__global__ void silu_mul_f32_kernel(const float *__restrict__ gate, const float *__restrict__ up, T *__restrict__ out,
+                                    int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    const float gv = gate[i];
+    out[i] = from_f32<T>(gv / (1.0f + __expf(-gv)) * up[i]);
+  }
+}
+template <typename T>
+void launch_silu_mul_f32(const float *gate, const float *up, T *out, int64_t n, hipStream_t s) {
+  if (n == 0) return;
+  int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  hipLaunchKernelGGL((silu_mul_f32_kernel<T>), dim3(grid), dim3(256), 0, s, gate, up, out, n);
+}
+template void launch_silu_mul_f32<float>(const float *, const float *, float *, int64_t, hipStream_t);
+template void launch_silu_mul_f32<bf16>(const float *, const float *, bf16 *, int64_t, hipStream_t);
+
+template <typename T>
+__global__ void residual_store_kernel(const float *__restrict__ C, const T *__restrict__ R, T *__restrict__ out,
+                                      int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = from_f32<T>(C[i] + (R != nullptr ? to_f32<T>(R[i]) : 0.f));
+}
+template <typename T>
+void launch_residual_store(const float *C, const T *R, T *out, int64_t n, hipStream_t s) {
+  if (n == 0) return;
+  int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  hipLaunchKernelGGL((residual_store_kernel<T>), dim3(grid), dim3(256), 0, s, C, R, out, n);
+}
+template void launch_residual_store<float>(const float *, const float *, float *, int64_t, hipStream_t);
+template void launch_residual_store<bf16>(const float *, const bf16 *, bf16 *, int64_t, hipStream_t);
 template void launch_silu_mul<float>(const float *, const float *, float *, int64_t, hipStream_t);
 template void launch_silu_mul<bf16>(const bf16 *, const bf16 *, bf16 *, int64_t, hipStream_t);
 
 // Gated low-rank term of Eq.6 added to an already computed linear, any shape and dtype:
 // C[row, :] += s_a * B_a (A_{a,part} x[row]) for adapted rows (a = row_adapter[row] >= 0).  One workgroup per row.
-template <typename T>
+template <typename T, typename TC>
 __global__ __launch_bounds__(256) void lowrank_add_plain_kernel(const T *__restrict__ x, int K, const T *__restrict__ A,
                                                                 int parts, int part, const T *__restrict__ B, int N,
                                                                 int rank, const int32_t *__restrict__ row_adapter,
-                                                                const float *__restrict__ scale, T *__restrict__ C) {
+                                                                const float *__restrict__ scale, TC *__restrict__ C) {
   __shared__ float t[256];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int a = row_adapter[row];
@@ -564,20 +610,22 @@ __global__ __launch_bounds__(256) void lowrank_add_plain_kernel(const T *__restr
     float acc = 0.f;
     for (int j = 0; j < rank; ++j) acc += to_f32<T>(br[j]) * t[j];
     const int64_t o = (int64_t)row * N + col;
-    C[o] = from_f32<T>(to_f32<T>(C[o]) + acc);
+    C[o] = from_f32<TC>(to_f32<TC>(C[o]) + acc);
   }
 }
 
-template <typename T>
+template <typename T, typename TC>
 void launch_lowrank_add_plain(const T *x, int K, const T *A, int parts, int part, const T *B, int N, int rank,
-                              const int32_t *row_adapter, const float *scale, T *C, int M, hipStream_t s) {
+                              const int32_t *row_adapter, const float *scale, TC *C, int M, hipStream_t s) {
   if (M == 0) return;
-  hipLaunchKernelGGL(lowrank_add_plain_kernel<T>, dim3(M), dim3(256), 0, s, x, K, A, parts, part, B, N, rank, row_adapter,
-                     scale, C);
+  hipLaunchKernelGGL((lowrank_add_plain_kernel<T, TC>), dim3(M), dim3(256), 0, s, x, K, A, parts, part, B, N, rank,
+                     row_adapter, scale, C);
 }
-template void launch_lowrank_add_plain<float>(const float *, int, const float *, int, int, const float *, int, int,
-                                              const int32_t *, const float *, float *, int, hipStream_t);
-template void launch_lowrank_add_plain<bf16>(const bf16 *, int, const bf16 *, int, int, const bf16 *, int, int,
-                                             const int32_t *, const float *, bf16 *, int, hipStream_t);
+template void launch_lowrank_add_plain<float, float>(const float *, int, const float *, int, int, const float *, int, int,
+                                                     const int32_t *, const float *, float *, int, hipStream_t);
+template void launch_lowrank_add_plain<bf16, bf16>(const bf16 *, int, const bf16 *, int, int, const bf16 *, int, int,
+                                                   const int32_t *, const float *, bf16 *, int, hipStream_t);
+template void launch_lowrank_add_plain<bf16, float>(const bf16 *, int, const bf16 *, int, int, const bf16 *, int, int,
+                                                    const int32_t *, const float *, float *, int, hipStream_t);
 
 }  // namespace alora
