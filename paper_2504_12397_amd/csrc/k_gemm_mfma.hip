@@ -692,8 +692,10 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else if (seg) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true, true>(g, s);
     else if (g.M > 4 * 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true>(g, s);
     // few row tiles: the kernel streams weights and eight waves (two per SIMD) hide its LDS and barrier
-    // latencies better than four; which way the 128x128 block is cut among them matters by a few percent
-    else if (g.M > 128) launch_cfg<128, 128, 32, 64, GEMM_EPI_PARTIAL>(g, s);
+    // latencies better than four.  The block is cut into 64x32 wave tiles: that variant stays under 128
+    // registers, so two workgroups share a compute unit -- with two row tiles and four reduction segments
+    // there are more workgroups than compute units (the 32x64 cut needs 131 registers: one workgroup per unit,
+    // a second round of workgroups, 34 instead of 31 us for a 256-row projection)
     else launch_cfg<128, 128, 64, 32, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
     g.k_splits = 1;
