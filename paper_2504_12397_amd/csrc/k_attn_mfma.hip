@@ -160,13 +160,10 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
       for (int v = 0; v < 16; ++v) o[cb][nb][v] = 0.f;
   const float c_scale = a.sm_scale * LOG2E;
   // softmax state of the lane's query row: the reference exponent m_ref (exp2 domain), the sum l_run of the
-  // probabilities of the keys this half of the wave holds, and for FOLD -m_ref in every register of negm
-  f32x16 negm;
+  // probabilities of the keys this half of the wave holds (for FOLD the score accumulators start at -m_ref)
   float m_ref = FOLD ? 0.f : -INFINITY;
   float l_run = 0.f;
   bool seen = false;        // the row has met a visible key (the same in both halves: derived from the shared maximum)
-#pragma unroll
-  for (int v = 0; v < 16; ++v) negm[v] = 0.f;
 
   // ---- tile loader: K rows as they are, V transposed in registers -------------------------
   // 512 threads: K = 1024 chunks of 16 B, two per thread; V = 16 key quads x 32 column groups of
@@ -270,7 +267,9 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kf[ks] = u4_as_f16x8(Ks[buf][key * 16 + ((2 * ks + kh) ^ (key & 15))]);
     if constexpr (FOLD) {
-      sv = negm;
+      const float neg_m = -m_ref;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[v] = neg_m;
     } else {
 #pragma unroll
       for (int v = 0; v < 16; ++v) sv[v] = 0.f;
@@ -292,7 +291,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     float mx = sv[0];
 #pragma unroll
     for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sv[v]);
-    mx = max_with_other_half(mx);
+    if constexpr (!FOLD) mx = max_with_other_half(mx);
     // The reference exponent of a row moves (and its 64 output accumulators and row sum are rescaled)
     // only in blocks where some row of the wave needs it -- a wave-uniform, rare branch: with random
     // scores a third of all blocks would otherwise move the maximum of some row.  The softmax is
@@ -301,16 +300,21 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_mfma_kernel(AttnArgs a) 
     if constexpr (FOLD) {
       // sv holds s - m_ref.  A row's first keys set the reference to their exact maximum (the largest
       // probability is then exactly 1, which matters most for rows that see few keys).
-      const bool fresh = !seen;                // nothing accumulated for this row yet
-      const bool want = mx > a.lazy || (fresh && mx > -INFINITY);
-      seen = seen || mx > -INFINITY;
-      if (__any(want)) {
+      // mx covers the keys of this half of the wave.  Whether ANY row of the wave has to move is decided from the
+      // half maxima (some half exceeds the threshold exactly when its row does); the exchange between the two
+      // halves of a row is needed only inside the rare branch.  A row's `seen` flag changes only there too: a half
+      // that meets its first key wants the branch, and both halves then take the row's maximum.
+      if (__any(mx > a.lazy || (!seen && mx > -INFINITY))) {
+        mx = max_with_other_half(mx);
+        const bool fresh = !seen;              // nothing accumulated for this row yet
+        const bool want = mx > a.lazy || (fresh && mx > -INFINITY);
+        seen = seen || mx > -INFINITY;
         const float delta = want ? mx : 0.f;
         const float alpha = fresh ? 1.0f : __builtin_amdgcn_exp2f(-delta);
         m_ref += delta;
         l_run *= alpha;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sv[v] -= delta; negm[v] -= delta; }
+        for (int v = 0; v < 16; ++v) sv[v] -= delta;
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
