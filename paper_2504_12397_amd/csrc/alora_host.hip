@@ -34,18 +34,18 @@ __global__ void stage_seqs_kernel(SeqChunk c, int n, SeqMeta *dst) {
   if ((int)threadIdx.x < n) dst[threadIdx.x] = c.m[threadIdx.x];
 }
 // the work list of the decode attention kernel for sequences without shared prefixes, in the order the host
-// builds it: item ((row * n_kv_heads) + g) * n_own + split covers split `split` of row `row`, kv head g
-__global__ void make_decode_items_kernel(DecItem *items, int n_items, int n_kv_heads, int n_own) {
+// builds it: item ((row * n_groups) + gb) * n_own + split covers split `split` of row `row`, kv heads gb * heads_per_wg ...
+__global__ void make_decode_items_kernel(DecItem *items, int n_items, int n_groups, int heads_per_wg, int n_own) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_items) return;
   DecItem it{};
   it.n_rows = 1;
   it.split = i % n_own;
-  it.g = (i / n_own) % n_kv_heads;
+  it.g = ((i / n_own) % n_groups) * heads_per_wg;
   it.n_splits = n_own;
   it.part = it.split;
   it.shared = 0;
-  it.rows[0] = i / (n_own * n_kv_heads);
+  it.rows[0] = i / (n_own * n_groups);
   items[i] = it;
 }
 
@@ -356,6 +356,7 @@ struct Workspace {
   float *partials;
   // layer-stack buffers
   void *attn, *h1, *hn, *gate, *up, *xa, *xb;
+  int dec_hw = 1, dec_kr = 1, dec_cols_max = 1;      // shape of the decode attention workgroups
   float *f0 = nullptr, *f1 = nullptr;      // plain bf16 stack: sums of a linear before their one rounding
   size_t bytes;
   bool mfma = false;
@@ -522,6 +523,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       a.n_q = L.n_q; a.n_kv = L.n_kv; a.n_q_heads = L.n_q_heads; a.n_kv_heads = L.n_kv_heads;
       a.items = w.ditems;
       a.n_parts = n_splits;
+      a.heads_per_wg = w.dec_hw; a.ranges_per_wg = w.dec_kr; a.cols_max = w.dec_cols_max;
       a.sm_scale = 1.0f / sqrtf((float)L.head_dim);
       a.partials = w.partials;
       launch_attn_decode_mfma(a, w.n_ditems, s);
@@ -756,24 +758,32 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
   const bool decode_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && decode &&
                            attn_decode_mfma_supported(L);
-  // Decode work list: per (row, kv head) n_own items over the row's own cache rows, and -- when
-  // sequences name shared prefixes -- per (group of up to 16 / G rows with the same prefix, kv head)
-  // n_shared items over that prefix.  Every (row, head) ends up with n_own + n_shared partial records.
+  // Decode work list: per (row, group of up to eight kv heads) n_own items over the row's own cache rows, and --
+  // when sequences name shared prefixes -- per (group of up to 16 / G rows with the same prefix, group of kv
+  // heads) n_shared items over that prefix.  Every (row, head) ends up with n_own + n_shared partial records.
+  // A workgroup's eight waves are heads_per_wg kv heads x ranges_per_wg sub-ranges of the item's keys.
   std::vector<DecItem> ditems;
   int n_static_items = 0, n_static_n_own = 1;
+  int dec_hw = 1, dec_kr = 1, dec_groups = 1, dec_cols_max = 1;
   if (decode_mfma) {
     const int G = L.n_q_heads / L.n_kv_heads;
     const int pack = std::max(1, 16 / G);
+    decode_mfma_shape(L.n_kv_heads, &dec_hw, &dec_kr);
+    dec_groups = (L.n_kv_heads + dec_hw - 1) / dec_hw;
+    dec_cols_max = G;
     int max_own = 1, max_pfx = 0;
     for (int b = 0; b < B; ++b) {
       max_own = std::max(max_own, pl.seqs[b].P + n_steps - pl.seqs[b].prefix_len);
       max_pfx = std::max(max_pfx, pl.seqs[b].prefix_len);
     }
-    // several workgroups of four waves per compute unit, at least 1024 keys each
+    // 32 waves per compute unit, each over a key range of at least 1024 keys (every range of a head costs a
+    // partial record unless it shares its workgroup): `items` (row, kv head) pairs need so many ranges each,
+    // ranges_per_wg of which share a workgroup (and a partial record)
     auto splits_for = [&](int64_t items, int longest) {
       if (ctx->opt_splits > 0) return ctx->opt_splits;
-      const int want = (int)std::max<int64_t>(1, (8 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1));
-      return std::max(1, std::min(std::min(want, 64), std::max(1, longest / 1024)));
+      const int64_t ranges = std::max<int64_t>(1, std::min<int64_t>((32 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1),
+                                                                    std::max(1, longest / 1024)));
+      return (int)std::max<int64_t>(1, std::min<int64_t>(64, (ranges + dec_kr - 1) / dec_kr));
     };
     const int n_own = splits_for((int64_t)pl.T * L.n_kv_heads, max_own);
     int n_shared = 0;
@@ -806,21 +816,22 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     }
     n_splits = n_own + n_shared;
     DecItem it{};
-    n_static_items = pl.T * L.n_kv_heads * n_own;     // (static entry point: the same list, built on the device)
+    n_static_items = pl.T * dec_groups * n_own;     // (static entry point: the same list, built on the device)
+    for (const auto &rows : chunks) dec_cols_max = std::max(dec_cols_max, (int)rows.size() * G);
     if (!use_static) {
     for (const auto &rows : chunks)
-      for (int g = 0; g < L.n_kv_heads; ++g)
+      for (int gb = 0; gb < dec_groups; ++gb)
         for (int sp = 0; sp < n_shared; ++sp) {
           it = DecItem{};
-          it.n_rows = (int)rows.size(); it.g = g; it.split = sp; it.n_splits = n_shared; it.part = n_own + sp; it.shared = 1;
+          it.n_rows = (int)rows.size(); it.g = gb * dec_hw; it.split = sp; it.n_splits = n_shared; it.part = n_own + sp; it.shared = 1;
           for (size_t i = 0; i < rows.size(); ++i) it.rows[i] = rows[i];
           ditems.push_back(it);
         }
     for (int row = 0; row < pl.T; ++row)
-      for (int g = 0; g < L.n_kv_heads; ++g)
+      for (int gb = 0; gb < dec_groups; ++gb)
         for (int sp = 0; sp < n_own; ++sp) {
           it = DecItem{};
-          it.n_rows = 1; it.g = g; it.split = sp; it.n_splits = n_own; it.part = sp; it.shared = 0;
+          it.n_rows = 1; it.g = gb * dec_hw; it.split = sp; it.n_splits = n_own; it.part = sp; it.shared = 0;
           it.rows[0] = row;
           ditems.push_back(it);
         }
@@ -917,7 +928,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     }
     if (decode_mfma && n_static_items > 0)
       hipLaunchKernelGGL(make_decode_items_kernel, dim3((n_static_items + 255) / 256), dim3(256), 0, s, items_dev,
-                         n_static_items, L.n_kv_heads, n_static_n_own);
+                         n_static_items, dec_groups, dec_hw, n_static_n_own);
     Workspace w = layout_workspace(base, L, pl.T, esz, n_splits, k_splits, 0, false);
     w.mfma = mfma;
     w.k_splits = k_splits;
@@ -928,6 +939,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     w.attn_waves = attn_waves;
     w.ditems = items_dev;
     w.n_ditems = decode_mfma ? n_static_items : 0;
+    w.dec_hw = dec_hw; w.dec_kr = dec_kr; w.dec_cols_max = dec_cols_max;
     w.any_adapter = pl.any_adapter;
     w.rope_by_row = true;
     w.rope_rows = (float2 *)(base + ws_bytes + seq_b + item_b);
@@ -1057,6 +1069,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.n_qtiles = (int)qtiles.size();
   w.ditems = (const DecItem *)(slot->dev + seq_bytes);
   w.n_ditems = (int)ditems.size();
+  w.dec_hw = dec_hw; w.dec_kr = dec_kr; w.dec_cols_max = dec_cols_max;
   w.scale_dev = (const float *)(slot->dev + seq_bytes + work_bytes);
   w.any_adapter = pl.any_adapter;
   w.rope = ctx->rope;

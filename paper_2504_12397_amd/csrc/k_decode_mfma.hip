@@ -1,8 +1,12 @@
 // Decode attention (Eq.4: one new query per sequence over its whole cache), memory-bound:
 // every cached key/value byte is read exactly once and everything else is kept out of the way.
 //
-// Work item: one workgroup = (rows, kv head, key split), listed by the host; its four waves take
-// disjoint key ranges and never synchronise until the final merge.  Normally an item is one row
+// Work item: one workgroup of eight waves = (rows, key split), listed by the host.  Wave w takes kv head
+// g0 + w % HW and sub-range w / HW of the item's keys (HW = kv heads per workgroup, 8 for eight or more kv heads):
+// the waves of a workgroup walk the same token rows of the cache at the same time, each its own 256-byte head
+// slice, so that between them they fetch whole rows of the token-major cache (2 KB at 8 kv heads) -- HBM delivers
+// 6.2 TB/s to that pattern and 5.6 TB/s when the heads of a row are fetched by unrelated workgroups.  The waves
+// never synchronise until the final merge of the sub-ranges.  Normally an item is one row
 // (one sequence's new token) over that sequence's own cache rows.  Sequences that name the same
 // shared prefix (Section 2, "Cache reuse patterns": several adapters on one context) are packed 16 / G to an item for the
 // prefix part: their heads fill the MFMA columns a single sequence leaves empty, and the prefix
@@ -49,14 +53,17 @@ __device__ __forceinline__ float dec_sum2(uint32_t pair, float acc) {
 constexpr float DEC_LOG2E = 1.4426950408889634f;
 constexpr float DEC_LN2 = 0.6931471805599453f;
 
-__global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(512) void attn_decode_mfma_kernel(DecodeArgs a) {
   constexpr int H = 128;
-  __shared__ float s_o[4][16][H + 2];      // per wave: [head][acc..., m, l]
+  extern __shared__ float s_o[];           // [wave][column < cols_max][acc..., m, l]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, kg = lane >> 4;           // j: head column / key row / V row; kg: k group
   const DecItem *it = a.items + blockIdx.x;
-  const int g = it->g, split = it->split;
+  const int HW = a.heads_per_wg, KR = a.ranges_per_wg, CM = a.cols_max;
+  const int hw = wave % HW, sub = wave / HW;
+  const bool active = sub < KR && it->g + hw < a.n_kv_heads;      // (a workgroup may hold fewer than eight (head, range) pairs)
+  const int g = min(it->g + hw, a.n_kv_heads - 1), split = it->split;
   const int G = a.n_q_heads / a.n_kv_heads;
   const int n_cols = it->n_rows * G;                 // MFMA columns in use: column = row index * G + head
   const int row_first = it->rows[0];
@@ -64,12 +71,12 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
   // the item's keys are pool rows key_row0 .. key_row0 + n_keys - 1
   const int n_keys = it->shared ? sm.prefix_len : a.rm.pos[row_first] + 1 - sm.prefix_len;
   const int64_t key_row0 = it->shared ? sm.prefix_off : sm.pool_off + sm.prefix_len;
-  // keys of this (split, wave): contiguous, multiple of 32
-  const int n_ranges = it->n_splits * 4;
+  // keys of this (split, sub-range): contiguous, multiple of 32
+  const int n_ranges = it->n_splits * KR;
   int per = (n_keys + n_ranges - 1) / n_ranges;
   per = (per + 31) & ~31;
-  const int kbeg = (split * 4 + wave) * per;
-  const int kend = min(n_keys, kbeg + per);
+  const int kbeg = active ? (split * KR + sub) * per : 0;
+  const int kend = active ? min(n_keys, kbeg + per) : 0;
   const bf16 *Kp = a.K + key_row0 * a.n_kv + g * H;
   const bf16 *Vp = a.V + key_row0 * a.n_kv + g * H;
 
@@ -169,32 +176,38 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(DecodeArgs a) {
     }
   }
 
-  // ---- merge the four waves (fixed order) and write the partial ---------------------------------
+  // ---- merge the sub-ranges of every head (fixed order) and write the partials ----------------------
   const float l_tot = l_run + __shfl_xor(l_run, 16, 64) + __shfl_xor(l_run, 32, 64) +
                       __shfl_xor(__shfl_xor(l_run, 16, 64), 32, 64);
   // o[c][v] of lane (j, kg) is O[column 8*(4*kg + v) + c][head j]
+  if (j < CM) {
+    float *mine = s_o + ((size_t)wave * CM + j) * (H + 2);
 #pragma unroll
-  for (int c = 0; c < 8; ++c)
+    for (int c = 0; c < 8; ++c)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) s_o[wave][j][8 * (4 * kg + v) + c] = o[c][v];
-  if (kg == 0) { s_o[wave][j][H] = m_run; s_o[wave][j][H + 1] = l_tot; }
+      for (int v = 0; v < 4; ++v) mine[8 * (4 * kg + v) + c] = o[c][v];
+    if (kg == 0) { mine[H] = m_run; mine[H + 1] = l_tot; }
+  }
   __syncthreads();
-  for (int i = tid; i < n_cols * H; i += 256) {
-    const int hd = i / H, col = i % H;
+  for (int i = tid; i < HW * n_cols * H; i += 512) {
+    const int hwi = i / (n_cols * H), rem = i - hwi * (n_cols * H);
+    const int hd = rem / H, col = rem % H;
+    const int gi = it->g + hwi;
+    if (gi >= a.n_kv_heads) continue;
     const int rj = hd / G, hj = hd - rj * G;
     const int orow = it->rows[rj];
+    // wave kr2 * HW + hwi holds sub-range kr2 of this head
     float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_o[w][hd][H]);
+    for (int kr2 = 0; kr2 < KR; ++kr2) M = fmaxf(M, s_o[((size_t)(kr2 * HW + hwi) * CM + hd) * (H + 2) + H]);
     float acc = 0.f, den = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float mw = s_o[w][hd][H];
+    for (int kr2 = 0; kr2 < KR; ++kr2) {
+      const float *src = s_o + ((size_t)(kr2 * HW + hwi) * CM + hd) * (H + 2);
+      const float mw = src[H];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      acc += wgt * s_o[w][hd][col];
-      den += wgt * s_o[w][hd][H + 1];
+      acc += wgt * src[col];
+      den += wgt * src[H + 1];
     }
-    float *pp = a.partials + (((int64_t)orow * a.n_q_heads + g * G + hj) * a.n_parts + it->part) * (H + 2);
+    float *pp = a.partials + (((int64_t)orow * a.n_q_heads + gi * G + hj) * a.n_parts + it->part) * (H + 2);
     pp[col] = acc;
     if (col == 0) {
       pp[H] = (M == -INFINITY) ? -INFINITY : M * DEC_LN2;     // natural-log domain for the merge kernel
@@ -208,9 +221,19 @@ bool attn_decode_mfma_supported(const LayerDims &L) {
   return L.head_dim == 128 && G <= 16;
 }
 
+void decode_mfma_shape(int n_kv_heads, int *heads_per_wg, int *ranges_per_wg) {
+  const int hw = n_kv_heads < 8 ? n_kv_heads : 8;
+  *heads_per_wg = hw;
+  *ranges_per_wg = 8 / hw;
+}
+
 void launch_attn_decode_mfma(const DecodeArgs &a, int n_items, hipStream_t s) {
   if (n_items == 0) return;
-  hipLaunchKernelGGL(attn_decode_mfma_kernel, dim3(n_items), dim3(256), 0, s, a);
+  const size_t smem = (size_t)8 * a.cols_max * (128 + 2) * sizeof(float);
+  // set on every launch that needs it: a host-side attribute write, safe from any thread and on any device
+  if (smem > 48 * 1024)
+    (void)hipFuncSetAttribute((const void *)attn_decode_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipLaunchKernelGGL(attn_decode_mfma_kernel, dim3(n_items), dim3(512), smem, s, a);
 }
 
 }  // namespace alora

@@ -75,7 +75,7 @@ struct AttnItem {
   int32_t n_addr;           // key positions that may be addressed from key_row0 (loads beyond kend are clamped to it)
   int32_t row0, ntok;       // packed rows row0 .. row0 + ntok - 1; ntok <= 0: padding item
   int32_t pos0;             // position of row0's token (token i sits at pos0 + i)
-  int32_t g;                // kv head
+  int32_t g;                // first kv head of the workgroup (its waves take g, g + 1, ...)
   int32_t part;             // which of the n_parts partial records of a (row, head) this item writes
   int32_t pad_[2];
 };
@@ -124,11 +124,15 @@ struct DecodeArgs {
   const DecItem *items;     // one per workgroup
   int n_q, n_kv, n_q_heads, n_kv_heads;
   int n_parts;              // partial records per (row, head)
+  int heads_per_wg;         // kv heads a workgroup covers (one wave each) and ...
+  int ranges_per_wg;        // ... sub-ranges its key split is cut in; heads_per_wg * ranges_per_wg <= 8 waves
+  int cols_max;             // largest n_rows * G over the items (MFMA columns in use; sizes the merge buffer)
   float sm_scale;
   float *partials;          // [rows, n_q_heads, n_parts, head_dim + 2]
 };
 bool attn_decode_mfma_supported(const LayerDims &L);
 void launch_attn_decode_mfma(const DecodeArgs &a, int n_items, hipStream_t s);
+void decode_mfma_shape(int n_kv_heads, int *heads_per_wg, int *ranges_per_wg);
 
 bool gemm_mfma_supported(int M, int N, int K);
 int gemm_mfma_pick_splits(int M, int N, int K, int n_cu);
