@@ -776,12 +776,12 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
       max_own = std::max(max_own, pl.seqs[b].P + n_steps - pl.seqs[b].prefix_len);
       max_pfx = std::max(max_pfx, pl.seqs[b].prefix_len);
     }
-    // 32 waves per compute unit, each over a key range of at least 1024 keys (every range of a head costs a
+    // 16 waves per compute unit (two rounds of workgroups), each over a key range of at least 1024 keys (every range of a head costs a
     // partial record unless it shares its workgroup): `items` (row, kv head) pairs need so many ranges each,
     // ranges_per_wg of which share a workgroup (and a partial record)
     auto splits_for = [&](int64_t items, int longest) {
       if (ctx->opt_splits > 0) return ctx->opt_splits;
-      const int64_t ranges = std::max<int64_t>(1, std::min<int64_t>((32 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1),
+      const int64_t ranges = std::max<int64_t>(1, std::min<int64_t>((16 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1),
                                                                     std::max(1, longest / 1024)));
       return (int)std::max<int64_t>(1, std::min<int64_t>(64, (ranges + dec_kr - 1) / dec_kr));
     };
