@@ -437,6 +437,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       pa.T = pl.T; pa.d = L.d; pa.seqs = seqs_dev; pa.n_seqs = pl.B; pa.pos_shift = pos_shift;
       pa.one = pl.seqs[0];
       pa.A = rank_used ? (const bf16 *)ly->A : nullptr; pa.rank = rank_used;
+      pa.n_adapters = L.n_adapters;
       pa.write_meta = write_meta ? 1 : 0;
       pa.xh = (bf16 *)w.xh; pa.tlow16 = (bf16 *)w.tlow; pa.rm = w.rm;
       launch_prep_rows_mfma(pa, s);

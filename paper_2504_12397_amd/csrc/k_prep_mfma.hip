@@ -41,7 +41,10 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
   const int row0 = blockIdx.x * PREP_ROWS;
   const int d = a.d;                            // = CH * 256
   const int col0 = blockIdx.y * 16 * NF;       // first column of t handled here
-  const bool lead = blockIdx.y == 0;
+  // gridDim.z > 1 (short batches of several sequences): workgroup z does the pass of adapter z only -- the passes
+  // of the adapters present in a row tile, each a memory round trip of its own, then run side by side
+  const int only = gridDim.z > 1 ? (int)blockIdx.z : -1;
+  const bool lead = blockIdx.y == 0 && blockIdx.z == 0;
   const int row = min(row0 + r16, a.T - 1);
   const bool row_ok = row0 + r16 < a.T;
   const int k_lo = wave * (CH * 32) + kg * 8;  // this lane's first element; chunk u is at k_lo + 32 u
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
 
   // ---- t partials over this wave's slice of d, one pass per adapter present in the row tile -------
   const int my_adapter = s_adapter[r16];
-  const unsigned long long present = NF > 0 ? s_present : 0ull;
+  const unsigned long long present = NF > 0 ? (only >= 0 ? s_present & (1ull << only) : s_present) : 0ull;
   const int rank = a.rank;
   f32x4 acc[NF > 0 ? NF : 1];
 #pragma unroll
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
     for (int i = tid; i < n_out; i += 512) {
       const int lr = i / (16 * NF), col = i % (16 * NF);
       const int orow = row0 + lr;
-      if (orow >= a.T || s_adapter[lr] < 0) continue;
+      if (orow >= a.T || s_adapter[lr] < 0 || (only >= 0 && s_adapter[lr] != only)) continue;
       float t = 0.f;
 #pragma unroll
       for (int w = 0; w < PREP_WAVES; ++w) t += s_part[(size_t)w * n_out + i];
@@ -262,7 +265,11 @@ bool prep_rows_mfma_supported(int d, int rank) {
 
 template <int NF, int CH, bool EARLY = false>
 static void launch_prep_cfg(const PrepArgs &a, int groups, hipStream_t s) {
-  const dim3 grid((a.T + PREP_ROWS - 1) / PREP_ROWS, groups);
+  const int row_tiles = (a.T + PREP_ROWS - 1) / PREP_ROWS;
+  // few row tiles, several sequences, several adapters: one workgroup per (row tile, column group, adapter)
+  const int per_adapter = (!EARLY && NF > 0 && a.n_adapters > 1 && a.n_adapters <= 16 && a.n_seqs > 1 &&
+                           row_tiles * groups * a.n_adapters <= 1024) ? a.n_adapters : 1;
+  const dim3 grid(row_tiles, groups, per_adapter);
   const size_t smem = (size_t)PREP_WAVES * PREP_ROWS * 16 * NF * sizeof(float);
   auto kern = prep_rows_mfma_kernel<NF, CH, EARLY>;
   // set on every launch that needs it: a host-side attribute write, safe from any thread and on any device

@@ -56,6 +56,7 @@ struct PrepArgs {
   int pos_shift;            // added to every position (step index of a multi-step decode)
   const bf16 *A;            // [n_adapters, 3, rank, d] or nullptr
   int rank;
+  int n_adapters;           // adapters stored in A (a short batch gives every adapter workgroups of its own)
   int write_meta;
   bf16 *xh;                 // [T, d]
   bf16 *tlow16;             // [T, 3, 2, rank]
@@ -75,7 +76,7 @@ struct AttnItem {
   int32_t n_addr;           // key positions that may be addressed from key_row0 (loads beyond kend are clamped to it)
   int32_t row0, ntok;       // packed rows row0 .. row0 + ntok - 1; ntok <= 0: padding item
   int32_t pos0;             // position of row0's token (token i sits at pos0 + i)
-  int32_t g;                // first kv head of the workgroup (its waves take g, g + 1, ...)
+  int32_t g;                // kv head
   int32_t part;             // which of the n_parts partial records of a (row, head) this item writes
   int32_t pad_[2];
 };
@@ -103,13 +104,13 @@ void launch_attn_prefill_mfma(const AttnArgs &a, int n_work, int G, int waves, b
 float attn_prefill_mfma_q_scale(const LayerDims &L, bool fold);
 
 // Decode attention (Eq.4): one query row per sequence over its whole cache.
-// One workgroup of the decode kernel: the query heads (of one GQA group) of up to 16 / G rows
-// against one range of keys.  shared = 0: the row's own cached positions [prefix_len, pos];
+// One workgroup of the decode kernel: the query heads of up to 16 / G rows, for up to eight kv heads (one wave
+// each), against one range of keys.  shared = 0: the row's own cached positions [prefix_len, pos];
 // shared = 1: the prefix [0, prefix_len) that all the item's rows name (one physical copy), so
 // its keys and values are read once for all of them.
 struct DecItem {
   int32_t n_rows;           // rows whose heads fill the MFMA columns (column = row index * G + head)
-  int32_t g;                // kv head
+  int32_t g;                // first kv head of the workgroup (its waves take g, g + 1, ...)
   int32_t split, n_splits;  // this item's share of its key range
   int32_t part;             // which of the n_parts partial records of (row, head) it writes
   int32_t shared;
