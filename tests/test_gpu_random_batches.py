@@ -85,3 +85,26 @@ def test_random_decode_batches(seed):
         H.report(test="random_decode", seed=seed, dtype=shape.dtype, opts=opts, err=worst)
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("heads", [(16, 16), (12, 6), (12, 12), (24, 12), (32, 8), (20, 10)])
+def test_decode_over_head_counts_that_do_not_fill_a_workgroup_evenly(heads):
+    """The decode kernel gives each of a workgroup's eight waves one kv head (Eq.4 per head; GQA grouping): more than
+    eight kv heads take several workgroups per key range, head counts that do not divide eight leave waves idle,
+    fewer than eight cut the key range among the spare waves.  Private and shared contexts, ragged lengths."""
+    from paper_2504_12397_amd import binding as ab
+    n_q_heads, n_kv_heads = heads
+    shape = wl.LayerShape(d=512, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=128, rank=16, n_adapters=3)
+    C = [1300, 90]
+    group = [0, 0, -1, 1, 0, 0, 0, 1, -1]
+    own = [0, 33, 2100, 5, 0, 1, 700, 0, 0]
+    n = len(group)
+    k = [C[g] if g >= 0 else 7 for g in group]
+    adapter = [b % 4 - 1 for b in range(n)]
+    ctx = ab.Context(0)
+    try:
+        case, ctx_kv = H.contexts_case(shape, C, group, own, [1] * n, k, adapter, seed=5000 + n_q_heads * 100 + n_kv_heads)
+        worst = H.run_contexts(ab, ctx, case, ctx_kv, C, group, own, decode=True)
+        H.report(test="decode_head_counts", heads=list(heads), err=worst)
+    finally:
+        ctx.close()
