@@ -252,6 +252,12 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    # what the host spends enqueueing a step (six steps: nothing in the library waits for the GPU that early)
+    t0 = time.perf_counter()
+    for i in range(min(6, steps)):
+        step(i)
+    host_ms_per_step = (time.perf_counter() - t0) / min(6, steps) * 1e3
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
         step(i)
@@ -286,8 +292,8 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
     result = {
         "metric": "alora_suffix_prefill_tok_per_s" if name != "c4" else "alora_decode_tok_per_s",
         "value": tok_s, "unit": "tok/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": shape.dtype, "data": "synthetic",
+        "ms_per_step": ms_per_step, "host_ms_per_step": round(host_ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": "", "sequences": batch.n_seqs, "suffix_tokens": batch.T,
                    "prefix_tokens": int(sum(batch.P)), "rank": shape.rank, "layers": n_layers,
                    "rotating_buffer_sets": rotate, "kernels": "plain" if args.plain else "auto",

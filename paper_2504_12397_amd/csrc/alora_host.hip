@@ -49,6 +49,13 @@ __global__ void make_decode_items_kernel(DecItem *items, int n_items, int n_grou
   items[i] = it;
 }
 
+// copies the staged metadata from the pinned host buffer (which the GPU can read directly) into device memory: as a
+// kernel it is one more dispatch in the stream's queue, where a copy operation is a hand-over to another engine
+__global__ void stage_meta_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int n16) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
 struct MetaSlot {
   char *host = nullptr;      // pinned
   char *dev = nullptr;
@@ -92,6 +99,7 @@ struct alora_ctx {
   int opt_gemm_tile = 0;
   int opt_attn_waves = 0;
   int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
+  int opt_stage_copy = 0;        // 1: the staged metadata travels by hipMemcpyAsync instead of a copy kernel
   int opt_attn_lazy = 3;         // lazy-maximum threshold of the prefill attention kernels, log2 units
   int opt_attn_partials16 = 1;   // split prefill attention (MFMA path): compact partial records
   int opt_rope_fuse = 1;         // rotation + cache append in the epilogue of the QKV projection where the shape allows
@@ -188,13 +196,23 @@ alora_status acquire_slot(alora_ctx *ctx, size_t bytes, MetaSlot **out) {
     sl.in_flight = false;
   }
   if (sl.cap < bytes) {
-    if (sl.host) HIP_TRY(ctx, hipHostFree(sl.host));
-    if (sl.dev) HIP_TRY(ctx, hipFree(sl.dev));
-    sl.host = nullptr; sl.dev = nullptr; sl.cap = 0;
-    size_t cap = std::max<size_t>(4096, bytes + bytes / 2);
-    HIP_TRY(ctx, hipHostMalloc((void **)&sl.host, cap, hipHostMallocDefault));
-    HIP_TRY(ctx, hipMalloc((void **)&sl.dev, cap));
-    sl.cap = cap;
+    // grow every slot of the ring now, not one per call: each growth is an allocation (and a wait for the slot's
+    // last user), which belongs in the first call of a given size and not in the seven after it
+    const size_t cap = (std::max<size_t>(4096, bytes + bytes / 2) + 15) & ~(size_t)15;
+    for (MetaSlot &o : ctx->slots) {
+      if (o.cap >= cap) continue;
+      if (o.in_flight) {
+        HIP_TRY(ctx, hipEventSynchronize(o.ev));
+        o.in_flight = false;
+      }
+      if (o.host) HIP_TRY(ctx, hipHostFree(o.host));
+      if (o.dev) HIP_TRY(ctx, hipFree(o.dev));
+      o.host = nullptr; o.dev = nullptr; o.cap = 0;
+      HIP_TRY(ctx, hipHostMalloc((void **)&o.host, cap, hipHostMallocDefault));
+      HIP_TRY(ctx, hipMalloc((void **)&o.dev, cap));
+      o.cap = cap;
+      if (!o.ev) HIP_TRY(ctx, hipEventCreateWithFlags(&o.ev, hipEventDisableTiming));
+    }
   }
   if (!sl.ev) HIP_TRY(ctx, hipEventCreateWithFlags(&sl.ev, hipEventDisableTiming));
   *out = &sl;
@@ -1055,7 +1073,13 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(AttnItem));
   if (!ditems.empty()) memcpy(slot->host + seq_bytes, ditems.data(), ditems.size() * sizeof(DecItem));
   if (scale_bytes) memcpy(slot->host + seq_bytes + work_bytes, layers[0].scale, scale_bytes);
-  HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
+  if (ctx->opt_stage_copy) {
+    HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
+  } else {
+    const int n16 = (int)((meta_bytes + 15) / 16);
+    hipLaunchKernelGGL(stage_meta_kernel, dim3((n16 + 255) / 256), dim3(256), 0, s, (const uint4 *)slot->host,
+                       (uint4 *)slot->dev, n16);
+  }
   const SeqMeta *seqs_dev = (const SeqMeta *)slot->dev;
   Workspace w = layout_workspace(ctx->ws, L, pl.T, esz, n_splits, k_splits, layers[0].intermediate, stack, f32_tail);
   w.mfma = mfma;
@@ -1204,6 +1228,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "lora_split")) {
     if (value < 0 || value > 2) return fail(ctx, ALORA_EINVAL, "lora_split must be 0, 1 or 2");
     ctx->opt_lora_split = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "stage_copy")) {
+    if (value < 0 || value > 1) return fail(ctx, ALORA_EINVAL, "stage_copy must be 0 or 1");
+    ctx->opt_stage_copy = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "attn_lazy")) {
