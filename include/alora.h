@@ -173,6 +173,8 @@ const char *alora_status_string(alora_status s);
  *   "attn_partials16" 1 (default): when prefill attention is split over the keys, the partial results travel
  *                     as compact records (accumulators scaled to [-1, 1] as fp16 plus three fp32 scalars,
  *                     272 bytes).  0: fp32 records (520 bytes).
+ *   "stage_copy"      0 (default): the per-call records (sequences, work lists) go from the pinned host ring to
+ *                     device memory by a small kernel on the call's stream.  1: by hipMemcpyAsync.
  *   "profile"         0 (default) / 1: see alora_profile_read.
  *
  * Summation order (Proposition 1 in its strong form: rows before the invocation index are the base model's
