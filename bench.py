@@ -182,8 +182,8 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
         if args.adapt_rest:
             import dataclasses
             shape = dataclasses.replace(shape, adapt_rest=True)
-    steps = args.steps or {"c2": 200, "c3": 20, "c4": 50, "c5": 10}[name]
-    warmup = args.warmup or {"c2": 20, "c3": 3, "c4": 5, "c5": 2}[name]
+    steps = args.steps or {"c2": 200, "c3": 60, "c4": 50, "c5": 10}[name]
+    warmup = args.warmup or {"c2": 20, "c3": 15, "c4": 5, "c5": 2}[name]
     rotate = args.rotate if args.rotate >= 0 else {"c2": 8, "c3": 2, "c4": 1, "c5": 1}[name]
     rotate = max(1, rotate)
 
