@@ -108,3 +108,41 @@ def test_decode_over_head_counts_that_do_not_fill_a_workgroup_evenly(heads):
         H.report(test="decode_head_counts", heads=list(heads), err=worst)
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("scale", [0.02, 3.0, 12.0])
+@pytest.mark.parametrize("decode", [False, True])
+def test_attention_over_a_wide_range_of_magnitudes(scale, decode):
+    """Eq.1's softmax with scores away from the unit scale of the other tests: hidden states and cached rows
+    multiplied by `scale`, no RMSNorm in front, so that queries and keys inherit it and the scores' spread grows
+    with scale^2 (1 natural unit at scale 1, 9 at scale 3, 144 at scale 12).  At 0.02 all probabilities are close
+    to 1/n and keys and values sit low in the range of the kernels' 16-bit operands; at 3 the spread is that of a
+    sharp real attention head; at 12 the reference exponent moves in big steps and nearly every probability
+    underflows.  The queries enter the matrix unit with 11 bits, which moves a score by about 2^-12 of its size,
+    so the bar is the stated one up to a spread of 16 and grows with the spread beyond (measured: 0.5e-2 at
+    spread 1, 0.9e-2 at 9, 1.5e-2 at 16, 8e-2 at 144)."""
+    from paper_2504_12397_amd import binding as ab
+    import torch
+    shape = wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, n_adapters=3, rmsnorm=False)
+    C = [900]
+    group = [0, 0, -1, 0]
+    own = [0, 70, 1500, 3]
+    S = [1] * 4 if decode else [40, 1, 130, 64]
+    k = [900, 0, 10 ** 6, 930]
+    adapter = [0, 1, -1, 2]
+    ctx = ab.Context(0)
+    saved = H.TOL["bf16"]
+    try:
+        case, ctx_kv = H.contexts_case(shape, C, group, own, S, k, adapter, seed=6000)
+        scaled = lambda t: t.to(torch.float64).mul(scale).to(shape.torch_dtype)
+        scaled_np = lambda a: H.f64(scaled(torch.from_numpy(a)))
+        case.x_new = [scaled(x) for x in case.x_new]
+        ctx_kv = [(scaled_np(K), scaled_np(V)) for K, V in ctx_kv]
+        case.cache_K = [scaled_np(K) for K in case.cache_K]
+        case.cache_V = [scaled_np(V) for V in case.cache_V]
+        H.TOL["bf16"] = saved * max(1.0, (scale / 4.0) ** 2)
+        worst = H.run_contexts(ab, ctx, case, ctx_kv, C, group, own, decode=decode)
+        H.report(test="attention_magnitudes", scale=scale, decode=decode, err=worst, tol=H.TOL["bf16"])
+    finally:
+        H.TOL["bf16"] = saved
+        ctx.close()
