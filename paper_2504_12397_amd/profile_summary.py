@@ -1,6 +1,6 @@
 """Turns rocprofv3 output of bench.py runs into the short summaries under profiles/ and profiles/traffic.json.
 
-    python -m paper_2504_12397_amd.profile_summary --in gpurun_out/prof --out profiles
+    python -m paper_2504_12397_amd.profile_summary --in <directory with the rocprofv3 output> --out profiles
 
 Expects under --in, per workload w in {c2, c3, c4, c5, r3p, r3pp} (any subset; r3p and r3pp are bench.py's r3p workload with
 --variant shared and --variant private):
