@@ -235,8 +235,9 @@ def regime3(n_contexts: int = 16, per_context: int = 4, context: int = 16384, ow
 
 
 def regime3_prefill(n_contexts: int = 4, per_context: int = 8, context: int = 16384, invocation: int = 16):
-    """The same regime at the moment the adapters are invoked (Section 2, "Cache reuse patterns"; Section 3's
-    invocation sequences are a handful of tokens): 4 contexts of 16384 base tokens, each invoked by 8 adapter calls
+    """The same regime at the moment the adapters are invoked (Section 2, "Cache reuse patterns"; the invocation
+    sequences of the appendix "Invocation sequences" are three or four tokens, Proposition 2's T_new counts them and
+    what follows): 4 contexts of 16384 base tokens, each invoked by 8 adapter calls
     whose 16-token invocation sequences are prefilled in one call.  Returns the batch and, per sequence, the index
     of its context."""
     n = n_contexts * per_context
