@@ -78,7 +78,7 @@ typedef struct {
   const void *rms_gain; /* DEVICE [d], or NULL: no RMSNorm before the projections      */
   float rms_eps;
   float rope_theta;
-  /* Rest of the layer, used by alora_stack_prefill only (all unadapted, may be NULL
+  /* Rest of the layer, used by alora_stack_prefill and alora_stack_decode only (may be NULL
    * otherwise): h = x + W_o attn; out = h + W_down( silu(W_gate n) * (W_up n) ),
    * n = RMSNorm(h; rms2_gain).                                                       */
   const void *W_o;      /* DEVICE [d, N_q]                                             */
@@ -89,7 +89,7 @@ typedef struct {
   /* Optional adapters of those linears (Section 2, remark after Eq.6: MLP blocks can be adapted
    * "via directly corresponding equations"; Proposition 1's proof covers them): the same rank,
    * scales and per-row gating (adapter >= 0 and position >= k) as q, k, v.  Each group is either
-   * given completely or NULL (that linear stays the base model's).  alora_stack_prefill only. */
+   * given completely or NULL (that linear stays the base model's).  alora_stack_prefill / alora_stack_decode only. */
   const void *A_o;      /* DEVICE [n_adapters, rank, N_q]                               */
   const void *B_o;      /* DEVICE [n_adapters, d, rank]                                 */
   const void *A_gu;     /* DEVICE [n_adapters, 2, rank, d]   (order gate, up)           */
@@ -260,6 +260,15 @@ alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers,
                                  alora_kv_cache *caches, const void *x, const int32_t *cu_seqlens,
                                  const int32_t *k_per_seq, const int32_t *adapter_per_seq,
                                  int32_t B, void *out, void *stream);
+
+/* One decode step through the same stack (Eq.4 in every layer: one new token per sequence over its whole
+ * cache; Section 3 lets an adapter generate 16 tokens after its first): alora_stack_prefill with one row per
+ * sequence, the attention of every layer running in the streaming decode kernel of alora_decode.
+ *   x_tok    DEVICE [B, d]  hidden state (embedding) of each sequence's new token
+ *   out      DEVICE [B, d]  hidden states after the last layer (alora_lm_head turns them into tokens) */
+alora_status alora_stack_decode(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers,
+                                alora_kv_cache *caches, const void *x_tok, const int32_t *k_per_seq,
+                                const int32_t *adapter_per_seq, int32_t B, void *out, void *stream);
 
 /* The first token itself (Section 3 times the adapter up to its first generated token): final
  * RMSNorm, projection on the vocabulary with the base model's (never adapted) output matrix, and

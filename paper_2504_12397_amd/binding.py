@@ -18,7 +18,7 @@ ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_ECAPACITY, ALORA_EADAPTER, ALORA_EDT
 ALORA_F32, ALORA_BF16 = 0, 1
 
 EXPORTS = ["alora_create", "alora_destroy", "alora_last_error", "alora_status_string", "alora_set_option",
-           "alora_profile_read", "alora_profile_reset", "alora_prefill", "alora_decode", "alora_decode_static", "alora_decode_steps", "alora_stack_prefill", "alora_lm_head"]
+           "alora_profile_read", "alora_profile_reset", "alora_prefill", "alora_decode", "alora_decode_static", "alora_decode_steps", "alora_stack_prefill", "alora_stack_decode", "alora_lm_head"]
 KERNELS = ["lm_head", "lm_argmax", "prep_rows", "qkv_gemm", "rope_append", "attn_prefill", "attn_decode", "attn_merge", "o_proj",
            "mlp_norm", "gate_up", "silu_mul", "down_proj"]
 
@@ -79,6 +79,9 @@ def load_library() -> C.CDLL:
     lib.alora_stack_prefill.restype = C.c_int
     lib.alora_stack_prefill.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int32, C.POINTER(KVCacheDesc),
                                         C.c_void_p, i32p, i32p, i32p, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.alora_stack_decode.restype = C.c_int
+    lib.alora_stack_decode.argtypes = [C.c_void_p, C.POINTER(LayerDesc), C.c_int32, C.POINTER(KVCacheDesc), C.c_void_p,
+                                       C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p]
     return lib
 
 
@@ -318,6 +321,26 @@ def alora_stack_prefill(ctx: Context, layers: List[Layer], caches: List[KVCache]
                                   ad.ctypes.data_as(p), B, _ptr(out), _stream_ptr(stream))
     ctx._check(st)
     # the library updated the seq_len array that caches[0] points at; mirror it to the others
+    for c in caches[1:]:
+        if c.seq_len is not caches[0].seq_len:
+            c.seq_len[:] = caches[0].seq_len
+    return out
+
+
+def alora_stack_decode(ctx: Context, layers: List[Layer], caches: List[KVCache], x_tok: torch.Tensor,
+                       k_per_seq: Sequence[int], adapter_per_seq: Sequence[int], out: Optional[torch.Tensor] = None,
+                       stream=None) -> torch.Tensor:
+    kk, ad = _i32(k_per_seq), _i32(adapter_per_seq)
+    B = len(kk)
+    n = len(layers)
+    descs = (LayerDesc * n)(*[l.desc for l in layers])
+    cdescs = (KVCacheDesc * n)(*[c.desc for c in caches])
+    if out is None:
+        out = torch.empty_like(x_tok)
+    p = C.POINTER(C.c_int32)
+    st = _lib.alora_stack_decode(ctx._h, descs, n, cdescs, _ptr(x_tok), kk.ctypes.data_as(p), ad.ctypes.data_as(p), B,
+                                 _ptr(out), _stream_ptr(stream))
+    ctx._check(st)
     for c in caches[1:]:
         if c.seq_len is not caches[0].seq_len:
             c.seq_len[:] = caches[0].seq_len

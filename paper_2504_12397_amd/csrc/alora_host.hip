@@ -758,7 +758,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (ctx->device < 0) {
     // a validation-only context still answers the size question of the static entry point
     if (use_static) {
-      const int ns = std::max(1, std::min(64, pl.max_len / 1024));      // upper bound on the key splits
+      const int ns = std::max(1, std::min(128, pl.max_len / 256));      // upper bound on the key splits
       const size_t need = layout_workspace(nullptr, L, pl.T, esz0, ns, 8, 0, false).bytes + (size_t)B * sizeof(SeqMeta) +
                           (size_t)pl.T * L.n_kv_heads * ns * sizeof(DecItem) + (size_t)pl.T * (L.head_dim / 2) * sizeof(float2) + 1024;
       if (need > SCRATCH_BYTES)
@@ -797,12 +797,14 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     }
     // 16 waves per compute unit (two rounds of workgroups), each over a key range of at least 1024 keys (every range of a head costs a
     // partial record unless it shares its workgroup): `items` (row, kv head) pairs need so many ranges each,
-    // ranges_per_wg of which share a workgroup (and a partial record)
+    // ranges_per_wg of which share a workgroup (and a partial record).  A handful of sequences over long caches
+    // cannot fill the chip with ranges that long: down to 256 keys then, up to 128 records per head.
     auto splits_for = [&](int64_t items, int longest) {
       if (ctx->opt_splits > 0) return ctx->opt_splits;
+      const bool few = 2 * items < ctx->n_cu;
       const int64_t ranges = std::max<int64_t>(1, std::min<int64_t>((16 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1),
-                                                                    std::max(1, longest / 1024)));
-      return (int)std::max<int64_t>(1, std::min<int64_t>(64, (ranges + dec_kr - 1) / dec_kr));
+                                                                    std::max(1, longest / (few ? 256 : 1024))));
+      return (int)std::max<int64_t>(1, std::min<int64_t>(few ? 128 : 64, (ranges + dec_kr - 1) / dec_kr));
     };
     const int n_own = splits_for((int64_t)pl.T * L.n_kv_heads, max_own);
     int n_shared = 0;
@@ -1113,10 +1115,10 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
     for (int l = 0; l < n_layers; ++l) {
       void *nxt = (l == n_layers - 1) ? out : ((l & 1) ? w.xb : w.xa);
       if (bf) {
-        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, seqs_dev, w, l == 0, n_splits, false, 0, (bf16 *)w.attn, s);
+        attention_block<bf16>(ctx, &layers[l], L, &caches[l], (const bf16 *)cur, pl, seqs_dev, w, l == 0, n_splits, decode, 0, (bf16 *)w.attn, s);
         layer_tail<bf16>(ctx, &layers[l], L, (const bf16 *)cur, w, pl.T, (bf16 *)nxt, s);
       } else {
-        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, seqs_dev, w, l == 0, n_splits, false, 0, (float *)w.attn, s);
+        attention_block<float>(ctx, &layers[l], L, &caches[l], (const float *)cur, pl, seqs_dev, w, l == 0, n_splits, decode, 0, (float *)w.attn, s);
         layer_tail<float>(ctx, &layers[l], L, (const float *)cur, w, pl.T, (float *)nxt, s);
       }
       cur = nxt;
@@ -1415,6 +1417,16 @@ alora_status alora_stack_prefill(alora_ctx *ctx, const alora_layer_desc *layers,
                                  const int32_t *k_per_seq, const int32_t *adapter_per_seq, int32_t B, void *out,
                                  void *stream) {
   return run(ctx, layers, n_layers, caches, x, cu_seqlens, k_per_seq, adapter_per_seq, B, out, stream, true);
+}
+
+alora_status alora_stack_decode(alora_ctx *ctx, const alora_layer_desc *layers, int32_t n_layers, alora_kv_cache *caches,
+                                const void *x_tok, const int32_t *k_per_seq, const int32_t *adapter_per_seq, int32_t B,
+                                void *out, void *stream) {
+  if (!ctx) return ALORA_EINVAL;
+  if (B < 1) return fail(ctx, ALORA_EINVAL, "B = %d must be at least 1", B);
+  std::vector<int32_t> cu(B + 1);
+  for (int b = 0; b <= B; ++b) cu[b] = b;
+  return run(ctx, layers, n_layers, caches, x_tok, cu.data(), k_per_seq, adapter_per_seq, B, out, stream, true, true);
 }
 
 }  // extern "C"

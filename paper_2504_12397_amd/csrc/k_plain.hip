@@ -453,8 +453,10 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const float *__restric
 }
 
 // One wave per (row, query head), four per workgroup.  The per-split maxima are fetched by the
-// first lanes in parallel, and the accumulators are read four splits at a time (fixed order).
-template <typename T>
+// first lanes in parallel, and the accumulators are read MU splits at a time (added in ascending order whatever
+// MU is: a short batch over a long cache has few (row, head) pairs and a hundred records each, and every group
+// of records is a memory round trip).
+template <typename T, int MU>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, LayerDims L, int n_splits,
                                                          int64_t n_rh, T *__restrict__ out) {
   const int lane = threadIdx.x & 63, h = L.head_dim;
@@ -469,10 +471,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
   M = wave_max(M);
   float denom = 0.f;
   float acc[ATT_DMAX] = {0.f, 0.f, 0.f, 0.f};
-  for (int s0 = 0; s0 < n_splits; s0 += 4) {
-    float ms[4], ls[4], v[4][ATT_DMAX];
+  for (int s0 = 0; s0 < n_splits; s0 += MU) {
+    float ms[MU], ls[MU], v[MU][ATT_DMAX];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < MU; ++u) {
       const int s = min(s0 + u, n_splits - 1);
       const float *ps = p + s * (h + 2);
       ms[u] = ps[h];
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < MU; ++u) {
       const float w = (s0 + u >= n_splits || ms[u] == -INFINITY) ? 0.f : __expf(ms[u] - M);
       denom += w * ls[u];
 #pragma unroll
@@ -496,6 +498,58 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
   for (int dd = 0; dd < ATT_DMAX; ++dd) {
     int c = lane + 64 * dd;
     if (c < h) out[rh * h + c] = from_f32<T>(acc[dd] * inv);
+  }
+}
+
+// The same merge for few (row, head) pairs with many records each (a handful of sequences decoding over long
+// caches): one workgroup per pair, its four waves take the records w, w + 4, w + 8, ... (eight in flight each, two
+// columns per lane and load), and their sums are added in wave order.  head_dim <= 128.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_merge_wide_kernel(const float *__restrict__ part, LayerDims L, int n_splits,
+                                                              T *__restrict__ out) {
+  __shared__ float s_acc[4][130];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = L.head_dim;
+  const int64_t rh = blockIdx.x;
+  const float *p = part + rh * n_splits * (h + 2);
+  float M = -INFINITY;
+  for (int s0 = 0; s0 < n_splits; s0 += 64) {
+    const int s = s0 + lane;
+    M = fmaxf(M, s < n_splits ? p[s * (h + 2) + h] : -INFINITY);
+  }
+  M = wave_max(M);
+  float denom = 0.f;
+  float2 acc = make_float2(0.f, 0.f);
+  const bool col_ok = 2 * lane < h;
+  constexpr int MU = 8;
+  for (int s0 = wave; s0 < n_splits; s0 += 4 * MU) {
+    float ms[MU], ls[MU];
+    float2 v[MU];
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      const int s = min(s0 + 4 * u, n_splits - 1);
+      const float *ps = p + s * (h + 2);
+      ms[u] = ps[h];
+      ls[u] = ps[h + 1];
+      v[u] = col_ok ? *reinterpret_cast<const float2 *>(ps + 2 * lane) : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      const float w = (s0 + 4 * u >= n_splits || ms[u] == -INFINITY) ? 0.f : __expf(ms[u] - M);
+      denom += w * ls[u];
+      acc.x += w * v[u].x;
+      acc.y += w * v[u].y;
+    }
+  }
+  if (col_ok) { s_acc[wave][2 * lane] = acc.x; s_acc[wave][2 * lane + 1] = acc.y; }
+  if (lane == 0) s_acc[wave][128] = denom;
+  __syncthreads();
+  if (wave == 0 && col_ok) {
+    const float d = ((s_acc[0][128] + s_acc[1][128]) + s_acc[2][128]) + s_acc[3][128];
+    const float inv = 1.0f / d;
+    const float x = ((s_acc[0][2 * lane] + s_acc[1][2 * lane]) + s_acc[2][2 * lane]) + s_acc[3][2 * lane];
+    const float y = ((s_acc[0][2 * lane + 1] + s_acc[1][2 * lane + 1]) + s_acc[2][2 * lane + 1]) + s_acc[3][2 * lane + 1];
+    out[rh * h + 2 * lane] = from_f32<T>(x * inv);
+    out[rh * h + 2 * lane + 1] = from_f32<T>(y * inv);
   }
 }
 
@@ -522,8 +576,14 @@ template <typename T>
 void launch_attn_merge(const float *partials, const LayerDims &L, int T_rows, int n_splits, T *out, hipStream_t s) {
   if (T_rows == 0) return;
   const int64_t n_rh = (int64_t)T_rows * L.n_q_heads;
-  hipLaunchKernelGGL((attn_merge_kernel<T>), dim3((unsigned)((n_rh + 3) / 4)), dim3(256), 0, s, partials, L, n_splits,
-                     n_rh, out);
+  if (n_splits >= 16 && n_rh <= 512 && L.head_dim <= 128 && L.head_dim % 2 == 0)
+    hipLaunchKernelGGL((attn_merge_wide_kernel<T>), dim3((unsigned)n_rh), dim3(256), 0, s, partials, L, n_splits, out);
+  else if (n_splits > 16)
+    hipLaunchKernelGGL((attn_merge_kernel<T, 32>), dim3((unsigned)((n_rh + 3) / 4)), dim3(256), 0, s, partials, L, n_splits,
+                       n_rh, out);
+  else
+    hipLaunchKernelGGL((attn_merge_kernel<T, 8>), dim3((unsigned)((n_rh + 3) / 4)), dim3(256), 0, s, partials, L, n_splits,
+                       n_rh, out);
 }
 template void launch_attn_merge<float>(const float *, const LayerDims &, int, int, float *, hipStream_t);
 template void launch_attn_merge<bf16>(const float *, const LayerDims &, int, int, bf16 *, hipStream_t);

@@ -453,6 +453,68 @@ def test_stack_cache_reuse_against_oracle_recompute(ab, ctx, shape):
     assert e2e <= 4 * H.TOL[shape.dtype]      # sanity bound on the compounded run; the bar is per layer, above
 
 
+@pytest.mark.parametrize("shape,opts", [(dataclasses.replace(SMALL_BF16, intermediate=1024), {}),
+                                        (dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=True), {}),
+                                        (dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=True), {"kernels": 1}),
+                                        (dataclasses.replace(SMALL_F32, intermediate=320), {})],
+                         ids=["bf16", "bf16-all-linears", "bf16-plain", "fp32"])
+def test_stack_decode_steps_continue_the_prefill(ab, shape, opts):
+    """Eq.4 through the stack: after the base model's prefill of P rows and the adapter's prefill of S rows, three
+    tokens are decoded one at a time with alora_stack_decode; the oracle recomputes the whole sequence with
+    position-gated weights.  Asserted layer by layer (each layer gets the oracle's own input for that layer), the
+    compounded two-layer figure is recorded; then a batch of three sequences of different lengths in one call."""
+    c = ab.Context(0)
+    try:
+        for k_, v in opts.items():
+            c.set_option(k_, v)
+        tol = H.TOL[shape.dtype]
+        n_layers, P, S, D, a = 2, 150, 20, 3, 1
+        tensors, layers, x_all = make_stack_case(shape, n_layers, P, S + D, seed=420)
+        x = H.f64(x_all)
+        for l, (t, L) in enumerate(zip(tensors, layers)):
+            xin = orc._store(x, shape.dtype)
+            want, _ = orc.ref_stack_full([L], xin, P, a, shape.dtype)
+            xg = torch.from_numpy(xin).to(shape.torch_dtype).cuda().contiguous()
+            gl = [H.gpu_layer(t, shape)]
+            cache = [ab.KVCache([P + S + D], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda")]
+            ab.alora_stack_prefill(c, gl, cache, xg[:P].contiguous(), [0, P], [0], [-1])
+            ab.alora_stack_prefill(c, gl, cache, xg[P:P + S].contiguous(), [0, S], [P], [a])
+            for t_ in range(D):
+                row = P + S + t_
+                got = ab.alora_stack_decode(c, gl, cache, xg[row:row + 1].contiguous(), [P], [a])
+                torch.cuda.synchronize()
+                assert int(cache[0].seq_len[0]) == row + 1
+                e = H.rel_err(H.f64(got), want[row:row + 1])
+                H.report(check="stack decode", layer=l, step=t_, err=e, tol=tol)
+                assert e <= tol, f"layer {l}, step {t_}: {e:.3e} > {tol}"
+            x = want
+        # the whole stack, and three sequences at once (different cached lengths, one base-only)
+        want, _ = orc.ref_stack_full(layers, H.f64(x_all), P, a, shape.dtype)
+        glayers = [H.gpu_layer(t, shape) for t in tensors]
+        Ps = [P + S, 37, P]
+        ks = [P, 10, 0]
+        ads = [a, 0, -1]
+        caches = [ab.KVCache([p_ + D + 1 for p_ in Ps], shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda")
+                  for _ in range(n_layers)]
+        xg = x_all.cuda().contiguous()
+        wants = [orc.ref_stack_full(layers, H.f64(x_all[:Ps[b] + D]), ks[b], ads[b], shape.dtype)[0] for b in range(3)]
+        # fill the three caches by prefill calls with the same gating the oracle used
+        ab.alora_stack_prefill(c, glayers, caches, torch.cat([xg[:Ps[0]], xg[:Ps[1]], xg[:Ps[2]]]).contiguous(),
+                               [0, Ps[0], Ps[0] + Ps[1], sum(Ps)], ks, ads)
+        worst = 0.0
+        for t_ in range(D):
+            xt = torch.stack([xg[Ps[b] + t_] for b in range(3)]).contiguous()
+            got = ab.alora_stack_decode(c, glayers, caches, xt, ks, ads)
+            torch.cuda.synchronize()
+            for b in range(3):
+                assert int(caches[0].seq_len[b]) == Ps[b] + t_ + 1 and int(caches[1].seq_len[b]) == Ps[b] + t_ + 1
+                worst = max(worst, H.rel_err(H.f64(got[b:b + 1]), wants[b][Ps[b] + t_:Ps[b] + t_ + 1]))
+        H.report(check="stack decode end to end, three sequences (recorded)", layers=n_layers, err=worst)
+        assert worst <= 4 * tol      # sanity bound on the compounded run; the bar is per layer, above
+    finally:
+        c.close()
+
+
 REST_BF16 = dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=True)
 REST_F32 = dataclasses.replace(SMALL_F32, intermediate=320, adapt_rest=True)
 
