@@ -47,7 +47,7 @@ __attribute__((amdgpu_waves_per_eu((WEAVE && SEG) ? 2 : 1))) void gemm_mfma_kern
   constexpr int BK = 64;
   constexpr int WAVES_N = BN / WN;
   constexpr int NT = 64 * (BM / WM) * WAVES_N;
-  static_assert(NT == 256 || NT == 512, "four or eight waves per block");
+  static_assert(NT == 128 || NT == 256 || NT == 512, "two, four or eight waves per block");
   constexpr int TM = WM / 32, TN = WN / 32;
   static_assert(EPI != GEMM_EPI_SWIGLU || TN % 2 == 0, "the SwiGLU epilogue pairs the 32-column blocks of a wave");
   constexpr int A_CHUNKS = BM * 8 / NT, B_CHUNKS = BN * 8 / NT;
@@ -673,6 +673,11 @@ bool gemm_mfma_rope_supported(const GemmArgs &g, int head_dim) {
 void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
   if (g.k_segments < 1) g.k_segments = 1;
+  if (epi == GEMM_EPI_SWIGLU) {
+    g.k_splits = 1;
+    g.lora_split = 0;
+    g.k_segments = 1;
+  }
   // one workgroup per output tile and a segmented reduction: the kernel adds the segment sums itself.  (The
   // tile shapes behind tile_hint are tuning experiments and do not carry that code.)
   const bool seg = g.k_splits == 1 && g.k_segments > 1 && g.tile_hint == 0 && (g.K / 64) % g.k_segments == 0;
@@ -691,6 +696,9 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL>(g, s);
     else if (seg) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true, true>(g, s);
     else if (g.M > 4 * 128) launch_cfg<128, 128, 64, 64, GEMM_EPI_PARTIAL, 2, true>(g, s);
+    // up to 32 rows (a decode step of a few sequences): a 32-row block does a quarter of the matrix and
+    // fragment work per weight tile and several workgroups share a compute unit
+    else if (g.M <= 32) launch_cfg<32, 128, 32, 32, GEMM_EPI_PARTIAL>(g, s);
     // few row tiles: the kernel streams weights and eight waves (two per SIMD) hide its LDS and barrier
     // latencies better than four.  The block is cut into 64x32 wave tiles: that variant stays under 128
     // registers, so two workgroups share a compute unit -- with two row tiles and four reduction segments
@@ -698,13 +706,11 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     // a second round of workgroups, 34 instead of 31 us for a 256-row projection)
     else launch_cfg<128, 128, 64, 32, GEMM_EPI_PARTIAL>(g, s);
   } else if (epi == GEMM_EPI_SWIGLU) {
-    g.k_splits = 1;
-    g.lora_split = 0;
-    g.k_segments = 1;
     if (g.tile_hint == 4) launch_cfg<128, 64, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     // (a wave needs a gate block and its up block: at least two 32-column blocks, so no 64x32 wave tiles here)
     else if (g.tile_hint == 5 || g.tile_hint == 6) launch_cfg<128, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
+    else if (g.M <= 32) launch_cfg<32, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     else if (g.M <= 128) launch_cfg<128, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     else launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
   } else {
@@ -714,7 +720,10 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else if (g.tile_hint == 5) launch_cfg<128, 128, 32, 64, GEMM_EPI_BF16>(g, s);
     else if (g.tile_hint == 6) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
     else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_BF16>(g, s);
-    else if (g.M <= 128) {
+    else if (g.M <= 32) {
+      if (seg) launch_cfg<32, 128, 32, 32, GEMM_EPI_BF16, 2, false, true>(g, s);
+      else launch_cfg<32, 128, 32, 32, GEMM_EPI_BF16>(g, s);
+    } else if (g.M <= 128) {
       if (seg) launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16, 2, false, true>(g, s);
       else launch_cfg<128, 128, 64, 32, GEMM_EPI_BF16>(g, s);
     } else {
