@@ -412,6 +412,7 @@ Workspace layout_workspace(char *base, const LayerDims &L, int T, size_t esz, in
   w.rm.pos = b.take<int32_t>(T);
   w.rm.adapter = b.take<int32_t>(T);
   w.rm.slot = b.take<int64_t>(T);
+  w.rm.present16 = b.take<unsigned long long>((T + 15) / 16);
   w.xh = b.take<char>((size_t)T * L.d * esz);
   w.tlow = b.take<float>((size_t)T * 3 * std::max(L.rank, 1));
   w.y_floats = (size_t)T * L.n_qkv * (std::max(k_splits, 1) + 1);
@@ -446,10 +447,11 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
                      const T *x, const Plan &pl, const SeqMeta *seqs_dev, const Workspace &w, bool write_meta,
                      int n_splits, bool decode, int pos_shift, T *out, hipStream_t s) {
   const bool mfma = w.mfma && std::is_same<T, bf16>::value;
+  const int rank_used = pl.any_adapter ? L.rank : 0;
+  const bool prep_mfma = mfma && prep_rows_mfma_supported(L.d, rank_used);      // it also leaves the adapter masks
   {
     ProfScope p(ctx, K_PREP, s);
-    const int rank_used = pl.any_adapter ? L.rank : 0;
-    if (mfma && prep_rows_mfma_supported(L.d, rank_used)) {
+    if (prep_mfma) {
       PrepArgs pa{};
       pa.x = (const bf16 *)x; pa.gain = (const bf16 *)ly->rms_gain; pa.eps = ly->rms_eps;
       pa.T = pl.T; pa.d = L.d; pa.seqs = seqs_dev; pa.n_seqs = pl.B; pa.pos_shift = pos_shift;
@@ -490,6 +492,7 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       g.Bq = (const bf16 *)ly->B_q; g.Bk = (const bf16 *)ly->B_k; g.Bv = (const bf16 *)ly->B_v;
       g.n_q = L.n_q; g.n_kv = L.n_kv;
       g.row_adapter = w.rm.adapter;
+      g.present16 = prep_mfma ? w.rm.present16 : nullptr;
       // many rows, unsplit reduction, one head per column tile: rotation and cache append happen in the
       // projection's epilogue and the fp32 projection never goes to memory
       if (ctx->opt_gemm_tile == 0 && ctx->opt_rope_fuse && q_half && !w.rope_by_row &&
@@ -586,6 +589,7 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
     g.Bq = (const bf16 *)B0; g.Bk = (const bf16 *)B1; g.Bv = nullptr;
     g.n_q = width; g.n_kv = parts == 1 ? 0 : width;
     g.row_adapter = w.rm.adapter;
+    g.present16 = prep_rows_mfma_supported(L.d, r) ? w.rm.present16 : nullptr;      // (the row preparation that wrote it)
   };
   // reduction segments of a linear [N, K]: fixed by the weight shape (or by the gemm_splits option), so that a
   // row's result does not depend on the number of rows in the call

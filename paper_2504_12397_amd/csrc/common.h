@@ -33,6 +33,8 @@ struct RowMeta {
   int32_t *pos;        // [T] absolute position p(i)
   int32_t *adapter;    // [T] adapter id if the row is adapted (a >= 0 and p >= k), else -1
   int64_t *slot;       // [T] pool row where this token's key/value go
+  unsigned long long *present16;   // [ceil(T / 16)] bit a set: a row of this group of 16 is adapted by adapter a
+                                   // (written by the MFMA row preparation; nullptr when nobody writes it)
 };
 
 struct LayerDims {

@@ -251,17 +251,25 @@ __attribute__((amdgpu_waves_per_eu((WEAVE && SEG) ? 2 : 1))) void gemm_mfma_kern
   // (runs while the first two main-loop tiles are already on their way from memory; its own loads
   // are issued two k-steps at a time before the MFMAs that use them)
   if (g.tlow != nullptr && (g.lora_split ? lora_only : split == 0)) {
-    if (tid == 0) s_present = 0ull;
-    __syncthreads();
-    for (int r = tid; r < BM; r += NT) {
-      int row = m0 + r;
-      if (row < M) {
-        int a = g.row_adapter[row];
-        if (a >= 0) atomicOr(&s_present, 1ull << a);
+    // the adapters among this tile's rows: from the per-16-row masks the row preparation left (uniform
+    // addresses, no barrier), else collected here from the rows' adapter ids
+    unsigned long long present = 0ull;
+    if (g.present16 != nullptr) {
+      const int t_end = min((m0 + BM) / 16, (M + 15) / 16);
+      for (int t = m0 / 16; t < t_end; ++t) present |= g.present16[t];
+    } else {
+      if (tid == 0) s_present = 0ull;
+      __syncthreads();
+      for (int r = tid; r < BM; r += NT) {
+        int row = m0 + r;
+        if (row < M) {
+          int a = g.row_adapter[row];
+          if (a >= 0) atomicOr(&s_present, 1ull << a);
+        }
       }
+      __syncthreads();
+      present = s_present;
     }
-    __syncthreads();
-    unsigned long long present = s_present;
     const int r = g.rank;
     int a_row[TM];
 #pragma unroll
@@ -316,16 +324,25 @@ __attribute__((amdgpu_waves_per_eu((WEAVE && SEG) ? 2 : 1))) void gemm_mfma_kern
           }
 #pragma unroll
           for (int mi = 0; mi < TM; ++mi) {
-            const int row = m0 + wm0 + mi * 32 + l32;
+            // every row's t is requested (rows past the end: the last row's) and the rows of other adapters are
+            // zeroed afterwards, so the request does not wait for the rows' adapter ids
+            const int row = min(m0 + wm0 + mi * 32 + l32, M - 1);
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni) {
               au[h2][mi][ni] = u32x4{0, 0, 0, 0};
-              if (live && a_row[mi] == a)
+              if (live)
                 au[h2][mi][ni] =
                     *reinterpret_cast<const u32x4 *>(g.tlow + ((int64_t)row * parts + p_of[ni]) * 2 * r + ks2 + lhi * 8);
             }
           }
         }
+#pragma unroll
+        for (int h2 = 0; h2 < PB; ++h2)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+              if (a_row[mi] != a) au[h2][mi][ni] = u32x4{0, 0, 0, 0};
 #pragma unroll
         for (int h2 = 0; h2 < PB; ++h2)
 #pragma unroll

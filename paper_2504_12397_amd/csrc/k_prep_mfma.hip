@@ -122,6 +122,7 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
     if (tid < d / 8) s_gain[tid] = gown;
   }
   __syncthreads();
+  if (lead && tid == 0 && a.rm.present16 != nullptr) a.rm.present16[blockIdx.x] = s_present;
   if (a.gain != nullptr) {
     float t = 0.f;
 #pragma unroll

@@ -31,6 +31,8 @@ struct GemmArgs {
   const bf16 *Bq, *Bk, *Bv;
   int n_q, n_kv;
   const int32_t *row_adapter;  // [M]: adapter id of adapted rows, -1 otherwise
+  const unsigned long long *present16;   // [ceil(M / 16)] adapters among each 16 rows as a bit mask, or nullptr (the
+                               // workgroup then finds the adapters of its rows itself: one more memory round trip)
   // ROPE epilogue (the QKV projection with an unsplit reduction and head_dim = 128 = the column tile): q and k
   // heads are rotated (Eq.3's K_t before it is appended) and every head goes where the rotary kernel would have
   // put it -- Q [M, n_q], the cache rows rope_slot[row] of K and V -- without the fp32 round trip through memory
