@@ -156,6 +156,10 @@ const char *alora_status_string(alora_status s);
  *                     (four waves); 5 / 6: 128x128 on eight waves of 32x64 / 64x32.  1 and 4..6 also apply to
  *                     the other linears of a stack.  A tuning experiment: with a value other than 0 the
  *                     summation-order guarantee below does not hold.
+ *   "prep_split"      1 (default): calls without any adapter, with 512 rows or more at hidden size 4096 (a
+ *                     base-model prefill), normalise their rows in a row-per-wave kernel; shorter calls and
+ *                     calls with adapters use the kernel that prepares 16 rows per workgroup.  0: never, 2: at any
+ *                     number of rows.  The normalised rows are bit-identical either way.
  *   "lora_split"      0 (default): automatic.  1: always, 2: never give the low-rank term of the QKV
  *                     projection workgroups (and a partial sum) of its own.
  *   "rope_fuse"       1 (default): where the shape allows (more than 256 rows, head size 128) the QKV

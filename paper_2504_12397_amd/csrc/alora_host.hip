@@ -97,6 +97,7 @@ struct alora_ctx {
   int opt_splits = 0;
   int opt_gemm_splits = 0;
   int opt_gemm_tile = 0;
+  int opt_prep_split = 1;        // calls without adapters: 1: many rows take the row-per-wave RMSNorm kernel; 0: never; 2: always
   int opt_attn_waves = 0;
   int opt_lora_split = 0;        // 0 = automatic, 1 = always, 2 = never: low-rank term in workgroups of its own
   int opt_stage_copy = 0;        // 1: the staged metadata travels by hipMemcpyAsync instead of a copy kernel
@@ -460,7 +461,14 @@ void attention_block(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims
       pa.n_adapters = L.n_adapters;
       pa.write_meta = write_meta ? 1 : 0;
       pa.xh = (bf16 *)w.xh; pa.tlow16 = (bf16 *)w.tlow; pa.rm = w.rm;
-      launch_prep_rows_mfma(pa, s);
+      // Many rows and no adapter in the call (a base-model prefill): the kernel that holds 16 rows per workgroup
+      // in registers runs one workgroup per compute unit and needs several rounds; a row-per-wave kernel does
+      // metadata and RMSNorm at streaming rate, with the same bits.
+      if (rank_used == 0 && ctx->opt_prep_split != 0 && norm_rows_mfma_supported(L.d) &&
+          (pl.T >= 512 || ctx->opt_prep_split == 2))
+        launch_norm_rows_mfma(pa, s);
+      else
+        launch_prep_rows_mfma(pa, s);
     } else {
       launch_prep_rows<T>(x, (const T *)ly->rms_gain, ly->rms_eps, pl.T, L.d, seqs_dev, pl.B, pos_shift,
                           (const T *)ly->A, rank_used, write_meta, (T *)w.xh, w.tlow, mfma ? (bf16 *)w.tlow : nullptr, w.rm, s);
@@ -1070,7 +1078,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   }
   const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
   const size_t work_bytes = (qtiles.size() * sizeof(AttnItem) + ditems.size() * sizeof(DecItem) + 15) & ~(size_t)15;   // one of the two lists
-  const size_t scale_bytes = stack ? (size_t)L.n_adapters * sizeof(float) : 0;
+  const size_t scale_bytes = stack ? (((size_t)L.n_adapters * sizeof(float) + 15) & ~(size_t)15) : 0;
   const size_t meta_bytes = seq_bytes + work_bytes + scale_bytes;
   MetaSlot *slot = nullptr;
   st = acquire_slot(ctx, meta_bytes, &slot);
@@ -1078,7 +1086,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   memcpy(slot->host, pl.seqs.data(), (size_t)B * sizeof(SeqMeta));
   if (!qtiles.empty()) memcpy(slot->host + seq_bytes, qtiles.data(), qtiles.size() * sizeof(AttnItem));
   if (!ditems.empty()) memcpy(slot->host + seq_bytes, ditems.data(), ditems.size() * sizeof(DecItem));
-  if (scale_bytes) memcpy(slot->host + seq_bytes + work_bytes, layers[0].scale, scale_bytes);
+  if (scale_bytes) memcpy(slot->host + seq_bytes + work_bytes, layers[0].scale, (size_t)L.n_adapters * sizeof(float));
   if (ctx->opt_stage_copy) {
     HIP_TRY(ctx, hipMemcpyAsync(slot->dev, slot->host, meta_bytes, hipMemcpyHostToDevice, s));
   } else {
@@ -1101,7 +1109,7 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   w.ditems = (const DecItem *)(slot->dev + seq_bytes);
   w.n_ditems = (int)ditems.size();
   w.dec_hw = dec_hw; w.dec_kr = dec_kr; w.dec_cols_max = dec_cols_max;
-  w.scale_dev = (const float *)(slot->dev + seq_bytes + work_bytes);
+  w.scale_dev = scale_bytes ? (const float *)(slot->dev + seq_bytes + work_bytes) : nullptr;
   w.any_adapter = pl.any_adapter;
   w.rope = ctx->rope;
 
@@ -1264,6 +1272,11 @@ alora_status alora_set_option(alora_ctx *ctx, const char *key, int value) {
   if (!strcmp(key, "attn_waves")) {
     if (value != 0 && value != 4 && value != 8) return fail(ctx, ALORA_EINVAL, "attn_waves must be 0, 4 or 8");
     ctx->opt_attn_waves = value;
+    return ALORA_OK;
+  }
+  if (!strcmp(key, "prep_split")) {
+    if (value < 0 || value > 2) return fail(ctx, ALORA_EINVAL, "prep_split must be 0, 1 or 2");
+    ctx->opt_prep_split = value;
     return ALORA_OK;
   }
   if (!strcmp(key, "gemm_tile")) {

@@ -17,6 +17,45 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int PREP_ROWS = 16;
 constexpr int PREP_WAVES = 8;
 
+// Sum of squares of a row, in ONE order for every kernel that normalises rows (a row's x_hat must not depend on
+// which of them ran -- the base rows of a long prefill and of a decode step are compared bit for bit): the
+// row is cut into 16-byte chunks, chunk index c = 64 w + 4 u + g (w < 8, u < d / 256, g < 4); a chunk's eight
+// squares are added in order starting from zero; the chunk sums of one (w, g) go through a balanced tree over u
+// (neighbours first), the four g of a w through a tree (g ^ 1, then g ^ 2), the eight w are added in order.
+__device__ __forceinline__ float chunk_ssq(u32x4 c) {
+  const bf16x8 v = __builtin_bit_cast(bf16x8, c);
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; s = __builtin_fmaf(f, f, s); }
+  return s;
+}
+__device__ __forceinline__ float row_rinv(float ssq, int d, float eps) { return 1.0f / sqrtf(ssq / (float)d + eps); }
+__device__ __forceinline__ u32x4 norm_chunk(u32x4 x, u32x4 g, float rinv) {
+  const bf16x8 xv = __builtin_bit_cast(bf16x8, x), gv = __builtin_bit_cast(bf16x8, g);
+  bf16x8 xh;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
+  return __builtin_bit_cast(u32x4, xh);
+}
+// Metadata of the rows [row0, tile_end) of one tile: a thread takes a sequence, fetches its record once and fills
+// in the rows of the tile that belong to it -- one memory round trip, where a search over the sequence table
+// per row costs log2(n_seqs) dependent ones.  s_adapter / s_scale may be nullptr.
+__device__ __forceinline__ void fill_row_meta(const PrepArgs &a, const SeqMeta &sm, int sq, int mrow, int row0, bool write,
+                                              int *s_adapter, float *s_scale, unsigned long long *s_present) {
+  const int pos = sm.P + a.pos_shift + (mrow - sm.row_start);
+  int adapter = -1;
+  float scale = 0.f;
+  if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
+  if (write) {
+    a.rm.seq[mrow] = sq;
+    a.rm.pos[mrow] = pos;
+    a.rm.adapter[mrow] = adapter;
+    a.rm.slot[mrow] = sm.pool_off + pos;
+  }
+  if (s_adapter != nullptr) { s_adapter[mrow - row0] = adapter; s_scale[mrow - row0] = scale; }
+  if (adapter >= 0) atomicOr(s_present, 1ull << adapter);
+}
+
 // NF = 16-column fragments of t this workgroup computes (0: no adapter work).  The 3*rank columns
 // of t are spread over gridDim.y workgroups so that short batches still fill the chip; group 0
 // also writes x_hat and the row metadata.  CH = d / 256: 16-byte chunks of its row each lane
@@ -82,19 +121,7 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
   // log2(n_seqs) dependent ones.
   const int tile_end = min(row0 + PREP_ROWS, a.T);
   auto fill_row = [&](const SeqMeta &sm, int sq, int mrow) {
-    const int pos = sm.P + a.pos_shift + (mrow - sm.row_start);
-    int adapter = -1;
-    float scale = 0.f;
-    if (sm.adapter >= 0 && pos >= sm.k) { adapter = sm.adapter; scale = sm.scale; }
-    if (a.write_meta && lead) {
-      a.rm.seq[mrow] = sq;
-      a.rm.pos[mrow] = pos;
-      a.rm.adapter[mrow] = adapter;
-      a.rm.slot[mrow] = sm.pool_off + pos;
-    }
-    s_adapter[mrow - row0] = adapter;
-    s_scale[mrow - row0] = scale;
-    if (adapter >= 0) atomicOr(&s_present, 1ull << adapter);
+    fill_row_meta(a, sm, sq, mrow, row0, a.write_meta && lead, s_adapter, s_scale, &s_present);
   };
   if constexpr (EARLY) {
     if (tid < PREP_ROWS && row0 + tid < tile_end) fill_row(a.one, 0, row0 + tid);
@@ -109,13 +136,14 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
   // ---- sum of squares: lane -> the 4 lanes of a row -> the 8 waves (fixed order) ------------------
   float rinv = 1.f;
   if (a.gain != nullptr) {
-    float ssq = 0.f;
+    float cs[CH];
 #pragma unroll
-    for (int u = 0; u < CH; ++u) {
-      const bf16x8 v = __builtin_bit_cast(bf16x8, xr[u]);
+    for (int u = 0; u < CH; ++u) cs[u] = chunk_ssq(xr[u]);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ssq += f * f; }
-    }
+    for (int st = 1; st < CH; st *= 2)
+#pragma unroll
+      for (int u = 0; u < CH; u += 2 * st) cs[u] += cs[u + st];
+    float ssq = cs[0];
     ssq += __shfl_xor(ssq, 16, 64);
     ssq += __shfl_xor(ssq, 32, 64);
     if (kg == 0) s_ssq[wave][r16] = ssq;
@@ -127,16 +155,10 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
     float t = 0.f;
 #pragma unroll
     for (int w = 0; w < PREP_WAVES; ++w) t += s_ssq[w][r16];
-    rinv = 1.0f / sqrtf(t / (float)d + a.eps);
+    rinv = row_rinv(t, d, a.eps);
     // normalise in place: x_hat = bf16(x * g * rinv)
 #pragma unroll
-    for (int u = 0; u < CH; ++u) {
-      const bf16x8 xv = __builtin_bit_cast(bf16x8, xr[u]), gv = __builtin_bit_cast(bf16x8, s_gain[(k_lo >> 3) + 4 * u]);
-      bf16x8 xh;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) xh[e] = (bf16)((float)xv[e] * (float)gv[e] * rinv);
-      xr[u] = __builtin_bit_cast(u32x4, xh);
-    }
+    for (int u = 0; u < CH; ++u) xr[u] = norm_chunk(xr[u], s_gain[(k_lo >> 3) + 4 * u], rinv);
   }
   if (lead && row_ok) {
     bf16 *dst = a.xh + (int64_t)row * d + k_lo;
@@ -258,6 +280,73 @@ __global__ __launch_bounds__(512, 2) void prep_rows_mfma_kernel(PrepArgs a) {
       dst[rank] = (bf16)(t - (float)hi);
     }
   }
+}
+
+// Many rows at d = 4096 and no adapter in the call (a base-model prefill): metadata and RMSNorm only.  A wave takes
+// four consecutive rows whole -- every load and store instruction covers 1 KB of one row, 32 KB are in flight per
+// wave -- sixteen rows per workgroup of four waves, several workgroups per compute unit; the 16-rows-per-tile
+// kernel above holds a whole tile in registers, runs one workgroup per compute unit and needs a second round of
+// workgroups from 4097 rows on.  Same arithmetic in the same order: lane l holds the chunks c = l + 64 j, so
+// l = 4 u + g and j = w in the terms of chunk_ssq's order.
+__global__ __launch_bounds__(256) void norm_rows_kernel(PrepArgs a) {
+  __shared__ unsigned long long s_present;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row0 = blockIdx.x * PREP_ROWS;
+  constexpr int D = 4096, NJ = D / 512, RW = PREP_ROWS / 4;      // rows per wave
+  const int wrow0 = row0 + wave * RW;
+  u32x4 xr[RW][NJ], gr[NJ];
+#pragma unroll
+  for (int i = 0; i < RW; ++i) {
+    const int row = min(wrow0 + i, a.T - 1);      // rows past the end repeat the last one and are not stored
+    const bf16 *xrow = a.x + (int64_t)row * D + lane * 8;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) xr[i][j] = *reinterpret_cast<const u32x4 *>(xrow + 512 * j);
+  }
+  if (a.gain != nullptr) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) gr[j] = *reinterpret_cast<const u32x4 *>(a.gain + lane * 8 + 512 * j);
+  }
+  if (tid == 0) s_present = 0ull;
+  __syncthreads();
+  const int tile_end = min(row0 + PREP_ROWS, a.T);
+  for (int sq = tid; sq < (a.seqs != nullptr ? a.n_seqs : 0); sq += 256) {
+    const SeqMeta sm = a.seqs[sq];
+    const int lo = max(sm.row_start, row0), hi = min(sm.row_start + sm.n_new, tile_end);
+    for (int mrow = lo; mrow < hi; ++mrow) fill_row_meta(a, sm, sq, mrow, row0, a.write_meta != 0, nullptr, nullptr, &s_present);
+  }
+  __syncthreads();
+  if (tid == 0 && a.rm.present16 != nullptr) a.rm.present16[blockIdx.x] = s_present;
+#pragma unroll
+  for (int i = 0; i < RW; ++i) {
+    if (a.gain != nullptr) {
+      float t = 0.f;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        float v = chunk_ssq(xr[i][j]);
+        v += __shfl_xor(v, 4, 64);       // tree over u (lane bits 2..5), neighbours first
+        v += __shfl_xor(v, 8, 64);
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        v += __shfl_xor(v, 1, 64);       // tree over g (lane bits 0, 1)
+        v += __shfl_xor(v, 2, 64);
+        t += v;                          // the eight w in order
+      }
+      const float rinv = row_rinv(t, D, a.eps);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) xr[i][j] = norm_chunk(xr[i][j], gr[j], rinv);
+    }
+    if (wrow0 + i < a.T) {
+      bf16 *dst = a.xh + (int64_t)(wrow0 + i) * D + lane * 8;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) *reinterpret_cast<u32x4 *>(dst + 512 * j) = xr[i][j];
+    }
+  }
+}
+
+bool norm_rows_mfma_supported(int d) { return d == 4096; }
+void launch_norm_rows_mfma(const PrepArgs &a, hipStream_t s) {
+  if (a.T == 0) return;
+  hipLaunchKernelGGL(norm_rows_kernel, dim3((a.T + PREP_ROWS - 1) / PREP_ROWS), dim3(256), 0, s, a);
 }
 
 bool prep_rows_mfma_supported(int d, int rank) {

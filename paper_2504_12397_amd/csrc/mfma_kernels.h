@@ -66,6 +66,10 @@ struct PrepArgs {
 };
 bool prep_rows_mfma_supported(int d, int rank);
 void launch_prep_rows_mfma(const PrepArgs &a, hipStream_t s);
+// metadata and RMSNorm only (A, rank, tlow16 unused), for many rows of a call without adapters: x_hat and
+// metadata bit-identical to launch_prep_rows_mfma's
+bool norm_rows_mfma_supported(int d);
+void launch_norm_rows_mfma(const PrepArgs &a, hipStream_t s);
 
 // One workgroup of the prefill attention kernel: up to 256/G consecutive packed rows (tokens) against the key
 // positions [kbeg, kend) of one kv head, counted from pool row key_row0.  Own rows of one sequence: key_row0 is

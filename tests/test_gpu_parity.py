@@ -345,6 +345,52 @@ def test_base_rows_do_not_depend_on_the_number_of_rows_at_the_8b_width(ab):
         c.close()
 
 
+def test_base_model_rows_are_normalised_to_the_same_bits_by_both_kernels(ab):
+    """A call without adapters at d = 4096 normalises its rows either in the kernel that prepares 16 rows per
+    workgroup or, from 512 rows on, in a row-per-wave kernel (option prep_split).  Both add the squares of a row
+    in the same order, so everything downstream -- cache rows and outputs (Eq.1-3 on the base weights) -- must be
+    the same bits; and the base rows an adapter call writes before its invocation point (Proposition 1) are those
+    bits too."""
+    shape = wl.SHAPE_8B_4AD
+    rng = wl.Rng(313, "cuda")
+    tensors = wl.make_layer(shape, rng)
+    S = [70, 33, 1, 40]
+    cu = [0]
+    for n in S:
+        cu.append(cu[-1] + n)
+    x = wl.make_hidden(rng, "x", cu[-1], shape)
+    got = {}
+    for tag, split, k, a in (("one kernel", 0, [0] * 4, [-1] * 4), ("row per wave", 2, [0] * 4, [-1] * 4),
+                             ("adapter call", 1, [50, 20, 1, 10 ** 6], [2, 0, 3, 1])):
+        c = ab.Context(0)
+        try:
+            c.set_option("prep_split", split)
+            layer = ab.Layer(tensors, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rms_eps, shape.rope_theta)
+            cache = ab.KVCache(S, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda", fill=H.CANARY)
+            out = ab.alora_prefill(c, layer, cache, x, cu, k, a)
+            torch.cuda.synchronize()
+            got[tag] = (out.clone(), [cache.rows(b, 0, S[b]) for b in range(len(S))], k)
+        finally:
+            c.close()
+    assert torch.equal(_bits(got["one kernel"][0]), _bits(got["row per wave"][0])), "outputs differ"
+    for b in range(len(S)):
+        for t in (0, 1):
+            assert torch.equal(_bits(got["one kernel"][1][b][t]), _bits(got["row per wave"][1][b][t])), f"sequence {b}"
+            base = min(S[b], got["adapter call"][2][b])
+            assert torch.equal(_bits(got["adapter call"][1][b][t][:base]), _bits(got["row per wave"][1][b][t][:base])), \
+                f"sequence {b}: rows before the invocation point"
+    host = {k_: (v.cpu() if isinstance(v, torch.Tensor) else v) for k_, v in tensors.items()}
+    worst = 0.0
+    for b in range(len(S)):
+        o_ref, K_ref, V_ref = orc.ref_full(H.oracle_layer(host, shape), H.f64(x[cu[b]:cu[b + 1]]), 0, -1, "bf16")
+        out, rows, _ = got["row per wave"]
+        e = max(H.rel_err(H.f64(out[cu[b]:cu[b + 1]]), o_ref), H.rel_err(H.f64(rows[b][0]).reshape(S[b], -1), K_ref),
+                H.rel_err(H.f64(rows[b][1]).reshape(S[b], -1), V_ref))
+        worst = max(worst, e)
+        assert e <= H.TOL["bf16"], f"sequence {b}: {e}"
+    H.report(check="base-model rows, row-per-wave normalisation", err=worst)
+
+
 def test_zero_delta_reproduces_base_model(ab, ctx):
     shape = SMALL_BF16
     case = H.make_case(shape, [120], [50], [120], [0], seed=306)
