@@ -234,7 +234,10 @@ alora_status alora_decode(alora_ctx *ctx, const alora_layer_desc *layer, alora_k
  * as is B > 4096.  Shared prefixes are not taken (ALORA_EINVAL); the "profile" option is ignored.  All calls on
  * one GPU -- from any context, stream or thread -- share that GPU's array and it keeps the last call's contents:
  * calls that overlap in time on one GPU race, so serialise them (one stream, or events).  Nothing in the array
- * has to start at zero, and nothing is cleared. */
+ * has to start at zero, and nothing is cleared.  Captured into a graph, the call's host-side effects (the checks,
+ * seq_len[b] += 1) happen once, at capture; a replay repeats the captured step -- same positions, same cache rows
+ * written -- on whatever the input buffer holds then.  The other entry points stage metadata through pinned host
+ * slots guarded by events and may grow their workspace: do not capture those. */
 alora_status alora_decode_static(alora_ctx *ctx, const alora_layer_desc *layer, alora_kv_cache *cache,
                                  const void *x_tok, const int32_t *k_per_seq,
                                  const int32_t *adapter_per_seq, int32_t B, void *attn_out, void *stream);

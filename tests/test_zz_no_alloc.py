@@ -1,6 +1,8 @@
 """The entry point that allocates nothing (alora_decode_static) against alora_decode: same kernels, so the
 outputs, the appended cache rows and seq_len must agree bit for bit; two calls in a row on the shared static
-scratch, the second smaller than the first; requests beyond the scratch size are rejected before any launch."""
+scratch, the second smaller than the first; requests beyond the scratch size are rejected before any launch; and,
+since the entry point issues kernel launches only (no allocation, no staging copy, no event), a captured HIP graph of
+it replays to the same bits, with eager work and synchronisations between the replays."""
 import numpy as np
 import pytest
 import torch
@@ -81,5 +83,58 @@ def test_requests_beyond_the_scratch_and_shared_prefixes_are_rejected():
         with pytest.raises(ab.AloraError) as e:
             ab.alora_decode_static(c, layer, small, x[:2].contiguous(), [0, 0], [0, 1], out[:2])
         assert e.value.status == ab.ALORA_EINVAL
+    finally:
+        c.close()
+
+
+def test_replays_of_a_captured_static_decode_step_equal_the_eager_call():
+    from paper_2504_12397_amd import binding as ab
+    c = ab.Context(0)
+    try:
+        case = H.make_case(SMALL_BF16, [700, 33, 1500, 64, 5], [1] * 5, [600, 33, 2000, 0, 0], [0, 1, 1, -1, 2], seed=951,
+                           prefix="random")
+        layer = H.gpu_layer(case, SMALL_BF16)
+        x = case.x_packed.cuda().contiguous()
+        P = np.asarray(case.P, dtype=np.int32)
+
+        def eager(xin):
+            cache = H.gpu_cache(case)
+            out = ab.alora_decode(c, layer, cache, xin, case.k, case.adapter)
+            torch.cuda.synchronize()
+            return out, cache
+
+        ref_out, ref_cache = eager(x)                       # also loads every kernel before the capture
+        warm = H.gpu_cache(case)
+        out_g = torch.zeros_like(ref_out)
+        ab.alora_decode_static(c, layer, warm, x, case.k, case.adapter, out_g)
+        torch.cuda.synchronize()
+
+        cache_g = H.gpu_cache(case)
+        x_g = x.clone()
+        out_g.zero_()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            ab.alora_decode_static(c, layer, cache_g, x_g, case.k, case.adapter, out_g)
+        torch.cuda.synchronize()
+        assert float(out_g.abs().max()) == 0.0, "capture must not execute anything"
+        assert np.array_equal(cache_g.seq_len, P + 1)       # the host-side bookkeeping of the captured call
+
+        for replay in range(4):
+            print(f"replay {replay}", flush=True)
+            if replay >= 2:                                  # new hidden states in the captured input buffer
+                x_g.copy_(torch.roll(x, shifts=replay, dims=1))
+                ref_out, ref_cache = eager(x_g.clone())
+            out_g.fill_(3.0)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(_bits(out_g), _bits(ref_out)), f"replay {replay}: outputs differ from the eager call"
+            assert torch.equal(_bits(cache_g.k), _bits(ref_cache.k)) and torch.equal(_bits(cache_g.v), _bits(ref_cache.v))
+            # eager work of the same library between replays (shares the static scratch)
+            other = H.gpu_cache(case)
+            tmp = torch.empty_like(ref_out)
+            ab.alora_decode_static(c, layer, other, x, case.k, case.adapter, tmp)
+            torch.cuda.synchronize()
+        H.report(check="alora_decode_static under graph capture", replays=4)
     finally:
         c.close()
