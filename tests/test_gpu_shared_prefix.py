@@ -269,3 +269,81 @@ def test_prefill_of_many_short_invocations_on_one_long_context(ab):
         H.report(test="prefill_many_invocations_one_context", err=worst)
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_a_stack_of_adapters_on_one_context_the_base_model_prefilled(ab, dtype):
+    """Section 3's pipeline through a layer stack with one copy of the context: the base model prefills the
+    context (adapter -1) into a slot of its own, layer by layer; N sequences name those rows as their prefix and
+    run N different adapters over their invocation tokens in ONE stack call (Proposition 2 with N adapters; Section
+    2, "Cache reuse patterns"), then generate three tokens each with alora_stack_decode.  The oracle recomputes every
+    sequence on its own -- context, invocation and generated rows -- with position-gated weights.  Asserted end to
+    end for two layers at four times the per-layer tolerance (each layer's own bar is asserted elsewhere); the same
+    run with a private copy of the context per sequence is held to the same bound against the shared one (an
+    indexing mistake in either shows as an error of order one)."""
+    if dtype == "bf16":
+        shape = wl.LayerShape(d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, rank=16, n_adapters=3, intermediate=1024)
+    else:
+        shape = dataclasses.replace(wl.SHAPE_TINY, n_adapters=3, rmsnorm=True, n_kv_heads=2, intermediate=320)
+    n_layers, C, n_dec = 2, 210, 3
+    S = [40, 7, 64, 1]
+    adapter = [0, 2, 1, -1]
+    n = len(S)
+    rng = wl.Rng(970)
+    tensors = [wl.make_layer(shape, rng, f"L{l}") for l in range(n_layers)]
+    layers = [H.oracle_layer(t, shape) for t in tensors]
+    x_ctx = wl.make_hidden(rng, "x_ctx", C, shape)
+    x_own = [wl.make_hidden(rng, f"x{b}", S[b] + n_dec, shape) for b in range(n)]
+    tol = H.TOL[shape.dtype]
+
+    def run(shared):
+        c = ab.Context(0)
+        try:
+            glayers = [H.gpu_layer(t, shape) for t in tensors]
+            if shared:
+                # the sequences hold their own rows only; slot n holds the context, prefilled once by the base model
+                caps = [S[b] + n_dec for b in range(n)] + [C]
+                caches = [ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda") for _ in range(n_layers)]
+                ab.alora_stack_prefill(c, glayers, caches, x_ctx.cuda().contiguous(), [0] * (n + 1) + [C], [0] * (n + 1),
+                                       [-1] * (n + 1))
+                assert int(caches[0].seq_len[n]) == C and int(caches[n_layers - 1].seq_len[n]) == C
+                for cache in caches:
+                    for b in range(n):
+                        cache.share_prefix(b, int(cache.seq_offset[n]), C)
+            else:
+                # every sequence has room for the context too and the base model prefills it n times
+                caps = [C + S[b] + n_dec for b in range(n)]
+                caches = [ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, "cuda") for _ in range(n_layers)]
+                ab.alora_stack_prefill(c, glayers, caches, torch.cat([x_ctx] * n).cuda().contiguous(),
+                                       [b * C for b in range(n + 1)], [0] * n, [-1] * n)
+            assert [int(v) for v in caches[0].seq_len[:n]] == [C] * n
+            cu = [0]
+            for b in range(n):
+                cu.append(cu[-1] + S[b])
+            x_inv = torch.cat([x_own[b][:S[b]] for b in range(n)]).cuda().contiguous()
+            # from here on the calls name the first n sequences only (the context slot is reached through the prefixes)
+            out_inv = ab.alora_stack_prefill(c, glayers, caches, x_inv, cu, [C] * n, adapter)
+            out_dec = []
+            for t in range(n_dec):
+                xt = torch.stack([x_own[b][S[b] + t] for b in range(n)]).cuda().contiguous()
+                out_dec.append(ab.alora_stack_decode(c, glayers, caches, xt, [C] * n, adapter))
+            torch.cuda.synchronize()
+            assert [int(v) for v in caches[n_layers - 1].seq_len[:n]] == [C + S[b] + n_dec for b in range(n)]
+            per_seq = [torch.cat([out_inv[cu[b]:cu[b + 1]]] + [o[b:b + 1] for o in out_dec]) for b in range(n)]
+            return per_seq
+        finally:
+            c.close()
+
+    shared, private = run(True), run(False)
+    worst, worst_sp = 0.0, 0.0
+    for b in range(n):
+        x_all = np.concatenate([H.f64(x_ctx), H.f64(x_own[b])])
+        want, _ = orc.ref_stack_full(layers, x_all, C, adapter[b], shape.dtype)
+        e = H.rel_err(H.f64(shared[b]), want[C:])
+        e_sp = H.rel_err(H.f64(shared[b]), H.f64(private[b]))
+        worst, worst_sp = max(worst, e), max(worst_sp, e_sp)
+        assert e <= 4 * tol, f"sequence {b}: {e:.3e} against the oracle"
+        # (two roundings of the same two-layer run: the private batch prefills the context in a call of another
+        # size, so its layer-0 attention is partitioned differently and layer 1 sees other bf16 neighbours)
+        assert e_sp <= 4 * tol, f"sequence {b}: shared and private copies of the context differ by {e_sp:.3e}"
+    H.report(check="stack of adapters on one shared context", dtype=shape.dtype, err_end_to_end=worst, shared_vs_private=worst_sp)
