@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c4x16", "c5", "r2", "r3", "r3p", "copy"],
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c4x16", "c5", "c5n", "r2", "r3", "r3p", "copy"],
                     help="c5 (default): the first-token workload the metric is quoted on, with the c3 and c4 records "
                          "alongside; copy: a plain 1 GiB device copy, the known-size kernel that calibrates the HBM counters")
     ap.add_argument("--only", action="store_true", help="c5 only: leave out the c3 and c4 records")
@@ -148,6 +148,8 @@ def main():
         return regime2(args, ab, wl, torch, np, dev)
     if name in ("r3", "r3p"):
         return regime3(args, ab, wl, torch, np, dev, prefill=name == "r3p")
+    if name == "c5n":
+        return evaluators(args, ab, wl, torch, np, dev)
     result = run_workload(name, args, ab, wl, torch, np, dev, cpu=not args.no_cpu_baseline)
     if name == "c5" and not args.only:
         # The metric is quoted on c5 (first-token latency against the k = 0 recompute); its two roofline claims
@@ -600,6 +602,124 @@ def regime3(args, ab, wl, torch, np, dev, prefill=False):
     if args.variant == "private":
         result["config"]["workload"] = result["config"]["workload"].replace(
             "the context rows stored once per context", "every sequence holding a private copy of its context's rows")
+    print(json.dumps(result))
+    ctx.close()
+
+
+def evaluators(args, ab, wl, torch, np, dev):
+    """Config 5 with N evaluators on one context, through the whole stack (Proposition 2 for N adapters; Section 2,
+    "Cache reuse patterns", third regime; Section 3's 16-token evaluator answers): one alora_stack_prefill over the N
+    invocation sequences, which all name the single copy of the context's rows, then 15 x (alora_stack_decode +
+    alora_lm_head) for the N sequences; beside it the same calls with a private copy of the context per sequence
+    and the call for a single evaluator."""
+    batch = wl.evaluators_on_one_context()
+    shape = batch.shape
+    n, C0, S = batch.n_seqs, batch.P[0], batch.S[0]
+    n_layers = args.layers or wl.N_LAYERS_STACK
+    n_gen = 16
+    steps, warmup = args.steps or 8, args.warmup or 2
+    ctx = ab.Context(0)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        ctx.set_option(key, int(val))
+    rng = wl.Rng(batch.seed, dev)
+    layers = [ab.Layer(wl.make_layer(shape, rng, f"c5n.L{l}"), shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                       shape.rms_eps, shape.rope_theta, shape.intermediate) for l in range(n_layers)]
+    x = wl.make_hidden(rng, "c5n.x", n * S, shape)
+    x_tok = wl.make_hidden(rng, "c5n.x_tok", n, shape)
+    out = torch.empty((n * S, shape.d), dtype=shape.torch_dtype, device=dev)
+    out_tok = torch.empty((n, shape.d), dtype=shape.torch_dtype, device=dev)
+    V = 128256
+    Wv = rng.normal("lm_head.W", (V, shape.d), 1.0 / np.sqrt(shape.d), dtype=shape.torch_dtype)
+    gf = rng.normal("lm_head.gain", (shape.d,), 0.1, 1.0, dtype=shape.torch_dtype)
+
+    def make_caches(shared, m):
+        caches = []
+        for l in range(n_layers):
+            caps = [(0 if shared else C0) + S + n_gen for _ in range(m)] + ([C0] if shared else [])
+            c = ab.KVCache(caps, shape.n_kv_heads, shape.head_dim, shape.torch_dtype, dev)
+            c.k.normal_()
+            c.v.normal_()
+            for b in range(m):
+                c.seq_len[b] = C0
+                if shared:
+                    c.share_prefix(b, int(c.seq_offset[m]), C0)
+            caches.append(c)
+        return caches
+
+    def run(shared, m, profile=False):
+        caches = make_caches(shared, m)
+        cu = [b * S for b in range(m + 1)]
+        kk, ad = batch.k[:m], batch.adapter[:m]
+
+        def first_tokens():
+            for c in caches:
+                c.seq_len[:m] = C0
+            ab.alora_stack_prefill(ctx, layers, caches, x[:m * S], cu, kk, ad, out[:m * S])
+            # the last row of every sequence goes through the output head
+            last = out[:m * S].view(m, S, shape.d)[:, -1].contiguous()
+            ab.alora_lm_head(ctx, last, gf, shape.rms_eps, Wv)
+
+        def generate(k_steps):
+            for _ in range(k_steps):
+                ab.alora_stack_decode(ctx, layers, caches, x_tok[:m], kk, ad, out_tok[:m])
+                ab.alora_lm_head(ctx, out_tok[:m], gf, shape.rms_eps, Wv)
+
+        for _ in range(warmup):
+            first_tokens()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            first_tokens()
+        torch.cuda.synchronize()
+        ttft = (time.perf_counter() - t0) / steps
+        generate(2)
+        torch.cuda.synchronize()
+        for c in caches:
+            c.seq_len[:m] = C0 + S
+        t0 = time.perf_counter()
+        generate(n_gen - 1)
+        torch.cuda.synchronize()
+        dec = (time.perf_counter() - t0) / (n_gen - 1)
+        prof = None
+        if profile:
+            ctx.set_option("profile", 1)
+            ctx.profile_reset()
+            first_tokens()
+            torch.cuda.synchronize()
+            prof = ctx.profile_read()
+            ctx.set_option("profile", 0)
+        del caches
+        torch.cuda.empty_cache()
+        return ttft, dec, prof
+
+    ttft, dec, prof = run(True, n, profile=True)
+    ttft_private, dec_private, _ = run(False, n) if args.variant == "both" else (None, None, None)
+    ttft_one, dec_one, _ = run(True, 1)
+    avg = prof["attn_prefill"]["ms"] / prof["attn_prefill"]["launches"]
+    alg = n * 4 * shape.head_dim * shape.n_q_heads * (S * C0 + S * (S + 1) // 2)
+    alg_bytes = (C0 + n * S) * 2 * shape.n_kv * 2
+    result = {
+        "metric": "alora_suffix_prefill_tok_per_s", "value": n * S / ttft, "unit": "tok/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ttft * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": "c5n: %d evaluators (one adapter each) x %d adapted tokens on one context of %d cached base "
+                               "tokens stored once, %d layers, output head included" % (n, S, C0, n_layers),
+                   "rank": shape.rank, "layers": n_layers},
+        "roofline": dict(kernel="attn_prefill", bound="mfma", achieved=alg / (avg * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS,
+                         unit="TFLOP/s", frac=alg / (avg * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, traffic=None, avg_ms=avg,
+                         algorithmic_flops=alg, algorithmic_bytes=alg_bytes),
+        "kernels": {k_: dict(avg_ms=round(r["ms"] / r["launches"], 5), launches=r["launches"]) for k_, r in prof.items()},
+        "first_tokens_ms": ttft * 1e3, "first_tokens_ms_per_evaluator": ttft * 1e3 / n,
+        "decode_step_ms": dec * 1e3, "evaluators_16_tokens_ms": (ttft + (n_gen - 1) * dec) * 1e3,
+        "one_evaluator_first_token_ms": ttft_one * 1e3, "one_evaluator_decode_step_ms": dec_one * 1e3,
+        "one_evaluator_16_tokens_ms": (ttft_one + (n_gen - 1) * dec_one) * 1e3,
+        "speedup_vs_one_evaluator_at_a_time": n * (ttft_one + (n_gen - 1) * dec_one) / (ttft + (n_gen - 1) * dec),
+    }
+    if ttft_private is not None:
+        result.update({"private_copies_first_tokens_ms": ttft_private * 1e3, "private_copies_decode_step_ms": dec_private * 1e3,
+                       "private_copies_16_tokens_ms": (ttft_private + (n_gen - 1) * dec_private) * 1e3,
+                       "speedup_vs_private_copies": (ttft_private + (n_gen - 1) * dec_private) / (ttft + (n_gen - 1) * dec)})
     print(json.dumps(result))
     ctx.close()
 

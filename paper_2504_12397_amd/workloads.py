@@ -257,3 +257,13 @@ def config5(full_lora: bool = False) -> Batch:
 
 
 N_LAYERS_STACK = 32
+
+
+def evaluators_on_one_context(n_evaluators: int = 8, context: int = 32768, invocation: int = 128):
+    """Config 5 with N adapters instead of one (Proposition 2: N adapters invoked on one context cost N small
+    prefills, not N recomputations; Section 3's pipeline runs several evaluators on one base answer): N sequences of
+    128 adapted tokens each, every one with an adapter of its own, all reading the same 32768 cached base tokens."""
+    shape = dataclasses.replace(SHAPE_8B_STACK, n_adapters=n_evaluators)
+    n = n_evaluators
+    return Batch(shape, P=[context] * n, S=[invocation] * n, k=[context] * n, adapter=list(range(n)), name="c5n",
+                 seed=BASE_SEED + 9)
