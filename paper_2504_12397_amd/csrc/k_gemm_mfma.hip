@@ -729,7 +729,9 @@ void launch_gemm_mfma(GemmArgs g, int epi, hipStream_t s) {
     else if (g.tile_hint == 1) launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU>(g, s);
     else if (g.M <= 32) launch_cfg<32, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
     else if (g.M <= 128) launch_cfg<128, 128, 32, 64, GEMM_EPI_SWIGLU>(g, s);
-    else launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
+    else if (g.tile_hint == 2 || g.M <= 512) launch_cfg<256, 128, 128, 64, GEMM_EPI_SWIGLU>(g, s);
+    // many row tiles: the woven 128x128 block, two workgroups per compute unit, as in the QKV projection
+    else launch_cfg<128, 128, 64, 64, GEMM_EPI_SWIGLU, 2, true>(g, s);
   } else {
     g.k_splits = 1;
     g.lora_split = 0;

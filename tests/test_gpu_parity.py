@@ -499,6 +499,19 @@ def test_stack_cache_reuse_against_oracle_recompute(ab, ctx, shape):
     assert e2e <= 4 * H.TOL[shape.dtype]      # sanity bound on the compounded run; the bar is per layer, above
 
 
+@pytest.mark.parametrize("adapt_rest", [False, True], ids=["qkv-adapters", "all-linears"])
+def test_stack_prefill_of_many_rows(ab, ctx, adapt_rest):
+    """The stack on calls of more than 512 rows (what the k = 0 recompute of a long context and a batch of several
+    evaluators look like to the linears: many row tiles, the blocks and epilogues chosen for them): the base model
+    prefills 650 rows, an adapter call adds 530 (Eq.6 on q, k, v, or on every linear).  Every layer against the
+    oracle's recompute at the stated tolerance."""
+    shape = dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=adapt_rest)
+    n_layers, P, S, a = 2, 650, 530, 2
+    tensors, layers, x_all = make_stack_case(shape, n_layers, P, S, seed=430)
+    worst = stack_layers_one_by_one(ab, ctx, shape, tensors, layers, x_all, P, a, "stack, many rows")
+    H.report(check="stack prefill of many rows", err=worst)
+
+
 @pytest.mark.parametrize("shape,opts", [(dataclasses.replace(SMALL_BF16, intermediate=1024), {}),
                                         (dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=True), {}),
                                         (dataclasses.replace(SMALL_BF16, intermediate=1024, adapt_rest=True), {"kernels": 1}),
