@@ -289,7 +289,7 @@ def test_base_rows_bitwise_independent_of_batch_composition(ab, ctx):
 def test_base_rows_do_not_depend_on_the_number_of_rows_at_the_8b_width(ab):
     """Proposition 1, strong form, with DEFAULT options at d = 4096 (N = 6144): the key and value rows of
     positions before the invocation point are bit-identical whether a 700-row straddling adapter call, a
-    640-row or a 256-row base call, a 64-row prefill or a 64-sequence decode step computed them -- the
+    650-row or a 256-row base call, a 64-row prefill or a 64-sequence decode step computed them -- the
     reduction axis of the projection is cut into the same segments, summed in the same order, in all of them
     (one workgroup per segment for few rows, one workgroup walking through the segments for many)."""
     shape = wl.SHAPE_8B_4AD
@@ -309,7 +309,7 @@ def test_base_rows_do_not_depend_on_the_number_of_rows_at_the_8b_width(ab):
 
         out_a, c_a = prefill(n, k_inv, 1)               # straddles its invocation point: rows < 600 are base rows
         ka, va = c_a.rows(0, 0, n)
-        for rows in (640, 256, 64):
+        for rows in (650, 256, 64):       # 650: not a multiple of the 16-row tiles of row preparation
             _, c_b = prefill(rows, 0, -1)
             kb, vb = c_b.rows(0, 0, rows)
             m = min(rows, k_inv)
