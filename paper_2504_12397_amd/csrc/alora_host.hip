@@ -734,6 +734,233 @@ void layer_tail(alora_ctx *ctx, const alora_layer_desc *ly, const LayerDims &L, 
   }
 }
 
+// Work list of the MFMA decode kernel: per (row, group of up to eight kv heads) n_own items over the row's own
+// cache rows, and -- when sequences name shared prefixes -- per (group of up to 16 / G rows with the same prefix,
+// group of kv heads) n_shared items over that prefix.  Every (row, head) ends up with n_own + n_shared partial
+// records.  A workgroup's eight waves are hw kv heads x kr sub-ranges of the item's keys.
+struct DecodePlan {
+  std::vector<DecItem> items;      // empty when the list is built on the device (the static entry point)
+  int n_own = 1, n_shared = 0;
+  int n_device_items = 0;          // size of the device-built list: rows x head groups x n_own
+  int hw = 1, kr = 1, groups = 1, cols_max = 1;
+};
+DecodePlan plan_decode_items(const alora_ctx *ctx, const Plan &pl, const LayerDims &L, int B, int n_steps, bool on_device) {
+  DecodePlan dp;
+  const int G = L.n_q_heads / L.n_kv_heads;
+  const int pack = std::max(1, 16 / G);
+  decode_mfma_shape(L.n_kv_heads, &dp.hw, &dp.kr);
+  dp.groups = (L.n_kv_heads + dp.hw - 1) / dp.hw;
+  dp.cols_max = G;
+  int max_own = 1, max_pfx = 0;
+  for (int b = 0; b < B; ++b) {
+    max_own = std::max(max_own, pl.seqs[b].P + n_steps - pl.seqs[b].prefix_len);
+    max_pfx = std::max(max_pfx, pl.seqs[b].prefix_len);
+  }
+  // 16 waves per compute unit (two rounds of workgroups), each over a key range of at least 1024 keys (every range
+  // of a head costs a partial record unless it shares its workgroup): `items` (row, kv head) pairs need so many
+  // ranges each, kr of which share a workgroup (and a partial record).  A handful of sequences over long caches
+  // cannot fill the chip with ranges that long: down to 256 keys then, up to 128 records per head.
+  auto splits_for = [&](int64_t items, int longest) {
+    if (ctx->opt_splits > 0) return ctx->opt_splits;
+    const bool few = 2 * items < ctx->n_cu;
+    const int64_t ranges = std::max<int64_t>(1, std::min<int64_t>((16 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1),
+                                                                  std::max(1, longest / (few ? 256 : 1024))));
+    return (int)std::max<int64_t>(1, std::min<int64_t>(few ? 128 : 64, (ranges + dp.kr - 1) / dp.kr));
+  };
+  dp.n_own = splits_for((int64_t)pl.T * L.n_kv_heads, max_own);
+  std::vector<std::vector<int>> chunks;      // rows that share one prefix, at most `pack` each
+  if (pl.any_prefix) {
+    std::vector<int> order(B);
+    for (int b = 0; b < B; ++b) order[b] = b;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+      if (pl.seqs[x].prefix_off != pl.seqs[y].prefix_off) return pl.seqs[x].prefix_off < pl.seqs[y].prefix_off;
+      return pl.seqs[x].prefix_len < pl.seqs[y].prefix_len;
+    });
+    for (int i = 0; i < B; ++i) {
+      const SeqMeta &m = pl.seqs[order[i]];
+      if (m.n_new <= 0 || m.prefix_len <= 0) continue;     // nothing to read: its records are zero-filled below
+      const bool same = !chunks.empty() && (int)chunks.back().size() < pack &&
+                        pl.seqs[order[i - 1]].prefix_off == m.prefix_off && pl.seqs[order[i - 1]].prefix_len == m.prefix_len &&
+                        pl.seqs[order[i - 1]].prefix_len > 0 && pl.seqs[order[i - 1]].n_new > 0;
+      if (!same) chunks.emplace_back();
+      chunks.back().push_back(m.row_start);
+    }
+    // rows without a prefix still need their shared-part records: empty items (no keys) write them
+    for (int b = 0; b < B; ++b) {
+      const SeqMeta &m = pl.seqs[b];
+      if (m.n_new <= 0 || m.prefix_len > 0) continue;
+      if (chunks.empty() || (int)chunks.back().size() >= pack ||
+          pl.seqs[a_seq_of_row(pl, chunks.back()[0])].prefix_len > 0) chunks.emplace_back();
+      chunks.back().push_back(m.row_start);
+    }
+    dp.n_shared = splits_for((int64_t)chunks.size() * L.n_kv_heads, max_pfx);
+  }
+  dp.n_device_items = pl.T * dp.groups * dp.n_own;
+  for (const auto &rows : chunks) dp.cols_max = std::max(dp.cols_max, (int)rows.size() * G);
+  if (on_device) return dp;
+  for (const auto &rows : chunks)
+    for (int gb = 0; gb < dp.groups; ++gb)
+      for (int sp = 0; sp < dp.n_shared; ++sp) {
+        DecItem it{};
+        it.n_rows = (int)rows.size(); it.g = gb * dp.hw; it.split = sp; it.n_splits = dp.n_shared; it.part = dp.n_own + sp; it.shared = 1;
+        for (size_t i = 0; i < rows.size(); ++i) it.rows[i] = rows[i];
+        dp.items.push_back(it);
+      }
+  for (int row = 0; row < pl.T; ++row)
+    for (int gb = 0; gb < dp.groups; ++gb)
+      for (int sp = 0; sp < dp.n_own; ++sp) {
+        DecItem it{};
+        it.n_rows = 1; it.g = gb * dp.hw; it.split = sp; it.n_splits = dp.n_own; it.part = sp; it.shared = 0;
+        it.rows[0] = row;
+        dp.items.push_back(it);
+      }
+  return dp;
+}
+
+// Work list of the MFMA prefill attention kernel, part 1: how the keys of a (row, head) are cut up.  Sequences that
+// name no shared prefix cut their visible keys into n_own ranges.  Sequences that do cut their own keys (positions
+// from prefix_len on) into n_own ranges, and the prefix into n_sh ranges that are walked once for ALL rows of a run
+// of consecutive sequences naming that same prefix (Section 2, "Cache reuse patterns": several adapters invoked on
+// one context): the rows of such a run are neighbours in the packed batch, so up to 256 / G of them share a
+// workgroup and the prefix keys and values are fetched once per run instead of once per sequence.
+struct PrefixRun { int64_t prefix_off; int prefix_len, row0, n_rows; };
+struct PrefillPlan {
+  std::vector<PrefixRun> runs;
+  int n_own = 1, n_sh = 0;
+};
+PrefillPlan plan_prefill_ranges(const alora_ctx *ctx, const Plan &pl, const LayerDims &L, int B, int attn_waves) {
+  PrefillPlan pp;
+  const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
+  int64_t tiles = 0;
+  int max_own = 1, max_pfx = 0;
+  for (int b = 0; b < B; ++b) {
+    const SeqMeta &m = pl.seqs[b];
+    if (m.n_new <= 0) continue;
+    tiles += (m.n_new + tq - 1) / tq;
+    max_own = std::max(max_own, m.P + m.n_new - m.prefix_len);
+    max_pfx = std::max(max_pfx, m.prefix_len);
+    if (m.prefix_len <= 0) continue;
+    if (!pp.runs.empty() && pp.runs.back().prefix_off == m.prefix_off && pp.runs.back().prefix_len == m.prefix_len &&
+        pp.runs.back().row0 + pp.runs.back().n_rows == m.row_start)
+      pp.runs.back().n_rows += m.n_new;
+    else
+      pp.runs.push_back(PrefixRun{m.prefix_off, m.prefix_len, m.row_start, m.n_new});
+  }
+  if (pp.runs.empty()) {
+    // aim at one full wave of workgroups over the chip, with at least 256 keys per range
+    tiles *= L.n_kv_heads;
+    const int want = (int)std::min<int64_t>(16, std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1)));
+    pp.n_own = ctx->opt_splits > 0 ? ctx->opt_splits : std::max(1, std::min(want, pl.max_len / 256));
+    return pp;
+  }
+  // The work is uneven (long contexts walked by few packed tiles, short own parts walked by many): size the
+  // ranges by work.  One unit = one 64-key tile of one workgroup; aim at two workgroups per compute unit of
+  // equal length, at least four tiles each.
+  int64_t units = 0;
+  for (int b = 0; b < B; ++b) {
+    const SeqMeta &m = pl.seqs[b];
+    for (int q0 = 0; q0 < m.n_new; q0 += tq) units += (m.P + std::min(m.n_new, q0 + tq) - m.prefix_len + 63) / 64;
+  }
+  for (const PrefixRun &r : pp.runs) units += (int64_t)((r.n_rows + tq - 1) / tq) * ((r.prefix_len + 63) / 64);
+  units *= L.n_kv_heads;
+  const int64_t target = std::max<int64_t>(4, units / (2 * (int64_t)ctx->n_cu));
+  auto ranges = [&](int longest) {
+    if (ctx->opt_splits > 0) return ctx->opt_splits;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(16, ((longest + 63) / 64 + target - 1) / target));
+  };
+  pp.n_own = ranges(max_own);
+  pp.n_sh = ranges(max_pfx);
+  return pp;
+}
+
+// Part 2: the items, one per workgroup, in launch order.  Workgroups are dealt round-robin to the 8 XCDs, each with
+// its own L2, and an XCD starts them in list order as compute units become free.  All q-tiles of one (sequence or
+// prefix run, kv head, key range) read the same keys and values, so such a group goes to one XCD: groups are
+// handed out heaviest first to the XCD with the least work so far, and inside an XCD the items run longest first
+// (which keeps the q-tiles of a group next to each other: their lengths differ least).
+std::vector<AttnItem> build_prefill_items(const Plan &pl, const LayerDims &L, int B, int attn_waves, const PrefillPlan &pp) {
+  const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
+  const int n_own = pp.n_own, n_sh = pp.n_sh;
+  struct Group { int64_t cost; std::vector<AttnItem> items; };      // the items of a group stream the same keys
+  std::vector<Group> groups;
+  // range `sp` of `parts` over the key positions [lo, hi), in whole tiles of 64 keys
+  auto cut = [](int lo, int hi, int parts, int sp, AttnItem *it) {
+    int chunk = (std::max(hi - lo, 0) + parts - 1) / parts;
+    chunk = (chunk + 63) & ~63;
+    it->kbeg = (int)std::min<int64_t>(hi, lo + (int64_t)sp * chunk);
+    it->kend = (int)std::min<int64_t>(hi, (int64_t)it->kbeg + chunk);
+  };
+  auto key_tiles = [](const AttnItem &it) { return (int64_t)(it.kend - it.kbeg + 63) / 64 + 1; };
+  for (int b = 0; b < B; ++b) {
+    const SeqMeta &m = pl.seqs[b];
+    if (m.n_new <= 0) continue;
+    // (a sequence without prefix still writes n_own + n_sh records per (row, head): all of them over its own keys)
+    const int parts = m.prefix_len > 0 ? n_own : n_own + n_sh;
+    const int last = ((m.n_new - 1) / tq) * tq;
+    for (int g = 0; g < L.n_kv_heads; ++g)
+      for (int sp = 0; sp < parts; ++sp) {
+        Group gr{0, {}};
+        for (int q0 = last; q0 >= 0; q0 -= tq) {
+          AttnItem it{};
+          it.ntok = std::min(tq, m.n_new - q0);
+          it.row0 = m.row_start + q0;
+          // key positions count from the sequence's first own row (position prefix_len)
+          it.pos0 = m.P + q0 - m.prefix_len;
+          it.key_row0 = m.pool_off + m.prefix_len;
+          it.n_addr = it.pos0 + it.ntok;                  // keys visible to the item's last token
+          cut(0, it.n_addr, parts, sp, &it);
+          it.g = g;
+          it.part = sp;
+          gr.cost += key_tiles(it);
+          gr.items.push_back(it);
+        }
+        groups.push_back(std::move(gr));
+      }
+  }
+  for (const PrefixRun &r : pp.runs)
+    for (int g = 0; g < L.n_kv_heads; ++g)
+      for (int sp = 0; sp < n_sh; ++sp) {
+        Group gr{0, {}};
+        for (int r0 = 0; r0 < r.n_rows; r0 += tq) {
+          AttnItem it{};
+          it.ntok = std::min(tq, r.n_rows - r0);
+          it.row0 = r.row0 + r0;
+          it.pos0 = 1 << 30;                              // every prefix key is visible to every row of the run
+          it.key_row0 = r.prefix_off;
+          it.n_addr = r.prefix_len;
+          cut(0, r.prefix_len, n_sh, sp, &it);
+          it.g = g;
+          it.part = n_own + sp;
+          gr.cost += key_tiles(it);
+          gr.items.push_back(it);
+        }
+        groups.push_back(std::move(gr));
+      }
+  std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
+  std::vector<AttnItem> per_xcd[8];
+  int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (const Group &gr : groups) {
+    int x = 0;
+    for (int i = 1; i < 8; ++i)
+      if (load[i] < load[x]) x = i;
+    load[x] += gr.cost;
+    per_xcd[x].insert(per_xcd[x].end(), gr.items.begin(), gr.items.end());
+  }
+  size_t longest = 0;
+  for (int x = 0; x < 8; ++x) {
+    std::stable_sort(per_xcd[x].begin(), per_xcd[x].end(),
+                     [&](const AttnItem &p, const AttnItem &q) { return key_tiles(p) > key_tiles(q); });
+    longest = std::max(longest, per_xcd[x].size());
+  }
+  std::vector<AttnItem> qtiles;
+  qtiles.reserve(longest * 8);
+  for (size_t i = 0; i < longest; ++i)
+    for (int x = 0; x < 8; ++x)
+      qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : AttnItem{});        // ntok = 0: padding
+  return qtiles;
+}
+
+
 alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, alora_kv_cache *caches,
                  const void *x, const int32_t *cu, const int32_t *kps, const int32_t *aps, int B, void *out,
                  void *stream, bool stack, bool decode = false, int n_steps = 1, bool use_static = false) {
@@ -789,140 +1016,20 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   int n_splits = pick_splits(ctx, pl.T, L.n_kv_heads, pl.max_len);
   const bool decode_mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && decode &&
                            attn_decode_mfma_supported(L);
-  // Decode work list: per (row, group of up to eight kv heads) n_own items over the row's own cache rows, and --
-  // when sequences name shared prefixes -- per (group of up to 16 / G rows with the same prefix, group of kv
-  // heads) n_shared items over that prefix.  Every (row, head) ends up with n_own + n_shared partial records.
-  // A workgroup's eight waves are heads_per_wg kv heads x ranges_per_wg sub-ranges of the item's keys.
-  std::vector<DecItem> ditems;
-  int n_static_items = 0, n_static_n_own = 1;
-  int dec_hw = 1, dec_kr = 1, dec_groups = 1, dec_cols_max = 1;
+  // work lists of the MFMA attention kernels (the number of partial records per (row, head) comes out of them)
+  DecodePlan dp;
+  PrefillPlan pp;
   if (decode_mfma) {
-    const int G = L.n_q_heads / L.n_kv_heads;
-    const int pack = std::max(1, 16 / G);
-    decode_mfma_shape(L.n_kv_heads, &dec_hw, &dec_kr);
-    dec_groups = (L.n_kv_heads + dec_hw - 1) / dec_hw;
-    dec_cols_max = G;
-    int max_own = 1, max_pfx = 0;
-    for (int b = 0; b < B; ++b) {
-      max_own = std::max(max_own, pl.seqs[b].P + n_steps - pl.seqs[b].prefix_len);
-      max_pfx = std::max(max_pfx, pl.seqs[b].prefix_len);
-    }
-    // 16 waves per compute unit (two rounds of workgroups), each over a key range of at least 1024 keys (every range of a head costs a
-    // partial record unless it shares its workgroup): `items` (row, kv head) pairs need so many ranges each,
-    // ranges_per_wg of which share a workgroup (and a partial record).  A handful of sequences over long caches
-    // cannot fill the chip with ranges that long: down to 256 keys then, up to 128 records per head.
-    auto splits_for = [&](int64_t items, int longest) {
-      if (ctx->opt_splits > 0) return ctx->opt_splits;
-      const bool few = 2 * items < ctx->n_cu;
-      const int64_t ranges = std::max<int64_t>(1, std::min<int64_t>((16 * (int64_t)ctx->n_cu + items - 1) / std::max<int64_t>(items, 1),
-                                                                    std::max(1, longest / (few ? 256 : 1024))));
-      return (int)std::max<int64_t>(1, std::min<int64_t>(few ? 128 : 64, (ranges + dec_kr - 1) / dec_kr));
-    };
-    const int n_own = splits_for((int64_t)pl.T * L.n_kv_heads, max_own);
-    int n_shared = 0;
-    std::vector<std::vector<int>> chunks;      // rows that share one prefix, at most `pack` each
-    if (pl.any_prefix) {
-      std::vector<int> order(B);
-      for (int b = 0; b < B; ++b) order[b] = b;
-      std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
-        if (pl.seqs[x].prefix_off != pl.seqs[y].prefix_off) return pl.seqs[x].prefix_off < pl.seqs[y].prefix_off;
-        return pl.seqs[x].prefix_len < pl.seqs[y].prefix_len;
-      });
-      for (int i = 0; i < B; ++i) {
-        const SeqMeta &m = pl.seqs[order[i]];
-        if (m.n_new <= 0 || m.prefix_len <= 0) continue;     // nothing to read: its records are zero-filled below
-        const bool same = !chunks.empty() && (int)chunks.back().size() < pack &&
-                          pl.seqs[order[i - 1]].prefix_off == m.prefix_off && pl.seqs[order[i - 1]].prefix_len == m.prefix_len &&
-                          pl.seqs[order[i - 1]].prefix_len > 0 && pl.seqs[order[i - 1]].n_new > 0;
-        if (!same) chunks.emplace_back();
-        chunks.back().push_back(m.row_start);
-      }
-      // rows without a prefix still need their shared-part records: empty items (no keys) write them
-      for (int b = 0; b < B; ++b) {
-        const SeqMeta &m = pl.seqs[b];
-        if (m.n_new <= 0 || m.prefix_len > 0) continue;
-        if (chunks.empty() || (int)chunks.back().size() >= pack ||
-            pl.seqs[a_seq_of_row(pl, chunks.back()[0])].prefix_len > 0) chunks.emplace_back();
-        chunks.back().push_back(m.row_start);
-      }
-      n_shared = splits_for((int64_t)chunks.size() * L.n_kv_heads, max_pfx);
-    }
-    n_splits = n_own + n_shared;
-    DecItem it{};
-    n_static_items = pl.T * dec_groups * n_own;     // (static entry point: the same list, built on the device)
-    for (const auto &rows : chunks) dec_cols_max = std::max(dec_cols_max, (int)rows.size() * G);
-    if (!use_static) {
-    for (const auto &rows : chunks)
-      for (int gb = 0; gb < dec_groups; ++gb)
-        for (int sp = 0; sp < n_shared; ++sp) {
-          it = DecItem{};
-          it.n_rows = (int)rows.size(); it.g = gb * dec_hw; it.split = sp; it.n_splits = n_shared; it.part = n_own + sp; it.shared = 1;
-          for (size_t i = 0; i < rows.size(); ++i) it.rows[i] = rows[i];
-          ditems.push_back(it);
-        }
-    for (int row = 0; row < pl.T; ++row)
-      for (int gb = 0; gb < dec_groups; ++gb)
-        for (int sp = 0; sp < n_own; ++sp) {
-          it = DecItem{};
-          it.n_rows = 1; it.g = gb * dec_hw; it.split = sp; it.n_splits = n_own; it.part = sp; it.shared = 0;
-          it.rows[0] = row;
-          ditems.push_back(it);
-        }
-    }
-    n_static_n_own = n_own;
+    dp = plan_decode_items(ctx, pl, L, B, n_steps, use_static);
+    n_splits = dp.n_own + dp.n_shared;
   }
-  // Prefill work list, part 1: how the keys of a (row, head) are cut up.  Sequences that name no shared prefix cut
-  // their visible keys into n_parts ranges.  Sequences that do cut their own keys (positions from prefix_len on)
-  // into n_own ranges, and the prefix into n_sh ranges that are walked once for ALL rows of a run of consecutive
-  // sequences naming that same prefix (Section 2, "Cache reuse patterns": several adapters invoked on one context):
-  // the rows of such a run are neighbours in the packed batch, so up to 256 / G of them share a workgroup and the
-  // prefix keys and values are fetched once per run instead of once per sequence.
-  struct PrefixRun { int64_t prefix_off; int prefix_len, row0, n_rows; };
-  std::vector<PrefixRun> runs;
-  int n_own = 1, n_sh = 0;
   if (attn_mfma) {
-    const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
-    int64_t tiles = 0;
-    int max_own = 1, max_pfx = 0;
-    for (int b = 0; b < B; ++b) {
-      const SeqMeta &m = pl.seqs[b];
-      if (m.n_new <= 0) continue;
-      tiles += (m.n_new + tq - 1) / tq;
-      max_own = std::max(max_own, m.P + m.n_new - m.prefix_len);
-      max_pfx = std::max(max_pfx, m.prefix_len);
-      if (m.prefix_len <= 0) continue;
-      if (!runs.empty() && runs.back().prefix_off == m.prefix_off && runs.back().prefix_len == m.prefix_len &&
-          runs.back().row0 + runs.back().n_rows == m.row_start)
-        runs.back().n_rows += m.n_new;
-      else
-        runs.push_back(PrefixRun{m.prefix_off, m.prefix_len, m.row_start, m.n_new});
-    }
-    if (runs.empty()) {
-      // aim at one full wave of workgroups over the chip, with at least 256 keys per range
-      tiles *= L.n_kv_heads;
-      const int want = (int)std::min<int64_t>(16, std::max<int64_t>(1, ctx->n_cu / std::max<int64_t>(tiles, 1)));
-      n_own = ctx->opt_splits > 0 ? ctx->opt_splits : std::max(1, std::min(want, pl.max_len / 256));
-    } else {
-      // The work is uneven (long contexts walked by few packed tiles, short own parts walked by many): size the
-      // ranges by work.  One unit = one 64-key tile of one workgroup; aim at two workgroups per compute unit of
-      // equal length, at least four tiles each.
-      int64_t units = 0;
-      for (int b = 0; b < B; ++b) {
-        const SeqMeta &m = pl.seqs[b];
-        for (int q0 = 0; q0 < m.n_new; q0 += tq) units += (m.P + std::min(m.n_new, q0 + tq) - m.prefix_len + 63) / 64;
-      }
-      for (const PrefixRun &r : runs) units += (int64_t)((r.n_rows + tq - 1) / tq) * ((r.prefix_len + 63) / 64);
-      units *= L.n_kv_heads;
-      const int64_t target = std::max<int64_t>(4, units / (2 * (int64_t)ctx->n_cu));
-      auto ranges = [&](int longest) {
-        if (ctx->opt_splits > 0) return ctx->opt_splits;
-        return (int)std::max<int64_t>(1, std::min<int64_t>(16, ((longest + 63) / 64 + target - 1) / target));
-      };
-      n_own = ranges(max_own);
-      n_sh = ranges(max_pfx);
-    }
-    n_splits = n_own + n_sh;
+    pp = plan_prefill_ranges(ctx, pl, L, B, attn_waves);
+    n_splits = pp.n_own + pp.n_sh;
   }
+  const std::vector<DecItem> &ditems = dp.items;
+  const int n_static_items = dp.n_device_items, n_static_n_own = dp.n_own;
+  const int dec_hw = dp.hw, dec_kr = dp.kr, dec_groups = dp.groups, dec_cols_max = dp.cols_max;
   // kernel family: MFMA for bf16 shapes it covers, plain otherwise
   const bool mfma = layers[0].dtype == ALORA_BF16 && ctx->opt_kernels == 0 && L.d % 64 == 0 &&
                     (L.n_adapters == 0 || (L.rank % 16 == 0 && L.n_adapters <= 64)) && L.n_q % 32 == 0 &&
@@ -992,90 +1099,9 @@ alora_status run(alora_ctx *ctx, const alora_layer_desc *layers, int n_layers, a
   if (st != ALORA_OK) return st;
   st = ensure_rope(ctx, pl.max_len, L.head_dim / 2, layers[0].rope_theta, s);
   if (st != ALORA_OK) return st;
-  // staged metadata: per-sequence records, then the work list of the MFMA attention kernel.
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2, and an XCD starts them
-  // in list order as compute units become free.  All q-tiles of one (sequence or prefix run, kv head,
-  // key range) read the same keys and values, so such a group goes to one XCD: groups are handed out
-  // heaviest first to the XCD with the least work so far, and inside an XCD the items run longest first
-  // (which keeps the q-tiles of a group next to each other: their lengths differ least).
+  // staged metadata: per-sequence records, then the work list of the MFMA attention kernel
   std::vector<AttnItem> qtiles;
-  if (attn_mfma) {
-    const int tq = attn_prefill_mfma_tokens_per_tile(L, attn_waves);
-    struct Group { int64_t cost; std::vector<AttnItem> items; };      // the items of a group stream the same keys
-    std::vector<Group> groups;
-    // range `sp` of `parts` over the key positions [lo, hi), in whole tiles of 64 keys
-    auto cut = [](int lo, int hi, int parts, int sp, AttnItem *it) {
-      int chunk = (std::max(hi - lo, 0) + parts - 1) / parts;
-      chunk = (chunk + 63) & ~63;
-      it->kbeg = (int)std::min<int64_t>(hi, lo + (int64_t)sp * chunk);
-      it->kend = (int)std::min<int64_t>(hi, (int64_t)it->kbeg + chunk);
-    };
-    auto key_tiles = [](const AttnItem &it) { return (int64_t)(it.kend - it.kbeg + 63) / 64 + 1; };
-    for (int b = 0; b < B; ++b) {
-      const SeqMeta &m = pl.seqs[b];
-      if (m.n_new <= 0) continue;
-      const int parts = m.prefix_len > 0 ? n_own : n_splits;
-      const int last = ((m.n_new - 1) / tq) * tq;
-      for (int g = 0; g < L.n_kv_heads; ++g)
-        for (int sp = 0; sp < parts; ++sp) {
-          Group gr{0, {}};
-          for (int q0 = last; q0 >= 0; q0 -= tq) {
-            AttnItem it{};
-            it.ntok = std::min(tq, m.n_new - q0);
-            it.row0 = m.row_start + q0;
-            // key positions count from the sequence's first own row (position prefix_len)
-            it.pos0 = m.P + q0 - m.prefix_len;
-            it.key_row0 = m.pool_off + m.prefix_len;
-            it.n_addr = it.pos0 + it.ntok;                  // keys visible to the item's last token
-            cut(0, it.n_addr, parts, sp, &it);
-            it.g = g;
-            it.part = sp;
-            gr.cost += key_tiles(it);
-            gr.items.push_back(it);
-          }
-          groups.push_back(std::move(gr));
-        }
-    }
-    for (const PrefixRun &r : runs)
-      for (int g = 0; g < L.n_kv_heads; ++g)
-        for (int sp = 0; sp < n_sh; ++sp) {
-          Group gr{0, {}};
-          for (int r0 = 0; r0 < r.n_rows; r0 += tq) {
-            AttnItem it{};
-            it.ntok = std::min(tq, r.n_rows - r0);
-            it.row0 = r.row0 + r0;
-            it.pos0 = 1 << 30;                              // every prefix key is visible to every row of the run
-            it.key_row0 = r.prefix_off;
-            it.n_addr = r.prefix_len;
-            cut(0, r.prefix_len, n_sh, sp, &it);
-            it.g = g;
-            it.part = n_own + sp;
-            gr.cost += key_tiles(it);
-            gr.items.push_back(it);
-          }
-          groups.push_back(std::move(gr));
-        }
-    std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.cost > y.cost; });
-    std::vector<AttnItem> per_xcd[8];
-    int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (const Group &gr : groups) {
-      int x = 0;
-      for (int i = 1; i < 8; ++i)
-        if (load[i] < load[x]) x = i;
-      load[x] += gr.cost;
-      per_xcd[x].insert(per_xcd[x].end(), gr.items.begin(), gr.items.end());
-    }
-    size_t longest = 0;
-    for (int x = 0; x < 8; ++x) {
-      std::stable_sort(per_xcd[x].begin(), per_xcd[x].end(),
-                       [&](const AttnItem &p, const AttnItem &q) { return key_tiles(p) > key_tiles(q); });
-      longest = std::max(longest, per_xcd[x].size());
-    }
-    qtiles.reserve(longest * 8);
-    for (size_t i = 0; i < longest; ++i)
-      for (int x = 0; x < 8; ++x)
-        qtiles.push_back(i < per_xcd[x].size() ? per_xcd[x][i] : AttnItem{});        // ntok = 0: padding
-  }
+  if (attn_mfma) qtiles = build_prefill_items(pl, L, B, attn_waves, pp);
   const size_t seq_bytes = ((size_t)B * sizeof(SeqMeta) + 15) & ~(size_t)15;
   const size_t work_bytes = (qtiles.size() * sizeof(AttnItem) + ditems.size() * sizeof(DecItem) + 15) & ~(size_t)15;   // one of the two lists
   const size_t scale_bytes = stack ? (((size_t)L.n_adapters * sizeof(float) + 15) & ~(size_t)15) : 0;
