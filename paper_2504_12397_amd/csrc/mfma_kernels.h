@@ -12,7 +12,8 @@ struct GemmArgs {
   const bf16 *B; int ldb;      // [N, K]
   const bf16 *B2;              // SwiGLU only: the "up" weights; B holds the "gate" weights, N = 2 * I
   int M, N, K;
-  int tile_hint;               // 0 = automatic; 1 = 128x128 (4 waves), 2 = 256x128, 3 = 256x256, 4 = 128x64, 5/6 = 128x128 with 8 waves of 32x64 / 64x32
+  int tile_hint;               // 0 = automatic; 1 = 128x128 (4 waves), 2 = 256x128, 3 = 256x256, 4 = 128x64,
+                               // 5 / 6 = 128x128 with 8 waves of 32x64 / 64x32
   int k_splits;                // PARTIAL only: workgroups per output tile along the reduction axis, 1 or k_segments
   int k_segments;              // equal segments the reduction axis is cut in, each summed from zero and the sums added
                                // in ascending order (by the consumer of the partials when k_splits == k_segments, by
@@ -73,9 +74,10 @@ void launch_norm_rows_mfma(const PrepArgs &a, hipStream_t s);
 
 // One workgroup of the prefill attention kernel: up to 256/G consecutive packed rows (tokens) against the key
 // positions [kbeg, kend) of one kv head, counted from pool row key_row0.  Own rows of one sequence: key_row0 is
-// its first own row, pos0 the position of the first token counted from there, and the causal mask applies.  Rows of several consecutive sequences over the shared
-// prefix they all name (Section 2, "Cache reuse patterns", several adapters on one context): key_row0 is the prefix,
-// pos0 lies beyond every key, the prefix tile is fetched once for all of them.
+// its first own row, pos0 the position of the first token counted from there, and the causal mask applies.
+// Rows of several consecutive sequences over the shared prefix they all name (Section 2, "Cache reuse patterns",
+// several adapters on one context): key_row0 is the prefix, pos0 lies beyond every key, the prefix tile is
+// fetched once for all of them.
 struct AttnItem {
   int64_t key_row0;         // pool row that holds key position 0 of this item
   int32_t kbeg, kend;       // key positions of this item
