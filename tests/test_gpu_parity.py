@@ -736,6 +736,52 @@ def test_config5_one_layer_full_length(ab, ctx):
     check_case(ab, ctx, case)
 
 
+def test_config5_three_layers_at_full_size_and_a_generated_token(ab, ctx):
+    """The call bench.py times, on three of its 32 layers: d = 4096, 32/8 heads, I = 14336, rank 64, 128 adapted tokens
+    over 32768 cached base tokens per layer (Section 3's first-token measurement), then one token through
+    alora_stack_decode on the caches that call left behind (the first step of the evaluator's answer).  Every layer is
+    checked on its own at the stated tolerance -- layer l of the GPU gets the oracle's layer-l input -- and the
+    three-layer call as a whole is recorded (and bounded at four times that)."""
+    b = wl.config5()
+    shape = b.shape
+    P, S, a = b.P[0], b.S[0], b.adapter[0]
+    n_layers = 3
+    tol = H.TOL["bf16"]
+    cases = [H.make_case(shape, b.P, b.S, b.k, b.adapter, b.seed + 10 * l, prefix="random") for l in range(n_layers)]
+    glayers = [H.gpu_layer(c, shape) for c in cases]
+    caches = [H.gpu_cache(c) for c in cases]
+    x0 = cases[0].x_packed
+    rng = wl.Rng(b.seed + 99)
+    x_tok = wl.make_hidden(rng, "x_tok", 1, shape)
+    out = ab.alora_stack_prefill(ctx, glayers, caches, x0.cuda().contiguous(), cases[0].cu, b.k, b.adapter)
+    out_tok = ab.alora_stack_decode(ctx, glayers, caches, x_tok.cuda().contiguous(), b.k, b.adapter)
+    torch.cuda.synchronize()
+    assert int(caches[0].seq_len[0]) == P + S + 1 and int(caches[n_layers - 1].seq_len[0]) == P + S + 1
+
+    x, xt = H.f64(x0), H.f64(x_tok)
+    pos = P + np.arange(S)
+    for l, c in enumerate(cases):
+        xin, xtin = orc._store(x, "bf16"), orc._store(xt, "bf16")
+        o, kn, vn = orc.ref_cached(c.layer, c.cache_K[0], c.cache_V[0], P, xin, P, a, "bf16")
+        want = orc.layer_tail(c.layer, xin, o, "bf16", pos, P, a)
+        # the generated token reads the cached rows and the 128 rows the prefill appended
+        K1, V1 = np.concatenate([c.cache_K[0], kn]), np.concatenate([c.cache_V[0], vn])
+        ot, _, _ = orc.ref_cached(c.layer, K1, V1, P + S, xtin, P, a, "bf16")
+        want_tok = orc.layer_tail(c.layer, xtin, ot, "bf16", np.asarray([P + S]), P, a)
+        # layer l alone on the oracle's layer input
+        cache_l = H.gpu_cache(c, extra_capacity=5)
+        got = ab.alora_stack_prefill(ctx, [glayers[l]], [cache_l], torch.from_numpy(xin).to(torch.bfloat16).cuda(), c.cu, b.k, b.adapter)
+        got_tok = ab.alora_stack_decode(ctx, [glayers[l]], [cache_l], torch.from_numpy(xtin).to(torch.bfloat16).cuda(), b.k, b.adapter)
+        torch.cuda.synchronize()
+        e, et = H.rel_err(H.f64(got), want), H.rel_err(H.f64(got_tok), want_tok)
+        H.report(check="config 5, layer by layer", layer=l, err_first_tokens=e, err_generated_token=et, tol=tol)
+        assert e <= tol and et <= tol, f"layer {l}: {e:.3e} / {et:.3e} > {tol}"
+        x, xt = want, want_tok
+    e2e, e2e_tok = H.rel_err(H.f64(out), x), H.rel_err(H.f64(out_tok), xt)
+    H.report(check="config 5, three layers in one call (recorded)", err_first_tokens=e2e, err_generated_token=e2e_tok)
+    assert e2e <= 4 * tol and e2e_tok <= 4 * tol
+
+
 # ------------------------------------------------------------------ shapes off the main path and kernel options
 @pytest.mark.parametrize("hq,hkv,h,r", [(4, 4, 128, 16), (8, 4, 128, 32), (16, 2, 128, 16), (8, 2, 64, 16), (6, 2, 96, 8),
                                          (8, 8, 128, 64)])
