@@ -888,3 +888,50 @@ def test_workspace_regrowth_and_context_reuse(ab):
         assert torch.equal(a1.view(torch.int16), a2.view(torch.int16))
     finally:
         c.close()
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other(ab):
+    """A serving process runs several streams: two contexts, each on a stream of its own, enqueue prefill and decode
+    calls alternately without waiting for each other (nothing in a context is shared with another: workspace,
+    staging slots, rotary table).  Every result must be the bits the same call gives when it runs alone."""
+    shape = SMALL_BF16
+    pre = H.make_case(shape, [700, 10, 0], [150, 33, 64], [700, 20, 0], [0, 2, 1], seed=960, prefix="random")
+    dec = H.make_case(shape, [900, 64, 3, 1500], [1, 1, 1, 1], [100, 64, 0, 10 ** 6], [1, -1, 2, 0], seed=961, prefix="random")
+    layer_p, layer_d = H.gpu_layer(pre, shape), H.gpu_layer(dec, shape)
+    xp, xd = pre.x_packed.cuda().contiguous(), dec.x_packed.cuda().contiguous()
+
+    def alone(case, layer, x, decode):
+        c = ab.Context(0)
+        try:
+            cache = H.gpu_cache(case)
+            out = (ab.alora_decode(c, layer, cache, x, case.k, case.adapter) if decode
+                   else ab.alora_prefill(c, layer, cache, x, case.cu, case.k, case.adapter))
+            torch.cuda.synchronize()
+            return out.clone(), cache.k.clone(), cache.v.clone()
+        finally:
+            c.close()
+
+    ref_p, ref_d = alone(pre, layer_p, xp, False), alone(dec, layer_d, xd, True)
+    ca, cb = ab.Context(0), ab.Context(0)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        torch.cuda.synchronize()
+        rounds = 6
+        caches_p = [H.gpu_cache(pre) for _ in range(rounds)]
+        caches_d = [H.gpu_cache(dec) for _ in range(rounds)]
+        outs_p = [torch.empty_like(ref_p[0]) for _ in range(rounds)]
+        outs_d = [torch.empty_like(ref_d[0]) for _ in range(rounds)]
+        torch.cuda.synchronize()
+        for r in range(rounds):
+            ab.alora_prefill(ca, layer_p, caches_p[r], xp, pre.cu, pre.k, pre.adapter, outs_p[r], stream=sa)
+            ab.alora_decode(cb, layer_d, caches_d[r], xd, dec.k, dec.adapter, outs_d[r], stream=sb)
+        sa.synchronize()
+        sb.synchronize()
+        for r in range(rounds):
+            assert torch.equal(_bits(outs_p[r]), _bits(ref_p[0])) and torch.equal(_bits(caches_p[r].k), _bits(ref_p[1])) \
+                and torch.equal(_bits(caches_p[r].v), _bits(ref_p[2])), f"prefill, round {r}"
+            assert torch.equal(_bits(outs_d[r]), _bits(ref_d[0])) and torch.equal(_bits(caches_d[r].k), _bits(ref_d[1])) \
+                and torch.equal(_bits(caches_d[r].v), _bits(ref_d[2])), f"decode, round {r}"
+    finally:
+        ca.close()
+        cb.close()
