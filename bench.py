@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c4x16", "c5", "c5n", "r2", "r3", "r3p", "copy"],
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c4x16", "c4s", "c5", "c5n", "r2", "r3", "r3p", "copy"],
                     help="c5 (default): the first-token workload the metric is quoted on, with the c3 and c4 records "
                          "alongside; copy: a plain 1 GiB device copy, the known-size kernel that calibrates the HBM counters")
     ap.add_argument("--only", action="store_true", help="c5 only: leave out the c3 and c4 records")
@@ -150,7 +150,9 @@ def main():
         return regime3(args, ab, wl, torch, np, dev, prefill=name == "r3p")
     if name == "c5n":
         return evaluators(args, ab, wl, torch, np, dev)
-    result = run_workload(name, args, ab, wl, torch, np, dev, cpu=not args.no_cpu_baseline)
+    # (c4s carries no cpu_baseline: the oracle sample of c4 covers its attention block, the stack's other linears
+    # are those of c5's sample)
+    result = run_workload(name, args, ab, wl, torch, np, dev, cpu=not args.no_cpu_baseline and name != "c4s")
     if name == "c5" and not args.only:
         # The metric is quoted on c5 (first-token latency against the k = 0 recompute); its two roofline claims
         # live on other shapes -- the MFMA fraction of the projection and prefill attention on the mixed batch c3,
@@ -176,16 +178,25 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
     n_dec = 1
     if name == "c4x16":
         name, n_dec = "c4", 16
+    # c4s: the c4 decode step through the whole stack (alora_stack_decode: attention, output projection and MLP of
+    # every layer), what a token of the batch costs end to end
+    stack_decode = name == "c4s"
+    if stack_decode:
+        name = "c4"
     batch = {"c2": wl.config2, "c3": wl.config3, "c4": wl.config4, "c5": wl.config5}[name]()
     shape = batch.shape
     n_layers = 1
+    if stack_decode:
+        import dataclasses
+        shape = dataclasses.replace(shape, intermediate=wl.SHAPE_8B_STACK.intermediate)
+        n_layers = args.layers or wl.N_LAYERS_STACK
     if name == "c5":
         n_layers = args.layers or wl.N_LAYERS_STACK
         if args.adapt_rest:
             import dataclasses
             shape = dataclasses.replace(shape, adapt_rest=True)
-    steps = args.steps or {"c2": 200, "c3": 60, "c4": 50, "c5": 10}[name]
-    warmup = args.warmup or {"c2": 20, "c3": 15, "c4": 5, "c5": 2}[name]
+    steps = args.steps or (10 if stack_decode else {"c2": 200, "c3": 60, "c4": 50, "c5": 10}[name])
+    warmup = args.warmup or (2 if stack_decode else {"c2": 20, "c3": 15, "c4": 5, "c5": 2}[name])
     rotate = args.rotate if args.rotate >= 0 else {"c2": 8, "c3": 2, "c4": 1, "c5": 1}[name]
     rotate = max(1, rotate)
 
@@ -221,6 +232,12 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
             # the real flow: a base-model prefill (adapter -1) of the prefix creates the cache
             xp = wl.make_hidden(rng, f"{tag}.x_prefix", batch.P[0], shape)
             ab.alora_prefill(ctx, layers[0], caches[0], xp, [0, batch.P[0]], [0], [-1])
+        elif stack_decode:
+            # (tens of GB over the layers: filled in place by the device generator)
+            for c in caches:
+                c.k.normal_()
+                c.v.normal_()
+                c.seq_len[:] = np.asarray(batch.P, dtype=np.int32)
         else:
             # prefixes too long for a base pass inside a benchmark: N(0,1) keys/values, the
             # distribution the seeded weights and inputs produce
@@ -236,7 +253,7 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
     for i, (layers, caches) in enumerate(sets):
         fill_prefix(layers, caches, f"set{i}")
 
-    out = torch.empty((batch.T, shape.d if name == "c5" else shape.n_q), dtype=shape.torch_dtype, device=dev)
+    out = torch.empty((batch.T, shape.d if (name == "c5" or stack_decode) else shape.n_q), dtype=shape.torch_dtype, device=dev)
 
     def step(i, b=batch, x=x_new, o=out):
         layers, caches = sets[i % rotate]
@@ -244,6 +261,8 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
             c.seq_len[:] = np.asarray(b.P, dtype=np.int32)
         if n_dec > 1:
             ab.alora_decode_steps(ctx, layers[0], caches[0], x_steps, b.k, b.adapter, out_steps)
+        elif stack_decode:
+            ab.alora_stack_decode(ctx, layers, caches, x, b.k, b.adapter, o)
         elif name == "c4":
             ab.alora_decode(ctx, layers[0], caches[0], x, b.k, b.adapter, o)
         elif name == "c5":
@@ -311,6 +330,10 @@ def run_workload(name, args, ab, wl, torch, np, dev, cpu=True):
         "c5": "c5: %d-layer 8B-class stack, 32768 cached base tokens + 128 adapted suffix tokens, rank 64, "
               "time to the first adapter token against the k = 0 full-LoRA recompute" % n_layers,
     }[name]
+    if stack_decode:
+        result["config"]["workload"] = ("c4s: decode step through %d layers of the 8B-class stack (attention, output "
+                                        "projection, SwiGLU MLP), 64 sequences x (16384 base + 64 adapted cached tokens)"
+                                        % n_layers)
     if n_dec > 1:
         result["config"]["workload"] = ("c4x16: the c4 batch decoding %d tokens per sequence in one staged call "
                                         "(64 sequences x 16448 cached tokens at the start)" % n_dec)
